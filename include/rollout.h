@@ -1,0 +1,211 @@
+/*
+ * rollout.h - C ABI of the MI355X rollout-generation library (librollout.so).
+ *
+ * The library runs the generation stage of an RL-for-LLM iteration on one GPU: for a
+ * batch of prompts it computes the key-value cache (prefill phase), then generates n
+ * sampled responses per prompt token by token (decoding phase) until each sample meets
+ * its termination criterion, and it evaluates the inference stage's single forward pass
+ * that yields per-token log-probs of given sequences (paper section 2.1, "Optimization
+ * Workflow").  Requests live and die sample by sample: prompts can be added while others
+ * decode and any sample can be aborted (paper section 4.1, "Rollout Scheduler"; section
+ * 4.3, "Sample-level Rollout Lifecycle Control").
+ *
+ * Conventions
+ *   - Every function returns ROLLOUT_OK (0) or a negative ROLLOUT_E_* code unless stated
+ *     otherwise; rollout_last_error() gives the text.  A failing call changes no state.
+ *     No C++ exception crosses this boundary.
+ *   - "host" pointers are ordinary CPU memory owned by the caller; "device" pointers are
+ *     HIP device memory on the current device.  Output buffers are caller-allocated and
+ *     valid when the call returns (the library synchronises its stream once per call).
+ *   - A context is bound to the device that was current in rollout_init and is not
+ *     thread-safe; calls on one context must not overlap.
+ *   - Sample id = (global prompt counter) * n_samples + j.  A sample's tokens depend only
+ *     on the weights, its prompt, the seed and its id, never on what else is in flight.
+ *   - Response position t = 0 is emitted by rollout_prefill, position t >= 1 by the t-th
+ *     rollout_decode_step after it.  A sample finishes when it emits eos_id (the token is
+ *     reported) or its max_new_tokens-th token.
+ */
+#ifndef ROLLOUT_H
+#define ROLLOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ROLLOUT_ABI_VERSION 1
+
+#define ROLLOUT_OK 0
+#define ROLLOUT_E_INVAL (-1) /* bad argument or unsupported shape */
+#define ROLLOUT_E_NOMEM (-2) /* KV pool, live-sample table or workspace too small; nothing admitted */
+#define ROLLOUT_E_HIP (-3)   /* a HIP call failed or no usable GPU */
+#define ROLLOUT_E_STATE (-4) /* call not valid in the context's current state */
+
+#define ROLLOUT_DTYPE_F32 0
+#define ROLLOUT_DTYPE_BF16 1
+
+/* runtime flags */
+#define ROLLOUT_RT_SIMPLE_KERNELS 1u /* run every operator with the plain one-op-per-kernel path */
+
+typedef struct rollout_ctx rollout_ctx; /* opaque; created by rollout_init, freed by rollout_destroy */
+
+/* Decoder-only transformer shape.  Operators: RMSNorm, bias-free projections, half-split
+ * rotary embedding, grouped-query causal attention, SwiGLU feed-forward or (n_experts > 0)
+ * a mixture of SwiGLU experts with top_k softmax routing, untied lm_head.  flags must be 0. */
+typedef struct {
+  int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
+  int32_t n_experts, top_k, expert_ffn_dim; /* 0, 0, 0 = dense */
+  float rms_eps, rope_theta;
+  int32_t dtype; /* ROLLOUT_DTYPE_*: storage type of weights and of the KV cache */
+  uint32_t flags;
+} rollout_model_desc;
+
+/* One layer's tensors: DEVICE pointers, model dtype, row-major [out_features][in_features]
+ * (y = W x).  Dense: w_gate, w_up [ffn][hidden], w_down [hidden][ffn], router NULL.
+ * MoE: router [n_experts][hidden]; w_gate, w_up [n_experts][expert_ffn][hidden];
+ * w_down [n_experts][hidden][expert_ffn]. */
+typedef struct {
+  const void *norm1, *wq, *wk, *wv, *wo, *norm2;
+  const void *w_gate, *w_up, *w_down;
+  const void *router;
+} rollout_layer_weights;
+
+/* embed [vocab][hidden], final_norm [hidden], lm_head [vocab][hidden]: DEVICE pointers.
+ * layers: HOST array of n_layers entries.  rollout_init copies every tensor into the
+ * library's own layout; the caller may free its copies as soon as rollout_init returns. */
+typedef struct {
+  const void *embed, *final_norm, *lm_head;
+  const rollout_layer_weights *layers;
+} rollout_weights;
+
+typedef struct {
+  size_t kv_pool_bytes;     /* device bytes for KV pages; the library allocates them */
+  int32_t page_tokens;      /* tokens per page: a multiple of 32 */
+  int32_t max_live_samples; /* capacity of the live-sample table */
+  int32_t max_context;      /* longest prompt + response per sample, in tokens */
+  int32_t max_batch_tokens; /* rows per prefill / log-prob chunk (workspace); >= longest sequence */
+  void *hip_stream;         /* hipStream_t the library launches on; NULL = the null stream */
+  uint64_t seed;            /* key of the Philox4x32-10 stream that drives sampling */
+  uint32_t flags;           /* ROLLOUT_RT_* */
+} rollout_runtime_desc;
+
+typedef struct {
+  uint64_t decode_steps, tokens_emitted, prompts_prefilled, prompt_tokens, samples_admitted,
+      samples_finished, samples_aborted;
+  int32_t live_samples, pages_total, pages_in_use, pages_reserved, pages_peak;
+} rollout_stats;
+
+/* Creates a context on the current device: copies the weights, allocates the KV pool and
+ * workspaces.  Paper section 2.1: the actor model that generates responses.
+ * Errors: E_INVAL (bad shape / descriptor), E_HIP (no device, allocation failed). */
+int rollout_init(rollout_ctx **out, const rollout_model_desc *model, const rollout_weights *weights,
+                 const rollout_runtime_desc *runtime);
+
+/* Prefill phase + first token ("add request", paper sections 2.1 and 4.3).  Admits
+ * n_prompts prompts with n_samples samples each, all or none: computes each prompt's KV
+ * cache once into pages shared by its samples, then draws response position 0 for every
+ * sample from the prompt's last-position logits.  May be called while other samples are
+ * live.
+ *   tokens            host int32, the prompts concatenated; offsets host int32 [n_prompts+1]
+ *   max_new_tokens    host int32 [n_prompts*n_samples], each >= 1
+ *   eos_id            token id that ends a sample, or -1
+ *   temperature, top_p  sampling parameters stored per sample (temperature > 0)
+ *   forced_first      NULL, or host int32 [n_prompts*n_samples]: tokens to emit instead of
+ *                     drawn ones (teacher forcing); their log-probs are reported
+ *   uniform_override  NULL, or host uint32 [n_prompts*n_samples]: words to use instead of
+ *                     the Philox stream for this draw
+ * Outputs (host, [n_prompts*n_samples], any may be NULL): sample_ids, first_tokens,
+ * first_logprobs, finished (1 when the sample already ended).
+ * Errors: E_INVAL; E_NOMEM when pages (worst case reserved up front: every sample's
+ * max_new_tokens), live slots or max_batch_tokens do not suffice - nothing is admitted. */
+int rollout_prefill(rollout_ctx *ctx, int32_t n_prompts, const int32_t *tokens, const int32_t *offsets,
+                    int32_t n_samples, const int32_t *max_new_tokens, int32_t eos_id, float temperature,
+                    float top_p, const int32_t *forced_first, const uint32_t *uniform_override,
+                    int64_t *sample_ids, int32_t *first_tokens, float *first_logprobs, uint8_t *finished);
+
+/* Number of live samples; when ids != NULL writes up to capacity ids in ascending order,
+ * the order every per-sample array of rollout_decode_step uses.  Returns the count. */
+int rollout_live_samples(rollout_ctx *ctx, int32_t capacity, int64_t *ids);
+
+/* One decoding-phase step (paper section 2.1): feeds every live sample's last token,
+ * extends its KV cache by one position and emits its next token and that token's log-prob
+ * (log-softmax of the temperature-scaled logits over the full vocabulary).  Finished
+ * samples leave the live set and their pages return to the pool.
+ *   forced_tokens     NULL, or host int32 [live]: tokens to emit instead of drawn ones
+ *   uniform_override  NULL, or host uint32 [live]
+ *   n_live            in: capacity of the output arrays; out: samples stepped
+ * Outputs (host, ascending sample id, any may be NULL): sample_ids, tokens, logprobs,
+ * finished.  Errors: E_INVAL (capacity too small). With no live sample: *n_live = 0, OK. */
+int rollout_decode_step(rollout_ctx *ctx, const int32_t *forced_tokens, const uint32_t *uniform_override,
+                        int32_t *n_live, int64_t *sample_ids, int32_t *tokens, float *logprobs,
+                        uint8_t *finished);
+
+/* Inference-stage forward (paper section 2.1: one forward pass over generated sequences,
+ * prefill only): log p(token_t | tokens_<t) at `temperature` for packed sequences, with the
+ * same kernels as prefill.  tokens host int32 [cu_seqlens[n_seqs]]; cu_seqlens host int32
+ * [n_seqs+1]; logprobs host float [total], 0 at each sequence's first token.  Uses free KV
+ * pages as scratch.  Errors: E_INVAL; E_NOMEM if one sequence exceeds max_batch_tokens,
+ * max_context or the free pages. */
+int rollout_logprobs(rollout_ctx *ctx, int32_t n_seqs, const int32_t *tokens, const int32_t *cu_seqlens,
+                     float temperature, float *logprobs);
+
+/* "Abort request" (paper section 4.3): drops the listed live samples and frees their
+ * pages.  Ids that are not live are ignored.  Returns the number aborted. */
+int rollout_abort(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids);
+
+/* Parity hook: copies the fp32 logits rows of the last prefill (one per prompt, prompt
+ * order) or decode step (one per stepped sample, ascending id) to host `out`
+ * [rows][vocab].  rows: in capacity, out count.  Errors: E_INVAL, E_STATE (none yet). */
+int rollout_debug_logits(rollout_ctx *ctx, int32_t *rows, float *out);
+
+int rollout_get_stats(rollout_ctx *ctx, rollout_stats *out);
+const char *rollout_last_error(rollout_ctx *ctx); /* ctx may be NULL: error of the last failed rollout_init */
+void rollout_destroy(rollout_ctx *ctx);
+int rollout_abi_version(void);
+
+/* Stand-alone sampling over given logits (the decode step's last stage): for each row,
+ * temperature scaling, top-p nucleus on integer weights, inverse-CDF draw with the row's
+ * 32-bit word, and the log-prob of the chosen token.
+ *   logits DEVICE float [rows][vocab] (row stride = vocab); uniforms host uint32 [rows];
+ *   forced NULL or host int32 [rows] (then tokens = forced, log-probs of those);
+ *   tokens host int32 [rows]; logprobs host float [rows]; weight_sums NULL or host uint64
+ *   [rows] (sum of the integer weights, for parity).  hip_stream as in the runtime desc.
+ * Errors: E_INVAL, E_HIP. */
+int rollout_sample(const float *logits, int32_t rows, int32_t vocab, float temperature, float top_p,
+                   const uint32_t *uniforms, const int32_t *forced, void *hip_stream, int32_t *tokens,
+                   float *logprobs, uint64_t *weight_sums);
+
+/* Writes words[i] = Philox4x32-10 output word 0 for key (seed lo, seed hi) and counter
+ * (sample_ids[i] lo, sample_ids[i] hi, steps[i], 0), computed on the device; all arrays
+ * host, length n.  Parity hook for the generator. */
+int rollout_philox_words(uint64_t seed, int32_t n, const int64_t *sample_ids, const uint32_t *steps,
+                         uint32_t *words);
+
+/* ---- paged KV allocator, host side (paper section 4.1: requests are added "based on
+ * current resource availability").  Pure CPU bookkeeping, usable without a GPU. ---- */
+typedef struct rollout_pool rollout_pool;
+rollout_pool *rollout_pool_create(int32_t n_pages);
+void rollout_pool_destroy(rollout_pool *p);
+int32_t rollout_pool_free_pages(const rollout_pool *p);     /* pages on the free list */
+int32_t rollout_pool_unreserved(const rollout_pool *p);     /* free pages not promised to anyone */
+int rollout_pool_reserve(rollout_pool *p, int32_t n);       /* promise n pages; E_NOMEM if unavailable */
+void rollout_pool_unreserve(rollout_pool *p, int32_t n);    /* give back unused promises */
+int32_t rollout_pool_alloc(rollout_pool *p, int from_reservation); /* page id (refcount 1) or E_NOMEM */
+int rollout_pool_retain(rollout_pool *p, int32_t page);     /* refcount + 1; returns new count or E_INVAL */
+int rollout_pool_release(rollout_pool *p, int32_t page);    /* refcount - 1, frees at 0; new count or E_INVAL */
+int32_t rollout_pool_refcount(const rollout_pool *p, int32_t page);
+
+/* Pages one prompt and its samples need: *shared = full prompt pages (one copy, shared by
+ * all samples), *tail = 1 when the prompt ends inside a page (staged once, copied per
+ * sample), private_pages[j] = pages sample j will own when it runs to max_new_tokens[j]
+ * (0 when it emits a single token).  Returns the peak total, shared + tail + sum private. */
+int64_t rollout_plan_pages(int32_t prompt_len, int32_t page_tokens, int32_t n_samples,
+                           const int32_t *max_new_tokens, int32_t *shared, int32_t *tail,
+                           int32_t *private_pages);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROLLOUT_H */

@@ -1,0 +1,620 @@
+// extern "C" boundary of librollout.so: argument checks, the sample table and page
+// accounting on the host, and the launch sequences of prefill, decode step, teacher-forced
+// log-probs and abort.  See include/rollout.h for the contract of each entry point.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+#include "engine.h"
+
+static thread_local std::string g_init_error;
+
+static void fail(int code, const std::string& msg) { throw ApiError{code, msg}; }
+
+template <typename F>
+static int guarded(rollout_ctx* ctx, F&& body) {
+  std::string* err = ctx ? &ctx->err : &g_init_error;
+  try {
+    body();
+    return ROLLOUT_OK;
+  } catch (const ApiError& e) {
+    *err = e.msg;
+    return e.code;
+  } catch (const HipError& e) {
+    *err = std::string("HIP error ") + hipGetErrorString(e.code) + " in " + e.expr + " (" + e.file + ":" +
+           std::to_string(e.line) + ")";
+    return ROLLOUT_E_HIP;
+  } catch (const std::bad_alloc&) {
+    *err = "host allocation failed";
+    return ROLLOUT_E_NOMEM;
+  } catch (...) {
+    *err = "unexpected internal error";
+    return ROLLOUT_E_STATE;
+  }
+}
+
+static void h2d(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes) HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, s));
+}
+static void d2h(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes) HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, s));
+}
+
+__global__ void init_slots_kernel(SlotState st, const int* __restrict__ slots, const int* __restrict__ sample_row,
+                                  const int* __restrict__ pos, const int* __restrict__ tokens,
+                                  const long long* __restrict__ ids, const float* __restrict__ inv_temp,
+                                  const float* __restrict__ top_p, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  int sl = slots[i], row = sample_row[i];
+  st.last_token[sl] = tokens[row];
+  st.pos[sl] = pos[i];
+  st.step[sl] = 1;
+  st.sample_id[sl] = ids[row];
+  st.inv_temp[sl] = inv_temp[row];
+  st.top_p[sl] = top_p[row];
+}
+
+static void release_sample(rollout_ctx& c, Sample& s) {
+  for (int32_t p : s.pages) c.pool->release(p);
+  s.pages.clear();
+  if (s.slot >= 0) c.free_slots.push_back(s.slot);
+  s.slot = -1;
+}
+
+static void refresh_stats(rollout_ctx& c) {
+  c.stats.live_samples = (int32_t)c.live.size();
+  c.stats.pages_total = c.pool->total();
+  c.stats.pages_in_use = c.pool->in_use();
+  c.stats.pages_reserved = c.pool->reserved;
+  c.stats.pages_peak = c.pool->peak_in_use;
+}
+
+extern "C" {
+
+int rollout_abi_version(void) { return ROLLOUT_ABI_VERSION; }
+
+const char* rollout_last_error(rollout_ctx* ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+int rollout_init(rollout_ctx** out, const rollout_model_desc* model, const rollout_weights* weights,
+                 const rollout_runtime_desc* runtime) {
+  if (out) *out = nullptr;
+  rollout_ctx* c = nullptr;
+  int rc = guarded(nullptr, [&] {
+    if (!out || !model || !weights || !runtime) fail(ROLLOUT_E_INVAL, "null argument");
+    c = new rollout_ctx();
+    c->md = *model;
+    c->rd = *runtime;
+    engine_init(*c, *weights);
+    refresh_stats(*c);
+  });
+  if (rc != ROLLOUT_OK) {
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return ROLLOUT_OK;
+}
+
+void rollout_destroy(rollout_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipStreamSynchronize(ctx->stream);
+  delete ctx;
+}
+
+int rollout_get_stats(rollout_ctx* ctx, rollout_stats* out) {
+  if (!ctx || !out) return ROLLOUT_E_INVAL;
+  refresh_stats(*ctx);
+  *out = ctx->stats;
+  return ROLLOUT_OK;
+}
+
+int rollout_live_samples(rollout_ctx* ctx, int32_t capacity, int64_t* ids) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  if (ids) {
+    int32_t i = 0;
+    for (auto& kv : ctx->live) {
+      if (i >= capacity) break;
+      ids[i++] = kv.first;
+    }
+  }
+  return (int)ctx->live.size();
+}
+
+int rollout_prefill(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, const int32_t* offsets,
+                    int32_t n_samples, const int32_t* max_new_tokens, int32_t eos_id, float temperature,
+                    float top_p, const int32_t* forced_first, const uint32_t* uniform_override,
+                    int64_t* sample_ids, int32_t* first_tokens, float* first_logprobs, uint8_t* finished) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    const rollout_model_desc& m = c.md;
+    const int P = n_prompts, n = n_samples, T = c.rd.page_tokens, R = c.r_max;
+    // ---- validation (no state changes before all of it passed) ----
+    if (P < 1 || n < 1 || !tokens || !offsets || !max_new_tokens) fail(ROLLOUT_E_INVAL, "bad prompt arguments");
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
+    if (!(top_p >= 0.f)) fail(ROLLOUT_E_INVAL, "top_p must be >= 0");
+    if (eos_id < -1 || eos_id >= m.vocab) fail(ROLLOUT_E_INVAL, "eos_id out of range");
+    if (offsets[0] != 0) fail(ROLLOUT_E_INVAL, "offsets[0] must be 0");
+    if ((long long)P * n > R) fail(ROLLOUT_E_NOMEM, "n_prompts * n_samples exceeds the workspace rows");
+    if (P > rollout_ctx::kTempSlots || P > c.logit_rows) fail(ROLLOUT_E_NOMEM, "too many prompts in one call");
+    int need_slots = 0;
+    long long need_pages = 0;
+    for (int p = 0; p < P; ++p) {
+      int len = offsets[p + 1] - offsets[p];
+      if (len < 1) fail(ROLLOUT_E_INVAL, "empty prompt");
+      if (len > c.rd.max_batch_tokens) fail(ROLLOUT_E_NOMEM, "prompt longer than max_batch_tokens");
+      for (int j = 0; j < n; ++j) {
+        int mn = max_new_tokens[p * n + j];
+        if (mn < 1) fail(ROLLOUT_E_INVAL, "max_new_tokens must be >= 1");
+        if ((long long)len + mn - 1 > c.rd.max_context) fail(ROLLOUT_E_NOMEM, "prompt + response exceeds max_context");
+        if (mn > 1) ++need_slots;
+        if (forced_first && (forced_first[p * n + j] < 0 || forced_first[p * n + j] >= m.vocab))
+          fail(ROLLOUT_E_INVAL, "forced token out of range");
+      }
+      for (int i = offsets[p]; i < offsets[p + 1]; ++i)
+        if (tokens[i] < 0 || tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "prompt token out of range");
+      need_pages += plan_pages(len, T, n, max_new_tokens + p * n, nullptr, nullptr, nullptr);
+    }
+    if (need_slots > (int)c.free_slots.size()) fail(ROLLOUT_E_NOMEM, "not enough free live-sample slots");
+    if (need_pages > c.pool->unreserved()) fail(ROLLOUT_E_NOMEM, "not enough free KV pages");
+
+    // ---- pages and page tables ----
+    const float inv_t = 1.0f / temperature;
+    struct PromptPages {
+      std::vector<int32_t> shared;
+      int32_t tail = -1;
+    };
+    std::vector<PromptPages> pp(P);
+    std::vector<Sample> fresh((size_t)P * n);
+    std::vector<int> copy_pairs;
+    for (int p = 0; p < P; ++p) {
+      int len = offsets[p + 1] - offsets[p];
+      int full = len / T, has_tail = (len % T) != 0;
+      int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + p) * c.max_pages];
+      for (int i = 0; i < full; ++i) {
+        int32_t pg = c.pool->alloc(false);
+        pp[p].shared.push_back(pg);
+        prow[i] = pg;
+      }
+      if (has_tail) {
+        pp[p].tail = c.pool->alloc(false);
+        prow[full] = pp[p].tail;
+      }
+      for (int j = 0; j < n; ++j) {
+        Sample& s = fresh[(size_t)p * n + j];
+        s.id = (c.prompt_counter + p) * n + j;
+        s.slot = -1;
+        s.prompt_len = len;
+        s.n_emitted = 0;
+        s.max_new = max_new_tokens[p * n + j];
+        s.eos_id = eos_id;
+        if (s.max_new <= 1) continue;
+        s.slot = c.free_slots.back();
+        c.free_slots.pop_back();
+        int* srow = &c.h_page_table[(size_t)s.slot * c.max_pages];
+        for (int i = 0; i < full; ++i) {
+          c.pool->retain(pp[p].shared[i]);
+          s.pages.push_back(pp[p].shared[i]);
+          srow[i] = pp[p].shared[i];
+        }
+        int total = ceil_div((long long)len + s.max_new - 1, T);
+        for (int i = full; i < total; ++i) {
+          int32_t pg = c.pool->alloc(false);
+          s.pages.push_back(pg);
+          srow[i] = pg;
+        }
+        if (has_tail) {
+          copy_pairs.push_back(pp[p].tail);
+          copy_pairs.push_back(srow[full]);
+        }
+      }
+    }
+    engine_upload_page_table(c);
+
+    // ---- forward over the prompts, in chunks of whole prompts ----
+    int p0 = 0;
+    while (p0 < P) {
+      int p1 = p0, rows = 0;
+      while (p1 < P && rows + (offsets[p1 + 1] - offsets[p1]) <= c.rd.max_batch_tokens) {
+        rows += offsets[p1 + 1] - offsets[p1];
+        ++p1;
+      }
+      int* ht = c.h_int.p;
+      int r = 0;
+      for (int p = p0; p < p1; ++p) {
+        for (int i = offsets[p]; i < offsets[p + 1]; ++i, ++r) {
+          ht[r] = tokens[i];
+          ht[R + r] = i - offsets[p];
+          ht[2 * R + r] = c.temp_slot0 + p;
+        }
+        ht[3 * R + (p - p0)] = r - 1;  // last row of the prompt
+      }
+      h2d(c.row_token.p, ht, rows * sizeof(int), c.stream);
+      h2d(c.row_pos.p, ht + R, rows * sizeof(int), c.stream);
+      h2d(c.row_slot.p, ht + 2 * R, rows * sizeof(int), c.stream);
+      h2d(c.row_aux.p, ht + 3 * R, (p1 - p0) * sizeof(int), c.stream);
+      engine_forward_rows(c, rows);
+      engine_logits(c, c.row_aux.p, 0, p1 - p0, c.logits.p + (size_t)p0 * m.vocab);
+      HIP_TRY(hipStreamSynchronize(c.stream));  // staging buffers are reused by the next chunk
+      c.stats.prompt_tokens += rows;
+      p0 = p1;
+    }
+    c.last_logit_rows = P;
+
+    // ---- private copies of each prompt's partial last page ----
+    if (!copy_pairs.empty()) {
+      if (copy_pairs.size() > c.row_aux.n) fail(ROLLOUT_E_STATE, "internal: page copy list too long");
+      std::memcpy(c.h_int.p, copy_pairs.data(), copy_pairs.size() * sizeof(int));
+      h2d(c.row_aux.p, c.h_int.p, copy_pairs.size() * sizeof(int), c.stream);
+      launch_copy_pages(c.kv_pool.p, c.row_aux.p, (int)copy_pairs.size() / 2, m.n_layers,
+                        c.geom.layer_stride * c.elem, c.geom.page_stride * c.elem, c.stream);
+      HIP_TRY(hipStreamSynchronize(c.stream));
+    }
+
+    // ---- response position 0 of every sample ----
+    const int Rs = P * n;
+    int* hi = c.h_int.p;
+    float* hf = c.h_float.p;
+    int n_new = 0;
+    for (int i = 0; i < Rs; ++i) {
+      hi[i] = i / n;                                       // logits row = prompt
+      hi[R + i] = forced_first ? forced_first[i] : -1;
+      hi[2 * R + i] = 0;                                   // response position
+      hi[3 * R + i] = uniform_override ? (int)uniform_override[i] : 0;
+      hf[i] = inv_t;
+      hf[R + i] = top_p;
+      c.h_ll.p[i] = fresh[i].id;
+      if (fresh[i].slot >= 0) {
+        hi[4 * R + n_new] = fresh[i].slot;
+        hi[5 * R + n_new] = i;
+        hi[6 * R + n_new] = fresh[i].prompt_len;
+        ++n_new;
+      }
+    }
+    h2d(c.row_aux.p, hi, Rs * sizeof(int), c.stream);
+    h2d(c.row_forced.p, hi + R, Rs * sizeof(int), c.stream);
+    h2d(c.row_step.p, hi + 2 * R, Rs * sizeof(int), c.stream);
+    h2d(c.row_uniform.p, hi + 3 * R, Rs * sizeof(int), c.stream);
+    h2d(c.row_inv_temp.p, hf, Rs * sizeof(float), c.stream);
+    h2d(c.row_top_p.p, hf + R, Rs * sizeof(float), c.stream);
+    h2d(c.row_sample_id.p, c.h_ll.p, Rs * sizeof(long long), c.stream);
+    SampleRows sr{};
+    sr.logits = c.logits.p;
+    sr.logits_row = c.row_aux.p;
+    sr.inv_temp = c.row_inv_temp.p;
+    sr.top_p = c.row_top_p.p;
+    sr.uniforms = uniform_override ? c.row_uniform.p : nullptr;
+    sr.sample_id = c.row_sample_id.p;
+    sr.step = c.row_step.p;
+    sr.forced = c.row_forced.p;
+    sr.seed = c.rd.seed;
+    sr.tokens = c.out_tokens.p;
+    sr.logprobs = c.out_logprobs.p;
+    sr.weight_sums = nullptr;
+    launch_sample(sr, Rs, m.vocab, c.stream);
+    if (n_new) {
+      h2d(c.row_token.p, hi + 4 * R, n_new * sizeof(int), c.stream);  // slots
+      h2d(c.row_pos.p, hi + 5 * R, n_new * sizeof(int), c.stream);    // sample rows
+      h2d(c.row_slot.p, hi + 6 * R, n_new * sizeof(int), c.stream);   // positions
+      init_slots_kernel<<<ceil_div(n_new, 256), 256, 0, c.stream>>>(c.st, c.row_token.p, c.row_pos.p, c.row_slot.p,
+                                                                    c.out_tokens.p, c.row_sample_id.p,
+                                                                    c.row_inv_temp.p, c.row_top_p.p, n_new);
+    }
+    d2h(hi + 7 * R, c.out_tokens.p, Rs * sizeof(int), c.stream);
+    d2h(hf + 2 * R, c.out_logprobs.p, Rs * sizeof(float), c.stream);
+    HIP_TRY(hipStreamSynchronize(c.stream));
+
+    // ---- host bookkeeping ----
+    for (int i = 0; i < Rs; ++i) {
+      Sample& s = fresh[i];
+      int tok = hi[7 * R + i];
+      s.n_emitted = 1;
+      bool done = s.max_new <= 1 || (eos_id >= 0 && tok == eos_id);
+      if (sample_ids) sample_ids[i] = s.id;
+      if (first_tokens) first_tokens[i] = tok;
+      if (first_logprobs) first_logprobs[i] = hf[2 * R + i];
+      if (finished) finished[i] = done ? 1 : 0;
+      c.stats.tokens_emitted += 1;
+      c.stats.samples_admitted += 1;
+      if (done) {
+        release_sample(c, s);
+        c.stats.samples_finished += 1;
+      } else {
+        c.live.emplace(s.id, std::move(s));
+      }
+    }
+    for (int p = 0; p < P; ++p) {
+      for (int32_t pg : pp[p].shared) c.pool->release(pg);
+      if (pp[p].tail >= 0) c.pool->release(pp[p].tail);
+    }
+    c.prompt_counter += P;
+    c.stats.prompts_prefilled += P;
+    c.live_dirty = true;
+    refresh_stats(c);
+  });
+}
+
+int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const uint32_t* uniform_override,
+                        int32_t* n_live, int64_t* sample_ids, int32_t* tokens, float* logprobs,
+                        uint8_t* finished) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    const rollout_model_desc& m = c.md;
+    if (!n_live) fail(ROLLOUT_E_INVAL, "n_live is null");
+    const int B = (int)c.live.size(), R = c.r_max;
+    if (B == 0) {
+      *n_live = 0;
+      return;
+    }
+    if (*n_live < B) fail(ROLLOUT_E_INVAL, "output capacity smaller than the live-sample count");
+    if (forced_tokens)
+      for (int i = 0; i < B; ++i)
+        if (forced_tokens[i] < 0 || forced_tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "forced token out of range");
+    int* hi = c.h_int.p;
+    if (c.live_dirty) {
+      int i = 0;
+      for (auto& kv : c.live) hi[i++] = kv.second.slot;
+      h2d(c.d_live.p, hi, B * sizeof(int), c.stream);
+      c.live_dirty = false;
+    }
+    launch_gather_decode_rows(c.st, c.d_live.p, B, c.row_token.p, c.row_pos.p, c.row_slot.p, c.row_inv_temp.p,
+                              c.row_top_p.p, c.row_sample_id.p, c.row_step.p, c.stream);
+    engine_forward_rows(c, B);
+    engine_logits(c, nullptr, 0, B, c.logits.p);
+    c.last_logit_rows = B;
+    if (forced_tokens) {
+      std::memcpy(hi + R, forced_tokens, B * sizeof(int));
+      h2d(c.row_forced.p, hi + R, B * sizeof(int), c.stream);
+    }
+    if (uniform_override) {
+      std::memcpy(hi + 2 * R, uniform_override, B * sizeof(int));
+      h2d(c.row_uniform.p, hi + 2 * R, B * sizeof(int), c.stream);
+    }
+    SampleRows sr{};
+    sr.logits = c.logits.p;
+    sr.logits_row = nullptr;
+    sr.inv_temp = c.row_inv_temp.p;
+    sr.top_p = c.row_top_p.p;
+    sr.uniforms = uniform_override ? c.row_uniform.p : nullptr;
+    sr.sample_id = c.row_sample_id.p;
+    sr.step = c.row_step.p;
+    sr.forced = forced_tokens ? c.row_forced.p : nullptr;
+    sr.seed = c.rd.seed;
+    sr.tokens = c.out_tokens.p;
+    sr.logprobs = c.out_logprobs.p;
+    launch_sample(sr, B, m.vocab, c.stream);
+    launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);
+    d2h(hi + 3 * R, c.out_tokens.p, B * sizeof(int), c.stream);
+    d2h(c.h_float.p, c.out_logprobs.p, B * sizeof(float), c.stream);
+    HIP_TRY(hipStreamSynchronize(c.stream));
+
+    int i = 0;
+    for (auto it = c.live.begin(); it != c.live.end(); ++i) {
+      Sample& s = it->second;
+      int tok = hi[3 * R + i];
+      s.n_emitted += 1;
+      bool done = s.n_emitted >= s.max_new || (s.eos_id >= 0 && tok == s.eos_id);
+      if (sample_ids) sample_ids[i] = s.id;
+      if (tokens) tokens[i] = tok;
+      if (logprobs) logprobs[i] = c.h_float.p[i];
+      if (finished) finished[i] = done ? 1 : 0;
+      if (done) {
+        release_sample(c, s);
+        it = c.live.erase(it);
+        c.stats.samples_finished += 1;
+        c.live_dirty = true;
+      } else {
+        ++it;
+      }
+    }
+    *n_live = B;
+    c.stats.decode_steps += 1;
+    c.stats.tokens_emitted += B;
+    refresh_stats(c);
+  });
+}
+
+int rollout_abort(rollout_ctx* ctx, int32_t n, const int64_t* sample_ids) {
+  if (!ctx || n < 0 || (n > 0 && !sample_ids)) return ROLLOUT_E_INVAL;
+  int aborted = 0;
+  for (int i = 0; i < n; ++i) {
+    auto it = ctx->live.find(sample_ids[i]);
+    if (it == ctx->live.end()) continue;
+    release_sample(*ctx, it->second);
+    ctx->live.erase(it);
+    ++aborted;
+  }
+  if (aborted) ctx->live_dirty = true;
+  ctx->stats.samples_aborted += aborted;
+  refresh_stats(*ctx);
+  return aborted;
+}
+
+int rollout_debug_logits(rollout_ctx* ctx, int32_t* rows, float* out) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    if (!rows || !out) fail(ROLLOUT_E_INVAL, "null argument");
+    if (c.last_logit_rows < 1) fail(ROLLOUT_E_STATE, "no logits computed yet");
+    if (*rows < c.last_logit_rows) fail(ROLLOUT_E_INVAL, "capacity smaller than the number of rows");
+    HIP_TRY(hipMemcpyAsync(out, c.logits.p, (size_t)c.last_logit_rows * c.md.vocab * sizeof(float),
+                           hipMemcpyDeviceToHost, c.stream));
+    HIP_TRY(hipStreamSynchronize(c.stream));
+    *rows = c.last_logit_rows;
+  });
+}
+
+int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, const int32_t* cu_seqlens,
+                     float temperature, float* logprobs) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    const rollout_model_desc& m = c.md;
+    const int T = c.rd.page_tokens, R = c.r_max;
+    if (n_seqs < 0 || !cu_seqlens || (n_seqs > 0 && (!tokens || !logprobs))) fail(ROLLOUT_E_INVAL, "null argument");
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
+    if (n_seqs && cu_seqlens[0] != 0) fail(ROLLOUT_E_INVAL, "cu_seqlens[0] must be 0");
+    const int max_seq = std::min(c.rd.max_batch_tokens, c.rd.max_context);
+    for (int s = 0; s < n_seqs; ++s) {
+      int len = cu_seqlens[s + 1] - cu_seqlens[s];
+      if (len < 1) fail(ROLLOUT_E_INVAL, "empty sequence");
+      if (len > max_seq) fail(ROLLOUT_E_NOMEM, "sequence longer than max_batch_tokens or max_context");
+      if (ceil_div(len, T) > c.pool->unreserved()) fail(ROLLOUT_E_NOMEM, "not enough free KV pages for one sequence");
+      for (int i = cu_seqlens[s]; i < cu_seqlens[s + 1]; ++i)
+        if (tokens[i] < 0 || tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "token out of range");
+    }
+    const float inv_t = 1.0f / temperature;
+    int s0 = 0;
+    while (s0 < n_seqs) {
+      // chunk of whole sequences bounded by rows, temporary slots and free pages
+      int s1 = s0, rows = 0, pages = 0;
+      while (s1 < n_seqs && s1 - s0 < rollout_ctx::kTempSlots) {
+        int len = cu_seqlens[s1 + 1] - cu_seqlens[s1];
+        if (rows + len > c.rd.max_batch_tokens || pages + ceil_div(len, T) > c.pool->unreserved()) break;
+        rows += len;
+        pages += ceil_div(len, T);
+        ++s1;
+      }
+      std::vector<int32_t> held;
+      int* ht = c.h_int.p;
+      int r = 0;
+      for (int s = s0; s < s1; ++s) {
+        int len = cu_seqlens[s + 1] - cu_seqlens[s];
+        int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + (s - s0)) * c.max_pages];
+        for (int i = 0; i < ceil_div(len, T); ++i) {
+          int32_t pg = c.pool->alloc(false);
+          held.push_back(pg);
+          prow[i] = pg;
+        }
+        for (int i = 0; i < len; ++i, ++r) {
+          int g = cu_seqlens[s] + i;
+          ht[r] = tokens[g];
+          ht[R + r] = i;
+          ht[2 * R + r] = c.temp_slot0 + (s - s0);
+          ht[3 * R + r] = i + 1 < len ? tokens[g + 1] : -1;  // target of this row
+        }
+      }
+      engine_upload_page_table(c);
+      h2d(c.row_token.p, ht, rows * sizeof(int), c.stream);
+      h2d(c.row_pos.p, ht + R, rows * sizeof(int), c.stream);
+      h2d(c.row_slot.p, ht + 2 * R, rows * sizeof(int), c.stream);
+      h2d(c.row_aux.p, ht + 3 * R, rows * sizeof(int), c.stream);
+      engine_forward_rows(c, rows);
+      for (int off = 0; off < rows; off += c.logit_rows) {
+        int nr = std::min(c.logit_rows, rows - off);
+        engine_logits(c, nullptr, off, nr, c.logits.p);
+        launch_logprob_gather(c.logits.p, c.row_aux.p + off, inv_t, c.out_logprobs.p + off, nr, m.vocab, c.stream);
+      }
+      d2h(c.h_float.p, c.out_logprobs.p, rows * sizeof(float), c.stream);
+      HIP_TRY(hipStreamSynchronize(c.stream));
+      // row i of a sequence holds log p(token i+1); shift by one and zero the first entry
+      r = 0;
+      for (int s = s0; s < s1; ++s) {
+        int a = cu_seqlens[s], len = cu_seqlens[s + 1] - a;
+        logprobs[a] = 0.f;
+        for (int i = 0; i + 1 < len; ++i) logprobs[a + i + 1] = c.h_float.p[r + i];
+        r += len;
+      }
+      for (int32_t pg : held) c.pool->release(pg);
+      c.last_logit_rows = 0;
+      s0 = s1;
+    }
+    refresh_stats(c);
+  });
+}
+
+int rollout_sample(const float* logits, int32_t rows, int32_t vocab, float temperature, float top_p,
+                   const uint32_t* uniforms, const int32_t* forced, void* hip_stream, int32_t* tokens,
+                   float* logprobs, uint64_t* weight_sums) {
+  return guarded(nullptr, [&] {
+    if (!logits || rows < 0 || vocab < 1 || !uniforms || !tokens || !logprobs) fail(ROLLOUT_E_INVAL, "bad argument");
+    if (!(temperature > 0.f) || !std::isfinite(temperature) || !(top_p >= 0.f)) fail(ROLLOUT_E_INVAL, "bad sampling parameters");
+    if (forced)
+      for (int i = 0; i < rows; ++i)
+        if (forced[i] >= vocab) fail(ROLLOUT_E_INVAL, "forced token out of range");
+    if (rows == 0) return;
+    hipStream_t s = (hipStream_t)hip_stream;
+    DevBuf<float> invt, tp, lp;
+    DevBuf<unsigned> un;
+    DevBuf<int> fo, tok;
+    DevBuf<unsigned long long> ws;
+    std::vector<float> hv(rows, 1.0f / temperature), hp(rows, top_p);
+    invt.alloc(rows); tp.alloc(rows); lp.alloc(rows); un.alloc(rows); fo.alloc(rows); tok.alloc(rows); ws.alloc(rows);
+    HIP_TRY(hipMemcpyAsync(invt.p, hv.data(), rows * sizeof(float), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(tp.p, hp.data(), rows * sizeof(float), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(un.p, uniforms, rows * sizeof(unsigned), hipMemcpyHostToDevice, s));
+    if (forced) HIP_TRY(hipMemcpyAsync(fo.p, forced, rows * sizeof(int), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));  // host staging vectors are pageable
+    SampleRows sr{};
+    sr.logits = logits;
+    sr.inv_temp = invt.p;
+    sr.top_p = tp.p;
+    sr.uniforms = un.p;
+    sr.forced = forced ? fo.p : nullptr;
+    sr.tokens = tok.p;
+    sr.logprobs = lp.p;
+    sr.weight_sums = ws.p;
+    launch_sample(sr, rows, vocab, s);
+    HIP_TRY(hipMemcpyAsync(tokens, tok.p, rows * sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(logprobs, lp.p, rows * sizeof(float), hipMemcpyDeviceToHost, s));
+    if (weight_sums)
+      HIP_TRY(hipMemcpyAsync(weight_sums, ws.p, rows * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+  });
+}
+
+int rollout_philox_words(uint64_t seed, int32_t n, const int64_t* sample_ids, const uint32_t* steps,
+                         uint32_t* words) {
+  return guarded(nullptr, [&] {
+    if (n < 0 || (n > 0 && (!sample_ids || !steps || !words))) fail(ROLLOUT_E_INVAL, "bad argument");
+    if (n == 0) return;
+    DevBuf<long long> ids;
+    DevBuf<unsigned> st, out;
+    ids.alloc(n); st.alloc(n); out.alloc(n);
+    HIP_TRY(hipMemcpy(ids.p, sample_ids, n * sizeof(long long), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(st.p, steps, n * sizeof(unsigned), hipMemcpyHostToDevice));
+    launch_philox_words(seed, ids.p, st.p, out.p, n, nullptr);
+    HIP_TRY(hipMemcpy(words, out.p, n * sizeof(unsigned), hipMemcpyDeviceToHost));
+  });
+}
+
+// ---- host-side page pool ------------------------------------------------------------------
+rollout_pool* rollout_pool_create(int32_t n_pages) { return n_pages > 0 ? new (std::nothrow) rollout_pool(n_pages) : nullptr; }
+void rollout_pool_destroy(rollout_pool* p) { delete p; }
+int32_t rollout_pool_free_pages(const rollout_pool* p) { return p ? p->free_pages() : ROLLOUT_E_INVAL; }
+int32_t rollout_pool_unreserved(const rollout_pool* p) { return p ? p->unreserved() : ROLLOUT_E_INVAL; }
+int rollout_pool_reserve(rollout_pool* p, int32_t n) {
+  if (!p || n < 0) return ROLLOUT_E_INVAL;
+  return p->reserve(n) ? ROLLOUT_OK : ROLLOUT_E_NOMEM;
+}
+void rollout_pool_unreserve(rollout_pool* p, int32_t n) {
+  if (p && n > 0) p->unreserve(n);
+}
+int32_t rollout_pool_alloc(rollout_pool* p, int from_reservation) {
+  if (!p) return ROLLOUT_E_INVAL;
+  int32_t pg = p->alloc(from_reservation != 0);
+  return pg < 0 ? ROLLOUT_E_NOMEM : pg;
+}
+int rollout_pool_retain(rollout_pool* p, int32_t page) {
+  if (!p) return ROLLOUT_E_INVAL;
+  int32_t r = p->retain(page);
+  return r < 0 ? ROLLOUT_E_INVAL : r;
+}
+int rollout_pool_release(rollout_pool* p, int32_t page) {
+  if (!p) return ROLLOUT_E_INVAL;
+  int32_t r = p->release(page);
+  return r < 0 ? ROLLOUT_E_INVAL : r;
+}
+int32_t rollout_pool_refcount(const rollout_pool* p, int32_t page) {
+  if (!p || page < 0 || page >= p->total()) return ROLLOUT_E_INVAL;
+  return p->refcount[page];
+}
+int64_t rollout_plan_pages(int32_t prompt_len, int32_t page_tokens, int32_t n_samples, const int32_t* max_new_tokens,
+                           int32_t* shared, int32_t* tail, int32_t* private_pages) {
+  if (prompt_len < 1 || page_tokens < 1 || n_samples < 0 || (n_samples > 0 && !max_new_tokens)) return ROLLOUT_E_INVAL;
+  return plan_pages(prompt_len, page_tokens, n_samples, max_new_tokens, shared, tail, private_pages);
+}
+
+}  // extern "C"

@@ -1,0 +1,139 @@
+// Rollout engine: library-owned weights, paged KV pool, per-slot decode state, the
+// sample table and the forward pass over a batch of rows.  One context = one GPU.
+#pragma once
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/rollout.h"
+#include "common.h"
+#include "kernels.h"
+#include "page_pool.h"
+
+struct ApiError {
+  int code;
+  std::string msg;
+};
+
+template <typename T>
+struct DevBuf {
+  T* p = nullptr;
+  size_t n = 0;
+  void alloc(size_t count) {
+    release();
+    n = count;
+    if (count) HIP_TRY(hipMalloc((void**)&p, count * sizeof(T)));
+  }
+  void release() {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    n = 0;
+  }
+  ~DevBuf() { release(); }
+  DevBuf() = default;
+  DevBuf(const DevBuf&) = delete;
+  DevBuf& operator=(const DevBuf&) = delete;
+  DevBuf(DevBuf&& o) noexcept : p(o.p), n(o.n) {
+    o.p = nullptr;
+    o.n = 0;
+  }
+};
+
+template <typename T>
+struct PinnedBuf {
+  T* p = nullptr;
+  size_t n = 0;
+  void alloc(size_t count) {
+    release();
+    n = count;
+    if (count) HIP_TRY(hipHostMalloc((void**)&p, count * sizeof(T), hipHostMallocDefault));
+  }
+  void release() {
+    if (p) (void)hipHostFree(p);
+    p = nullptr;
+    n = 0;
+  }
+  ~PinnedBuf() { release(); }
+  PinnedBuf() = default;
+  PinnedBuf(const PinnedBuf&) = delete;
+  PinnedBuf& operator=(const PinnedBuf&) = delete;
+};
+
+struct LayerWeights {
+  DevBuf<float> norm1, norm2;
+  DevBuf<char> wqkv;       // [(Hq + 2 Hkv) dh][hidden]
+  DevBuf<char> wo;         // [hidden][Hq dh]
+  DevBuf<char> w_gate_up;  // dense [2F][hidden] (gate rows, then up rows); MoE [E][2Fe][hidden]
+  DevBuf<char> w_down;     // dense [hidden][F]; MoE [E][hidden][Fe]
+  DevBuf<char> router;     // MoE [E][hidden]
+};
+
+struct Sample {
+  int64_t id;
+  int slot;
+  int prompt_len, n_emitted, max_new, eos_id;
+  std::vector<int32_t> pages;  // one reference held on each
+};
+
+struct rollout_ctx {
+  rollout_model_desc md{};
+  rollout_runtime_desc rd{};
+  hipStream_t stream = nullptr;
+  int device = 0;
+  bool simple = true;
+  std::string err;
+
+  // derived sizes
+  int q_dim = 0, kv_dim = 0, qkv_dim = 0, elem = 4;
+  int max_pages = 0, n_slots = 0, temp_slot0 = 0, r_max = 0, logit_rows = 0;
+  static constexpr int kTempSlots = 1024;
+
+  // weights
+  DevBuf<char> embed, lm_head;
+  DevBuf<float> final_norm;
+  std::vector<LayerWeights> layers;
+  DevBuf<float> cos_sin;
+
+  // KV cache
+  DevBuf<char> kv_pool;
+  KvGeom geom{};
+  rollout_pool* pool = nullptr;
+  DevBuf<int> d_page_table;
+  std::vector<int> h_page_table;
+
+  // per-slot decode state
+  DevBuf<int> st_last_token, st_pos, st_step;
+  DevBuf<long long> st_sample_id;
+  DevBuf<float> st_inv_temp, st_top_p;
+  SlotState st{};
+
+  // sample table
+  std::map<int64_t, Sample> live;
+  std::vector<int> free_slots;
+  int64_t prompt_counter = 0;
+  bool live_dirty = true;
+  DevBuf<int> d_live;
+
+  // workspaces
+  DevBuf<float> x, h, qkv, attn, gate_up, act, hn, logits, router_logits, moe_wt;
+  DevBuf<int> moe_idx;
+  DevBuf<int> row_token, row_pos, row_slot, row_step, row_aux, row_forced, out_tokens;
+  DevBuf<long long> row_sample_id;
+  DevBuf<float> row_inv_temp, row_top_p, out_logprobs;
+  DevBuf<unsigned> row_uniform;
+  PinnedBuf<int> h_int;      // staging, 8 * r_max ints
+  PinnedBuf<float> h_float;  // staging, 4 * r_max floats
+  PinnedBuf<long long> h_ll; // staging, r_max
+  int last_logit_rows = 0;
+
+  rollout_stats stats{};
+
+  ~rollout_ctx() { delete pool; }
+};
+
+// engine.hip
+void engine_init(rollout_ctx& c, const rollout_weights& w);
+void engine_forward_rows(rollout_ctx& c, int rows);  // uses c.row_token / row_pos / row_slot; result in c.x
+// logits of `n` rows of c.x selected by rows_index (device, or NULL for rows first..first+n) into out
+void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, float* out);
+void engine_upload_page_table(rollout_ctx& c);

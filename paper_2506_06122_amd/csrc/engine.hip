@@ -1,0 +1,245 @@
+// Engine set-up and the forward pass over a batch of rows (prompt tokens during prefill,
+// one row per live sample during decoding, all tokens of packed sequences in the
+// teacher-forced pass): paper section 2.1, "Optimization Workflow".
+#include "engine.h"
+
+#include <cmath>
+#include <cstring>
+
+static void fail(int code, const std::string& msg) { throw ApiError{code, msg}; }
+
+static void copy_d2d(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  if (bytes) HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
+}
+
+static void load_gain(rollout_ctx& c, DevBuf<float>& dst, const void* src, const char* what) {
+  if (!src) fail(ROLLOUT_E_INVAL, std::string("null weight pointer: ") + what);
+  dst.alloc(c.md.hidden);
+  launch_convert_to_f32(src, c.md.dtype, dst.p, c.md.hidden, c.stream);
+}
+
+static void load_matrix(rollout_ctx& c, DevBuf<char>& dst, size_t dst_off_elems, const void* src, size_t elems,
+                        const char* what) {
+  if (!src) fail(ROLLOUT_E_INVAL, std::string("null weight pointer: ") + what);
+  copy_d2d(dst.p + dst_off_elems * c.elem, src, elems * c.elem, c.stream);
+}
+
+void engine_init(rollout_ctx& c, const rollout_weights& w) {
+  const rollout_model_desc& m = c.md;
+  const rollout_runtime_desc& r = c.rd;
+  if (m.n_layers < 1 || m.hidden < 1 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.vocab < 2)
+    fail(ROLLOUT_E_INVAL, "model shape fields must be positive");
+  if (m.n_q_heads % m.n_kv_heads) fail(ROLLOUT_E_INVAL, "n_q_heads must be a multiple of n_kv_heads");
+  if (m.head_dim < 32 || m.head_dim > 256 || m.head_dim % 32)
+    fail(ROLLOUT_E_INVAL, "head_dim must be a multiple of 32 in [32, 256]");
+  if (m.dtype != ROLLOUT_DTYPE_F32 && m.dtype != ROLLOUT_DTYPE_BF16) fail(ROLLOUT_E_INVAL, "unknown dtype");
+  if (m.flags) fail(ROLLOUT_E_INVAL, "model flags must be 0");
+  const bool moe = m.n_experts > 0;
+  if (moe) {
+    if (m.top_k < 1 || m.top_k > m.n_experts || m.top_k > 64 || m.n_experts > 256 || m.expert_ffn_dim < 1)
+      fail(ROLLOUT_E_INVAL, "MoE needs 1 <= top_k <= min(n_experts, 64), n_experts <= 256, expert_ffn_dim >= 1");
+  } else if (m.ffn_dim < 1) {
+    fail(ROLLOUT_E_INVAL, "ffn_dim must be positive for a dense model");
+  }
+  if (!(m.rms_eps >= 0.f) || !(m.rope_theta > 0.f)) fail(ROLLOUT_E_INVAL, "rms_eps >= 0 and rope_theta > 0 required");
+  if (r.page_tokens < 32 || r.page_tokens % 32) fail(ROLLOUT_E_INVAL, "page_tokens must be a positive multiple of 32");
+  if (r.max_live_samples < 1 || r.max_context < 2 || r.max_batch_tokens < 1)
+    fail(ROLLOUT_E_INVAL, "max_live_samples, max_context, max_batch_tokens must be positive");
+  if (r.flags & ~ROLLOUT_RT_SIMPLE_KERNELS) fail(ROLLOUT_E_INVAL, "unknown runtime flag");
+  if (!w.embed || !w.final_norm || !w.lm_head || !w.layers) fail(ROLLOUT_E_INVAL, "null weight pointer");
+
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) fail(ROLLOUT_E_HIP, "no HIP device");
+  HIP_TRY(hipGetDevice(&c.device));
+  c.stream = (hipStream_t)r.hip_stream;
+  c.simple = true;  // the matrix-core path is selected in engine_init_fast when available
+  c.elem = m.dtype == ROLLOUT_DTYPE_BF16 ? 2 : 4;
+  c.q_dim = m.n_q_heads * m.head_dim;
+  c.kv_dim = m.n_kv_heads * m.head_dim;
+  c.qkv_dim = c.q_dim + 2 * c.kv_dim;
+  c.max_pages = ceil_div(r.max_context, r.page_tokens);
+  c.temp_slot0 = r.max_live_samples;
+  c.n_slots = r.max_live_samples + rollout_ctx::kTempSlots;
+  c.r_max = std::max(r.max_batch_tokens, r.max_live_samples);
+  c.logit_rows = std::max(r.max_live_samples, std::min(c.r_max, 1024));
+
+  // ---- weights ----
+  const size_t d = m.hidden;
+  c.embed.alloc((size_t)m.vocab * d * c.elem);
+  load_matrix(c, c.embed, 0, w.embed, (size_t)m.vocab * d, "embed");
+  c.lm_head.alloc((size_t)m.vocab * d * c.elem);
+  load_matrix(c, c.lm_head, 0, w.lm_head, (size_t)m.vocab * d, "lm_head");
+  load_gain(c, c.final_norm, w.final_norm, "final_norm");
+  c.layers.resize(m.n_layers);
+  for (int l = 0; l < m.n_layers; ++l) {
+    const rollout_layer_weights& s = w.layers[l];
+    LayerWeights& L = c.layers[l];
+    load_gain(c, L.norm1, s.norm1, "norm1");
+    load_gain(c, L.norm2, s.norm2, "norm2");
+    L.wqkv.alloc((size_t)c.qkv_dim * d * c.elem);
+    load_matrix(c, L.wqkv, 0, s.wq, (size_t)c.q_dim * d, "wq");
+    load_matrix(c, L.wqkv, (size_t)c.q_dim * d, s.wk, (size_t)c.kv_dim * d, "wk");
+    load_matrix(c, L.wqkv, (size_t)(c.q_dim + c.kv_dim) * d, s.wv, (size_t)c.kv_dim * d, "wv");
+    L.wo.alloc(d * c.q_dim * c.elem);
+    load_matrix(c, L.wo, 0, s.wo, d * c.q_dim, "wo");
+    if (!s.w_gate || !s.w_up || !s.w_down) fail(ROLLOUT_E_INVAL, "null weight pointer: feed-forward");
+    if (moe) {
+      const size_t fe = m.expert_ffn_dim, E = m.n_experts;
+      L.router.alloc(E * d * c.elem);
+      load_matrix(c, L.router, 0, s.router, E * d, "router");
+      L.w_gate_up.alloc(E * 2 * fe * d * c.elem);
+      // per expert: gate rows then up rows
+      HIP_TRY(hipMemcpy2DAsync(L.w_gate_up.p, 2 * fe * d * c.elem, s.w_gate, fe * d * c.elem, fe * d * c.elem, E,
+                               hipMemcpyDeviceToDevice, c.stream));
+      HIP_TRY(hipMemcpy2DAsync(L.w_gate_up.p + fe * d * c.elem, 2 * fe * d * c.elem, s.w_up, fe * d * c.elem,
+                               fe * d * c.elem, E, hipMemcpyDeviceToDevice, c.stream));
+      L.w_down.alloc(E * d * fe * c.elem);
+      load_matrix(c, L.w_down, 0, s.w_down, E * d * fe, "w_down");
+    } else {
+      const size_t f = m.ffn_dim;
+      L.w_gate_up.alloc(2 * f * d * c.elem);
+      load_matrix(c, L.w_gate_up, 0, s.w_gate, f * d, "w_gate");
+      load_matrix(c, L.w_gate_up, f * d, s.w_up, f * d, "w_up");
+      L.w_down.alloc(d * f * c.elem);
+      load_matrix(c, L.w_down, 0, s.w_down, d * f, "w_down");
+    }
+  }
+
+  // ---- rotary table: cos/sin of pos * theta^(-2i/dh), computed in double ----
+  {
+    const int half = m.head_dim / 2;
+    std::vector<float> tab((size_t)r.max_context * m.head_dim);
+    for (int i = 0; i < half; ++i) {
+      double inv_freq = std::pow((double)m.rope_theta, -2.0 * i / m.head_dim);
+      for (int p = 0; p < r.max_context; ++p) {
+        double phi = (double)p * inv_freq;
+        tab[(size_t)p * m.head_dim + 2 * i] = (float)std::cos(phi);
+        tab[(size_t)p * m.head_dim + 2 * i + 1] = (float)std::sin(phi);
+      }
+    }
+    c.cos_sin.alloc(tab.size());
+    HIP_TRY(hipMemcpyAsync(c.cos_sin.p, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice, c.stream));
+    HIP_TRY(hipStreamSynchronize(c.stream));
+  }
+
+  // ---- KV pool ----
+  c.geom.n_kv_heads = m.n_kv_heads;
+  c.geom.head_dim = m.head_dim;
+  c.geom.page_tokens = r.page_tokens;
+  c.geom.layout = KV_LINEAR;
+  c.geom.page_stride = (long long)m.n_kv_heads * 2 * r.page_tokens * m.head_dim;
+  const size_t page_bytes_all_layers = (size_t)c.geom.page_stride * c.elem * m.n_layers;
+  long long n_pages = (long long)(r.kv_pool_bytes / page_bytes_all_layers);
+  if (n_pages < 1) fail(ROLLOUT_E_INVAL, "kv_pool_bytes holds less than one page");
+  if (n_pages > 0x7fffffff) n_pages = 0x7fffffff;
+  c.geom.layer_stride = n_pages * c.geom.page_stride;
+  c.kv_pool.alloc((size_t)n_pages * page_bytes_all_layers);
+  c.pool = new rollout_pool((int32_t)n_pages);
+  c.h_page_table.assign((size_t)c.n_slots * c.max_pages, 0);
+  c.d_page_table.alloc(c.h_page_table.size());
+  HIP_TRY(hipMemsetAsync(c.d_page_table.p, 0, c.h_page_table.size() * sizeof(int), c.stream));
+
+  // ---- slot state ----
+  c.st_last_token.alloc(c.n_slots);
+  c.st_pos.alloc(c.n_slots);
+  c.st_step.alloc(c.n_slots);
+  c.st_sample_id.alloc(c.n_slots);
+  c.st_inv_temp.alloc(c.n_slots);
+  c.st_top_p.alloc(c.n_slots);
+  c.st = SlotState{c.st_last_token.p, c.st_pos.p, c.st_step.p, c.st_sample_id.p, c.st_inv_temp.p, c.st_top_p.p};
+  c.d_live.alloc(r.max_live_samples);
+  for (int s = r.max_live_samples - 1; s >= 0; --s) c.free_slots.push_back(s);
+
+  // ---- workspaces ----
+  const size_t R = c.r_max;
+  c.x.alloc(R * d);
+  c.h.alloc(R * d);
+  c.qkv.alloc(R * c.qkv_dim);
+  c.attn.alloc(R * c.q_dim);
+  if (moe) {
+    c.router_logits.alloc(R * m.n_experts);
+    c.moe_idx.alloc(R * m.top_k);
+    c.moe_wt.alloc(R * m.top_k);
+    c.act.alloc(R * m.top_k * m.expert_ffn_dim);
+  } else {
+    c.gate_up.alloc(R * 2 * m.ffn_dim);
+    c.act.alloc(R * m.ffn_dim);
+  }
+  c.hn.alloc((size_t)c.logit_rows * d);
+  c.logits.alloc((size_t)c.logit_rows * m.vocab);
+  c.row_token.alloc(R);
+  c.row_pos.alloc(R);
+  c.row_slot.alloc(R);
+  c.row_step.alloc(R);
+  c.row_aux.alloc(2 * R);
+  c.row_forced.alloc(R);
+  c.out_tokens.alloc(R);
+  c.row_sample_id.alloc(R);
+  c.row_inv_temp.alloc(R);
+  c.row_top_p.alloc(R);
+  c.out_logprobs.alloc(R);
+  c.row_uniform.alloc(R);
+  c.h_int.alloc(8 * R);
+  c.h_float.alloc(4 * R);
+  c.h_ll.alloc(R);
+  HIP_TRY(hipStreamSynchronize(c.stream));
+}
+
+void engine_upload_page_table(rollout_ctx& c) {
+  HIP_TRY(hipMemcpyAsync(c.d_page_table.p, c.h_page_table.data(), c.h_page_table.size() * sizeof(int),
+                         hipMemcpyHostToDevice, c.stream));
+}
+
+// ------------------------------------------------------------------------------------------
+template <typename T>
+static void forward_rows_simple(rollout_ctx& c, int R) {
+  const rollout_model_desc& m = c.md;
+  hipStream_t s = c.stream;
+  const int d = m.hidden;
+  launch_embed<T>((const T*)c.embed.p, c.row_token.p, c.x.p, R, d, s);
+  for (int l = 0; l < m.n_layers; ++l) {
+    LayerWeights& L = c.layers[l];
+    launch_rmsnorm_f32(c.x.p, L.norm1.p, c.h.p, nullptr, R, d, m.rms_eps, s);
+    launch_linear_simple<T>(c.h.p, d, (const T*)L.wqkv.p, c.qkv.p, c.qkv_dim, nullptr, 0, R, c.qkv_dim, d, s);
+    launch_rope_kvwrite<T>(c.qkv.p, c.cos_sin.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
+                           (T*)c.kv_pool.p, c.geom, l, R, m.n_q_heads, s);
+    launch_attention_simple<T>(c.qkv.p, c.attn.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
+                               (const T*)c.kv_pool.p, c.geom, l, R, m.n_q_heads, s);
+    launch_linear_simple<T>(c.attn.p, c.q_dim, (const T*)L.wo.p, c.x.p, d, c.x.p, d, R, d, c.q_dim, s);
+    launch_rmsnorm_f32(c.x.p, L.norm2.p, c.h.p, nullptr, R, d, m.rms_eps, s);
+    if (m.n_experts > 0) {
+      launch_linear_simple<T>(c.h.p, d, (const T*)L.router.p, c.router_logits.p, m.n_experts, nullptr, 0, R,
+                              m.n_experts, d, s);
+      launch_moe_route(c.router_logits.p, c.moe_idx.p, c.moe_wt.p, R, m.n_experts, m.top_k, s);
+      launch_moe_gate_up_simple<T>(c.h.p, (const T*)L.w_gate_up.p, c.moe_idx.p, c.act.p, R, m.top_k, d,
+                                   m.expert_ffn_dim, s);
+      launch_moe_down_simple<T>(c.act.p, (const T*)L.w_down.p, c.moe_idx.p, c.moe_wt.p, c.x.p, R, m.top_k, d,
+                                m.expert_ffn_dim, s);
+    } else {
+      launch_linear_simple<T>(c.h.p, d, (const T*)L.w_gate_up.p, c.gate_up.p, 2 * m.ffn_dim, nullptr, 0, R,
+                              2 * m.ffn_dim, d, s);
+      launch_swiglu_f32(c.gate_up.p, c.act.p, R, m.ffn_dim, s);
+      launch_linear_simple<T>(c.act.p, m.ffn_dim, (const T*)L.w_down.p, c.x.p, d, c.x.p, d, R, d, m.ffn_dim, s);
+    }
+  }
+}
+
+void engine_forward_rows(rollout_ctx& c, int rows) {
+  if (rows < 1) return;
+  if (c.md.dtype == ROLLOUT_DTYPE_F32)
+    forward_rows_simple<float>(c, rows);
+  else
+    forward_rows_simple<bf16_t>(c, rows);
+}
+
+void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, float* out) {
+  if (n < 1) return;
+  const int d = c.md.hidden;
+  launch_rmsnorm_f32(c.x.p + (size_t)first * d, c.final_norm.p, c.hn.p, rows_index, n, d, c.md.rms_eps, c.stream);
+  if (c.md.dtype == ROLLOUT_DTYPE_F32)
+    launch_linear_simple<float>(c.hn.p, d, (const float*)c.lm_head.p, out, c.md.vocab, nullptr, 0, n, c.md.vocab,
+                                d, c.stream);
+  else
+    launch_linear_simple<bf16_t>(c.hn.p, d, (const bf16_t*)c.lm_head.p, out, c.md.vocab, nullptr, 0, n,
+                                 c.md.vocab, d, c.stream);
+}
