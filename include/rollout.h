@@ -48,6 +48,7 @@ extern "C" {
 
 /* runtime flags */
 #define ROLLOUT_RT_SIMPLE_KERNELS 1u /* run every operator with the plain one-op-per-kernel path */
+#define ROLLOUT_RT_RECORD_ROUTING 2u /* MoE: keep each forward's expert choices for rollout_debug_routing */
 
 typedef struct rollout_ctx rollout_ctx; /* opaque; created by rollout_init, freed by rollout_destroy */
 
@@ -159,6 +160,12 @@ int rollout_abort(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids);
  * order) or decode step (one per stepped sample, ascending id) to host `out`
  * [rows][vocab].  rows: in capacity, out count.  Errors: E_INVAL, E_STATE (none yet). */
 int rollout_debug_logits(rollout_ctx *ctx, int32_t *rows, float *out);
+
+/* Parity hook (MoE models, ROLLOUT_RT_RECORD_ROUTING): the experts chosen for every row of
+ * the last forward pass (the last prefill chunk's prompt tokens in packed order, or the last
+ * decode step's samples in ascending id), host int32 `out` [n_layers][rows][top_k].
+ * rows: in capacity, out count.  Errors: E_INVAL, E_STATE (not recording / nothing yet). */
+int rollout_debug_routing(rollout_ctx *ctx, int32_t *rows, int32_t *out);
 
 int rollout_get_stats(rollout_ctx *ctx, rollout_stats *out);
 const char *rollout_last_error(rollout_ctx *ctx); /* ctx may be NULL: error of the last failed rollout_init */

@@ -71,6 +71,13 @@ class Model:
         self.shape = shape
         self._w = weights
         self._cache = {} if cache else None
+        # Test hook for MoE parity: routing is an integer decision taken from floats, so a
+        # lower-precision implementation may legitimately pick another expert on a near-tie.
+        # When routing_override[layer] holds an int array [rows][top_k], `ffn` uses those
+        # expert sets (mixing weights still come from this model's own router logits) and
+        # appends to routing_regret how far each set is from optimal in those logits.
+        self.routing_override = {}
+        self.routing_regret = []
 
     def w(self, name: str) -> np.ndarray:
         if self._cache is None:
@@ -96,8 +103,14 @@ class Model:
         r = h @ self.w(p + "router").T                                   # [rows][E]
         wg, wu, wd = (self.w(p + "experts." + n) for n in ("w_gate", "w_up", "w_down"))
         out = np.zeros_like(h)
+        forced = self.routing_override.get(layer)
         for i in range(len(h)):
             experts, mix = route(r[i], s.top_k)
+            if forced is not None:
+                chosen = np.asarray(forced[i], dtype=np.int64)
+                assert len(set(chosen.tolist())) == s.top_k
+                self.routing_regret.append(float(np.min(r[i][experts]) - np.min(r[i][chosen])))
+                experts, mix = chosen, softmax(r[i][chosen])
             for e, m in zip(experts, mix):
                 act = silu(wg[e] @ h[i]) * (wu[e] @ h[i])
                 out[i] += m * (wd[e] @ act)

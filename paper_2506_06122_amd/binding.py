@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "librollout.so")
 OK, E_INVAL, E_NOMEM, E_HIP, E_STATE = 0, -1, -2, -3, -4
 DTYPE_F32, DTYPE_BF16 = 0, 1
 RT_SIMPLE_KERNELS = 1
+RT_RECORD_ROUTING = 2
 
 
 class RolloutError(RuntimeError):
@@ -66,6 +67,7 @@ SIGNATURES = {
     "rollout_logprobs": (C.c_int, [_P, C.c_int32, _P, _P, C.c_float, _P]),
     "rollout_abort": (C.c_int, [_P, C.c_int32, _P]),
     "rollout_debug_logits": (C.c_int, [_P, C.POINTER(C.c_int32), _P]),
+    "rollout_debug_routing": (C.c_int, [_P, C.POINTER(C.c_int32), _P]),
     "rollout_get_stats": (C.c_int, [_P, C.POINTER(rollout_stats)]),
     "rollout_last_error": (C.c_char_p, [_P]),
     "rollout_destroy": (None, [_P]),
@@ -231,6 +233,13 @@ class Rollout:
         out = np.empty((rows.value, self.shape.vocab), np.float32)
         self._check(self.lib.rollout_debug_logits(self.ctx, C.byref(rows), _ptr(out)))
         return out[:rows.value]
+
+    def rollout_debug_routing(self, max_rows):
+        rows = C.c_int32(max_rows)
+        out = np.empty(self.shape.n_layers * max_rows * self.shape.top_k, np.int32)
+        self._check(self.lib.rollout_debug_routing(self.ctx, C.byref(rows), _ptr(out)))
+        n = rows.value
+        return out[:self.shape.n_layers * n * self.shape.top_k].reshape(self.shape.n_layers, n, self.shape.top_k)
 
     def rollout_get_stats(self) -> dict:
         st = rollout_stats()

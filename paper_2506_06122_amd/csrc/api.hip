@@ -446,6 +446,21 @@ int rollout_debug_logits(rollout_ctx* ctx, int32_t* rows, float* out) {
   });
 }
 
+int rollout_debug_routing(rollout_ctx* ctx, int32_t* rows, int32_t* out) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    if (!rows || !out) fail(ROLLOUT_E_INVAL, "null argument");
+    if (!c.route_log.p || c.last_route_rows < 1) fail(ROLLOUT_E_STATE, "routing is not being recorded");
+    if (*rows < c.last_route_rows) fail(ROLLOUT_E_INVAL, "capacity smaller than the number of rows");
+    const int k = c.md.top_k, n = c.last_route_rows;
+    HIP_TRY(hipMemcpy2DAsync(out, (size_t)n * k * sizeof(int), c.route_log.p, (size_t)c.r_max * k * sizeof(int),
+                             (size_t)n * k * sizeof(int), c.md.n_layers, hipMemcpyDeviceToHost, c.stream));
+    HIP_TRY(hipStreamSynchronize(c.stream));
+    *rows = n;
+  });
+}
+
 int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, const int32_t* cu_seqlens,
                      float temperature, float* logprobs) {
   if (!ctx) return ROLLOUT_E_INVAL;

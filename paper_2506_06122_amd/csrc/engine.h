@@ -116,7 +116,8 @@ struct rollout_ctx {
 
   // workspaces
   DevBuf<float> x, h, qkv, attn, gate_up, act, hn, logits, router_logits, moe_wt;
-  DevBuf<int> moe_idx;
+  DevBuf<int> moe_idx, route_log;  // route_log [n_layers][r_max][top_k] when recording
+  int last_route_rows = 0;
   DevBuf<int> row_token, row_pos, row_slot, row_step, row_aux, row_forced, out_tokens;
   DevBuf<long long> row_sample_id;
   DevBuf<float> row_inv_temp, row_top_p, out_logprobs;

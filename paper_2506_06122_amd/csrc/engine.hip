@@ -45,7 +45,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (r.page_tokens < 32 || r.page_tokens % 32) fail(ROLLOUT_E_INVAL, "page_tokens must be a positive multiple of 32");
   if (r.max_live_samples < 1 || r.max_context < 2 || r.max_batch_tokens < 1)
     fail(ROLLOUT_E_INVAL, "max_live_samples, max_context, max_batch_tokens must be positive");
-  if (r.flags & ~ROLLOUT_RT_SIMPLE_KERNELS) fail(ROLLOUT_E_INVAL, "unknown runtime flag");
+  if (r.flags & ~(ROLLOUT_RT_SIMPLE_KERNELS | ROLLOUT_RT_RECORD_ROUTING)) fail(ROLLOUT_E_INVAL, "unknown runtime flag");
   if (!w.embed || !w.final_norm || !w.lm_head || !w.layers) fail(ROLLOUT_E_INVAL, "null weight pointer");
 
   int n_dev = 0;
@@ -161,6 +161,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     c.moe_idx.alloc(R * m.top_k);
     c.moe_wt.alloc(R * m.top_k);
     c.act.alloc(R * m.top_k * m.expert_ffn_dim);
+    if (r.flags & ROLLOUT_RT_RECORD_ROUTING) c.route_log.alloc((size_t)m.n_layers * R * m.top_k);
   } else {
     c.gate_up.alloc(R * 2 * m.ffn_dim);
     c.act.alloc(R * m.ffn_dim);
@@ -211,6 +212,9 @@ static void forward_rows_simple(rollout_ctx& c, int R) {
       launch_linear_simple<T>(c.h.p, d, (const T*)L.router.p, c.router_logits.p, m.n_experts, nullptr, 0, R,
                               m.n_experts, d, s);
       launch_moe_route(c.router_logits.p, c.moe_idx.p, c.moe_wt.p, R, m.n_experts, m.top_k, s);
+      if (c.route_log.p)
+        HIP_TRY(hipMemcpyAsync(c.route_log.p + (size_t)l * c.r_max * m.top_k, c.moe_idx.p,
+                               (size_t)R * m.top_k * sizeof(int), hipMemcpyDeviceToDevice, s));
       launch_moe_gate_up_simple<T>(c.h.p, (const T*)L.w_gate_up.p, c.moe_idx.p, c.act.p, R, m.top_k, d,
                                    m.expert_ffn_dim, s);
       launch_moe_down_simple<T>(c.act.p, (const T*)L.w_down.p, c.moe_idx.p, c.moe_wt.p, c.x.p, R, m.top_k, d,
@@ -226,6 +230,7 @@ static void forward_rows_simple(rollout_ctx& c, int R) {
 
 void engine_forward_rows(rollout_ctx& c, int rows) {
   if (rows < 1) return;
+  c.last_route_rows = rows;
   if (c.md.dtype == ROLLOUT_DTYPE_F32)
     forward_rows_simple<float>(c, rows);
   else

@@ -45,7 +45,14 @@ def teacher_forced_compare(eng, model, prompt_tokens, offsets, n_samples, forced
     assert gpu_logits.shape[0] == P
     caches, worst, worst_lp = [], 0.0, 0.0
     from oracle import sampler
+    moe = bool(model.shape.n_experts)
+    # MoE: the oracle takes the GPU's expert choices (an integer decision made from floats in
+    # another precision) and records how far from optimal they are in its own router logits.
+    routing = eng.rollout_debug_routing(int(offsets[-1])) if moe else None
     for p in range(P):
+        if moe:
+            model.routing_override = {l: routing[l][offsets[p]:offsets[p + 1]]
+                                      for l in range(model.shape.n_layers)}
         prefix = fwd.new_cache()
         ref = fwd.extend([prefix], [prompt_tokens[offsets[p]:offsets[p + 1]]])[0][-1]
         worst = max(worst, float(np.max(np.abs(gpu_logits[p] - ref))))
@@ -58,9 +65,13 @@ def teacher_forced_compare(eng, model, prompt_tokens, offsets, n_samples, forced
         assert np.array_equal(ids2, ids) and np.array_equal(toks, forced[:, t])
         assert fin.all() == (t == steps - 1)
         gpu_logits = eng.rollout_debug_logits()
+        if moe:
+            routing = eng.rollout_debug_routing(len(caches))
+            model.routing_override = {l: routing[l] for l in range(model.shape.n_layers)}
         ref = fwd.extend(caches, [[int(x)] for x in forced[:, t - 1]])
         for i in range(len(caches)):
             worst = max(worst, float(np.max(np.abs(gpu_logits[i] - ref[i][0]))))
             want = sampler.log_prob(ref[i][0].astype(np.float32), inv_t, int(forced[i, t]))
             worst_lp = max(worst_lp, abs(want - float(lps[i])))
+    model.routing_override = {}
     return worst, worst_lp

@@ -69,7 +69,7 @@ def test_teacher_forced_logits_match_oracle(name, simple):
     shape, scale, kw = CASES[name]
     w = scaled_weights(shape, seed=1, scale=scale)
     model = oracle_model(shape, w)
-    eng = make_engine(shape, w, flags=1 if simple else 0, **kw)
+    eng = make_engine(shape, w, flags=(1 if simple else 0) | (2 if shape.is_moe else 0), **kw)
     toks, offs = workloads.make_prompts(3, 5, 70, shape.vocab, seed=2)     # ragged, crosses pages
     steps, n = 6, 2
     forced = np.random.default_rng(4).integers(0, shape.vocab, (3 * n, steps)).astype(np.int32)
@@ -77,6 +77,10 @@ def test_teacher_forced_logits_match_oracle(name, simple):
     print(f"{name}: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
     assert worst <= TOL[shape.dtype]
     assert worst_lp <= TOL[shape.dtype]
+    if shape.is_moe:      # the GPU's expert sets are optimal up to rounding in the oracle's own router logits
+        regret = max(model.routing_regret)
+        print(f"{name}: worst routing regret = {regret:.3e} over {len(model.routing_regret)} decisions")
+        assert regret <= TOL[shape.dtype]
     st = eng.rollout_get_stats()
     assert st["live_samples"] == 0 and st["pages_in_use"] == 0
     eng.close()
