@@ -221,7 +221,7 @@ int rollout_prefill(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, 
         ++p1;
       }
       int* ht = c.h_int.p;
-      int r = 0;
+      int r = 0, max_len = 0;
       for (int p = p0; p < p1; ++p) {
         for (int i = offsets[p]; i < offsets[p + 1]; ++i, ++r) {
           ht[r] = tokens[i];
@@ -229,12 +229,22 @@ int rollout_prefill(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, 
           ht[2 * R + r] = c.temp_slot0 + p;
         }
         ht[3 * R + (p - p0)] = r - 1;  // last row of the prompt
+        ht[4 * R + (p - p0)] = r - (offsets[p + 1] - offsets[p]);
+        ht[5 * R + (p - p0)] = offsets[p + 1] - offsets[p];
+        ht[6 * R + (p - p0)] = c.temp_slot0 + p;
+        max_len = std::max(max_len, offsets[p + 1] - offsets[p]);
+      }
+      SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, p1 - p0, max_len};
+      if (!c.simple) {
+        h2d(c.seq_row0.p, ht + 4 * R, (p1 - p0) * sizeof(int), c.stream);
+        h2d(c.seq_len.p, ht + 5 * R, (p1 - p0) * sizeof(int), c.stream);
+        h2d(c.seq_slot.p, ht + 6 * R, (p1 - p0) * sizeof(int), c.stream);
       }
       h2d(c.row_token.p, ht, rows * sizeof(int), c.stream);
       h2d(c.row_pos.p, ht + R, rows * sizeof(int), c.stream);
       h2d(c.row_slot.p, ht + 2 * R, rows * sizeof(int), c.stream);
       h2d(c.row_aux.p, ht + 3 * R, (p1 - p0) * sizeof(int), c.stream);
-      engine_forward_rows(c, rows);
+      engine_forward_rows(c, rows, &sb);
       engine_logits(c, c.row_aux.p, 0, p1 - p0, c.logits.p + (size_t)p0 * m.vocab);
       HIP_TRY(hipStreamSynchronize(c.stream));  // staging buffers are reused by the next chunk
       c.stats.prompt_tokens += rows;
@@ -361,7 +371,9 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
     }
     launch_gather_decode_rows(c.st, c.d_live.p, B, c.row_token.p, c.row_pos.p, c.row_slot.p, c.row_inv_temp.p,
                               c.row_top_p.p, c.row_sample_id.p, c.row_step.p, c.stream);
-    engine_forward_rows(c, B);
+    c.decode_max_ctx = 1;
+    for (auto& kv : c.live) c.decode_max_ctx = std::max(c.decode_max_ctx, kv.second.prompt_len + kv.second.n_emitted);
+    engine_forward_rows(c, B, nullptr);
     engine_logits(c, nullptr, 0, B, c.logits.p);
     c.last_logit_rows = B;
     if (forced_tokens) {
@@ -494,9 +506,13 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
       }
       std::vector<int32_t> held;
       int* ht = c.h_int.p;
-      int r = 0;
+      int r = 0, max_len = 0;
       for (int s = s0; s < s1; ++s) {
         int len = cu_seqlens[s + 1] - cu_seqlens[s];
+        ht[4 * R + (s - s0)] = r;
+        ht[5 * R + (s - s0)] = len;
+        ht[6 * R + (s - s0)] = c.temp_slot0 + (s - s0);
+        max_len = std::max(max_len, len);
         int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + (s - s0)) * c.max_pages];
         for (int i = 0; i < ceil_div(len, T); ++i) {
           int32_t pg = c.pool->alloc(false);
@@ -516,7 +532,13 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
       h2d(c.row_pos.p, ht + R, rows * sizeof(int), c.stream);
       h2d(c.row_slot.p, ht + 2 * R, rows * sizeof(int), c.stream);
       h2d(c.row_aux.p, ht + 3 * R, rows * sizeof(int), c.stream);
-      engine_forward_rows(c, rows);
+      SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, s1 - s0, max_len};
+      if (!c.simple) {
+        h2d(c.seq_row0.p, ht + 4 * R, (s1 - s0) * sizeof(int), c.stream);
+        h2d(c.seq_len.p, ht + 5 * R, (s1 - s0) * sizeof(int), c.stream);
+        h2d(c.seq_slot.p, ht + 6 * R, (s1 - s0) * sizeof(int), c.stream);
+      }
+      engine_forward_rows(c, rows, &sb);
       for (int off = 0; off < rows; off += c.logit_rows) {
         int nr = std::min(c.logit_rows, rows - off);
         engine_logits(c, nullptr, off, nr, c.logits.p);

@@ -8,6 +8,7 @@
 #include "../../include/rollout.h"
 #include "common.h"
 #include "kernels.h"
+#include "kernels_fast.h"
 #include "page_pool.h"
 
 struct ApiError {
@@ -66,6 +67,14 @@ struct LayerWeights {
   DevBuf<char> w_gate_up;  // dense [2F][hidden] (gate rows, then up rows); MoE [E][2Fe][hidden]
   DevBuf<char> w_down;     // dense [hidden][F]; MoE [E][hidden][Fe]
   DevBuf<char> router;     // MoE [E][hidden]
+  // matrix-core path: fragment-ordered copies (kernels_gemm.hip)
+  DevBuf<char> wqkv_p, wo_p, w_gate_up_p, w_down_p;  // gate/up: n-tiles alternate gate, up
+};
+
+// Packed sequences of a prefill / log-prob forward (device arrays); NULL = one row per sample.
+struct SeqBatch {
+  const int *row0, *len, *slot;
+  int n_seqs, max_len;
 };
 
 struct Sample {
@@ -89,7 +98,7 @@ struct rollout_ctx {
   static constexpr int kTempSlots = 1024;
 
   // weights
-  DevBuf<char> embed, lm_head;
+  DevBuf<char> embed, lm_head, lm_head_p;
   DevBuf<float> final_norm;
   std::vector<LayerWeights> layers;
   DevBuf<float> cos_sin;
@@ -118,6 +127,14 @@ struct rollout_ctx {
   DevBuf<float> x, h, qkv, attn, gate_up, act, hn, logits, router_logits, moe_wt;
   DevBuf<int> moe_idx, route_log;  // route_log [n_layers][r_max][top_k] when recording
   int last_route_rows = 0;
+  // matrix-core path workspaces
+  DevBuf<uint16_t> h_bf16, q_bf16, attn_bf16, act_bf16, hn_bf16;
+  DevBuf<float> partial, attn_part_o, attn_part_ml;
+  long long partial_rows = 0;   // capacity of `partial` in rows of partial_ld floats
+  int partial_ld = 0;
+  int attn_max_parts = 0;       // capacity of attn_part_* in (row, kv head, split) triples
+  int decode_max_ctx = 0;       // longest context among the rows of the current decode step
+  DevBuf<int> seq_row0, seq_len, seq_slot;
   DevBuf<int> row_token, row_pos, row_slot, row_step, row_aux, row_forced, out_tokens;
   DevBuf<long long> row_sample_id;
   DevBuf<float> row_inv_temp, row_top_p, out_logprobs;
@@ -134,7 +151,9 @@ struct rollout_ctx {
 
 // engine.hip
 void engine_init(rollout_ctx& c, const rollout_weights& w);
-void engine_forward_rows(rollout_ctx& c, int rows);  // uses c.row_token / row_pos / row_slot; result in c.x
+// uses c.row_token / row_pos / row_slot; result in c.x.  seqs describes packed sequences
+// (prefill, log-probs) or is NULL when every row is one sample's next position (decode).
+void engine_forward_rows(rollout_ctx& c, int rows, const SeqBatch* seqs);
 // logits of `n` rows of c.x selected by rows_index (device, or NULL for rows first..first+n) into out
 void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, float* out);
 void engine_upload_page_table(rollout_ctx& c);

@@ -52,7 +52,10 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) fail(ROLLOUT_E_HIP, "no HIP device");
   HIP_TRY(hipGetDevice(&c.device));
   c.stream = (hipStream_t)r.hip_stream;
-  c.simple = true;  // the matrix-core path is selected in engine_init_fast when available
+  // The matrix-core path needs bf16 storage, head_dim 128 and fragment-aligned dimensions;
+  // anything else (and mixture-of-experts models, for now) runs the plain path.
+  c.simple = (r.flags & ROLLOUT_RT_SIMPLE_KERNELS) || m.dtype != ROLLOUT_DTYPE_BF16 || m.head_dim != 128 ||
+             m.hidden % 32 || m.hidden > 8192 || m.vocab % 16 || moe || m.ffn_dim % 32;
   c.elem = m.dtype == ROLLOUT_DTYPE_BF16 ? 2 : 4;
   c.q_dim = m.n_q_heads * m.head_dim;
   c.kv_dim = m.n_kv_heads * m.head_dim;
@@ -67,8 +70,13 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   const size_t d = m.hidden;
   c.embed.alloc((size_t)m.vocab * d * c.elem);
   load_matrix(c, c.embed, 0, w.embed, (size_t)m.vocab * d, "embed");
-  c.lm_head.alloc((size_t)m.vocab * d * c.elem);
-  load_matrix(c, c.lm_head, 0, w.lm_head, (size_t)m.vocab * d, "lm_head");
+  if (c.simple) {
+    c.lm_head.alloc((size_t)m.vocab * d * c.elem);
+    load_matrix(c, c.lm_head, 0, w.lm_head, (size_t)m.vocab * d, "lm_head");
+  } else {
+    c.lm_head_p.alloc((size_t)m.vocab * d * 2);
+    launch_pack_weight(w.lm_head, c.lm_head_p.p, m.vocab, (int)d, 0, 1, c.stream);
+  }
   load_gain(c, c.final_norm, w.final_norm, "final_norm");
   c.layers.resize(m.n_layers);
   for (int l = 0; l < m.n_layers; ++l) {
@@ -76,6 +84,23 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     LayerWeights& L = c.layers[l];
     load_gain(c, L.norm1, s.norm1, "norm1");
     load_gain(c, L.norm2, s.norm2, "norm2");
+    if (!c.simple) {
+      if (!s.wq || !s.wk || !s.wv || !s.wo || !s.w_gate || !s.w_up || !s.w_down)
+        fail(ROLLOUT_E_INVAL, "null weight pointer in a layer");
+      const int f = m.ffn_dim;
+      L.wqkv_p.alloc((size_t)c.qkv_dim * d * 2);
+      launch_pack_weight(s.wq, L.wqkv_p.p, c.q_dim, (int)d, 0, 1, c.stream);
+      launch_pack_weight(s.wk, L.wqkv_p.p, c.kv_dim, (int)d, c.q_dim / 16, 1, c.stream);
+      launch_pack_weight(s.wv, L.wqkv_p.p, c.kv_dim, (int)d, (c.q_dim + c.kv_dim) / 16, 1, c.stream);
+      L.wo_p.alloc(d * c.q_dim * 2);
+      launch_pack_weight(s.wo, L.wo_p.p, (int)d, c.q_dim, 0, 1, c.stream);
+      L.w_gate_up_p.alloc((size_t)2 * f * d * 2);
+      launch_pack_weight(s.w_gate, L.w_gate_up_p.p, f, (int)d, 0, 2, c.stream);
+      launch_pack_weight(s.w_up, L.w_gate_up_p.p, f, (int)d, 1, 2, c.stream);
+      L.w_down_p.alloc(d * f * 2);
+      launch_pack_weight(s.w_down, L.w_down_p.p, (int)d, f, 0, 1, c.stream);
+      continue;
+    }
     L.wqkv.alloc((size_t)c.qkv_dim * d * c.elem);
     load_matrix(c, L.wqkv, 0, s.wq, (size_t)c.q_dim * d, "wq");
     load_matrix(c, L.wqkv, (size_t)c.q_dim * d, s.wk, (size_t)c.kv_dim * d, "wk");
@@ -126,7 +151,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   c.geom.n_kv_heads = m.n_kv_heads;
   c.geom.head_dim = m.head_dim;
   c.geom.page_tokens = r.page_tokens;
-  c.geom.layout = KV_LINEAR;
+  c.geom.layout = c.simple ? KV_LINEAR : KV_MATRIX;
   c.geom.page_stride = (long long)m.n_kv_heads * 2 * r.page_tokens * m.head_dim;
   const size_t page_bytes_all_layers = (size_t)c.geom.page_stride * c.elem * m.n_layers;
   long long n_pages = (long long)(r.kv_pool_bytes / page_bytes_all_layers);
@@ -134,6 +159,8 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (n_pages > 0x7fffffff) n_pages = 0x7fffffff;
   c.geom.layer_stride = n_pages * c.geom.page_stride;
   c.kv_pool.alloc((size_t)n_pages * page_bytes_all_layers);
+  // attention multiplies masked positions' values by zero: they must be finite
+  HIP_TRY(hipMemsetAsync(c.kv_pool.p, 0, (size_t)n_pages * page_bytes_all_layers, c.stream));
   c.pool = new rollout_pool((int32_t)n_pages);
   c.h_page_table.assign((size_t)c.n_slots * c.max_pages, 0);
   c.d_page_table.alloc(c.h_page_table.size());
@@ -153,20 +180,37 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   // ---- workspaces ----
   const size_t R = c.r_max;
   c.x.alloc(R * d);
-  c.h.alloc(R * d);
-  c.qkv.alloc(R * c.qkv_dim);
-  c.attn.alloc(R * c.q_dim);
-  if (moe) {
+  if (!c.simple) {
+    c.h_bf16.alloc(R * d);
+    c.q_bf16.alloc(R * c.q_dim);
+    c.attn_bf16.alloc(R * c.q_dim);
+    c.act_bf16.alloc(R * m.ffn_dim);
+    c.hn_bf16.alloc((size_t)c.logit_rows * d);
+    c.partial_ld = std::max(c.qkv_dim, (int)d);
+    c.partial_rows = std::max<long long>(R, 2048);
+    c.partial.alloc((size_t)c.partial_rows * c.partial_ld);
+    c.attn_max_parts = std::max(r.max_live_samples * m.n_kv_heads, 1024);
+    c.attn_part_o.alloc((size_t)c.attn_max_parts * 16 * 128);
+    c.attn_part_ml.alloc((size_t)c.attn_max_parts * 32);
+    c.seq_row0.alloc(rollout_ctx::kTempSlots);
+    c.seq_len.alloc(rollout_ctx::kTempSlots);
+    c.seq_slot.alloc(rollout_ctx::kTempSlots);
+  } else {
+    c.h.alloc(R * d);
+    c.qkv.alloc(R * c.qkv_dim);
+    c.attn.alloc(R * c.q_dim);
+    c.hn.alloc((size_t)c.logit_rows * d);
+  }
+  if (c.simple && moe) {
     c.router_logits.alloc(R * m.n_experts);
     c.moe_idx.alloc(R * m.top_k);
     c.moe_wt.alloc(R * m.top_k);
     c.act.alloc(R * m.top_k * m.expert_ffn_dim);
     if (r.flags & ROLLOUT_RT_RECORD_ROUTING) c.route_log.alloc((size_t)m.n_layers * R * m.top_k);
-  } else {
+  } else if (c.simple) {
     c.gate_up.alloc(R * 2 * m.ffn_dim);
     c.act.alloc(R * m.ffn_dim);
   }
-  c.hn.alloc((size_t)c.logit_rows * d);
   c.logits.alloc((size_t)c.logit_rows * m.vocab);
   c.row_token.alloc(R);
   c.row_pos.alloc(R);
@@ -228,10 +272,123 @@ static void forward_rows_simple(rollout_ctx& c, int R) {
   }
 }
 
-void engine_forward_rows(rollout_ctx& c, int rows) {
+// ------------------------------------------------------------------------------------------
+// Matrix-core path.  Per layer: QKV projection (split-K planes) -> sum + rotary + KV-page
+// write -> paged attention -> O projection (planes) -> residual + norm -> gate/up projection
+// with SwiGLU in the epilogue -> down projection (planes) -> residual + next norm.
+static int project(rollout_ctx& c, const uint16_t* a, int lda, const void* w, int M, int N, int K) {
+  GemmArgs g{};
+  g.a = a;
+  g.w = w;
+  g.out = c.partial.p;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.lda = lda;
+  g.ldo = N;
+  g.split_stride = (long long)M * N;
+  const int cap = (int)std::min<long long>(32, (c.partial_rows * c.partial_ld) / ((long long)M * N));
+  return launch_gemm_bf16(g, EPI_F32, gemm_pick_splits(M, N, K, std::max(1, cap)), c.stream);
+}
+
+static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
+  const rollout_model_desc& m = c.md;
+  hipStream_t s = c.stream;
+  const int d = m.hidden, f = m.ffn_dim;
+  RowNormArgs rn{};
+  rn.x = c.x.p;
+  rn.h = c.h_bf16.p;
+  rn.rows = R;
+  rn.hidden = d;
+  rn.eps = m.rms_eps;
+  rn.tokens = c.row_token.p;
+  rn.embed = (const uint16_t*)c.embed.p;
+  rn.gain = c.layers[0].norm1.p;
+  launch_row_norm(rn, s);
+  rn.tokens = nullptr;
+  rn.embed = nullptr;
+  rn.partial = c.partial.p;
+  for (int l = 0; l < m.n_layers; ++l) {
+    LayerWeights& L = c.layers[l];
+    int z = project(c, c.h_bf16.p, d, L.wqkv_p.p, R, c.qkv_dim, d);
+    QkvPostArgs qp{};
+    qp.partial = c.partial.p;
+    qp.split_stride = (long long)R * c.qkv_dim;
+    qp.splits = z;
+    qp.cos_sin = c.cos_sin.p;
+    qp.row_pos = c.row_pos.p;
+    qp.row_slot = c.row_slot.p;
+    qp.page_table = c.d_page_table.p;
+    qp.max_pages = c.max_pages;
+    qp.q_bf16 = c.q_bf16.p;
+    qp.kv_pool = (uint16_t*)c.kv_pool.p;
+    qp.geom = c.geom;
+    qp.layer = l;
+    qp.rows = R;
+    qp.n_q_heads = m.n_q_heads;
+    launch_qkv_post(qp, s);
+
+    AttnArgs at{};
+    at.q = c.q_bf16.p;
+    at.out = c.attn_bf16.p;
+    at.kv_pool = (const uint16_t*)c.kv_pool.p;
+    at.geom = c.geom;
+    at.page_table = c.d_page_table.p;
+    at.max_pages = c.max_pages;
+    at.layer = l;
+    at.n_q_heads = m.n_q_heads;
+    if (seqs) {
+      at.seq_row0 = seqs->row0;
+      at.seq_len = seqs->len;
+      at.seq_slot = seqs->slot;
+      at.n_seqs = seqs->n_seqs;
+      at.max_seq_len = seqs->max_len;
+      launch_attention_prefill(at, s);
+    } else {
+      at.row_pos = c.row_pos.p;
+      at.row_slot = c.row_slot.p;
+      at.rows = R;
+      // enough workgroups to fill the chip, at least 128 cached positions each
+      const int base = R * m.n_kv_heads;
+      int n_splits = std::max(1, std::min({ceil_div(768, base), ceil_div(c.decode_max_ctx, 128),
+                                           c.attn_max_parts / base, 64}));
+      at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
+      at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
+      at.part_o = c.attn_part_o.p;
+      at.part_ml = c.attn_part_ml.p;
+      launch_attention_decode(at, s);
+    }
+
+    z = project(c, c.attn_bf16.p, c.q_dim, L.wo_p.p, R, d, c.q_dim);
+    rn.splits = z;
+    rn.split_stride = (long long)R * d;
+    rn.gain = L.norm2.p;
+    launch_row_norm(rn, s);
+
+    GemmArgs gu{};
+    gu.a = c.h_bf16.p;
+    gu.w = L.w_gate_up_p.p;
+    gu.out = c.act_bf16.p;
+    gu.M = R;
+    gu.N = 2 * f;
+    gu.K = d;
+    gu.lda = d;
+    gu.ldo = f;
+    launch_gemm_bf16(gu, EPI_SWIGLU_BF16, 1, s);
+
+    z = project(c, c.act_bf16.p, f, L.w_down_p.p, R, d, f);
+    rn.splits = z;
+    rn.gain = l + 1 < m.n_layers ? c.layers[l + 1].norm1.p : c.final_norm.p;
+    launch_row_norm(rn, s);
+  }
+}
+
+void engine_forward_rows(rollout_ctx& c, int rows, const SeqBatch* seqs) {
   if (rows < 1) return;
   c.last_route_rows = rows;
-  if (c.md.dtype == ROLLOUT_DTYPE_F32)
+  if (!c.simple)
+    forward_rows_fast(c, rows, seqs);
+  else if (c.md.dtype == ROLLOUT_DTYPE_F32)
     forward_rows_simple<float>(c, rows);
   else
     forward_rows_simple<bf16_t>(c, rows);
@@ -240,6 +397,28 @@ void engine_forward_rows(rollout_ctx& c, int rows) {
 void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, float* out) {
   if (n < 1) return;
   const int d = c.md.hidden;
+  if (!c.simple) {
+    RowNormArgs rn{};
+    rn.x = c.x.p + (size_t)first * d;
+    rn.h = c.hn_bf16.p;
+    rn.gain = c.final_norm.p;
+    rn.rows_index = rows_index;
+    rn.rows = n;
+    rn.hidden = d;
+    rn.eps = c.md.rms_eps;
+    launch_row_norm(rn, c.stream);
+    GemmArgs g{};
+    g.a = c.hn_bf16.p;
+    g.w = c.lm_head_p.p;
+    g.out = out;
+    g.M = n;
+    g.N = c.md.vocab;
+    g.K = d;
+    g.lda = d;
+    g.ldo = c.md.vocab;
+    launch_gemm_bf16(g, EPI_F32, 1, c.stream);
+    return;
+  }
   launch_rmsnorm_f32(c.x.p + (size_t)first * d, c.final_norm.p, c.hn.p, rows_index, n, d, c.md.rms_eps, c.stream);
   if (c.md.dtype == ROLLOUT_DTYPE_F32)
     launch_linear_simple<float>(c.hn.p, d, (const float*)c.lm_head.p, out, c.md.vocab, nullptr, 0, n, c.md.vocab,
