@@ -1,0 +1,158 @@
+"""Rollout throughput on one MI355X.
+
+A "step" is one whole generation job of the workload: prefill of every prompt, then decode
+steps until every sample has finished (inputs and weights already resident in HBM).
+Prints one JSON line: output tokens/s, the roofline of the kernel that took the most time
+(HIP-event timings gathered by the library on its own stream during the timed steps), and
+the CPU oracle timed on a bounded slice of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def run_job(eng, load) -> int:
+    """One generation job; returns the number of response tokens emitted."""
+    ids, toks, lps, fin = eng.rollout_prefill(load.prompt_tokens, load.prompt_offsets, load.n_samples,
+                                              load.max_new_tokens, eos_id=-1, temperature=load.temperature,
+                                              top_p=load.top_p)
+    emitted = len(ids)
+    while True:
+        ids, toks, lps, fin = eng.rollout_decode_step()
+        if not len(ids):
+            return emitted
+        emitted += len(ids)
+
+
+def cpu_baseline(shape, weights, load) -> dict:
+    """The oracle, as it stands, on a bounded slice: one 128-token prompt, 2 samples, 16 new
+    tokens each (weights widened to fp64 beforehand, not timed)."""
+    from threadpoolctl import threadpool_info
+    from oracle import rollout as orollout
+    from oracle import transformer as T
+    model = T.Model(shape, weights)
+    for name in weights:
+        model.w(name)
+    prompt = load.prompt_tokens[:128]
+    t0 = time.perf_counter()
+    emitted = orollout.decode_slice_batched(model, prompt, 2, 16, load.temperature, load.top_p, load.sampler_seed)
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": emitted / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{shape.name}: 1 prompt x 128 tokens prefill, 2 samples x 16 new tokens, fp64, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--timing-stride", type=int, default=16,
+                    help="bracket kernels with HIP events on every n-th library call (0 = never)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prompts", type=int, default=32, help="smaller values only for quick checks")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2506_06122_amd as R
+    from paper_2506_06122_amd import binding as B
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    shape = workloads.C2_1P5B
+    load = workloads.load_c2(n_prompts=args.prompts)
+    t0 = time.perf_counter()
+    weights = workloads.make_weights(shape, seed=1, gains="ones")
+    print(f"# weights generated in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    max_prompt = int(np.diff(load.prompt_offsets).max())
+    flags = B.RT_KERNEL_TIMING if args.timing_stride > 0 else 0
+    eng = R.Rollout(shape, weights, kv_pool_bytes=12 << 30, page_tokens=32,
+                    max_live_samples=load.n_prompts * load.n_samples,
+                    max_context=max_prompt + int(load.max_new_tokens.max()),
+                    max_batch_tokens=max(16384, max_prompt), seed=load.sampler_seed, flags=flags,
+                    timing_stride=max(args.timing_stride, 1))
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
+    print("# engine ready", file=sys.stderr, flush=True)
+
+    for _ in range(args.warmup):
+        run_job(eng, load)
+    torch.cuda.synchronize()
+    before = {k["name"]: k for k in eng.rollout_kernel_stats()}
+    t0 = time.perf_counter()
+    emitted = 0
+    for _ in range(args.steps):
+        emitted += run_job(eng, load)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    stats = eng.rollout_get_stats()
+
+    kernels = []
+    for k in eng.rollout_kernel_stats():
+        b = before.get(k["name"], dict(launches=0, ms=0.0, bytes=0.0, flops=0.0))
+        n = k["launches"] - b["launches"]
+        if n:
+            kernels.append(dict(name=k["name"], launches=n, ms=k["ms"] - b["ms"], bytes=k["bytes"] - b["bytes"],
+                                flops=k["flops"] - b["flops"]))
+    kernels.sort(key=lambda k: -k["ms"])
+    roofline = None
+    if kernels:
+        top = kernels[0]
+        ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+        if top["flops"] / max(top["bytes"], 1.0) >= ridge:
+            ach = top["flops"] / (top["ms"] * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+        else:
+            ach = top["bytes"] / (top["ms"] * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": ach / HBM_PEAK_GBS, "traffic": None}
+        roofline["kernel"] = top["name"]
+        roofline["avg_launch_us"] = 1e3 * top["ms"] / top["launches"]
+        roofline["timed_launches"] = top["launches"]
+        roofline["per_kernel"] = [
+            {"name": k["name"], "launches": k["launches"], "avg_us": 1e3 * k["ms"] / k["launches"],
+             "GB/s": k["bytes"] / (k["ms"] * 1e-3) / 1e9, "TFLOP/s": k["flops"] / (k["ms"] * 1e-3) / 1e12}
+            for k in kernels]
+
+    out = {
+        "metric": "rollout output tokens/sec on 1 MI355X", "value": emitted / dt, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: Qwen2.5-1.5B-shaped dense decoder, bf16, %d prompts x %d samples, "
+                               "prompt 64-512, response geometric(mean 512) capped 2048, T=1.0 top-p=1.0"
+                               % (load.n_prompts, load.n_samples),
+                   "output_tokens_per_step": emitted // max(args.steps, 1),
+                   "decode_calls_per_step": int(stats["decode_steps"]) // (args.steps + args.warmup)},
+        "roofline": roofline,
+    }
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, weights, load)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -49,6 +49,7 @@ extern "C" {
 /* runtime flags */
 #define ROLLOUT_RT_SIMPLE_KERNELS 1u /* run every operator with the plain one-op-per-kernel path */
 #define ROLLOUT_RT_RECORD_ROUTING 2u /* MoE: keep each forward's expert choices for rollout_debug_routing */
+#define ROLLOUT_RT_KERNEL_TIMING 4u  /* bracket kernels with HIP events on sampled calls, see rollout_kernel_stats */
 
 typedef struct rollout_ctx rollout_ctx; /* opaque; created by rollout_init, freed by rollout_destroy */
 
@@ -90,13 +91,24 @@ typedef struct {
   void *hip_stream;         /* hipStream_t the library launches on; NULL = the null stream */
   uint64_t seed;            /* key of the Philox4x32-10 stream that drives sampling */
   uint32_t flags;           /* ROLLOUT_RT_* */
+  uint32_t timing_stride;   /* with ROLLOUT_RT_KERNEL_TIMING: time every timing_stride-th call (0 or 1 = all) */
 } rollout_runtime_desc;
 
 typedef struct {
   uint64_t decode_steps, tokens_emitted, prompts_prefilled, prompt_tokens, samples_admitted,
       samples_finished, samples_aborted;
   int32_t live_samples, pages_total, pages_in_use, pages_reserved, pages_peak;
+  int32_t matrix_core_path; /* 1 when the bf16 matrix-core kernels run, 0 for the plain path */
 } rollout_stats;
+
+/* Accumulated HIP-event timings of one kernel on the context's stream (sampled calls only):
+ * name = the kernel as a profiler shows it; bytes / flops = the algorithmic traffic and
+ * arithmetic of the timed launches (operands read once, results written once). */
+typedef struct {
+  char name[64];
+  uint64_t launches;
+  double ms, bytes, flops;
+} rollout_kernel_stat;
 
 /* Creates a context on the current device: copies the weights, allocates the KV pool and
  * workspaces.  Paper section 2.1: the actor model that generates responses.
@@ -168,6 +180,9 @@ int rollout_debug_logits(rollout_ctx *ctx, int32_t *rows, float *out);
 int rollout_debug_routing(rollout_ctx *ctx, int32_t *rows, int32_t *out);
 
 int rollout_get_stats(rollout_ctx *ctx, rollout_stats *out);
+/* Per-kernel timings gathered under ROLLOUT_RT_KERNEL_TIMING.  n: in capacity of `out`, out
+ * number of entries written (kernels with at least one timed launch). */
+int rollout_kernel_stats(rollout_ctx *ctx, int32_t *n, rollout_kernel_stat *out);
 const char *rollout_last_error(rollout_ctx *ctx); /* ctx may be NULL: error of the last failed rollout_init */
 void rollout_destroy(rollout_ctx *ctx);
 int rollout_abi_version(void);

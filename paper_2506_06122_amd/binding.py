@@ -17,6 +17,7 @@ OK, E_INVAL, E_NOMEM, E_HIP, E_STATE = 0, -1, -2, -3, -4
 DTYPE_F32, DTYPE_BF16 = 0, 1
 RT_SIMPLE_KERNELS = 1
 RT_RECORD_ROUTING = 2
+RT_KERNEL_TIMING = 4
 
 
 class RolloutError(RuntimeError):
@@ -44,7 +45,7 @@ class rollout_weights(C.Structure):
 class rollout_runtime_desc(C.Structure):
     _fields_ = [("kv_pool_bytes", C.c_size_t), ("page_tokens", C.c_int32), ("max_live_samples", C.c_int32),
                 ("max_context", C.c_int32), ("max_batch_tokens", C.c_int32), ("hip_stream", C.c_void_p),
-                ("seed", C.c_uint64), ("flags", C.c_uint32)]
+                ("seed", C.c_uint64), ("flags", C.c_uint32), ("timing_stride", C.c_uint32)]
 
 
 class rollout_stats(C.Structure):
@@ -52,7 +53,12 @@ class rollout_stats(C.Structure):
                                           "prompt_tokens", "samples_admitted", "samples_finished",
                                           "samples_aborted")] + \
                [(n, C.c_int32) for n in ("live_samples", "pages_total", "pages_in_use", "pages_reserved",
-                                         "pages_peak")]
+                                         "pages_peak", "matrix_core_path")]
+
+
+class rollout_kernel_stat(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("launches", C.c_uint64), ("ms", C.c_double), ("bytes", C.c_double),
+                ("flops", C.c_double)]
 
 
 # every symbol include/rollout.h declares: name -> (restype, argtypes)
@@ -69,6 +75,7 @@ SIGNATURES = {
     "rollout_debug_logits": (C.c_int, [_P, C.POINTER(C.c_int32), _P]),
     "rollout_debug_routing": (C.c_int, [_P, C.POINTER(C.c_int32), _P]),
     "rollout_get_stats": (C.c_int, [_P, C.POINTER(rollout_stats)]),
+    "rollout_kernel_stats": (C.c_int, [_P, C.POINTER(C.c_int32), C.POINTER(rollout_kernel_stat)]),
     "rollout_last_error": (C.c_char_p, [_P]),
     "rollout_destroy": (None, [_P]),
     "rollout_abi_version": (C.c_int, []),
@@ -134,7 +141,7 @@ class Rollout:
 
     def __init__(self, shape, weights: dict, *, kv_pool_bytes: int, page_tokens: int = 32,
                  max_live_samples: int = 64, max_context: int = 1024, max_batch_tokens: int = 4096,
-                 seed: int = 0, flags: int = 0, stream=None):
+                 seed: int = 0, flags: int = 0, stream=None, timing_stride: int = 0):
         import torch
         self.lib = load_library()
         self.shape = shape
@@ -163,7 +170,7 @@ class Rollout:
         w = rollout_weights(up("embed"), up("final_norm"), up("lm_head"), layers)
         md = model_desc_from_shape(shape)
         rd = rollout_runtime_desc(kv_pool_bytes, page_tokens, max_live_samples, max_context, max_batch_tokens,
-                                  stream, seed, flags)
+                                  stream, seed, flags, timing_stride)
         torch.cuda.synchronize()
         ctx = C.c_void_p()
         rc = self.lib.rollout_init(C.byref(ctx), C.byref(md), C.byref(w), C.byref(rd))
@@ -245,6 +252,17 @@ class Rollout:
         st = rollout_stats()
         self._check(self.lib.rollout_get_stats(self.ctx, C.byref(st)))
         return {n: getattr(st, n) for n, _ in rollout_stats._fields_}
+
+
+def _kernel_stats(self) -> list:
+    n = C.c_int32(32)
+    arr = (rollout_kernel_stat * 32)()
+    self._check(self.lib.rollout_kernel_stats(self.ctx, C.byref(n), arr))
+    return [dict(name=arr[i].name.decode(), launches=arr[i].launches, ms=arr[i].ms, bytes=arr[i].bytes,
+                 flops=arr[i].flops) for i in range(n.value)]
+
+
+Rollout.rollout_kernel_stats = _kernel_stats
 
 
 def rollout_sample(logits, temperature, top_p, uniforms, forced=None, stream=None):

@@ -68,6 +68,7 @@ static void refresh_stats(rollout_ctx& c) {
   c.stats.pages_in_use = c.pool->in_use();
   c.stats.pages_reserved = c.pool->reserved;
   c.stats.pages_peak = c.pool->peak_in_use;
+  c.stats.matrix_core_path = c.simple ? 0 : 1;
 }
 
 extern "C" {
@@ -106,6 +107,24 @@ int rollout_get_stats(rollout_ctx* ctx, rollout_stats* out) {
   if (!ctx || !out) return ROLLOUT_E_INVAL;
   refresh_stats(*ctx);
   *out = ctx->stats;
+  return ROLLOUT_OK;
+}
+
+int rollout_kernel_stats(rollout_ctx* ctx, int32_t* n, rollout_kernel_stat* out) {
+  if (!ctx || !n || (*n > 0 && !out)) return ROLLOUT_E_INVAL;
+  int k = 0;
+  for (int i = 0; i < KC_COUNT && k < *n; ++i) {
+    const KernelTimer::Acc& a = ctx->timer.acc[i];
+    if (!a.launches) continue;
+    std::memset(&out[k], 0, sizeof(out[k]));
+    std::strncpy(out[k].name, kKernelClassNames[i], sizeof(out[k].name) - 1);
+    out[k].launches = a.launches;
+    out[k].ms = a.ms;
+    out[k].bytes = a.bytes;
+    out[k].flops = a.flops;
+    ++k;
+  }
+  *n = k;
   return ROLLOUT_OK;
 }
 
@@ -244,9 +263,17 @@ int rollout_prefill(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, 
       h2d(c.row_pos.p, ht + R, rows * sizeof(int), c.stream);
       h2d(c.row_slot.p, ht + 2 * R, rows * sizeof(int), c.stream);
       h2d(c.row_aux.p, ht + 3 * R, (p1 - p0) * sizeof(int), c.stream);
+      c.timer.start_call();
+      c.kv_tokens_this_call = rows;
+      c.attn_flops_this_call = 0;
+      for (int p = p0; p < p1; ++p) {
+        double len = offsets[p + 1] - offsets[p];
+        c.attn_flops_this_call += 2.0 * len * (len + 1) * c.q_dim;
+      }
       engine_forward_rows(c, rows, &sb);
       engine_logits(c, c.row_aux.p, 0, p1 - p0, c.logits.p + (size_t)p0 * m.vocab);
       HIP_TRY(hipStreamSynchronize(c.stream));  // staging buffers are reused by the next chunk
+      c.timer.collect();
       c.stats.prompt_tokens += rows;
       p0 = p1;
     }
@@ -372,7 +399,14 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
     launch_gather_decode_rows(c.st, c.d_live.p, B, c.row_token.p, c.row_pos.p, c.row_slot.p, c.row_inv_temp.p,
                               c.row_top_p.p, c.row_sample_id.p, c.row_step.p, c.stream);
     c.decode_max_ctx = 1;
-    for (auto& kv : c.live) c.decode_max_ctx = std::max(c.decode_max_ctx, kv.second.prompt_len + kv.second.n_emitted);
+    c.kv_tokens_this_call = 0;
+    for (auto& kv : c.live) {
+      const int ctx = kv.second.prompt_len + kv.second.n_emitted;
+      c.decode_max_ctx = std::max(c.decode_max_ctx, ctx);
+      c.kv_tokens_this_call += ctx;
+    }
+    c.attn_flops_this_call = 4.0 * c.kv_tokens_this_call * c.q_dim;
+    c.timer.start_call();
     engine_forward_rows(c, B, nullptr);
     engine_logits(c, nullptr, 0, B, c.logits.p);
     c.last_logit_rows = B;
@@ -396,11 +430,14 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
     sr.seed = c.rd.seed;
     sr.tokens = c.out_tokens.p;
     sr.logprobs = c.out_logprobs.p;
+    c.timer.begin(KC_SAMPLE, 4.0 * B * m.vocab, 0, c.stream);
     launch_sample(sr, B, m.vocab, c.stream);
+    c.timer.end(c.stream);
     launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);
     d2h(hi + 3 * R, c.out_tokens.p, B * sizeof(int), c.stream);
     d2h(c.h_float.p, c.out_logprobs.p, B * sizeof(float), c.stream);
     HIP_TRY(hipStreamSynchronize(c.stream));
+    c.timer.collect();
 
     int i = 0;
     for (auto it = c.live.begin(); it != c.live.end(); ++i) {
@@ -538,6 +575,13 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
         h2d(c.seq_len.p, ht + 5 * R, (s1 - s0) * sizeof(int), c.stream);
         h2d(c.seq_slot.p, ht + 6 * R, (s1 - s0) * sizeof(int), c.stream);
       }
+      c.timer.start_call();
+      c.kv_tokens_this_call = rows;
+      c.attn_flops_this_call = 0;
+      for (int s = s0; s < s1; ++s) {
+        double len = cu_seqlens[s + 1] - cu_seqlens[s];
+        c.attn_flops_this_call += 2.0 * len * (len + 1) * c.q_dim;
+      }
       engine_forward_rows(c, rows, &sb);
       for (int off = 0; off < rows; off += c.logit_rows) {
         int nr = std::min(c.logit_rows, rows - off);
@@ -546,6 +590,7 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
       }
       d2h(c.h_float.p, c.out_logprobs.p, rows * sizeof(float), c.stream);
       HIP_TRY(hipStreamSynchronize(c.stream));
+      c.timer.collect();
       // row i of a sequence holds log p(token i+1); shift by one and zero the first entry
       r = 0;
       for (int s = s0; s < s1; ++s) {

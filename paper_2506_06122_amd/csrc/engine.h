@@ -77,6 +77,67 @@ struct SeqBatch {
   int n_seqs, max_len;
 };
 
+// HIP-event brackets around kernel launches on sampled calls (ROLLOUT_RT_KERNEL_TIMING).
+enum KernelClass {
+  KC_GEMM_F32_16, KC_GEMM_F32_32, KC_GEMM_F32_64, KC_GEMM_F32_128,
+  KC_GEMM_SWIGLU_16, KC_GEMM_SWIGLU_32, KC_GEMM_SWIGLU_64, KC_GEMM_SWIGLU_128,
+  KC_ATTN_DECODE, KC_ATTN_PREFILL, KC_ROW_NORM, KC_QKV_POST, KC_SAMPLE, KC_COUNT
+};
+extern const char* const kKernelClassNames[KC_COUNT];
+
+struct KernelTimer {
+  bool enabled = false, active = false;
+  unsigned stride = 1, calls = 0;
+  struct Rec {
+    int cls;
+    double bytes, flops;
+    hipEvent_t a, b;
+  };
+  std::vector<hipEvent_t> pool;
+  size_t used = 0;
+  std::vector<Rec> pending;
+  struct Acc {
+    uint64_t launches = 0;
+    double ms = 0, bytes = 0, flops = 0;
+  } acc[KC_COUNT];
+
+  void start_call() { active = enabled && (calls++ % (stride ? stride : 1)) == 0; }
+  hipEvent_t get() {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      HIP_TRY(hipEventCreate(&e));
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+  void begin(int cls, double bytes, double flops, hipStream_t s) {
+    if (!active) return;
+    Rec r{cls, bytes, flops, get(), get()};
+    HIP_TRY(hipEventRecord(r.a, s));
+    pending.push_back(r);
+  }
+  void end(hipStream_t s) {
+    if (active) HIP_TRY(hipEventRecord(pending.back().b, s));
+  }
+  void collect() {  // after the stream has been synchronised
+    for (Rec& r : pending) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+        acc[r.cls].launches += 1;
+        acc[r.cls].ms += ms;
+        acc[r.cls].bytes += r.bytes;
+        acc[r.cls].flops += r.flops;
+      }
+    }
+    pending.clear();
+    used = 0;
+    active = false;
+  }
+  ~KernelTimer() {
+    for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+  }
+};
+
 struct Sample {
   int64_t id;
   int slot;
@@ -134,6 +195,8 @@ struct rollout_ctx {
   int partial_ld = 0;
   int attn_max_parts = 0;       // capacity of attn_part_* in (row, kv head, split) triples
   int decode_max_ctx = 0;       // longest context among the rows of the current decode step
+  double kv_tokens_this_call = 0;   // cached positions attended by the current forward (for timing records)
+  double attn_flops_this_call = 0;
   DevBuf<int> seq_row0, seq_len, seq_slot;
   DevBuf<int> row_token, row_pos, row_slot, row_step, row_aux, row_forced, out_tokens;
   DevBuf<long long> row_sample_id;
@@ -145,6 +208,7 @@ struct rollout_ctx {
   int last_logit_rows = 0;
 
   rollout_stats stats{};
+  KernelTimer timer;
 
   ~rollout_ctx() { delete pool; }
 };

@@ -8,6 +8,18 @@
 
 static void fail(int code, const std::string& msg) { throw ApiError{code, msg}; }
 
+const char* const kKernelClassNames[KC_COUNT] = {
+    "gemm_bf16_kernel<1,2,4,false,0>", "gemm_bf16_kernel<2,2,4,true,0>", "gemm_bf16_kernel<4,2,4,true,0>",
+    "gemm_bf16_kernel<8,4,2,true,0>",  "gemm_bf16_kernel<1,2,4,false,1>", "gemm_bf16_kernel<2,2,4,true,1>",
+    "gemm_bf16_kernel<4,2,4,true,1>",  "gemm_bf16_kernel<8,4,2,true,1>", "attn_decode_kernel",
+    "attn_prefill_kernel", "row_norm_kernel", "qkv_post_kernel", "sample_kernel"};
+
+static int gemm_class(int M, bool swiglu) {
+  const int bm = gemm_rows_per_block(M);
+  const int b = bm == 16 ? 0 : bm == 32 ? 1 : bm == 64 ? 2 : 3;
+  return (swiglu ? KC_GEMM_SWIGLU_16 : KC_GEMM_F32_16) + b;
+}
+
 static void copy_d2d(void* dst, const void* src, size_t bytes, hipStream_t s) {
   if (bytes) HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
 }
@@ -45,7 +57,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (r.page_tokens < 32 || r.page_tokens % 32) fail(ROLLOUT_E_INVAL, "page_tokens must be a positive multiple of 32");
   if (r.max_live_samples < 1 || r.max_context < 2 || r.max_batch_tokens < 1)
     fail(ROLLOUT_E_INVAL, "max_live_samples, max_context, max_batch_tokens must be positive");
-  if (r.flags & ~(ROLLOUT_RT_SIMPLE_KERNELS | ROLLOUT_RT_RECORD_ROUTING)) fail(ROLLOUT_E_INVAL, "unknown runtime flag");
+  if (r.flags & ~(ROLLOUT_RT_SIMPLE_KERNELS | ROLLOUT_RT_RECORD_ROUTING | ROLLOUT_RT_KERNEL_TIMING)) fail(ROLLOUT_E_INVAL, "unknown runtime flag");
   if (!w.embed || !w.final_norm || !w.lm_head || !w.layers) fail(ROLLOUT_E_INVAL, "null weight pointer");
 
   int n_dev = 0;
@@ -57,6 +69,8 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   c.simple = (r.flags & ROLLOUT_RT_SIMPLE_KERNELS) || m.dtype != ROLLOUT_DTYPE_BF16 || m.head_dim != 128 ||
              m.hidden % 32 || m.hidden > 8192 || m.vocab % 16 || moe || m.ffn_dim % 32;
   c.elem = m.dtype == ROLLOUT_DTYPE_BF16 ? 2 : 4;
+  c.timer.enabled = (r.flags & ROLLOUT_RT_KERNEL_TIMING) != 0;
+  c.timer.stride = r.timing_stride;
   c.q_dim = m.n_q_heads * m.head_dim;
   c.kv_dim = m.n_kv_heads * m.head_dim;
   c.qkv_dim = c.q_dim + 2 * c.kv_dim;
@@ -288,7 +302,12 @@ static int project(rollout_ctx& c, const uint16_t* a, int lda, const void* w, in
   g.ldo = N;
   g.split_stride = (long long)M * N;
   const int cap = (int)std::min<long long>(32, (c.partial_rows * c.partial_ld) / ((long long)M * N));
-  return launch_gemm_bf16(g, EPI_F32, gemm_pick_splits(M, N, K, std::max(1, cap)), c.stream);
+  const int want = gemm_pick_splits(M, N, K, std::max(1, cap));
+  // algorithmic traffic: the weight matrix and the activations once, the result once
+  c.timer.begin(gemm_class(M, false), 2.0 * N * K + 2.0 * M * K + 4.0 * M * N, 2.0 * M * N * K, c.stream);
+  const int z = launch_gemm_bf16(g, EPI_F32, want, c.stream);
+  c.timer.end(c.stream);
+  return z;
 }
 
 static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
@@ -304,7 +323,10 @@ static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
   rn.tokens = c.row_token.p;
   rn.embed = (const uint16_t*)c.embed.p;
   rn.gain = c.layers[0].norm1.p;
+  const double rn_bytes = (double)R * d * (4 + 4 + 2);
+  c.timer.begin(KC_ROW_NORM, rn_bytes, 0, s);
   launch_row_norm(rn, s);
+  c.timer.end(s);
   rn.tokens = nullptr;
   rn.embed = nullptr;
   rn.partial = c.partial.p;
@@ -326,7 +348,9 @@ static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
     qp.layer = l;
     qp.rows = R;
     qp.n_q_heads = m.n_q_heads;
+    c.timer.begin(KC_QKV_POST, (double)R * c.qkv_dim * (4 + 2), 0, s);
     launch_qkv_post(qp, s);
+    c.timer.end(s);
 
     AttnArgs at{};
     at.q = c.q_bf16.p;
@@ -343,7 +367,10 @@ static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
       at.seq_slot = seqs->slot;
       at.n_seqs = seqs->n_seqs;
       at.max_seq_len = seqs->max_len;
+      c.timer.begin(KC_ATTN_PREFILL, c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2,
+                    c.attn_flops_this_call, s);
       launch_attention_prefill(at, s);
+      c.timer.end(s);
     } else {
       at.row_pos = c.row_pos.p;
       at.row_slot = c.row_slot.p;
@@ -356,14 +383,20 @@ static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
       at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
       at.part_o = c.attn_part_o.p;
       at.part_ml = c.attn_part_ml.p;
+      // every cached key and value of every live sample once (no prefix reuse), plus q and out
+      c.timer.begin(KC_ATTN_DECODE, c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2 + 4.0 * R * c.q_dim,
+                    c.attn_flops_this_call, s);
       launch_attention_decode(at, s);
+      c.timer.end(s);
     }
 
     z = project(c, c.attn_bf16.p, c.q_dim, L.wo_p.p, R, d, c.q_dim);
     rn.splits = z;
     rn.split_stride = (long long)R * d;
     rn.gain = L.norm2.p;
+    c.timer.begin(KC_ROW_NORM, rn_bytes + 4.0 * z * R * d, 0, s);
     launch_row_norm(rn, s);
+    c.timer.end(s);
 
     GemmArgs gu{};
     gu.a = c.h_bf16.p;
@@ -374,12 +407,16 @@ static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
     gu.K = d;
     gu.lda = d;
     gu.ldo = f;
+    c.timer.begin(gemm_class(R, true), 2.0 * 2 * f * d + 2.0 * R * d + 2.0 * R * f, 2.0 * R * 2 * f * d, s);
     launch_gemm_bf16(gu, EPI_SWIGLU_BF16, 1, s);
+    c.timer.end(s);
 
     z = project(c, c.act_bf16.p, f, L.w_down_p.p, R, d, f);
     rn.splits = z;
     rn.gain = l + 1 < m.n_layers ? c.layers[l + 1].norm1.p : c.final_norm.p;
+    c.timer.begin(KC_ROW_NORM, rn_bytes + 4.0 * z * R * d, 0, s);
     launch_row_norm(rn, s);
+    c.timer.end(s);
   }
 }
 
@@ -416,7 +453,9 @@ void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, floa
     g.K = d;
     g.lda = d;
     g.ldo = c.md.vocab;
+    c.timer.begin(gemm_class(n, false), 2.0 * g.N * d + 2.0 * n * d + 4.0 * n * g.N, 2.0 * n * g.N * d, c.stream);
     launch_gemm_bf16(g, EPI_F32, 1, c.stream);
+    c.timer.end(c.stream);
     return;
   }
   launch_rmsnorm_f32(c.x.p + (size_t)first * d, c.final_norm.p, c.hn.p, rows_index, n, d, c.md.rms_eps, c.stream);

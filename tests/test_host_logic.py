@@ -33,7 +33,7 @@ def test_init_validates_and_fails_loudly_without_gpu():
     lib = R.load_library()
     layers = (B.rollout_layer_weights * 2)()
     w = B.rollout_weights(1, 1, 1, layers)
-    rd = B.rollout_runtime_desc(1 << 20, 32, 8, 128, 256, None, 0, 0)
+    rd = B.rollout_runtime_desc(1 << 20, 32, 8, 128, 256, None, 0, 0, 0)
     ctx = C.c_void_p()
 
     def init(**over):
