@@ -113,15 +113,14 @@ int rollout_get_stats(rollout_ctx* ctx, rollout_stats* out) {
 int rollout_kernel_stats(rollout_ctx* ctx, int32_t* n, rollout_kernel_stat* out) {
   if (!ctx || !n || (*n > 0 && !out)) return ROLLOUT_E_INVAL;
   int k = 0;
-  for (int i = 0; i < KC_COUNT && k < *n; ++i) {
-    const KernelTimer::Acc& a = ctx->timer.acc[i];
-    if (!a.launches) continue;
+  for (auto& kv : ctx->timer.acc) {
+    if (k >= *n) break;
     std::memset(&out[k], 0, sizeof(out[k]));
-    std::strncpy(out[k].name, kKernelClassNames[i], sizeof(out[k].name) - 1);
-    out[k].launches = a.launches;
-    out[k].ms = a.ms;
-    out[k].bytes = a.bytes;
-    out[k].flops = a.flops;
+    std::strncpy(out[k].name, kv.first.c_str(), sizeof(out[k].name) - 1);
+    out[k].launches = kv.second.launches;
+    out[k].ms = kv.second.ms;
+    out[k].bytes = kv.second.bytes;
+    out[k].flops = kv.second.flops;
     ++k;
   }
   *n = k;
@@ -430,7 +429,7 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
     sr.seed = c.rd.seed;
     sr.tokens = c.out_tokens.p;
     sr.logprobs = c.out_logprobs.p;
-    c.timer.begin(KC_SAMPLE, 4.0 * B * m.vocab, 0, c.stream);
+    c.timer.begin("sample_kernel", 4.0 * B * m.vocab, 0, c.stream);
     launch_sample(sr, B, m.vocab, c.stream);
     c.timer.end(c.stream);
     launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);

@@ -37,8 +37,37 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
   return out;
 }
 
+// v = hi + lo with both parts bf16: carries about 16 significant bits through bf16 arithmetic
+__host__ __device__ inline void split_bf16(float v, uint16_t& hi, uint16_t& lo) {
+  const bf16_t h = f32_to_bf16(v);
+  hi = h.bits;
+  lo = f32_to_bf16(v - bf16_to_f32(h)).bits;
+}
+
+// IEEE half: the 16-bit format of the KV cache of bf16 models.  Keys and values are of order
+// one, so the three extra mantissa bits over bf16 are what keeps 28-layer logits within
+// tolerance of the unrounded reference at the same bytes per cached token.  Values saturate
+// at the largest finite half.
+struct f16_t {
+  uint16_t bits;
+};
+__host__ __device__ inline float f16_to_f32(f16_t v) { return (float)__builtin_bit_cast(_Float16, v.bits); }
+__host__ __device__ inline f16_t f32_to_f16(float f) {
+  f = f > 65504.f ? 65504.f : (f < -65504.f ? -65504.f : f);
+  f16_t out;
+  out.bits = __builtin_bit_cast(uint16_t, (_Float16)f);
+  return out;
+}
+// v = hi + lo with both parts half precision (about 22 significant bits)
+__host__ __device__ inline void split_f16(float v, uint16_t& hi, uint16_t& lo) {
+  const _Float16 h = (_Float16)v;
+  hi = __builtin_bit_cast(uint16_t, h);
+  lo = __builtin_bit_cast(uint16_t, (_Float16)(v - (float)h));
+}
+
 __host__ __device__ inline float to_f32(float v) { return v; }
 __host__ __device__ inline float to_f32(bf16_t v) { return bf16_to_f32(v); }
+__host__ __device__ inline float to_f32(f16_t v) { return f16_to_f32(v); }
 template <typename T>
 __host__ __device__ inline T from_f32(float v);
 template <>
@@ -48,6 +77,10 @@ __host__ __device__ inline float from_f32<float>(float v) {
 template <>
 __host__ __device__ inline bf16_t from_f32<bf16_t>(float v) {
   return f32_to_bf16(v);
+}
+template <>
+__host__ __device__ inline f16_t from_f32<f16_t>(float v) {
+  return f32_to_f16(v);
 }
 
 // ---- wavefront reductions (every lane gets the result) ---------------------------------

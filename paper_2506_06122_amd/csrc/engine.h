@@ -77,29 +77,24 @@ struct SeqBatch {
   int n_seqs, max_len;
 };
 
-// HIP-event brackets around kernel launches on sampled calls (ROLLOUT_RT_KERNEL_TIMING).
-enum KernelClass {
-  KC_GEMM_F32_16, KC_GEMM_F32_32, KC_GEMM_F32_64, KC_GEMM_F32_128,
-  KC_GEMM_SWIGLU_16, KC_GEMM_SWIGLU_32, KC_GEMM_SWIGLU_64, KC_GEMM_SWIGLU_128,
-  KC_ATTN_DECODE, KC_ATTN_PREFILL, KC_ROW_NORM, KC_QKV_POST, KC_SAMPLE, KC_COUNT
-};
-extern const char* const kKernelClassNames[KC_COUNT];
-
+// HIP-event brackets around kernel launches on sampled calls (ROLLOUT_RT_KERNEL_TIMING),
+// accumulated per kernel name.
 struct KernelTimer {
   bool enabled = false, active = false;
   unsigned stride = 1, calls = 0;
   struct Rec {
-    int cls;
+    const char* name;
     double bytes, flops;
     hipEvent_t a, b;
+  };
+  struct Acc {
+    uint64_t launches = 0;
+    double ms = 0, bytes = 0, flops = 0;
   };
   std::vector<hipEvent_t> pool;
   size_t used = 0;
   std::vector<Rec> pending;
-  struct Acc {
-    uint64_t launches = 0;
-    double ms = 0, bytes = 0, flops = 0;
-  } acc[KC_COUNT];
+  std::map<std::string, Acc> acc;
 
   void start_call() { active = enabled && (calls++ % (stride ? stride : 1)) == 0; }
   hipEvent_t get() {
@@ -110,9 +105,9 @@ struct KernelTimer {
     }
     return pool[used++];
   }
-  void begin(int cls, double bytes, double flops, hipStream_t s) {
+  void begin(const char* name, double bytes, double flops, hipStream_t s) {
     if (!active) return;
-    Rec r{cls, bytes, flops, get(), get()};
+    Rec r{name, bytes, flops, get(), get()};
     HIP_TRY(hipEventRecord(r.a, s));
     pending.push_back(r);
   }
@@ -123,10 +118,11 @@ struct KernelTimer {
     for (Rec& r : pending) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
-        acc[r.cls].launches += 1;
-        acc[r.cls].ms += ms;
-        acc[r.cls].bytes += r.bytes;
-        acc[r.cls].flops += r.flops;
+        Acc& a = acc[r.name];
+        a.launches += 1;
+        a.ms += ms;
+        a.bytes += r.bytes;
+        a.flops += r.flops;
       }
     }
     pending.clear();
@@ -198,6 +194,9 @@ struct rollout_ctx {
   double kv_tokens_this_call = 0;   // cached positions attended by the current forward (for timing records)
   double attn_flops_this_call = 0;
   DevBuf<int> seq_row0, seq_len, seq_slot;
+  DevBuf<float> ssq;            // [partials][256] partial sums of squares of the residual rows (decode path)
+  int ssq_partials = 0;
+  bool h_is_final = false;      // the last forward left x * final gain in h_bf16 (decode path)
   DevBuf<int> row_token, row_pos, row_slot, row_step, row_aux, row_forced, out_tokens;
   DevBuf<long long> row_sample_id;
   DevBuf<float> row_inv_temp, row_top_p, out_logprobs;

@@ -8,18 +8,6 @@
 
 static void fail(int code, const std::string& msg) { throw ApiError{code, msg}; }
 
-const char* const kKernelClassNames[KC_COUNT] = {
-    "gemm_bf16_kernel<1,2,4,false,0>", "gemm_bf16_kernel<2,2,4,true,0>", "gemm_bf16_kernel<4,2,4,true,0>",
-    "gemm_bf16_kernel<8,4,2,true,0>",  "gemm_bf16_kernel<1,2,4,false,1>", "gemm_bf16_kernel<2,2,4,true,1>",
-    "gemm_bf16_kernel<4,2,4,true,1>",  "gemm_bf16_kernel<8,4,2,true,1>", "attn_decode_kernel",
-    "attn_prefill_kernel", "row_norm_kernel", "qkv_post_kernel", "sample_kernel"};
-
-static int gemm_class(int M, bool swiglu) {
-  const int bm = gemm_rows_per_block(M);
-  const int b = bm == 16 ? 0 : bm == 32 ? 1 : bm == 64 ? 2 : 3;
-  return (swiglu ? KC_GEMM_SWIGLU_16 : KC_GEMM_F32_16) + b;
-}
-
 static void copy_d2d(void* dst, const void* src, size_t bytes, hipStream_t s) {
   if (bytes) HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
 }
@@ -195,17 +183,19 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   const size_t R = c.r_max;
   c.x.alloc(R * d);
   if (!c.simple) {
-    c.h_bf16.alloc(R * d);
-    c.q_bf16.alloc(R * c.q_dim);
-    c.attn_bf16.alloc(R * c.q_dim);
-    c.act_bf16.alloc(R * m.ffn_dim);
-    c.hn_bf16.alloc((size_t)c.logit_rows * d);
+    // activation buffers hold two planes each: hi parts, then lo parts
+    c.h_bf16.alloc(2 * R * d);
+    c.q_bf16.alloc(2 * R * c.q_dim);
+    c.attn_bf16.alloc(2 * R * c.q_dim);
+    c.act_bf16.alloc(2 * R * m.ffn_dim);
+    c.hn_bf16.alloc(2 * (size_t)c.logit_rows * d);
     c.partial_ld = std::max(c.qkv_dim, (int)d);
     c.partial_rows = std::max<long long>(R, 2048);
     c.partial.alloc((size_t)c.partial_rows * c.partial_ld);
     c.attn_max_parts = std::max(r.max_live_samples * m.n_kv_heads, 1024);
     c.attn_part_o.alloc((size_t)c.attn_max_parts * 16 * 128);
     c.attn_part_ml.alloc((size_t)c.attn_max_parts * 32);
+    c.ssq.alloc((size_t)(d / 16 + 1) * 256);
     c.seq_row0.alloc(rollout_ctx::kTempSlots);
     c.seq_len.alloc(rollout_ctx::kTempSlots);
     c.seq_slot.alloc(rollout_ctx::kTempSlots);
@@ -250,7 +240,9 @@ void engine_upload_page_table(rollout_ctx& c) {
 }
 
 // ------------------------------------------------------------------------------------------
-template <typename T>
+// T = storage type of the weights; KT = storage type of the KV cache (fp32 models: fp32,
+// bf16 models: IEEE half, see common.h)
+template <typename T, typename KT>
 static void forward_rows_simple(rollout_ctx& c, int R) {
   const rollout_model_desc& m = c.md;
   hipStream_t s = c.stream;
@@ -260,10 +252,10 @@ static void forward_rows_simple(rollout_ctx& c, int R) {
     LayerWeights& L = c.layers[l];
     launch_rmsnorm_f32(c.x.p, L.norm1.p, c.h.p, nullptr, R, d, m.rms_eps, s);
     launch_linear_simple<T>(c.h.p, d, (const T*)L.wqkv.p, c.qkv.p, c.qkv_dim, nullptr, 0, R, c.qkv_dim, d, s);
-    launch_rope_kvwrite<T>(c.qkv.p, c.cos_sin.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
-                           (T*)c.kv_pool.p, c.geom, l, R, m.n_q_heads, s);
-    launch_attention_simple<T>(c.qkv.p, c.attn.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
-                               (const T*)c.kv_pool.p, c.geom, l, R, m.n_q_heads, s);
+    launch_rope_kvwrite<KT>(c.qkv.p, c.cos_sin.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
+                            (KT*)c.kv_pool.p, c.geom, l, R, m.n_q_heads, s);
+    launch_attention_simple<KT>(c.qkv.p, c.attn.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
+                                (const KT*)c.kv_pool.p, c.geom, l, R, m.n_q_heads, s);
     launch_linear_simple<T>(c.attn.p, c.q_dim, (const T*)L.wo.p, c.x.p, d, c.x.p, d, R, d, c.q_dim, s);
     launch_rmsnorm_f32(c.x.p, L.norm2.p, c.h.p, nullptr, R, d, m.rms_eps, s);
     if (m.n_experts > 0) {
@@ -287,12 +279,19 @@ static void forward_rows_simple(rollout_ctx& c, int R) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Matrix-core path.  Per layer: QKV projection (split-K planes) -> sum + rotary + KV-page
-// write -> paged attention -> O projection (planes) -> residual + norm -> gate/up projection
-// with SwiGLU in the epilogue -> down projection (planes) -> residual + next norm.
-static int project(rollout_ctx& c, const uint16_t* a, int lda, const void* w, int M, int N, int K) {
+// Matrix-core path, many rows (prefill, teacher-forced pass, decode steps with more than 32
+// live samples).  Per layer: QKV projection -> sum + rotary + KV-page write -> paged
+// attention -> O projection -> residual + norm -> gate/up projection with SwiGLU in the
+// epilogue -> down projection -> residual + next norm.
+static double gemm_bytes(int M, int N, int K, int out_elem) {  // operands once, result once
+  return 2.0 * N * K + 2.0 * M * K + (double)out_elem * M * N;
+}
+
+static int project(rollout_ctx& c, const uint16_t* a, long long a_lo_off, int lda, const void* w, int M, int N,
+                   int K) {
   GemmArgs g{};
   g.a = a;
+  g.a_lo = a + a_lo_off;
   g.w = w;
   g.out = c.partial.p;
   g.M = M;
@@ -301,38 +300,67 @@ static int project(rollout_ctx& c, const uint16_t* a, int lda, const void* w, in
   g.lda = lda;
   g.ldo = N;
   g.split_stride = (long long)M * N;
-  const int cap = (int)std::min<long long>(32, (c.partial_rows * c.partial_ld) / ((long long)M * N));
-  const int want = gemm_pick_splits(M, N, K, std::max(1, cap));
-  // algorithmic traffic: the weight matrix and the activations once, the result once
-  c.timer.begin(gemm_class(M, false), 2.0 * N * K + 2.0 * M * K + 4.0 * M * N, 2.0 * M * N * K, c.stream);
-  const int z = launch_gemm_bf16(g, EPI_F32, want, c.stream);
+  const int cap = (int)std::min<long long>(4, (c.partial_rows * c.partial_ld) / ((long long)M * N));
+  const GemmPlan pl = gemm_plan(M, N, K, EPI_F32, std::max(1, cap));
+  c.timer.begin(pl.name, gemm_bytes(M, N, K, 4), 2.0 * M * N * K, c.stream);
+  const int z = launch_gemm_bf16(g, EPI_F32, pl, c.stream);
   c.timer.end(c.stream);
   return z;
 }
 
-static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
-  const rollout_model_desc& m = c.md;
-  hipStream_t s = c.stream;
-  const int d = m.hidden, f = m.ffn_dim;
+static void gate_up(rollout_ctx& c, LayerWeights& L, int R) {
+  const int d = c.md.hidden, f = c.md.ffn_dim;
+  GemmArgs gu{};
+  gu.a = c.h_bf16.p;
+  gu.a_lo = c.h_bf16.p + c.h_bf16.n / 2;
+  gu.w = L.w_gate_up_p.p;
+  gu.out = c.act_bf16.p;
+  gu.out_lo_offset = (long long)(c.act_bf16.n / 2);
+  gu.M = R;
+  gu.N = 2 * f;
+  gu.K = d;
+  gu.lda = d;
+  gu.ldo = f;
+  const GemmPlan pl = gemm_plan(R, 2 * f, d, EPI_SWIGLU_BF16, 1);
+  c.timer.begin(pl.name, 2.0 * 2 * f * d + 2.0 * R * d + 2.0 * R * f, 2.0 * R * 2 * f * d, c.stream);
+  launch_gemm_bf16(gu, EPI_SWIGLU_BF16, pl, c.stream);
+  c.timer.end(c.stream);
+}
+
+static void embed_and_norm(rollout_ctx& c, int R) {
   RowNormArgs rn{};
   rn.x = c.x.p;
   rn.h = c.h_bf16.p;
+  rn.h_lo_offset = (long long)(c.h_bf16.n / 2);
   rn.rows = R;
-  rn.hidden = d;
-  rn.eps = m.rms_eps;
+  rn.hidden = c.md.hidden;
+  rn.eps = c.md.rms_eps;
   rn.tokens = c.row_token.p;
   rn.embed = (const uint16_t*)c.embed.p;
   rn.gain = c.layers[0].norm1.p;
-  const double rn_bytes = (double)R * d * (4 + 4 + 2);
-  c.timer.begin(KC_ROW_NORM, rn_bytes, 0, s);
-  launch_row_norm(rn, s);
-  c.timer.end(s);
-  rn.tokens = nullptr;
-  rn.embed = nullptr;
+  c.timer.begin("row_norm_kernel", (double)R * c.md.hidden * (2 + 4 + 2), 0, c.stream);
+  launch_row_norm(rn, c.stream);
+  c.timer.end(c.stream);
+}
+
+static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
+  const rollout_model_desc& m = c.md;
+  hipStream_t s = c.stream;
+  const int d = m.hidden, f = m.ffn_dim;
+  embed_and_norm(c, R);
+  RowNormArgs rn{};
+  rn.x = c.x.p;
+  rn.h = c.h_bf16.p;
+  rn.h_lo_offset = (long long)(c.h_bf16.n / 2);
+  rn.rows = R;
+  rn.hidden = d;
+  rn.eps = m.rms_eps;
   rn.partial = c.partial.p;
+  rn.split_stride = (long long)R * d;
+  const double rn_bytes = (double)R * d * (4 + 4 + 2);
   for (int l = 0; l < m.n_layers; ++l) {
     LayerWeights& L = c.layers[l];
-    int z = project(c, c.h_bf16.p, d, L.wqkv_p.p, R, c.qkv_dim, d);
+    int z = project(c, c.h_bf16.p, (long long)(c.h_bf16.n / 2), d, L.wqkv_p.p, R, c.qkv_dim, d);
     QkvPostArgs qp{};
     qp.partial = c.partial.p;
     qp.split_stride = (long long)R * c.qkv_dim;
@@ -343,109 +371,233 @@ static void forward_rows_fast(rollout_ctx& c, int R, const SeqBatch* seqs) {
     qp.page_table = c.d_page_table.p;
     qp.max_pages = c.max_pages;
     qp.q_bf16 = c.q_bf16.p;
+    qp.q_lo_offset = (long long)(c.q_bf16.n / 2);
     qp.kv_pool = (uint16_t*)c.kv_pool.p;
     qp.geom = c.geom;
     qp.layer = l;
     qp.rows = R;
     qp.n_q_heads = m.n_q_heads;
-    c.timer.begin(KC_QKV_POST, (double)R * c.qkv_dim * (4 + 2), 0, s);
+    c.timer.begin("qkv_post_kernel", (double)R * c.qkv_dim * (4 + 2), 0, s);
     launch_qkv_post(qp, s);
     c.timer.end(s);
 
     AttnArgs at{};
     at.q = c.q_bf16.p;
+    at.q_lo_offset = (long long)(c.q_bf16.n / 2);
     at.out = c.attn_bf16.p;
+    at.out_lo_offset = (long long)(c.attn_bf16.n / 2);
     at.kv_pool = (const uint16_t*)c.kv_pool.p;
     at.geom = c.geom;
     at.page_table = c.d_page_table.p;
     at.max_pages = c.max_pages;
     at.layer = l;
     at.n_q_heads = m.n_q_heads;
+    const double kv_bytes = c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2;
     if (seqs) {
       at.seq_row0 = seqs->row0;
       at.seq_len = seqs->len;
       at.seq_slot = seqs->slot;
       at.n_seqs = seqs->n_seqs;
       at.max_seq_len = seqs->max_len;
-      c.timer.begin(KC_ATTN_PREFILL, c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2,
-                    c.attn_flops_this_call, s);
+      c.timer.begin("attn_prefill_kernel", kv_bytes + 4.0 * R * c.q_dim, c.attn_flops_this_call, s);
       launch_attention_prefill(at, s);
       c.timer.end(s);
     } else {
       at.row_pos = c.row_pos.p;
       at.row_slot = c.row_slot.p;
       at.rows = R;
-      // enough workgroups to fill the chip, at least 128 cached positions each
       const int base = R * m.n_kv_heads;
-      int n_splits = std::max(1, std::min({ceil_div(768, base), ceil_div(c.decode_max_ctx, 128),
-                                           c.attn_max_parts / base, 64}));
+      const int n_splits = std::max(1, std::min({ceil_div(512, base), ceil_div(c.decode_max_ctx, 256),
+                                                 c.attn_max_parts / base, 16}));
       at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
       at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
       at.part_o = c.attn_part_o.p;
       at.part_ml = c.attn_part_ml.p;
-      // every cached key and value of every live sample once (no prefix reuse), plus q and out
-      c.timer.begin(KC_ATTN_DECODE, c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2 + 4.0 * R * c.q_dim,
-                    c.attn_flops_this_call, s);
+      c.timer.begin("attn_decode_kernel", kv_bytes + 4.0 * R * c.q_dim, c.attn_flops_this_call, s);
       launch_attention_decode(at, s);
       c.timer.end(s);
     }
 
-    z = project(c, c.attn_bf16.p, c.q_dim, L.wo_p.p, R, d, c.q_dim);
+    z = project(c, c.attn_bf16.p, (long long)(c.attn_bf16.n / 2), c.q_dim, L.wo_p.p, R, d, c.q_dim);
     rn.splits = z;
-    rn.split_stride = (long long)R * d;
     rn.gain = L.norm2.p;
-    c.timer.begin(KC_ROW_NORM, rn_bytes + 4.0 * z * R * d, 0, s);
+    c.timer.begin("row_norm_kernel", rn_bytes + 4.0 * z * R * d, 0, s);
     launch_row_norm(rn, s);
     c.timer.end(s);
 
-    GemmArgs gu{};
-    gu.a = c.h_bf16.p;
-    gu.w = L.w_gate_up_p.p;
-    gu.out = c.act_bf16.p;
-    gu.M = R;
-    gu.N = 2 * f;
-    gu.K = d;
-    gu.lda = d;
-    gu.ldo = f;
-    c.timer.begin(gemm_class(R, true), 2.0 * 2 * f * d + 2.0 * R * d + 2.0 * R * f, 2.0 * R * 2 * f * d, s);
-    launch_gemm_bf16(gu, EPI_SWIGLU_BF16, 1, s);
-    c.timer.end(s);
+    gate_up(c, L, R);
 
-    z = project(c, c.act_bf16.p, f, L.w_down_p.p, R, d, f);
+    z = project(c, c.act_bf16.p, (long long)(c.act_bf16.n / 2), f, L.w_down_p.p, R, d, f);
     rn.splits = z;
     rn.gain = l + 1 < m.n_layers ? c.layers[l + 1].norm1.p : c.final_norm.p;
-    c.timer.begin(KC_ROW_NORM, rn_bytes + 4.0 * z * R * d, 0, s);
+    c.timer.begin("row_norm_kernel", rn_bytes + 4.0 * z * R * d, 0, s);
     launch_row_norm(rn, s);
     c.timer.end(s);
   }
+  c.h_is_final = false;
+}
+
+// ------------------------------------------------------------------------------------------
+// Matrix-core path, one decode step with at most 32 live samples: five launches per layer
+// (six when attention is split over the cached positions).
+//   QKV projection -> fused attention (rotary, KV-page write, paged attention) -> O projection
+//   with the residual add -> gate/up projection with SwiGLU -> down projection with the
+//   residual add.
+// RMSNorm is split around the launches: a residual-producing epilogue stores x * gain and
+// partial sums of squares, the consuming projection scales its output rows by
+// rsqrt(mean + eps).  The last down projection uses the final norm's gain, so the logits
+// projection reads its operand directly.
+static void stream_project(rollout_ctx& c, const DevBuf<uint16_t>& a, int lda, const void* w, int M, int N, int K,
+                           int epi, bool normalise_input, void* out, int ldo, long long out_lo_offset,
+                           const float* resid_gain) {
+  GemmArgs g{};
+  g.a = a.p;
+  g.a_lo = a.p + a.n / 2;
+  g.w = w;
+  g.out = out;
+  g.out_lo_offset = out_lo_offset;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.lda = lda;
+  g.ldo = ldo;
+  g.eps = c.md.rms_eps;
+  g.ssq_stride = 256;
+  if (normalise_input) {
+    g.rinv_ssq = c.ssq.p;
+    g.rinv_partials = c.ssq_partials;
+  }
+  const GemmPlan pl = gemm_plan(M, N, K, epi, 1);
+  double bytes = 2.0 * N * K + 2.0 * 2 * M * K;  // weights once, both activation planes once
+  if (epi == EPI_RESID) {
+    g.x = c.x.p;
+    g.gain = resid_gain;
+    g.h = c.h_bf16.p;
+    g.h_lo_offset = (long long)(c.h_bf16.n / 2);
+    g.ssq_out = c.ssq.p;
+    bytes += (double)M * N * (4 + 4 + 2 + 2);  // x read and written, two operand planes written
+  } else if (epi == EPI_SWIGLU_BF16) {
+    bytes += (double)M * (N / 2) * (2 + 2);
+  } else {
+    bytes += 4.0 * M * N;
+  }
+  c.timer.begin(pl.name, bytes, 2.0 * M * N * K, c.stream);
+  launch_gemm_bf16(g, epi, pl, c.stream);
+  c.timer.end(c.stream);
+  if (epi == EPI_RESID) c.ssq_partials = ceil_div(N >> 4, pl.nt);
+}
+
+static void forward_rows_decode(rollout_ctx& c, int R) {
+  const rollout_model_desc& m = c.md;
+  hipStream_t s = c.stream;
+  const int d = m.hidden, f = m.ffn_dim;
+  {
+    RowNormArgs rn{};
+    rn.x = c.x.p;
+    rn.h = c.h_bf16.p;
+    rn.h_lo_offset = (long long)(c.h_bf16.n / 2);
+    rn.rows = R;
+    rn.hidden = d;
+    rn.eps = m.rms_eps;
+    rn.tokens = c.row_token.p;
+    rn.embed = (const uint16_t*)c.embed.p;
+    rn.gain = c.layers[0].norm1.p;
+    rn.ssq_out = c.ssq.p;
+    c.timer.begin("row_norm_kernel", (double)R * d * (2 + 4 + 2 + 2), 0, s);
+    launch_row_norm(rn, s);
+    c.timer.end(s);
+    c.ssq_partials = 1;
+  }
+  for (int l = 0; l < m.n_layers; ++l) {
+    LayerWeights& L = c.layers[l];
+    stream_project(c, c.h_bf16, d, L.wqkv_p.p, R, c.qkv_dim, d, EPI_F32, true, c.partial.p, c.qkv_dim, 0, nullptr);
+
+    AttnArgs at{};
+    at.out = c.attn_bf16.p;
+    at.out_lo_offset = (long long)(c.attn_bf16.n / 2);
+    at.kv_pool = (const uint16_t*)c.kv_pool.p;
+    at.kv_pool_w = (uint16_t*)c.kv_pool.p;
+    at.geom = c.geom;
+    at.page_table = c.d_page_table.p;
+    at.max_pages = c.max_pages;
+    at.layer = l;
+    at.n_q_heads = m.n_q_heads;
+    at.row_pos = c.row_pos.p;
+    at.row_slot = c.row_slot.p;
+    at.rows = R;
+    at.qkv_raw = c.partial.p;
+    at.cos_sin = c.cos_sin.p;
+    // enough workgroups to fill the chip, at least 256 cached positions each, at most 16 splits
+    const int base = R * m.n_kv_heads;
+    const int n_splits = std::max(1, std::min({ceil_div(512, base), ceil_div(c.decode_max_ctx, 256),
+                                               c.attn_max_parts / base, 16}));
+    at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
+    at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
+    at.part_o = c.attn_part_o.p;
+    at.part_ml = c.attn_part_ml.p;
+    // every cached key and value of every live sample once (no prefix reuse), q in, out
+    c.timer.begin("attn_decode_fused_kernel",
+                  c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2 + (double)R * (4.0 * c.qkv_dim + 4.0 * c.q_dim),
+                  c.attn_flops_this_call, s);
+    launch_attention_decode_fused(at, s);
+    c.timer.end(s);
+
+    stream_project(c, c.attn_bf16, c.q_dim, L.wo_p.p, R, d, c.q_dim, EPI_RESID, false, nullptr, d, 0, L.norm2.p);
+    stream_project(c, c.h_bf16, d, L.w_gate_up_p.p, R, 2 * f, d, EPI_SWIGLU_BF16, true, c.act_bf16.p, f,
+                   (long long)(c.act_bf16.n / 2), nullptr);
+    stream_project(c, c.act_bf16, f, L.w_down_p.p, R, d, f, EPI_RESID, false, nullptr, d, 0,
+                   l + 1 < m.n_layers ? c.layers[l + 1].norm1.p : c.final_norm.p);
+  }
+  c.h_is_final = true;
 }
 
 void engine_forward_rows(rollout_ctx& c, int rows, const SeqBatch* seqs) {
   if (rows < 1) return;
   c.last_route_rows = rows;
-  if (!c.simple)
-    forward_rows_fast(c, rows, seqs);
-  else if (c.md.dtype == ROLLOUT_DTYPE_F32)
-    forward_rows_simple<float>(c, rows);
-  else
-    forward_rows_simple<bf16_t>(c, rows);
+  if (!c.simple) {
+    if (!seqs && rows <= 32)
+      forward_rows_decode(c, rows);
+    else
+      forward_rows_tiled(c, rows, seqs);
+  } else if (c.md.dtype == ROLLOUT_DTYPE_F32) {
+    forward_rows_simple<float, float>(c, rows);
+  } else {
+    forward_rows_simple<bf16_t, f16_t>(c, rows);
+  }
 }
 
 void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, float* out) {
   if (n < 1) return;
   const int d = c.md.hidden;
   if (!c.simple) {
-    RowNormArgs rn{};
-    rn.x = c.x.p + (size_t)first * d;
-    rn.h = c.hn_bf16.p;
-    rn.gain = c.final_norm.p;
-    rn.rows_index = rows_index;
-    rn.rows = n;
-    rn.hidden = d;
-    rn.eps = c.md.rms_eps;
-    launch_row_norm(rn, c.stream);
+    const uint16_t* hn = c.hn_bf16.p;
+    long long hn_lo = (long long)(c.hn_bf16.n / 2);
+    if (c.h_is_final && !rows_index) {
+      hn = c.h_bf16.p + (size_t)first * d;  // the fused decode path already applied the final norm
+      hn_lo = (long long)(c.h_bf16.n / 2);
+    } else {
+      RowNormArgs rn{};
+      rn.x = c.x.p + (size_t)first * d;
+      rn.h = c.hn_bf16.p;
+      rn.h_lo_offset = hn_lo;
+      rn.gain = c.final_norm.p;
+      rn.rows_index = rows_index;
+      rn.rows = n;
+      rn.hidden = d;
+      rn.eps = c.md.rms_eps;
+      c.timer.begin("row_norm_kernel", (double)n * d * (4 + 2), 0, c.stream);
+      launch_row_norm(rn, c.stream);
+      c.timer.end(c.stream);
+    }
     GemmArgs g{};
-    g.a = c.hn_bf16.p;
+    g.a = hn;
+    g.a_lo = hn + hn_lo;
+    if (c.h_is_final && !rows_index) {  // h holds x * gain; the rsqrt factor rides in the epilogue
+      g.rinv_ssq = c.ssq.p;
+      g.rinv_partials = c.ssq_partials;
+      g.ssq_stride = 256;
+      g.eps = c.md.rms_eps;
+    }
     g.w = c.lm_head_p.p;
     g.out = out;
     g.M = n;
@@ -453,8 +605,9 @@ void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, floa
     g.K = d;
     g.lda = d;
     g.ldo = c.md.vocab;
-    c.timer.begin(gemm_class(n, false), 2.0 * g.N * d + 2.0 * n * d + 4.0 * n * g.N, 2.0 * n * g.N * d, c.stream);
-    launch_gemm_bf16(g, EPI_F32, 1, c.stream);
+    const GemmPlan pl = gemm_plan(n, g.N, d, EPI_F32, 1);
+    c.timer.begin(pl.name, gemm_bytes(n, g.N, d, 4), 2.0 * n * g.N * d, c.stream);
+    launch_gemm_bf16(g, EPI_F32, pl, c.stream);
     c.timer.end(c.stream);
     return;
   }

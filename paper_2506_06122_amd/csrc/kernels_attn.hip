@@ -1,10 +1,12 @@
-// Paged grouped-query attention on the matrix cores, head_dim 128, bf16 KV pages in the
-// KV_MATRIX element order (common.h).
+// Paged grouped-query attention on the matrix cores, head_dim 128, half-precision KV pages in
+// the KV_MATRIX element order (common.h).  Queries and probabilities enter the matrix
+// instructions as hi + lo half-precision pairs, so keys and values are the only rounded
+// operands; the result leaves as hi + lo bf16 planes for the output projection.
 //
 // Decoding is memory-bound (paper section 2.1) and its attention streams every cached key
 // and value once per step, so the kernels are built around that stream: each wavefront
 // takes 32 cached positions at a time as sixteen contiguous 1 KiB loads (8 key fragments,
-// 8 value fragments), computes transposed scores S^T = K q^T with 16x16x32 bf16 matrix
+// 8 value fragments), computes transposed scores S^T = K q^T with 16x16x32 f16 matrix
 // instructions (columns = the query rows that share the KV head), runs the online softmax
 // on the fragment (per-column max and sum are a register reduction plus two cross-lane
 // steps), and feeds the probabilities straight back as the B operand of O^T += V^T P^T.
@@ -18,35 +20,38 @@
 //             causal limit per column.
 #include "kernels_fast.h"
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 union Frag {
   uint4 u;
-  bf16x8 v;
+  f16x8 v;
   uint16_t h[8];
 };
+#define MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0)
 
 #define DH 128
 #define GROUP_U4 512  // uint4 per 32-position group of one K (or V) block: 32 * 128 * 2 / 16
+// Probabilities are scaled by 2^10 before they become half-precision operands, so that the
+// small probabilities of a long, flat attention row stay in the normal range; the output
+// accumulators carry the same factor until the final normalisation.
+#define P_SCALE 1024.0f
 
-// One 32-position group against this lane's query column.  limit = last visible position
-// of the column.  m, l in log2 units; o = unnormalised output^T fragments.
-__device__ inline void attend_group(const uint4* __restrict__ kblk, const uint4* __restrict__ vblk,
-                                    const Frag (&q)[4], int tok0, int limit, float scale_log2, float& m,
-                                    float& l, f32x4 (&o)[8], int lane) {
+// One 32-position group (fragments already in registers) against this lane's query column.
+// limit = last visible position of the column.  m, l in log2 units; o = unnormalised
+// output^T fragments.
+__device__ inline void attend_frags(const Frag (&k)[2][4], const Frag (&v)[8], const Frag (&q)[8], int tok0,
+                                    int limit, float scale_log2, float& m, float& l, f32x4 (&o)[8], int lane) {
   const int g = lane >> 4;
-  Frag k[2][4], v[8];
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) k[t][ks].u = kblk[(t * 4 + ks) * 64 + lane];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) v[j].u = vblk[j * 64 + lane];
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {  // q[4..7] = lo parts of the query, q[0..3] = hi parts
+    s0 = MFMA16(k[0][ks].v, q[4 + ks].v, s0);
+    s1 = MFMA16(k[1][ks].v, q[4 + ks].v, s1);
+  }
+#pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[0][ks].v, q[ks].v, s0, 0, 0, 0);
-    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[1][ks].v, q[ks].v, s1, 0, 0, 0);
+    s0 = MFMA16(k[0][ks].v, q[ks].v, s0);
+    s1 = MFMA16(k[1][ks].v, q[ks].v, s1);
   }
   float sc[8];
   const int tbase = tok0 + 4 * g;
@@ -63,12 +68,12 @@ __device__ inline void attend_group(const uint4* __restrict__ kblk, const uint4*
   const float m_new = fmaxf(m, mx);
   const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
   float ps = 0.f;
-  Frag pb;
+  Frag pb, pl;  // probabilities as hi + lo half-precision parts
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     float p = exp2f(sc[e] - m_use);
     ps += p;
-    pb.h[e] = f32_to_bf16(p).bits;
+    split_f16(p * P_SCALE, pb.h[e], pl.h[e]);
   }
   ps += __shfl_xor(ps, 16, WAVE);
   ps += __shfl_xor(ps, 32, WAVE);
@@ -81,8 +86,23 @@ __device__ inline void attend_group(const uint4* __restrict__ kblk, const uint4*
     o[j][1] *= alpha;
     o[j][2] *= alpha;
     o[j][3] *= alpha;
-    o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[j].v, pb.v, o[j], 0, 0, 0);
+    o[j] = MFMA16(v[j].v, pl.v, o[j]);
+    o[j] = MFMA16(v[j].v, pb.v, o[j]);
   }
+}
+
+// The same, with the group's key and value fragments streamed from a KV page.
+__device__ inline void attend_group(const uint4* __restrict__ kblk, const uint4* __restrict__ vblk,
+                                    const Frag (&q)[8], int tok0, int limit, float scale_log2, float& m,
+                                    float& l, f32x4 (&o)[8], int lane) {
+  Frag k[2][4], v[8];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) k[t][ks].u = kblk[(t * 4 + ks) * 64 + lane];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j].u = vblk[j * 64 + lane];
+  attend_frags(k, v, q, tok0, limit, scale_log2, m, l, o, lane);
 }
 
 __device__ inline const uint4* group_block(const AttnArgs& a, int slot, int kv_head, int tok0, int is_v) {
@@ -91,9 +111,21 @@ __device__ inline const uint4* group_block(const AttnArgs& a, int slot, int kv_h
   return (const uint4*)(a.kv_pool + kv_block_base(a.geom, a.layer, page, kv_head, is_v)) + gip * GROUP_U4;
 }
 
-__device__ inline uint2 pack4_bf16(float a, float b, float c, float d) {
-  return make_uint2((uint32_t)f32_to_bf16(a).bits | ((uint32_t)f32_to_bf16(b).bits << 16),
-                    (uint32_t)f32_to_bf16(c).bits | ((uint32_t)f32_to_bf16(d).bits << 16));
+// four consecutive values as hi + lo bf16 parts into the two planes of an activation buffer
+__device__ inline void store4_split(uint16_t* dst, long long lo_offset, float a, float b, float c, float d) {
+  uint16_t hi[4], lo[4];
+  split_bf16(a, hi[0], lo[0]);
+  split_bf16(b, hi[1], lo[1]);
+  split_bf16(c, hi[2], lo[2]);
+  split_bf16(d, hi[3], lo[3]);
+  *(uint2*)dst = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+  *(uint2*)(dst + lo_offset) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
+}
+__device__ inline void store1_split(uint16_t* dst, long long lo_offset, float a) {
+  uint16_t hi, lo;
+  split_bf16(a, hi, lo);
+  dst[0] = hi;
+  dst[lo_offset] = lo;
 }
 
 // ------------------------------------------------------------------------------ decode
@@ -111,11 +143,16 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
   const int t_end = min(ctx, t_begin + a.split_tokens);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
 
-  Frag q[4];
+  Frag q[8];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
     q[ks].u = make_uint4(0, 0, 0, 0);
-    if (c < G) q[ks].u = *(const uint4*)(a.q + ((long long)b * a.n_q_heads + kvh * G + c) * DH + ks * 32 + g * 8);
+    q[4 + ks].u = make_uint4(0, 0, 0, 0);
+    if (c < G) {
+      const uint16_t* src = a.q + ((long long)b * a.n_q_heads + kvh * G + c) * DH + ks * 32 + g * 8;
+      q[ks].u = *(const uint4*)src;
+      q[4 + ks].u = *(const uint4*)(src + a.q_lo_offset);
+    }
   }
   float m = -INFINITY, l = 0.f;
   f32x4 o[8];
@@ -144,7 +181,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
     const float acc = o_s[0][e] + o_s[1][e] + o_s[2][e] + o_s[3][e];
     if (a.n_splits == 1) {
       const float L = l_s[0][col] + l_s[1][col] + l_s[2][col] + l_s[3][col];
-      a.out[((long long)b * a.n_q_heads + kvh * G + col) * DH + dim] = f32_to_bf16(acc / L).bits;
+      store1_split(a.out + ((long long)b * a.n_q_heads + kvh * G + col) * DH + dim, a.out_lo_offset, acc / (L * P_SCALE));
     } else {
       a.part_o[part * (16 * DH) + e] = acc;
     }
@@ -172,7 +209,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
       L += a.part_ml[(part0 + s) * 32 + 16 + col] * w;
       acc += a.part_o[(part0 + s) * (16 * DH) + e] * w;
     }
-    a.out[((long long)b * a.n_q_heads + kvh * G) * DH + e] = f32_to_bf16(acc / L).bits;
+    store1_split(a.out + ((long long)b * a.n_q_heads + kvh * G) * DH + e, a.out_lo_offset, acc / (L * P_SCALE));
   }
 }
 
@@ -180,6 +217,188 @@ void launch_attention_decode(const AttnArgs& a, hipStream_t s) {
   if (!a.rows) return;
   attn_decode_kernel<<<dim3(a.n_splits, a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
   if (a.n_splits > 1) attn_merge_kernel<<<dim3(a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
+}
+
+// ------------------------------------------------------------------------------ fused decode
+// One launch per layer for a decode step: sums nothing and stores nothing in between.
+// Prologue: rotary embedding of this sample's G query rows (kept in LDS as hi + lo half-precision parts) and, in the
+// workgroup whose split holds the new position, of the new key; that key and the new value
+// are written to the sample's page and also kept in LDS.  Main loop: the cached positions
+// 0..pos-1 from the pages.  The new position itself is attended from LDS as a one-token
+// group, so nothing written in this launch is read back from memory.  With several KV
+// splits per (sample, KV head) the partial results go to attn_merge_fused_kernel.
+__global__ __launch_bounds__(256) void attn_decode_fused_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t q_s[2][16][DH];  // hi parts, lo parts
+  __shared__ __attribute__((aligned(16))) uint16_t kv_s[2][DH];
+  __shared__ float m_s[4][16];
+  __shared__ float l_s[4][16];
+  __shared__ float o_s[4][16 * DH];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int n_kv = a.geom.n_kv_heads;
+  const int G = a.n_q_heads / n_kv;
+  const int pos = a.row_pos[b];
+  const int used = pos / a.split_tokens + 1;  // splits that hold at least the new position
+  if (split >= used) return;
+  const bool owner = split == used - 1;
+  const int slot = a.row_slot[b];
+  const int q_dim = a.n_q_heads * DH, kv_dim = n_kv * DH;
+  const float* row = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim);
+  const float* cs = a.cos_sin + (long long)pos * DH;
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+
+  for (int idx = tid; idx < 16 * (DH / 2); idx += 256) {
+    const int hc = idx >> 6, i = idx & 63;
+    float u = 0.f, w = 0.f;
+    if (hc < G) {
+      const float* src = row + (kvh * G + hc) * DH;
+      const float cc = cs[2 * i], sn = cs[2 * i + 1];
+      const float x0 = src[i], x1 = src[i + 64];
+      u = x0 * cc - x1 * sn;
+      w = x1 * cc + x0 * sn;
+    }
+    split_f16(u, q_s[0][hc][i], q_s[1][hc][i]);
+    split_f16(w, q_s[0][hc][i + 64], q_s[1][hc][i + 64]);
+  }
+  if (owner && tid < 128) {
+    const int page = a.page_table[(long long)slot * a.max_pages + pos / a.geom.page_tokens];
+    const int tok = pos % a.geom.page_tokens;
+    const int i = tid & 63;
+    if (tid < 64) {
+      const float* src = row + q_dim + kvh * DH;
+      const float cc = cs[2 * i], sn = cs[2 * i + 1];
+      const float x0 = src[i], x1 = src[i + 64];
+      const uint16_t k0 = f32_to_f16(x0 * cc - x1 * sn).bits, k1 = f32_to_f16(x1 * cc + x0 * sn).bits;
+      kv_s[0][i] = k0;
+      kv_s[0][i + 64] = k1;
+      uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, page, kvh, 0);
+      dst[kv_k_offset(a.geom, tok, i)] = k0;
+      dst[kv_k_offset(a.geom, tok, i + 64)] = k1;
+    } else {
+      const float* src = row + q_dim + kv_dim + kvh * DH;
+      const uint16_t v0 = f32_to_f16(src[i]).bits, v1 = f32_to_f16(src[i + 64]).bits;
+      kv_s[1][i] = v0;
+      kv_s[1][i + 64] = v1;
+      uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, page, kvh, 1);
+      dst[kv_v_offset(a.geom, tok, i)] = v0;
+      dst[kv_v_offset(a.geom, tok, i + 64)] = v1;
+    }
+  }
+  __syncthreads();
+
+  Frag q[8];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    q[ks].u = *(const uint4*)&q_s[0][c][ks * 32 + g * 8];
+    q[4 + ks].u = *(const uint4*)&q_s[1][c][ks * 32 + g * 8];
+  }
+  float m = -INFINITY, l = 0.f;
+  f32x4 o[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int t_begin = split * a.split_tokens;
+  const int t_end = min(pos, t_begin + a.split_tokens);  // cached positions only
+  for (int tok0 = t_begin + wave * 32; tok0 < t_end; tok0 += 128)
+    attend_group(group_block(a, slot, kvh, tok0, 0), group_block(a, slot, kvh, tok0, 1), q, tok0, pos - 1,
+                 scale_log2, m, l, o, lane);
+  if (owner && wave == 3) {  // the new position, from LDS: token 0 of a group that starts at pos
+    Frag k[2][4], v[8];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      k[0][ks].u = make_uint4(0, 0, 0, 0);
+      k[1][ks].u = make_uint4(0, 0, 0, 0);
+      if (c == 0) k[0][ks].u = *(const uint4*)&kv_s[0][ks * 32 + g * 8];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      v[j].u = make_uint4(0, 0, 0, 0);
+      if (g == 0) v[j].h[0] = kv_s[1][16 * j + c];
+    }
+    attend_frags(k, v, q, pos, pos, scale_log2, m, l, o, lane);
+  }
+
+  // merge the 4 wavefronts: common max, rescale, sum
+  if (g == 0) m_s[wave][c] = m;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(m_s[0][c], m_s[1][c]), fmaxf(m_s[2][c], m_s[3][c]));
+  const float M_use = (M == -INFINITY) ? 0.f : M;
+  const float w = exp2f(m - M_use);
+  if (g == 0) l_s[wave][c] = l * w;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o_s[wave][c * DH + 16 * j + 4 * g + i] = o[j][i] * w;
+  __syncthreads();
+  const long long pair = (long long)b * n_kv + kvh;
+  const long long part = pair * a.n_splits + split;
+  uint16_t* out = a.out + ((long long)b * a.n_q_heads + kvh * G) * DH;
+  for (int e = tid; e < G * DH; e += 256) {
+    const int col = e >> 7;
+    const float acc = o_s[0][e] + o_s[1][e] + o_s[2][e] + o_s[3][e];
+    if (used == 1) {
+      const float L = l_s[0][col] + l_s[1][col] + l_s[2][col] + l_s[3][col];
+      store1_split(out + e, a.out_lo_offset, acc / (L * P_SCALE));
+    } else {
+      a.part_o[part * (16 * DH) + e] = acc;
+    }
+  }
+  if (used > 1 && tid < 16) {
+    a.part_ml[part * 32 + tid] = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
+    a.part_ml[part * 32 + 16 + tid] = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
+  }
+}
+
+// Merge of the KV splits of one (sample, KV head), at most 16 of them: a launch of its own,
+// because a launch boundary is the cheapest way to publish results between workgroups here.
+__global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
+  __shared__ float w_s[16][16];  // [split][column] weight 2^(m_s - M) / (L 2^10)
+  const int tid = threadIdx.x, kvh = blockIdx.x, b = blockIdx.y;
+  const int n_kv = a.geom.n_kv_heads;
+  const int G = a.n_q_heads / n_kv;
+  const int used = a.row_pos[b] / a.split_tokens + 1;
+  if (used == 1) return;  // the attention kernel wrote the result itself
+  const long long part0 = ((long long)b * n_kv + kvh) * a.n_splits;
+  {
+    const int s = tid >> 4, col = tid & 15;  // 256 threads = 16 splits x 16 columns
+    const float m = s < used ? a.part_ml[(part0 + s) * 32 + col] : -INFINITY;
+    const float l = s < used ? a.part_ml[(part0 + s) * 32 + 16 + col] : 0.f;
+    w_s[s][col] = m;
+    __syncthreads();
+    float M = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) M = fmaxf(M, w_s[q][col]);
+    const float w = exp2f(m - M);  // 0 for unused splits
+    __syncthreads();
+    w_s[s][col] = w;
+    // total weight of the column, same order in every thread
+    __shared__ float lw_s[16][16];
+    lw_s[s][col] = l * w;
+    __syncthreads();
+    float L = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) L += lw_s[q][col];
+    __syncthreads();
+    w_s[s][col] = w / (L * P_SCALE);
+    __syncthreads();
+  }
+  uint16_t* out = a.out + ((long long)b * a.n_q_heads + kvh * G) * DH;
+  for (int e = tid; e < G * DH; e += 256) {
+    const int col = e >> 7;
+    float v[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) v[s] = s < used ? a.part_o[(part0 + s) * (16 * DH) + e] : 0.f;
+    float acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) acc += v[s] * w_s[s][col];
+    store1_split(out + e, a.out_lo_offset, acc);
+  }
+}
+
+void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s) {
+  if (!a.rows) return;
+  attn_decode_fused_kernel<<<dim3(a.n_splits, a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
+  if (a.n_splits > 1) attn_merge_fused_kernel<<<dim3(a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
 }
 
 // ------------------------------------------------------------------------------ prefill
@@ -194,11 +413,16 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
   const int kvh = head / (a.n_q_heads / a.geom.n_kv_heads);
   const int pos = q0 + c;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  Frag q[4];
+  Frag q[8];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
     q[ks].u = make_uint4(0, 0, 0, 0);
-    if (pos < len) q[ks].u = *(const uint4*)(a.q + ((long long)(row0 + pos) * a.n_q_heads + head) * DH + ks * 32 + g * 8);
+    q[4 + ks].u = make_uint4(0, 0, 0, 0);
+    if (pos < len) {
+      const uint16_t* src = a.q + ((long long)(row0 + pos) * a.n_q_heads + head) * DH + ks * 32 + g * 8;
+      q[ks].u = *(const uint4*)src;
+      q[4 + ks].u = *(const uint4*)(src + a.q_lo_offset);
+    }
   }
   float m = -INFINITY, l = 0.f;
   f32x4 o[8];
@@ -210,10 +434,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
                  m, l, o, lane);
   if (pos < len) {
     uint16_t* dst = a.out + ((long long)(row0 + pos) * a.n_q_heads + head) * DH + 4 * g;
-    const float inv = 1.0f / l;
+    const float inv = 1.0f / (l * P_SCALE);
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      *(uint2*)(dst + 16 * j) = pack4_bf16(o[j][0] * inv, o[j][1] * inv, o[j][2] * inv, o[j][3] * inv);
+      store4_split(dst + 16 * j, a.out_lo_offset, o[j][0] * inv, o[j][1] * inv, o[j][2] * inv, o[j][3] * inv);
   }
 }
 

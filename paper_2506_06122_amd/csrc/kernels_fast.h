@@ -5,16 +5,37 @@
 
 #include "common.h"
 
-enum { EPI_F32 = 0, EPI_SWIGLU_BF16 = 1 };
+// Epilogues of the projection kernels:
+//   EPI_F32          out[m][n] fp32 (split-K planes allowed)
+//   EPI_SWIGLU_BF16  column tiles alternate gate, up: act[m][f] = silu(gate) * up as bf16 hi/lo
+//   EPI_RESID        stream kernel only: x[m][n] += result (fp32, in place); h = x * gain as
+//                    bf16 hi/lo planes (the next projection's operand, not yet normalised);
+//                    ssq_out[workgroup column][m] = sum of x^2 over the workgroup's columns
+// Any stream-kernel epilogue first scales row m by rsqrt(sum_p rinv_ssq[p][m] / K + eps) when
+// rinv_ssq is given: the second half of the RMSNorm of the projection's input.
+enum { EPI_F32 = 0, EPI_SWIGLU_BF16 = 1, EPI_RESID = 2 };
 
 struct GemmArgs {
-  const void* a;     // bf16 [rows][K], row stride lda
+  const void* a;     // bf16 [rows][K], row stride lda: hi parts of the activations
+  const void* a_lo;  // same shape: lo parts (value = hi + lo)
   const void* w;     // packed bf16 weight, N/16 x K/32 fragments of 1 KiB
   void* out;         // EPI_F32: float [splits][M][ldo]; EPI_SWIGLU_BF16: bf16 [M][ldo] (ldo = N/2)
   int M, N, K, lda, ldo;
+  long long out_lo_offset = 0;  // EPI_SWIGLU_BF16: elements from the hi plane of `out` to its lo plane
   long long split_stride;  // floats between split planes (EPI_F32)
   int k_tiles_per_split;   // filled by the launcher
-  // grouped launch (mixture of experts): row block y works on rows
+  // input normalisation (stream kernel)
+  const float* rinv_ssq = nullptr;  // [rinv_partials][ssq_stride] partial sums of squares of the input rows
+  int rinv_partials = 0;
+  int ssq_stride = 0;
+  float eps = 0.f;
+  // EPI_RESID
+  float* x = nullptr;            // [M][N] residual stream, updated in place
+  const float* gain = nullptr;   // [N] gain of the RMSNorm that follows
+  uint16_t* h = nullptr;         // bf16 [M][N], hi plane
+  long long h_lo_offset = 0;     // elements from the hi plane of h to its lo plane
+  float* ssq_out = nullptr;      // [grid columns][ssq_stride]
+  // grouped launch (mixture of experts, tile kernel): row block y works on rows
   // [block_row_begin[y], block_row_end[y]) of the expert-sorted order with the weights of
   // group_of_block[y]; row_map maps a sorted row to its source row in `a`.
   const int* group_of_block = nullptr;
@@ -23,13 +44,16 @@ struct GemmArgs {
   const int* row_map = nullptr;
   long long group_stride16 = 0;  // 16-byte units between consecutive groups' packed weights
   int n_row_blocks = 0;
-  int rows_per_block = 0;        // 0 = pick from M
 };
 
-int gemm_rows_per_block(int M);
-int gemm_pick_splits(int M, int N, int K, int max_splits);
-// returns the number of split planes actually written (<= splits)
-int launch_gemm_bf16(GemmArgs a, int epi, int splits, hipStream_t s);
+// How one projection is launched: kind 0 = gemm_stream_kernel (rows <= 256), 1 = gemm_tile_kernel.
+struct GemmPlan {
+  int kind, mt, nt, nw, splits;
+  const char* name;  // kernel name as a profiler shows it (without the argument list)
+};
+GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits);
+// returns the number of split planes written (EPI_F32; <= plan.splits)
+int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& plan, hipStream_t s);
 void launch_pack_weight(const void* src, void* dst, int N, int K, int tile_offset, int tile_stride, hipStream_t s);
 
 // x[r] (+= sum of `splits` partial planes) ; h[r] = bf16(x[r] * gain * rsqrt(mean(x[r]^2) + eps)).
@@ -41,7 +65,9 @@ struct RowNormArgs {
   long long split_stride;
   int splits;
   const float* gain;
-  uint16_t* h;              // bf16 [rows][hidden]
+  uint16_t* h;              // bf16 [rows][hidden], hi plane
+  long long h_lo_offset;    // elements from the hi plane to the lo plane
+  float* ssq_out;           // when set: h = x * gain without the rsqrt factor, ssq_out[r] = sum x[r]^2
   const int* tokens;
   const uint16_t* embed;
   const int* rows_index;
@@ -60,7 +86,8 @@ struct QkvPostArgs {
   const float* cos_sin;
   const int *row_pos, *row_slot, *page_table;
   int max_pages;
-  uint16_t* q_bf16;
+  uint16_t* q_bf16;         // hi plane [rows][q_dim]
+  long long q_lo_offset;    // elements to the lo plane
   float* q_f32;
   int q_f32_ld;
   uint16_t* kv_pool;
@@ -73,8 +100,10 @@ void launch_f32_to_bf16(const float* src, uint16_t* dst, long long n, hipStream_
 
 // Paged grouped-query attention on the matrix cores (KV_MATRIX pool, head_dim 128).
 struct AttnArgs {
-  const uint16_t* q;        // bf16 [rows][n_q_heads][128], rotary applied
-  uint16_t* out;            // bf16 [rows][n_q_heads][128]
+  const uint16_t* q;        // bf16 hi plane [rows][n_q_heads][128], rotary applied (unfused kernels)
+  long long q_lo_offset;    // elements to its lo plane
+  uint16_t* out;            // bf16 hi plane [rows][n_q_heads][128]
+  long long out_lo_offset;  // elements to its lo plane
   const uint16_t* kv_pool;
   KvGeom geom;
   const int* page_table;
@@ -85,9 +114,14 @@ struct AttnArgs {
   int n_splits, split_tokens;      // KV range per workgroup (multiple of 128)
   float* part_o;                   // [rows][n_kv_heads][n_splits][16][128]
   float* part_ml;                  // [rows][n_kv_heads][n_splits][2][16]
+  // fused decode (rotary + KV write + attention + split merge in one launch)
+  const float* qkv_raw;            // fp32 [rows][(n_q_heads + 2 n_kv_heads) * 128], projections before rotary
+  const float* cos_sin;
+  uint16_t* kv_pool_w;
   // prefill: packed sequences
   const int *seq_row0, *seq_len, *seq_slot;
   int n_seqs, max_seq_len;
 };
 void launch_attention_decode(const AttnArgs& a, hipStream_t s);
 void launch_attention_prefill(const AttnArgs& a, hipStream_t s);
+void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s);

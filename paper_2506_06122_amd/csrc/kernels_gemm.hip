@@ -5,14 +5,35 @@
 // at load time, into the fragment order of the 16x16x32 bf16 matrix instruction
 //     packed[n_tile][k_tile][lane][8],  lane = (k % 32 / 8) * 16 + n % 16
 // so that a wavefront reads each 16-column x 32-deep weight fragment as one contiguous
-// 1 KiB load straight into registers (no LDS round trip for the operand that is read once).
-// Activations (small, re-read by every workgroup, L2-resident) are staged through LDS in
-// the same fragment order.  The instruction computes D = W_frag . A_frag^T, i.e. a tile of
+// 1 KiB load straight into registers, and a whole row of fragments [n_tile][*] is one
+// contiguous stream.  The instruction computes D = W_frag . A_frag^T, i.e. a tile of
 // out^T, so each lane ends up with four consecutive output columns of one row.
 //
-// A workgroup of 4 wavefronts covers MT*16 rows x 4*NT*16 columns over one K split;
-// split-K partials go to separate fp32 planes that the consumer kernel sums in a fixed
-// order (deterministic).
+// Activations keep near-fp32 precision through the bf16 instruction: every activation value v
+// travels as two bf16 numbers, hi = bf16(v) and lo = bf16(v - hi), in two planes of the same
+// shape, and each weight fragment is multiplied with both (the weights themselves are bf16
+// exactly, so nothing else is rounded).  That doubles the matrix instructions, which the
+// memory-bound decode step does not notice.
+//
+// Two kernels:
+//   gemm_stream_kernel  (rows <= 32, decoding): the NW wavefronts of a workgroup share NT
+//       column tiles and interleave over the K range in chunks of KU fragments, so one
+//       workgroup walks one contiguous weight stream with NW x KU x NT KiB in flight; the
+//       partial accumulators meet in LDS.  Activations come straight from L2.  Narrow
+//       outputs (few column tiles) use wide workgroups (16 wavefronts) rather than split-K
+//       planes, so every output element is complete inside one workgroup and the epilogue
+//       can carry the neighbouring element-wise work:
+//         - RMSNorm is split in two.  The producer of the residual stream (EPI_RESID) adds
+//           its result to x, stores x * gain as the next projection's operand and one
+//           partial sum of squares per (workgroup, row); the consumer sums those partials
+//           in a fixed order and scales its output rows by rsqrt(mean + eps) - a row scale
+//           commutes with the projection.  No workgroup ever waits for another.
+//         - SwiGLU on interleaved gate/up column tiles (EPI_SWIGLU_BF16).
+//   gemm_tile_kernel    (more than 32 rows: large decode batches, prefill, teacher-forced
+//       pass): up to 128 x 256 output tile per workgroup, activations staged through LDS in
+//       fragment order and double-buffered, weights still read directly.
+#include <cstdio>
+
 #include "kernels_fast.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -25,9 +46,173 @@ union Frag {
 
 __device__ inline float silu_f(float a) { return a / (1.0f + __expf(-a)); }
 
-template <int MT, int NT, int KC, bool A_LDS, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
-  __shared__ uint4 a_lds[A_LDS ? KC * MT * 64 : 1];
+__device__ inline uint2 pack4(const uint16_t (&h)[4]) {
+  return make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+}
+
+// D[n][m] tile(s) -> memory.  lane (r, g) holds rows n = 4g..4g+3 of a tile at column m = r.
+template <int EPI>
+__device__ inline void store_unit(const GemmArgs& p, int m, int nt, const f32x4& t0, const f32x4& t1, int g,
+                                  int z, bool two) {
+  if (EPI == EPI_F32) {
+    float* out = (float*)p.out + (long long)z * p.split_stride + (long long)m * p.ldo;
+    *(float4*)(out + nt * 16 + g * 4) = make_float4(t0[0], t0[1], t0[2], t0[3]);
+    if (two) *(float4*)(out + (nt + 1) * 16 + g * 4) = make_float4(t1[0], t1[1], t1[2], t1[3]);
+  } else {  // EPI_SWIGLU_BF16: tile nt = gate, nt + 1 = up; act[m][f] = silu(gate) * up
+    uint16_t* out = (uint16_t*)p.out + (long long)m * p.ldo + (nt >> 1) * 16 + g * 4;
+    uint16_t h[4], lo[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split_bf16(silu_f(t0[e]) * t1[e], h[e], lo[e]);
+    *(uint2*)out = pack4(h);
+    *(uint2*)(out + p.out_lo_offset) = pack4(lo);
+  }
+}
+
+template <int MT, int NT, int KU, int NW, int EPI>
+__global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
+  static_assert(EPI != EPI_RESID || NT <= 2, "one unit must cover a workgroup's columns");
+  __shared__ float4 red[NW * MT * NT * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int n_tiles = p.N >> 4, k_tiles = p.K >> 5;
+  const int nt0 = blockIdx.x * NT;
+  const int m0 = blockIdx.y * (MT * 16);
+  const int kt_begin = blockIdx.z * p.k_tiles_per_split;
+  const int kt_end = min(k_tiles, kt_begin + p.k_tiles_per_split);
+  const uint4* wp = (const uint4*)p.w;
+  const uint16_t* a_base = (const uint16_t*)p.a;
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // activation row pointers of this lane (row m0 + 16 i + r), or null past the last row
+  const uint16_t* a_row[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int m = m0 + i * 16 + r;
+    a_row[i] = m < p.M ? a_base + (long long)m * p.lda + g * 8 : nullptr;
+  }
+  const long long lo_off = (const uint16_t*)p.a_lo - a_base;
+
+  for (int kt = kt_begin + wave * KU; kt < kt_end; kt += NW * KU) {
+    Frag b[KU][NT], a[KU][MT], al[KU][MT];
+#pragma unroll
+    for (int kk = 0; kk < KU; ++kk) {
+      const bool live = kt + kk < kt_end;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        b[kk][j].u = make_uint4(0, 0, 0, 0);
+        if (live && nt0 + j < n_tiles) b[kk][j].u = wp[((long long)(nt0 + j) * k_tiles + kt + kk) * 64 + lane];
+      }
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        a[kk][i].u = make_uint4(0, 0, 0, 0);
+        al[kk][i].u = make_uint4(0, 0, 0, 0);
+        if (live && a_row[i]) {
+          a[kk][i].u = *(const uint4*)(a_row[i] + (kt + kk) * 32);
+          al[kk][i].u = *(const uint4*)(a_row[i] + lo_off + (kt + kk) * 32);
+        }
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < KU; ++kk)
+#pragma unroll
+      for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[kk][j].v, al[kk][i].v, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[kk][j].v, a[kk][i].v, acc[i][j], 0, 0, 0);
+        }
+  }
+
+  // the wavefronts' partial tiles meet in LDS; units of (one row tile, two column tiles)
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+      red[(wave * MT * NT + i * NT + j) * 64 + lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+  __syncthreads();
+  constexpr int NU = NT >= 2 ? NT / 2 : 1;  // units per row tile
+  constexpr int TW = NT >= 2 ? 2 : 1;       // column tiles per unit
+  for (int u = wave; u < MT * NU; u += NW) {
+    const int i = u / NU, j = (u % NU) * TW;
+    const int m = m0 + i * 16 + r;
+    f32x4 t[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int q = 0; q < TW; ++q)
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const float4 v = red[(w * MT * NT + i * NT + j + q) * 64 + lane];
+        t[q][0] += v.x;
+        t[q][1] += v.y;
+        t[q][2] += v.z;
+        t[q][3] += v.w;
+      }
+    if (p.rinv_ssq) {
+      // second half of the RMSNorm of this projection's input: scale row m by
+      // rsqrt(mean(x^2) + eps); the 4 lanes of a row share the partial sums
+      float s = 0.f;
+      for (int pp = g; pp < p.rinv_partials; pp += 4) s += m < p.M ? p.rinv_ssq[(long long)pp * p.ssq_stride + m] : 0.f;
+      s += __shfl_xor(s, 16, WAVE);
+      s += __shfl_xor(s, 32, WAVE);
+      const float rinv = 1.0f / sqrtf(s / (float)p.K + p.eps);
+#pragma unroll
+      for (int q = 0; q < TW; ++q) {
+        t[q][0] *= rinv;
+        t[q][1] *= rinv;
+        t[q][2] *= rinv;
+        t[q][3] *= rinv;
+      }
+    }
+    const bool valid = m < p.M && nt0 + j + TW - 1 < n_tiles;
+    if (EPI == EPI_RESID) {
+      float ss = 0.f;
+      if (valid) {
+#pragma unroll
+        for (int q = 0; q < TW; ++q) {
+          const int n = (nt0 + j + q) * 16 + g * 4;
+          float4* xp = (float4*)(p.x + (long long)m * p.N + n);
+          float4 xv = *xp;
+          xv.x += t[q][0];
+          xv.y += t[q][1];
+          xv.z += t[q][2];
+          xv.w += t[q][3];
+          *xp = xv;
+          ss += xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
+          const float4 gn = *(const float4*)(p.gain + n);
+          uint16_t hi[4], lo[4];
+          split_bf16(xv.x * gn.x, hi[0], lo[0]);
+          split_bf16(xv.y * gn.y, hi[1], lo[1]);
+          split_bf16(xv.z * gn.z, hi[2], lo[2]);
+          split_bf16(xv.w * gn.w, hi[3], lo[3]);
+          uint16_t* hp = p.h + (long long)m * p.N + n;
+          *(uint2*)hp = pack4(hi);
+          *(uint2*)(hp + p.h_lo_offset) = pack4(lo);
+        }
+      }
+      ss += __shfl_xor(ss, 16, WAVE);
+      ss += __shfl_xor(ss, 32, WAVE);
+      if (g == 0 && m < p.M) p.ssq_out[(long long)blockIdx.x * p.ssq_stride + m] = ss;
+    } else if (valid) {
+      store_unit<EPI>(p, m, nt0 + j, t[0], t[1], g, blockIdx.z, TW == 2);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Tiled kernel: a workgroup of 4 wavefronts computes MT*16 rows x 4*NT*16 columns; each
+// wavefront owns NT column tiles and reads its weight fragments straight from memory, the
+// activation fragments (hi and lo planes) of KC k-tiles are staged in LDS for all four.
+// Double-buffered: while one stage is multiplied, the next stage's activations and weights
+// are already in flight (registers), and are written to the other LDS buffer afterwards.
+template <int MT, int NT, int KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
+  constexpr int FR = 2 * MT * KC;      // activation fragments per stage: [kk][plane][mt]
+  constexpr int PER = (FR + 3) / 4;    // fragments each wavefront stages
+  __shared__ uint4 a_lds[2][FR * 64];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int n_tiles = p.N >> 4, k_tiles = p.K >> 5;
@@ -35,7 +220,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
   int m0 = blockIdx.y * (MT * 16);
   const int kt_begin = blockIdx.z * p.k_tiles_per_split;
   const int kt_end = min(k_tiles, kt_begin + p.k_tiles_per_split);
-  const bool wave_active = nt0 < n_tiles;
 
   // grouped (per-expert) launches: this row block belongs to one group with its own weights
   const uint4* wp = (const uint4*)p.w;
@@ -48,6 +232,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
     m_limit = p.block_row_end[blockIdx.y];
     row_map = p.row_map;
   }
+  const uint16_t* a_base = (const uint16_t*)p.a;
+  const long long lo_off = (const uint16_t*)p.a_lo - a_base;
+
+  // the activation fragments this wavefront stages: f = wave + 4 s -> (kk, plane, mt)
+  const uint16_t* st_src[PER];
+#pragma unroll
+  for (int s = 0; s < PER; ++s) {
+    const int f = wave + 4 * s;
+    st_src[s] = nullptr;
+    if (f < FR) {
+      const int kk = f / (2 * MT), plane = (f / MT) & 1, mt = f % MT;
+      const int m = m0 + mt * 16 + r;
+      if (m < m_limit) {
+        const long long row = row_map ? row_map[m] : m;
+        st_src[s] = a_base + row * p.lda + (long long)kk * 32 + g * 8 + (plane ? lo_off : 0);
+      }
+    }
+  }
 
   f32x4 acc[MT][NT];
 #pragma unroll
@@ -55,126 +257,184 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const uint16_t* a_base = (const uint16_t*)p.a;
-  for (int kt = kt_begin; kt < kt_end; kt += KC) {
-    const int kc = min(KC, kt_end - kt);
-    // weight fragments of this chunk: contiguous 1 KiB per (n_tile, k_tile)
-    Frag b[KC][NT];
-    if (wave_active) {
+  uint4 st[PER];
+  Frag bc[KC][NT], bn[KC][NT];
+  auto load_stage = [&](int kt, Frag (&b)[KC][NT]) {
+#pragma unroll
+    for (int s = 0; s < PER; ++s) {
+      const int kk = (wave + 4 * s) / (2 * MT);
+      st[s] = make_uint4(0, 0, 0, 0);
+      if (st_src[s] && kt + kk < kt_end) st[s] = *(const uint4*)(st_src[s] + (long long)kt * 32);
+    }
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        b[kk][j].u = make_uint4(0, 0, 0, 0);
+        if (kt + kk < kt_end && nt0 + j < n_tiles) b[kk][j].u = wp[((long long)(nt0 + j) * k_tiles + kt + kk) * 64 + lane];
+      }
+  };
+  auto store_stage = [&](int buf) {
+#pragma unroll
+    for (int s = 0; s < PER; ++s)
+      if (wave + 4 * s < FR) a_lds[buf][(wave + 4 * s) * 64 + lane] = st[s];
+  };
+
+  load_stage(kt_begin, bc);
+  store_stage(0);
+  __syncthreads();
+  int buf = 0;
+  for (int kt = kt_begin; kt < kt_end; kt += KC, buf ^= 1) {
+    const bool more = kt + KC < kt_end;
+    if (more) load_stage(kt + KC, bn);
+#pragma unroll
+    for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+      for (int plane = 1; plane >= 0; --plane) {  // lo parts first, then hi
+        Frag a[MT];
+#pragma unroll
+        for (int i = 0; i < MT; ++i) a[i].u = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+          for (int j = 0; j < NT; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bc[kk][j].v, a[i].v, acc[i][j], 0, 0, 0);
+      }
+    if (more) {
+      store_stage(buf ^ 1);
 #pragma unroll
       for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-          if (kk < kc && nt0 + j < n_tiles) b[kk][j].u = wp[((long long)(nt0 + j) * k_tiles + kt + kk) * 64 + lane];
+        for (int j = 0; j < NT; ++j) bc[kk][j] = bn[kk][j];
     }
-    if (A_LDS) {
-      __syncthreads();  // previous chunk fully consumed
-      for (int f = wave; f < kc * MT; f += 4) {
-        int kk = f / MT, mt = f % MT;
-        int m = m0 + mt * 16 + r;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (m < m_limit) {
-          long long row = row_map ? row_map[m] : m;
-          v = *(const uint4*)(a_base + row * p.lda + (long long)(kt + kk) * 32 + g * 8);
-        }
-        a_lds[(kk * MT + mt) * 64 + lane] = v;
-      }
-      __syncthreads();
-    }
-#pragma unroll
-    for (int kk = 0; kk < KC; ++kk) {
-      if (kk < kc) {
-        Frag a[MT];
-#pragma unroll
-        for (int i = 0; i < MT; ++i) {
-          if (A_LDS) {
-            a[i].u = a_lds[(kk * MT + i) * 64 + lane];
-          } else {
-            int m = m0 + i * 16 + r;
-            a[i].u = make_uint4(0, 0, 0, 0);
-            if (m < m_limit) {
-              long long row = row_map ? row_map[m] : m;
-              a[i].u = *(const uint4*)(a_base + row * p.lda + (long long)(kt + kk) * 32 + g * 8);
-            }
-          }
-        }
-        if (wave_active) {
-#pragma unroll
-          for (int i = 0; i < MT; ++i)
-#pragma unroll
-            for (int j = 0; j < NT; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[kk][j].v, a[i].v, acc[i][j], 0, 0, 0);
-        }
-      }
-    }
+    __syncthreads();
   }
-  if (!wave_active) return;
-
-  // D[n][m]: lane (r, g) holds rows n = 4g..4g+3 of the tile at column m = r
+  if (nt0 >= n_tiles) return;
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     const int m = m0 + i * 16 + r;
     if (m >= m_limit) continue;
-    if (EPI == EPI_F32) {
-      float* out = (float*)p.out + (long long)blockIdx.z * p.split_stride + (long long)m * p.ldo;
 #pragma unroll
-      for (int j = 0; j < NT; ++j)
-        if (nt0 + j < n_tiles)
-          *(float4*)(out + (nt0 + j) * 16 + g * 4) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
-    } else {  // EPI_SWIGLU_BF16: n-tiles alternate gate, up; act[m][f] = silu(gate) * up
-      uint16_t* out = (uint16_t*)p.out + (long long)m * p.ldo;
-#pragma unroll
-      for (int j = 0; j < NT; j += 2) {
-        if (nt0 + j + 1 >= n_tiles) break;
-        uint16_t h[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16(silu_f(acc[i][j][e]) * acc[i][j + 1][e]).bits;
-        uint2 packed = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
-        *(uint2*)(out + ((nt0 + j) >> 1) * 16 + g * 4) = packed;
+    for (int j = 0; j < NT; j += 2)
+      if (nt0 + j + 1 < n_tiles) store_unit<EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z, true);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+template <int MT, int NT, int KU, int NW>
+static void launch_stream(const GemmArgs& a, int epi, dim3 grid, hipStream_t s) {
+  if (epi == EPI_F32)
+    gemm_stream_kernel<MT, NT, KU, NW, EPI_F32><<<grid, NW * 64, 0, s>>>(a);
+  else if (epi == EPI_SWIGLU_BF16)
+    gemm_stream_kernel<MT, NT, KU, NW, EPI_SWIGLU_BF16><<<grid, NW * 64, 0, s>>>(a);
+  else
+    gemm_stream_kernel<MT, NT, KU, NW, EPI_RESID><<<grid, NW * 64, 0, s>>>(a);
+}
+
+static const char* stream_name(int mt, int nt, int nw, int epi) {
+  static char names[3][2][2][3][40];
+  static bool init = false;
+  if (!init) {
+    const int mts[3] = {1, 2, 4}, nws[2] = {4, 16};
+    for (int a = 0; a < 3; ++a)
+      for (int b = 0; b < 2; ++b)
+        for (int c = 0; c < 2; ++c)
+          for (int e = 0; e < 3; ++e)
+            snprintf(names[a][b][c][e], 40, "gemm_stream_kernel<%d,%d,%d,%d,%d>", mts[a], b + 1, mts[a] == 4 ? 2 : 4,
+                     nws[c], e);
+    init = true;
+  }
+  return names[mt == 1 ? 0 : mt == 2 ? 1 : 2][nt - 1][nw == 4 ? 0 : 1][epi];
+}
+
+GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
+  GemmPlan pl{};
+  const int n_tiles = N >> 4, k_tiles = K >> 5;
+  if (M > 32) {
+    // tiled kernel: the largest tile that still gives every CU a workgroup, then split-K planes
+    pl.kind = 1;
+    pl.nw = 4;
+    static const int cfg[3][2] = {{8, 4}, {4, 4}, {4, 2}};
+    static const char* const names[3][2] = {{"gemm_tile_kernel<8,4,2,0>", "gemm_tile_kernel<8,4,2,1>"},
+                                            {"gemm_tile_kernel<4,4,2,0>", "gemm_tile_kernel<4,4,2,1>"},
+                                            {"gemm_tile_kernel<4,2,2,0>", "gemm_tile_kernel<4,2,2,1>"}};
+    int pick = 2;
+    long long blocks = 0;
+    for (int c = 0; c < 3; ++c) {
+      blocks = (long long)ceil_div(M, 16 * cfg[c][0]) * ceil_div(n_tiles, 4 * cfg[c][1]);
+      if (blocks >= 256 || c == 2) {
+        pick = c;
+        break;
       }
     }
+    pl.mt = cfg[pick][0];
+    pl.nt = cfg[pick][1];
+    pl.splits = 1;
+    if (epi == EPI_F32 && blocks < 256) {
+      int z = (int)((384 + blocks - 1) / blocks);
+      z = std::min(z, std::max(1, k_tiles / 8));
+      pl.splits = std::max(1, std::min({z, max_splits, 4}));
+    }
+    pl.name = names[pick][epi == EPI_F32 ? 0 : 1];
+    return pl;
   }
+  pl.kind = 0;
+  pl.mt = M <= 16 ? 1 : M <= 32 ? 2 : 4;
+  const int m_blocks = ceil_div(M, 16 * pl.mt);
+  // wide outputs: two column tiles and 4 wavefronts per workgroup; narrow outputs: one column
+  // tile and 16 wavefronts, so that the K range, not the column count, fills the CUs
+  const bool wide = (long long)(n_tiles / 2) * m_blocks >= 512;
+  pl.nt = (wide || epi == EPI_SWIGLU_BF16) ? 2 : 1;
+  pl.nw = wide ? 4 : 16;
+  if (epi == EPI_SWIGLU_BF16 && !wide) pl.nw = 4;
+  pl.splits = 1;
+  if (epi == EPI_F32 && !wide && max_splits > 1) {
+    const long long blocks = (long long)n_tiles * m_blocks;
+    int z = (int)((256 + blocks - 1) / blocks);
+    z = std::min(z, std::max(1, k_tiles / 64));
+    pl.splits = std::max(1, std::min({z, max_splits, 4}));
+  }
+  pl.name = stream_name(pl.mt, pl.nt, pl.nw, epi);
+  return pl;
 }
 
-template <int MT, int NT, int KC, bool A_LDS>
-static void launch_cfg(const GemmArgs& a, int epi, dim3 grid, hipStream_t s) {
-  if (epi == EPI_F32)
-    gemm_bf16_kernel<MT, NT, KC, A_LDS, EPI_F32><<<grid, 256, 0, s>>>(a);
-  else
-    gemm_bf16_kernel<MT, NT, KC, A_LDS, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+template <int MT, int KU>
+static void launch_stream_mt(const GemmArgs& a, int epi, const GemmPlan& pl, dim3 grid, hipStream_t s) {
+  if (pl.nt == 1 && pl.nw == 4) launch_stream<MT, 1, KU, 4>(a, epi, grid, s);
+  else if (pl.nt == 1) launch_stream<MT, 1, KU, 16>(a, epi, grid, s);
+  else if (pl.nw == 4) launch_stream<MT, 2, KU, 4>(a, epi, grid, s);
+  else launch_stream<MT, 2, KU, 16>(a, epi, grid, s);
 }
 
-int gemm_rows_per_block(int M) { return M <= 16 ? 16 : M <= 32 ? 32 : M <= 64 ? 64 : 128; }
-
-int gemm_pick_splits(int M, int N, int K, int max_splits) {
-  const int bm = gemm_rows_per_block(M);
-  const int nt = bm == 128 ? 4 : 2;
-  const long long blocks = (long long)ceil_div(N >> 4, 4 * nt) * ceil_div(M, bm);
-  const int k_tiles = K >> 5;
-  int z = (int)((768 + blocks - 1) / blocks);       // aim for about three workgroups per CU
-  z = std::min(z, std::max(1, k_tiles / 8));        // at least 8 k-tiles (256 deep) per split
-  return std::max(1, std::min(z, max_splits));
-}
-
-int launch_gemm_bf16(GemmArgs a, int epi, int splits, hipStream_t s) {
+int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
   if (a.M < 1 || a.N < 16) return 0;
-  const int k_tiles = a.K >> 5;
-  const int bm = a.rows_per_block ? a.rows_per_block : gemm_rows_per_block(a.M);
-  const int nt = bm == 128 ? 4 : 2;
-  const int kc = bm == 128 ? 2 : 4;
-  splits = std::max(1, std::min(splits, k_tiles));
-  int per = ceil_div(k_tiles, splits);
-  per = ceil_div(per, kc) * kc;
-  splits = ceil_div(k_tiles, per);
-  a.k_tiles_per_split = per;
-  const int m_blocks = a.group_of_block ? a.n_row_blocks : ceil_div(a.M, bm);
-  dim3 grid(ceil_div(a.N >> 4, 4 * nt), m_blocks, splits);
-  switch (bm) {
-    case 16: launch_cfg<1, 2, 4, false>(a, epi, grid, s); break;
-    case 32: launch_cfg<2, 2, 4, true>(a, epi, grid, s); break;
-    case 64: launch_cfg<4, 2, 4, true>(a, epi, grid, s); break;
-    default: launch_cfg<8, 4, 2, true>(a, epi, grid, s); break;
+  const int n_tiles = a.N >> 4, k_tiles = a.K >> 5;
+  if (pl.kind == 1) {
+    int per = ceil_div(ceil_div(k_tiles, epi == EPI_F32 ? pl.splits : 1), 2) * 2;
+    const int splits = ceil_div(k_tiles, per);
+    a.k_tiles_per_split = per;
+    const int m_blocks = a.group_of_block ? a.n_row_blocks : ceil_div(a.M, 16 * pl.mt);
+    dim3 grid(ceil_div(n_tiles, 4 * pl.nt), m_blocks, splits);
+    const bool f32 = epi == EPI_F32;
+    if (pl.mt == 8) {
+      if (f32) gemm_tile_kernel<8, 4, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
+      else gemm_tile_kernel<8, 4, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+    } else if (pl.nt == 4) {
+      if (f32) gemm_tile_kernel<4, 4, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
+      else gemm_tile_kernel<4, 4, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+    } else {
+      if (f32) gemm_tile_kernel<4, 2, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
+      else gemm_tile_kernel<4, 2, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+    }
+    return splits;
   }
+  int per = ceil_div(k_tiles, epi == EPI_F32 ? pl.splits : 1);
+  const int splits = ceil_div(k_tiles, per);
+  a.k_tiles_per_split = per;
+  dim3 grid(ceil_div(n_tiles, pl.nt), ceil_div(a.M, 16 * pl.mt), splits);
+  if (pl.mt == 1) launch_stream_mt<1, 4>(a, epi, pl, grid, s);
+  else if (pl.mt == 2) launch_stream_mt<2, 4>(a, epi, pl, grid, s);
+  else launch_stream_mt<4, 2>(a, epi, pl, grid, s);
   return splits;
 }
 

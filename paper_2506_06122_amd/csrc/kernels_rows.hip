@@ -4,31 +4,32 @@
 #include "kernels_fast.h"
 
 #define ROW_T 256
-#define ROW_MAX_PER_THREAD 32  // hidden <= 8192
 
+// One workgroup per row; the row is staged in LDS between the two passes (hidden <= 8192).
 __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
+  __shared__ float row_s[8192];
   __shared__ float partial[ROW_T / WAVE];
   const int r = blockIdx.x, t = threadIdx.x;
   const long long src_row = a.rows_index ? a.rows_index[r] : r;
-  float v[ROW_MAX_PER_THREAD];
+  const long long tok = a.tokens ? a.tokens[r] : 0;
   float ss = 0.f;
-  const int n_per = (a.hidden + ROW_T - 1) / ROW_T;
-#pragma unroll
-  for (int j = 0; j < ROW_MAX_PER_THREAD; ++j) {
-    if (j >= n_per) break;
-    int i = t + j * ROW_T;
-    float x = 0.f;
-    if (i < a.hidden) {
-      if (a.tokens) {
-        bf16_t e;
-        e.bits = a.embed[(long long)a.tokens[r] * a.hidden + i];
-        x = bf16_to_f32(e);
-      } else {
-        x = a.x[src_row * a.hidden + i];
-      }
-      for (int z = 0; z < a.splits; ++z) x += a.partial[z * a.split_stride + (long long)r * a.hidden + i];
+  for (int i = t; i < a.hidden; i += ROW_T) {
+    float x;
+    if (a.tokens) {
+      bf16_t e;
+      e.bits = a.embed[tok * a.hidden + i];
+      x = bf16_to_f32(e);
+    } else {
+      x = a.x[src_row * a.hidden + i];
     }
-    v[j] = x;
+    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;  // at most 4 split planes, loads issued together
+    const float* pp = a.partial + (long long)r * a.hidden + i;
+    if (a.splits > 0) p0 = pp[0];
+    if (a.splits > 1) p1 = pp[a.split_stride];
+    if (a.splits > 2) p2 = pp[2 * a.split_stride];
+    if (a.splits > 3) p3 = pp[3 * a.split_stride];
+    x = (((x + p0) + p1) + p2) + p3;
+    row_s[i] = x;
     ss += x * x;
   }
   ss = wave_sum(ss);
@@ -37,69 +38,80 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
   float total = 0.f;
 #pragma unroll
   for (int w = 0; w < ROW_T / WAVE; ++w) total += partial[w];
-  const float rinv = 1.0f / sqrtf(total / (float)a.hidden + a.eps);
-#pragma unroll
-  for (int j = 0; j < ROW_MAX_PER_THREAD; ++j) {
-    if (j >= n_per) break;
-    int i = t + j * ROW_T;
-    if (i < a.hidden) {
-      if (!a.rows_index && (a.splits || a.tokens)) a.x[(long long)r * a.hidden + i] = v[j];
-      a.h[(long long)r * a.hidden + i] = f32_to_bf16(v[j] * a.gain[i] * rinv).bits;
-    }
+  const float rinv = a.ssq_out ? 1.0f : 1.0f / sqrtf(total / (float)a.hidden + a.eps);
+  if (a.ssq_out && t == 0) a.ssq_out[r] = total;
+  const bool write_x = !a.rows_index && (a.splits || a.tokens);
+  for (int i = t; i < a.hidden; i += ROW_T) {
+    const float x = row_s[i];
+    if (write_x) a.x[(long long)r * a.hidden + i] = x;
+    uint16_t hi, lo;
+    split_bf16(x * a.gain[i] * rinv, hi, lo);
+    a.h[(long long)r * a.hidden + i] = hi;
+    a.h[a.h_lo_offset + (long long)r * a.hidden + i] = lo;
   }
 }
 void launch_row_norm(const RowNormArgs& a, hipStream_t s) {
   if (a.rows) row_norm_kernel<<<a.rows, ROW_T, 0, s>>>(a);
 }
 
-__global__ void qkv_post_kernel(QkvPostArgs a) {
+// One thread per rotary pair (head, i): grid (rows, heads / 4), 4 heads of 64 pairs per block.
+__global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
   const int r = blockIdx.x;
   const KvGeom& g = a.geom;
   const int dh = g.head_dim, half = dh >> 1;
   const int n_heads = a.n_q_heads + 2 * g.n_kv_heads;
+  const int per_block = 256 / half;  // heads per block
+  const int head = blockIdx.y * per_block + threadIdx.x / half, i = threadIdx.x % half;
+  if (head >= n_heads) return;
   const int pos = a.row_pos[r];
-  const int page = a.page_table[(long long)a.row_slot[r] * a.max_pages + pos / g.page_tokens];
-  const int tok = pos % g.page_tokens;
-  const float* cs = a.cos_sin + (long long)pos * dh;
-  const long long row_off = (long long)r * n_heads * dh;
-  for (int idx = threadIdx.x; idx < n_heads * half; idx += blockDim.x) {
-    int head = idx / half, i = idx % half;
-    float u = 0.f, w = 0.f;
-    for (int z = 0; z < a.splits; ++z) {
-      const float* p = a.partial + z * a.split_stride + row_off + head * dh;
-      u += p[i];
-      w += p[i + half];
+  const long long row_off = (long long)r * n_heads * dh + head * dh;
+  const float* p = a.partial + row_off;
+  float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f, w0 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
+  if (a.splits > 0) { u0 = p[i]; w0 = p[i + half]; }
+  if (a.splits > 1) { u1 = p[a.split_stride + i]; w1 = p[a.split_stride + i + half]; }
+  if (a.splits > 2) { u2 = p[2 * a.split_stride + i]; w2 = p[2 * a.split_stride + i + half]; }
+  if (a.splits > 3) { u3 = p[3 * a.split_stride + i]; w3 = p[3 * a.split_stride + i + half]; }
+  float u = ((u0 + u1) + u2) + u3, w = ((w0 + w1) + w2) + w3;
+  if (head < a.n_q_heads + g.n_kv_heads) {
+    const float* cs = a.cos_sin + (long long)pos * dh;
+    float c = cs[2 * i], sn = cs[2 * i + 1];
+    float ru = u * c - w * sn, rw = w * c + u * sn;
+    u = ru;
+    w = rw;
+  }
+  if (head < a.n_q_heads) {
+    long long o = ((long long)r * a.n_q_heads + head) * dh;
+    uint16_t hi, lo;  // the attention kernels multiply q with half-precision keys
+    split_f16(u, hi, lo);
+    a.q_bf16[o + i] = hi;
+    a.q_bf16[a.q_lo_offset + o + i] = lo;
+    split_f16(w, hi, lo);
+    a.q_bf16[o + i + half] = hi;
+    a.q_bf16[a.q_lo_offset + o + i + half] = lo;
+    if (a.q_f32) {
+      a.q_f32[(long long)r * a.q_f32_ld + head * dh + i] = u;
+      a.q_f32[(long long)r * a.q_f32_ld + head * dh + i + half] = w;
     }
-    if (head < a.n_q_heads + g.n_kv_heads) {
-      float c = cs[2 * i], sn = cs[2 * i + 1];
-      float ru = u * c - w * sn, rw = w * c + u * sn;
-      u = ru;
-      w = rw;
-    }
-    if (head < a.n_q_heads) {
-      long long o = ((long long)r * a.n_q_heads + head) * dh;
-      a.q_bf16[o + i] = f32_to_bf16(u).bits;
-      a.q_bf16[o + i + half] = f32_to_bf16(w).bits;
-      if (a.q_f32) {
-        a.q_f32[(long long)r * a.q_f32_ld + head * dh + i] = u;
-        a.q_f32[(long long)r * a.q_f32_ld + head * dh + i + half] = w;
-      }
+  } else {
+    const int page = a.page_table[(long long)a.row_slot[r] * a.max_pages + pos / g.page_tokens];
+    const int tok = pos % g.page_tokens;
+    int is_v = head >= a.n_q_heads + g.n_kv_heads;
+    int kvh = head - a.n_q_heads - (is_v ? g.n_kv_heads : 0);
+    uint16_t* dst = a.kv_pool + kv_block_base(g, a.layer, page, kvh, is_v);
+    if (is_v) {
+      dst[kv_v_offset(g, tok, i)] = f32_to_f16(u).bits;
+      dst[kv_v_offset(g, tok, i + half)] = f32_to_f16(w).bits;
     } else {
-      int is_v = head >= a.n_q_heads + g.n_kv_heads;
-      int kvh = head - a.n_q_heads - (is_v ? g.n_kv_heads : 0);
-      uint16_t* dst = a.kv_pool + kv_block_base(g, a.layer, page, kvh, is_v);
-      if (is_v) {
-        dst[kv_v_offset(g, tok, i)] = f32_to_bf16(u).bits;
-        dst[kv_v_offset(g, tok, i + half)] = f32_to_bf16(w).bits;
-      } else {
-        dst[kv_k_offset(g, tok, i)] = f32_to_bf16(u).bits;
-        dst[kv_k_offset(g, tok, i + half)] = f32_to_bf16(w).bits;
-      }
+      dst[kv_k_offset(g, tok, i)] = f32_to_f16(u).bits;
+      dst[kv_k_offset(g, tok, i + half)] = f32_to_f16(w).bits;
     }
   }
 }
 void launch_qkv_post(const QkvPostArgs& a, hipStream_t s) {
-  if (a.rows) qkv_post_kernel<<<a.rows, 256, 0, s>>>(a);
+  if (!a.rows) return;
+  const int per_block = 256 / (a.geom.head_dim / 2);
+  const int n_heads = a.n_q_heads + 2 * a.geom.n_kv_heads;
+  qkv_post_kernel<<<dim3(a.rows, ceil_div(n_heads, per_block)), 256, 0, s>>>(a);
 }
 
 __global__ void f32_to_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst, long long n) {

@@ -134,8 +134,8 @@ void launch_rope_kvwrite(float* qkv, const float* cos_sin, const int* row_pos, c
 }
 template void launch_rope_kvwrite<float>(float*, const float*, const int*, const int*, const int*, int, float*,
                                          KvGeom, int, int, int, hipStream_t);
-template void launch_rope_kvwrite<bf16_t>(float*, const float*, const int*, const int*, const int*, int,
-                                          bf16_t*, KvGeom, int, int, int, hipStream_t);
+template void launch_rope_kvwrite<f16_t>(float*, const float*, const int*, const int*, const int*, int, f16_t*,
+                                         KvGeom, int, int, int, hipStream_t);
 
 // ---------------------------------------------------------------- attention
 // One block of ATT_T threads per (row, query head).  Cached positions are taken ATT_T at a
@@ -210,8 +210,8 @@ void launch_attention_simple(const float* qkv, float* out, const int* row_pos, c
 }
 template void launch_attention_simple<float>(const float*, float*, const int*, const int*, const int*, int,
                                              const float*, KvGeom, int, int, int, hipStream_t);
-template void launch_attention_simple<bf16_t>(const float*, float*, const int*, const int*, const int*, int,
-                                              const bf16_t*, KvGeom, int, int, int, hipStream_t);
+template void launch_attention_simple<f16_t>(const float*, float*, const int*, const int*, const int*, int,
+                                             const f16_t*, KvGeom, int, int, int, hipStream_t);
 
 // ---------------------------------------------------------------- SwiGLU
 __global__ void swiglu_f32_kernel(const float* __restrict__ gate_up, float* __restrict__ act, int ffn) {

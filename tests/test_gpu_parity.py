@@ -83,6 +83,45 @@ def test_teacher_forced_logits_match_oracle(name, simple):
         assert regret <= TOL[shape.dtype]
     st = eng.rollout_get_stats()
     assert st["live_samples"] == 0 and st["pages_in_use"] == 0
+    assert st["matrix_core_path"] == int(not simple and shape.dtype == "bf16" and not shape.is_moe)
+    eng.close()
+
+
+@pytest.mark.parametrize("n_prompts,n_samples,lo,hi", [(3, 8, 5, 40), (5, 8, 5, 40), (9, 8, 3, 20), (2, 1, 300, 700),
+                                                      (1, 3, 1, 1)],
+                         ids=["24rows", "40rows", "72rows", "long-context-splits", "one-token-prompt"])
+def test_matrix_core_decode_shapes(n_prompts, n_samples, lo, hi):
+    """Row-tile configurations of the streamed projections (<=16, <=32, <=64, several row
+    blocks) and attention over several KV splits with the merge in the last workgroup."""
+    shape = workloads.SMALL_BF16
+    w = scaled_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, max_live_samples=80, max_context=1024, max_batch_tokens=2048)
+    toks, offs = workloads.make_prompts(n_prompts, lo, hi, shape.vocab, seed=11)
+    steps = 4
+    forced = np.random.default_rng(5).integers(0, shape.vocab, (n_prompts * n_samples, steps)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, n_samples, forced, steps)
+    print(f"max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"]
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
+    eng.close()
+
+
+@pytest.mark.parametrize("simple", [False, True], ids=["fast", "plain"])
+def test_c2_shape_slice_matches_oracle(simple):
+    """The benchmark's model shape (28 layers, hidden 1536, 12/2 heads, FFN 8960, vocab 151936,
+    bf16) on a slice the oracle can afford: 2 prompts x 2 samples, 4 teacher-forced steps."""
+    shape = workloads.C2_1P5B
+    w = workloads.make_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, kv_pool_bytes=1 << 30, max_live_samples=8, max_context=512, max_batch_tokens=512,
+                      flags=int(simple))
+    toks, offs = workloads.make_prompts(2, 40, 90, shape.vocab, seed=12)
+    forced = np.random.default_rng(6).integers(0, shape.vocab, (4, 4)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, 2, forced, 4)
+    print(f"c2 shape: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
+    assert eng.rollout_get_stats()["matrix_core_path"] == int(not simple)
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"]
     eng.close()
 
 
