@@ -55,6 +55,18 @@ __global__ void init_slots_kernel(SlotState st, const int* __restrict__ slots, c
   st.top_p[sl] = top_p[row];
 }
 
+// A decode step ends with a few hundred bytes coming back; polling an event answers within
+// microseconds where a blocking wait costs a scheduler round trip per step.
+static void wait_step_done(rollout_ctx& c) {
+  if (!c.step_done) HIP_TRY(hipEventCreateWithFlags(&c.step_done, hipEventDisableTiming));
+  HIP_TRY(hipEventRecord(c.step_done, c.stream));
+  for (;;) {
+    hipError_t e = hipEventQuery(c.step_done);
+    if (e == hipSuccess) return;
+    if (e != hipErrorNotReady) throw HipError(e, "hipEventQuery", __FILE__, __LINE__);
+  }
+}
+
 static void release_sample(rollout_ctx& c, Sample& s) {
   for (int32_t p : s.pages) c.pool->release(p);
   s.pages.clear();
@@ -435,7 +447,7 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
     launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);
     d2h(hi + 3 * R, c.out_tokens.p, B * sizeof(int), c.stream);
     d2h(c.h_float.p, c.out_logprobs.p, B * sizeof(float), c.stream);
-    HIP_TRY(hipStreamSynchronize(c.stream));
+    wait_step_done(c);
     c.timer.collect();
 
     int i = 0;
@@ -610,7 +622,8 @@ int rollout_sample(const float* logits, int32_t rows, int32_t vocab, float tempe
                    const uint32_t* uniforms, const int32_t* forced, void* hip_stream, int32_t* tokens,
                    float* logprobs, uint64_t* weight_sums) {
   return guarded(nullptr, [&] {
-    if (!logits || rows < 0 || vocab < 1 || !uniforms || !tokens || !logprobs) fail(ROLLOUT_E_INVAL, "bad argument");
+    if (!logits || rows < 0 || vocab < 1 || vocab > 262144 || !uniforms || !tokens || !logprobs)
+      fail(ROLLOUT_E_INVAL, "bad argument");
     if (!(temperature > 0.f) || !std::isfinite(temperature) || !(top_p >= 0.f)) fail(ROLLOUT_E_INVAL, "bad sampling parameters");
     if (forced)
       for (int i = 0; i < rows; ++i)

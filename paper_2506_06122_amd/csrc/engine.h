@@ -208,8 +208,12 @@ struct rollout_ctx {
 
   rollout_stats stats{};
   KernelTimer timer;
+  hipEvent_t step_done = nullptr;
 
-  ~rollout_ctx() { delete pool; }
+  ~rollout_ctx() {
+    delete pool;
+    if (step_done) (void)hipEventDestroy(step_done);
+  }
 };
 
 // engine.hip

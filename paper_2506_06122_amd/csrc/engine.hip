@@ -29,6 +29,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   const rollout_runtime_desc& r = c.rd;
   if (m.n_layers < 1 || m.hidden < 1 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.vocab < 2)
     fail(ROLLOUT_E_INVAL, "model shape fields must be positive");
+  if (m.vocab > 262144) fail(ROLLOUT_E_INVAL, "vocab must be at most 262144");
   if (m.n_q_heads % m.n_kv_heads) fail(ROLLOUT_E_INVAL, "n_q_heads must be a multiple of n_kv_heads");
   if (m.head_dim < 32 || m.head_dim > 256 || m.head_dim % 32)
     fail(ROLLOUT_E_INVAL, "head_dim must be a multiple of 32 in [32, 256]");

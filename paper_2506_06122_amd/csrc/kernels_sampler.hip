@@ -159,19 +159,130 @@ void launch_philox_words(unsigned long long seed, const long long* ids, const un
   if (n) philox_words_kernel<<<ceil_div(n, 256), 256, 0, s>>>(seed, ids, steps, out, n);
 }
 
+// The vocabulary is walked in segments of 256 consecutive ids: one wavefront, 4 ids per lane,
+// 16 segments per 4096-id tile of the block.  Every pass is a coalesced sweep that leaves one
+// value per segment in LDS; a prefix search over at most 1024 segment values then names the
+// segment that holds the id in question, and one wavefront resolves it inside the segment.
+struct Seg4 {
+  unsigned long long w[4];
+};
+
+__device__ inline Seg4 load_weights4(const float* __restrict__ row, int i0, int vocab, bool vec_ok, float inv_t,
+                                     float m) {
+  float v[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  if (vec_ok && i0 + 3 < vocab) {
+    const float4 t = *(const float4*)(row + i0);
+    v[0] = t.x;
+    v[1] = t.y;
+    v[2] = t.z;
+    v[3] = t.w;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (i0 + e < vocab) v[e] = row[i0 + e];
+  }
+  Seg4 out;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) out.w[e] = i0 + e < vocab ? fixexp_weight(shifted(scaled_logit(v[e], inv_t), m)) : 0ull;
+  return out;
+}
+
+// Smallest segment whose inclusive prefix of sh.vals[0..n_seg) exceeds target, and the
+// exclusive prefix before it.  Requires the total to exceed target.
+__device__ inline void find_segment(SampShared& sh, int n_seg, unsigned long long target, int& seg,
+                                    unsigned long long& before) {
+  const int tid = threadIdx.x;
+  if (tid == 0) {
+    sh.bcast[0] = 0;
+    sh.bcast[1] = 0;
+  }
+  __syncthreads();
+  if (tid < WAVE) {
+    const int per = SAMP_T / WAVE;
+    unsigned long long mine = 0;
+    for (int j = 0; j < per; ++j) mine += tid * per + j < n_seg ? sh.vals[tid * per + j] : 0ull;
+    unsigned long long inc = mine;
+    for (int o = 1; o < WAVE; o <<= 1) {
+      unsigned long long up = shfl_up_u64(inc, o);
+      if (tid >= o) inc += up;
+    }
+    unsigned long long exc = inc - mine;
+    if (exc <= target && target < inc) {
+      unsigned long long acc = exc;
+      int j = 0;
+      for (; j < per - 1; ++j) {
+        unsigned long long v = tid * per + j < n_seg ? sh.vals[tid * per + j] : 0ull;
+        if (acc + v > target) break;
+        acc += v;
+      }
+      sh.bcast[0] = (unsigned long long)(tid * per + j);
+      sh.bcast[1] = acc;
+    }
+  }
+  __syncthreads();
+  seg = (int)sh.bcast[0];
+  before = sh.bcast[1];
+  __syncthreads();
+}
+
+// One wavefront: index of the element of its 4-per-lane values whose running sum first exceeds
+// target (values in ascending id order: lane-major, element-minor).
+__device__ inline int resolve_in_segment(const unsigned long long (&v)[4], unsigned long long target, int lane) {
+  const unsigned long long mine = v[0] + v[1] + v[2] + v[3];
+  unsigned long long inc = mine;
+  for (int o = 1; o < WAVE; o <<= 1) {
+    unsigned long long up = shfl_up_u64(inc, o);
+    if (lane >= o) inc += up;
+  }
+  const unsigned long long exc = inc - mine;
+  int found = -1;
+  if (exc <= target && target < inc) {
+    unsigned long long acc = exc;
+    found = lane * 4 + 3;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc += v[e];
+      if (acc > target && found == lane * 4 + 3) found = lane * 4 + e;
+    }
+  }
+  // exactly one lane found it
+  for (int o = WAVE / 2; o > 0; o >>= 1) found = max(found, __shfl_xor(found, o, WAVE));
+  return found;
+}
+
 __global__ __launch_bounds__(SAMP_T) void sample_kernel(SampleRows a, int vocab) {
   __shared__ SampShared sh;
-  const int tid = threadIdx.x, r = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = blockIdx.x;
   const float* row = a.logits + (long long)(a.logits_row ? a.logits_row[r] : r) * vocab;
   const float inv_t = a.inv_temp[r];
+  const bool vec_ok = (vocab & 3) == 0 && (((unsigned long long)row) & 15ull) == 0;
+  const int n_seg = (vocab + 255) >> 8;
+  const int n_tiles = (vocab + 4095) >> 12;
 
   float m = -INFINITY;
-  for (int i = tid; i < vocab; i += SAMP_T) m = fmaxf(m, scaled_logit(row[i], inv_t));
+  for (int t = 0; t < n_tiles; ++t) {
+    const int i0 = t * 4096 + tid * 4;
+    if (vec_ok && i0 + 3 < vocab) {
+      const float4 v = *(const float4*)(row + i0);
+      m = fmaxf(fmaxf(m, fmaxf(scaled_logit(v.x, inv_t), scaled_logit(v.y, inv_t))),
+                fmaxf(scaled_logit(v.z, inv_t), scaled_logit(v.w, inv_t)));
+    } else {
+      for (int e = 0; e < 4; ++e)
+        if (i0 + e < vocab) m = fmaxf(m, scaled_logit(row[i0 + e], inv_t));
+    }
+  }
   m = block_max(m, sh);
 
+  // pass: all weights, one sum per segment
   unsigned long long local = 0;
-  for (int i = tid; i < vocab; i += SAMP_T) local += fixexp_weight(shifted(scaled_logit(row[i], inv_t), m));
-  const unsigned long long S = block_sum_u64(local, sh);
+  for (int t = 0; t < n_tiles; ++t) {
+    const Seg4 q = load_weights4(row, t * 4096 + tid * 4, vocab, vec_ok, inv_t, m);
+    const unsigned long long mine = q.w[0] + q.w[1] + q.w[2] + q.w[3];
+    local += mine;
+    const unsigned long long ws = wave_sum_u64(mine);
+    if (lane == 0 && t * 16 + wave < n_seg) sh.vals[t * 16 + wave] = ws;
+  }
+  const unsigned long long S = block_sum_u64(local, sh);  // also orders the writes to sh.vals
 
   int token = a.forced ? a.forced[r] : -1;
   if (token < 0) {
@@ -185,72 +296,73 @@ __global__ __launch_bounds__(SAMP_T) void sample_kernel(SampleRows a, int vocab)
       if (theta < 1) theta = 1;
       // largest tau with sum_{w >= tau} w >= theta, bit by bit (w <= 2^40)
       for (int b = 40; b >= 0; --b) {
-        unsigned long long cand = tau | (1ull << b);
+        const unsigned long long cand = tau | (1ull << b);
         unsigned long long part = 0;
-        for (int i = tid; i < vocab; i += SAMP_T) {
-          unsigned long long w = fixexp_weight(shifted(scaled_logit(row[i], inv_t), m));
-          if (w >= cand) part += w;
+        for (int t = 0; t < n_tiles; ++t) {
+          const Seg4 q = load_weights4(row, t * 4096 + tid * 4, vocab, vec_ok, inv_t, m);
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (q.w[e] >= cand) part += q.w[e];
         }
         if (block_sum_u64(part, sh) >= theta) tau = cand;
       }
-      unsigned long long above = 0, ties = 0;
-      const int seg = (vocab + SAMP_T - 1) / SAMP_T;
-      const int lo = min(vocab, tid * seg), hi = min(vocab, lo + seg);
-      for (int i = lo; i < hi; ++i) {
-        unsigned long long w = fixexp_weight(shifted(scaled_logit(row[i], inv_t), m));
-        if (w > tau) above += w;
-        if (w == tau) ties += 1;
-      }
-      unsigned long long sum_above = block_sum_u64(above, sh);
-      unsigned long long need = theta - sum_above;          // > 0 by maximality of tau
-      unsigned long long k_ties = (need + tau - 1) / tau;   // ties admitted, ascending id
-      int t_star;
-      unsigned long long before;
-      block_find(ties, k_ties - 1, sh, t_star, before);
-      if (tid == t_star) {
-        unsigned long long seen = before;
-        int cut = hi - 1;
-        for (int i = lo; i < hi; ++i) {
-          if (fixexp_weight(shifted(scaled_logit(row[i], inv_t), m)) == tau && ++seen == k_ties) {
-            cut = i;
-            break;
-          }
+      // weight above tau, and ties at tau counted per segment
+      unsigned long long above = 0;
+      for (int t = 0; t < n_tiles; ++t) {
+        const Seg4 q = load_weights4(row, t * 4096 + tid * 4, vocab, vec_ok, inv_t, m);
+        unsigned long long ties = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (q.w[e] > tau) above += q.w[e];
+          if (q.w[e] == tau) ties += 1;
         }
-        sh.bcast[0] = (unsigned long long)cut;
+        const unsigned long long ws = wave_sum_u64(ties);
+        if (lane == 0 && t * 16 + wave < n_seg) sh.vals[t * 16 + wave] = ws;
+      }
+      const unsigned long long sum_above = block_sum_u64(above, sh);
+      const unsigned long long need = theta - sum_above;         // > 0 by maximality of tau
+      const unsigned long long k_ties = (need + tau - 1) / tau;  // ties admitted, ascending id
+      int seg;
+      unsigned long long before;
+      find_segment(sh, n_seg, k_ties - 1, seg, before);
+      if (wave == 0) {
+        const Seg4 q = load_weights4(row, seg * 256 + lane * 4, vocab, vec_ok, inv_t, m);
+        const unsigned long long is_tie[4] = {q.w[0] == tau, q.w[1] == tau, q.w[2] == tau, q.w[3] == tau};
+        const int idx = resolve_in_segment(is_tie, k_ties - 1 - before, lane);
+        if (lane == 0) sh.bcast[0] = (unsigned long long)(seg * 256 + idx);
       }
       __syncthreads();
       tie_cut = (int)sh.bcast[0];
       __syncthreads();
       s_n = sum_above + k_ties * tau;
+      // nucleus weight per segment
+      for (int t = 0; t < n_tiles; ++t) {
+        const int i0 = t * 4096 + tid * 4;
+        const Seg4 q = load_weights4(row, i0, vocab, vec_ok, inv_t, m);
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (q.w[e] > tau || (q.w[e] == tau && i0 + e <= tie_cut)) mine += q.w[e];
+        const unsigned long long ws = wave_sum_u64(mine);
+        if (lane == 0 && t * 16 + wave < n_seg) sh.vals[t * 16 + wave] = ws;
+      }
+      __syncthreads();
     }
     // inverse CDF in ascending id order over the nucleus
     const unsigned x = a.uniforms ? a.uniforms[r]
                                   : philox_word0(a.seed, (unsigned long long)a.sample_id[r], (unsigned)a.step[r]);
     const unsigned long long R = (s_n >> 32) * x + (((s_n & 0xffffffffull) * x) >> 32);
-    const int seg = (vocab + SAMP_T - 1) / SAMP_T;
-    const int lo = min(vocab, tid * seg), hi = min(vocab, lo + seg);
-    unsigned long long mine = 0;
-    for (int i = lo; i < hi; ++i) {
-      unsigned long long w = fixexp_weight(shifted(scaled_logit(row[i], inv_t), m));
-      if (w > tau || (w == tau && i <= tie_cut)) mine += w;
-    }
-    int t_star;
+    int seg;
     unsigned long long before;
-    block_find(mine, R, sh, t_star, before);
-    if (tid == t_star) {
-      unsigned long long acc = before;
-      int pick = hi - 1;
-      for (int i = lo; i < hi; ++i) {
-        unsigned long long w = fixexp_weight(shifted(scaled_logit(row[i], inv_t), m));
-        if (w > tau || (w == tau && i <= tie_cut)) {
-          acc += w;
-          if (acc > R) {
-            pick = i;
-            break;
-          }
-        }
-      }
-      sh.bcast[0] = (unsigned long long)pick;
+    find_segment(sh, n_seg, R, seg, before);
+    if (wave == 0) {
+      const int i0 = seg * 256 + lane * 4;
+      const Seg4 q = load_weights4(row, i0, vocab, vec_ok, inv_t, m);
+      unsigned long long v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (q.w[e] > tau || (q.w[e] == tau && i0 + e <= tie_cut)) ? q.w[e] : 0ull;
+      const int idx = resolve_in_segment(v, R - before, lane);
+      if (lane == 0) sh.bcast[0] = (unsigned long long)(seg * 256 + idx);
     }
     __syncthreads();
     token = (int)sh.bcast[0];
