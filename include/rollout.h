@@ -60,7 +60,9 @@ typedef struct {
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
   int32_t n_experts, top_k, expert_ffn_dim; /* 0, 0, 0 = dense */
   float rms_eps, rope_theta;
-  int32_t dtype; /* ROLLOUT_DTYPE_*: storage type of weights and of the KV cache */
+  int32_t dtype; /* ROLLOUT_DTYPE_*: storage type of the weights.  The KV cache is fp32 for F32
+                    models and 16-bit IEEE half for BF16 models (same bytes per token as bf16,
+                    three more mantissa bits); activations are fp32 or bf16 hi+lo pairs. */
   uint32_t flags;
 } rollout_model_desc;
 

@@ -301,7 +301,7 @@ static int project(rollout_ctx& c, const uint16_t* a, long long a_lo_off, int ld
   g.lda = lda;
   g.ldo = N;
   g.split_stride = (long long)M * N;
-  const int cap = (int)std::min<long long>(4, (c.partial_rows * c.partial_ld) / ((long long)M * N));
+  const int cap = (int)std::min<long long>(16, (c.partial_rows * c.partial_ld) / ((long long)M * N));
   const GemmPlan pl = gemm_plan(M, N, K, EPI_F32, std::max(1, cap));
   c.timer.begin(pl.name, gemm_bytes(M, N, K, 4), 2.0 * M * N * K, c.stream);
   const int z = launch_gemm_bf16(g, EPI_F32, pl, c.stream);

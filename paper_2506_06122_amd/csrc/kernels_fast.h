@@ -48,7 +48,7 @@ struct GemmArgs {
 
 // How one projection is launched: kind 0 = gemm_stream_kernel (rows <= 256), 1 = gemm_tile_kernel.
 struct GemmPlan {
-  int kind, mt, nt, nw, splits;
+  int kind, mt, nt, nw, splits, kc;
   const char* name;  // kernel name as a profiler shows it (without the argument list)
 };
 GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits);

@@ -369,11 +369,12 @@ GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
     }
     pl.mt = cfg[pick][0];
     pl.nt = cfg[pick][1];
+    pl.kc = 2;
     pl.splits = 1;
     if (epi == EPI_F32 && blocks < 256) {
-      int z = (int)((384 + blocks - 1) / blocks);
+      int z = (int)((768 + blocks - 1) / blocks);
       z = std::min(z, std::max(1, k_tiles / 8));
-      pl.splits = std::max(1, std::min({z, max_splits, 4}));
+      pl.splits = std::max(1, std::min(z, max_splits));
     }
     pl.name = names[pick][epi == EPI_F32 ? 0 : 1];
     return pl;

@@ -22,13 +22,14 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
     } else {
       x = a.x[src_row * a.hidden + i];
     }
-    float p0 = 0.f, p1 = 0.f, p2 = 0.f, p3 = 0.f;  // at most 4 split planes, loads issued together
     const float* pp = a.partial + (long long)r * a.hidden + i;
-    if (a.splits > 0) p0 = pp[0];
-    if (a.splits > 1) p1 = pp[a.split_stride];
-    if (a.splits > 2) p2 = pp[2 * a.split_stride];
-    if (a.splits > 3) p3 = pp[3 * a.split_stride];
-    x = (((x + p0) + p1) + p2) + p3;
+    for (int z = 0; z < a.splits; z += 4) {  // four planes at a time, loads issued together
+      float p0 = pp[(long long)z * a.split_stride], p1 = 0.f, p2 = 0.f, p3 = 0.f;
+      if (z + 1 < a.splits) p1 = pp[(long long)(z + 1) * a.split_stride];
+      if (z + 2 < a.splits) p2 = pp[(long long)(z + 2) * a.split_stride];
+      if (z + 3 < a.splits) p3 = pp[(long long)(z + 3) * a.split_stride];
+      x = (((x + p0) + p1) + p2) + p3;
+    }
     row_s[i] = x;
     ss += x * x;
   }
@@ -66,12 +67,16 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
   const int pos = a.row_pos[r];
   const long long row_off = (long long)r * n_heads * dh + head * dh;
   const float* p = a.partial + row_off;
-  float u0 = 0.f, u1 = 0.f, u2 = 0.f, u3 = 0.f, w0 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
-  if (a.splits > 0) { u0 = p[i]; w0 = p[i + half]; }
-  if (a.splits > 1) { u1 = p[a.split_stride + i]; w1 = p[a.split_stride + i + half]; }
-  if (a.splits > 2) { u2 = p[2 * a.split_stride + i]; w2 = p[2 * a.split_stride + i + half]; }
-  if (a.splits > 3) { u3 = p[3 * a.split_stride + i]; w3 = p[3 * a.split_stride + i + half]; }
-  float u = ((u0 + u1) + u2) + u3, w = ((w0 + w1) + w2) + w3;
+  float u = 0.f, w = 0.f;
+  for (int z = 0; z < a.splits; z += 4) {  // four planes at a time, loads issued together
+    const float* q = p + (long long)z * a.split_stride;
+    float u0 = q[i], w0 = q[i + half], u1 = 0.f, u2 = 0.f, u3 = 0.f, w1 = 0.f, w2 = 0.f, w3 = 0.f;
+    if (z + 1 < a.splits) { u1 = q[a.split_stride + i]; w1 = q[a.split_stride + i + half]; }
+    if (z + 2 < a.splits) { u2 = q[2 * a.split_stride + i]; w2 = q[2 * a.split_stride + i + half]; }
+    if (z + 3 < a.splits) { u3 = q[3 * a.split_stride + i]; w3 = q[3 * a.split_stride + i + half]; }
+    u = (((u + u0) + u1) + u2) + u3;
+    w = (((w + w0) + w1) + w2) + w3;
+  }
   if (head < a.n_q_heads + g.n_kv_heads) {
     const float* cs = a.cos_sin + (long long)pos * dh;
     float c = cs[2 * i], sn = cs[2 * i + 1];
