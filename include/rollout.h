@@ -183,7 +183,10 @@ int rollout_debug_routing(rollout_ctx *ctx, int32_t *rows, int32_t *out);
 
 int rollout_get_stats(rollout_ctx *ctx, rollout_stats *out);
 /* Per-kernel timings gathered under ROLLOUT_RT_KERNEL_TIMING.  n: in capacity of `out`, out
- * number of entries written (kernels with at least one timed launch). */
+ * number of entries written (kernels with at least one timed launch).  The entry named
+ * "(empty bracket)" is a pair of event records around nothing, taken once in every timed
+ * decode step: the cost of the measurement itself, which every other entry's ms includes
+ * once per launch. */
 int rollout_kernel_stats(rollout_ctx *ctx, int32_t *n, rollout_kernel_stat *out);
 const char *rollout_last_error(rollout_ctx *ctx); /* ctx may be NULL: error of the last failed rollout_init */
 void rollout_destroy(rollout_ctx *ctx);

@@ -419,6 +419,7 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
     c.attn_flops_this_call = 4.0 * c.kv_tokens_this_call * c.q_dim;
     c.timer.start_call();
     engine_forward_rows(c, B, nullptr);
+    c.timer.empty_bracket(c.stream);
     engine_logits(c, nullptr, 0, B, c.logits.p);
     c.last_logit_rows = B;
     if (forced_tokens) {

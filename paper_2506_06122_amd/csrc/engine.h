@@ -97,6 +97,13 @@ struct KernelTimer {
   std::map<std::string, Acc> acc;
 
   void start_call() { active = enabled && (calls++ % (stride ? stride : 1)) == 0; }
+  // A bracket with nothing inside, recorded under the name "(empty bracket)" in mid-stream of a
+  // timed call: what two event records cost by themselves, for the reader of the figures
+  // to subtract.
+  void empty_bracket(hipStream_t s) {
+    begin("(empty bracket)", 0, 0, s);
+    end(s);
+  }
   hipEvent_t get() {
     if (used == pool.size()) {
       hipEvent_t e;

@@ -125,6 +125,30 @@ def test_c2_shape_slice_matches_oracle(simple):
     eng.close()
 
 
+@pytest.mark.parametrize("which", ["c3-dense", "c4-moe"])
+def test_large_config_shapes_reduced_depth(which):
+    """Every matrix shape of configs 3/5 (hidden 3584, 28/4 heads, FFN 18944, vocab 152064) and
+    of config 4 (hidden 2048, 32/4 heads, 128 experts, top-8, expert FFN 768), with the layer
+    count cut (4 and 2 layers) so that the fp64 oracle fits in host memory: 2 prompts x 2
+    samples, 3 teacher-forced steps."""
+    import dataclasses
+    if which == "c3-dense":
+        shape = dataclasses.replace(workloads.C3_7B, n_layers=4, name="qwen2.5-7b-shape-4-layers")
+    else:
+        shape = dataclasses.replace(workloads.C4_30B_A3B, n_layers=2, name="qwen3-30b-a3b-shape-2-layers")
+    w = workloads.make_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, kv_pool_bytes=1 << 30, max_live_samples=8, max_context=512, max_batch_tokens=512,
+                      flags=2 if shape.is_moe else 0)
+    toks, offs = workloads.make_prompts(2, 40, 90, shape.vocab, seed=14)
+    forced = np.random.default_rng(8).integers(0, shape.vocab, (4, 3)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, 2, forced, 3)
+    print(f"{shape.name}: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
+    assert eng.rollout_get_stats()["matrix_core_path"] == int(which == "c3-dense")
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"]
+    eng.close()
+
+
 def test_c1_full_config_rollout():
     """Config 1 as stated: 4 prompts x 2 samples, prompt length 32, exactly 32 new tokens,
     temperature 1.0, top-p 0.9, Philox uniforms.  Free-running on the GPU; every emitted
