@@ -69,6 +69,7 @@ struct LayerWeights {
   DevBuf<char> router;     // MoE [E][hidden]
   // matrix-core path: fragment-ordered copies (kernels_gemm.hip)
   DevBuf<char> wqkv_p, wo_p, w_gate_up_p, w_down_p;  // gate/up: n-tiles alternate gate, up
+  DevBuf<char> router_p;   // MoE: w_gate_up_p, w_down_p hold the experts one after another
 };
 
 // Packed sequences of a prefill / log-prob forward (device arrays); NULL = one row per sample.
@@ -190,6 +191,10 @@ struct rollout_ctx {
   // workspaces
   DevBuf<float> x, h, qkv, attn, gate_up, act, hn, logits, router_logits, moe_wt;
   DevBuf<int> moe_idx, route_log;  // route_log [n_layers][r_max][top_k] when recording
+  // matrix-core MoE block: expert-sorted slots and the row blocks of the grouped projections
+  DevBuf<int> moe_pos, moe_count, moe_row_map, moe_slot_of, moe_group_of_block, moe_block_begin, moe_block_end;
+  DevBuf<float> moe_y;             // [r_max * top_k][hidden] expert results per slot
+  int moe_max_blocks = 0;
   int last_route_rows = 0;
   // matrix-core path workspaces
   DevBuf<uint16_t> h_bf16, q_bf16, attn_bf16, act_bf16, hn_bf16;

@@ -54,9 +54,10 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   HIP_TRY(hipGetDevice(&c.device));
   c.stream = (hipStream_t)r.hip_stream;
   // The matrix-core path needs bf16 storage, head_dim 128 and fragment-aligned dimensions;
-  // anything else (and mixture-of-experts models, for now) runs the plain path.
+  // anything else runs the plain path.
   c.simple = (r.flags & ROLLOUT_RT_SIMPLE_KERNELS) || m.dtype != ROLLOUT_DTYPE_BF16 || m.head_dim != 128 ||
-             m.hidden % 32 || m.hidden > 8192 || m.vocab % 16 || moe || m.ffn_dim % 32;
+             m.hidden % 32 || m.hidden > 8192 || m.vocab % 16 ||
+             (moe ? (m.n_experts % 16 || m.expert_ffn_dim % 32) : m.ffn_dim % 32);
   c.elem = m.dtype == ROLLOUT_DTYPE_BF16 ? 2 : 4;
   c.timer.enabled = (r.flags & ROLLOUT_RT_KERNEL_TIMING) != 0;
   c.timer.stride = r.timing_stride;
@@ -88,9 +89,17 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     load_gain(c, L.norm1, s.norm1, "norm1");
     load_gain(c, L.norm2, s.norm2, "norm2");
     if (!c.simple) {
-      if (!s.wq || !s.wk || !s.wv || !s.wo || !s.w_gate || !s.w_up || !s.w_down)
+      if (!s.wq || !s.wk || !s.wv || !s.wo || !s.w_gate || !s.w_up || !s.w_down || (moe && !s.router))
         fail(ROLLOUT_E_INVAL, "null weight pointer in a layer");
-      const int f = m.ffn_dim;
+      // MoE: the experts' matrices are stacked, [E * Fe][hidden] and [E * hidden][Fe]; Fe is a
+      // multiple of 16, so the stacked gate/up column tiles still alternate inside every expert
+      const int f = moe ? m.n_experts * m.expert_ffn_dim : m.ffn_dim;
+      const int down_rows = moe ? m.n_experts * (int)d : (int)d;
+      const int down_k = moe ? m.expert_ffn_dim : m.ffn_dim;
+      if (moe) {
+        L.router_p.alloc((size_t)m.n_experts * d * 2);
+        launch_pack_weight(s.router, L.router_p.p, m.n_experts, (int)d, 0, 1, c.stream);
+      }
       L.wqkv_p.alloc((size_t)c.qkv_dim * d * 2);
       launch_pack_weight(s.wq, L.wqkv_p.p, c.q_dim, (int)d, 0, 1, c.stream);
       launch_pack_weight(s.wk, L.wqkv_p.p, c.kv_dim, (int)d, c.q_dim / 16, 1, c.stream);
@@ -100,8 +109,8 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
       L.w_gate_up_p.alloc((size_t)2 * f * d * 2);
       launch_pack_weight(s.w_gate, L.w_gate_up_p.p, f, (int)d, 0, 2, c.stream);
       launch_pack_weight(s.w_up, L.w_gate_up_p.p, f, (int)d, 1, 2, c.stream);
-      L.w_down_p.alloc(d * f * 2);
-      launch_pack_weight(s.w_down, L.w_down_p.p, (int)d, f, 0, 1, c.stream);
+      L.w_down_p.alloc((size_t)down_rows * down_k * 2);
+      launch_pack_weight(s.w_down, L.w_down_p.p, down_rows, down_k, 0, 1, c.stream);
       continue;
     }
     L.wqkv.alloc((size_t)c.qkv_dim * d * c.elem);
@@ -188,9 +197,24 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     c.h_bf16.alloc(2 * R * d);
     c.q_bf16.alloc(2 * R * c.q_dim);
     c.attn_bf16.alloc(2 * R * c.q_dim);
-    c.act_bf16.alloc(2 * R * m.ffn_dim);
+    c.act_bf16.alloc(2 * R * (moe ? (size_t)m.top_k * m.expert_ffn_dim : (size_t)m.ffn_dim));
+    if (moe) {
+      const size_t picks = R * m.top_k;
+      c.moe_max_blocks = (int)(std::min<size_t>(m.n_experts, picks) + picks / kMoeBlockRows + 1);
+      c.moe_idx.alloc(picks);
+      c.moe_wt.alloc(picks);
+      c.moe_pos.alloc(picks);
+      c.moe_row_map.alloc(picks);
+      c.moe_slot_of.alloc(picks);
+      c.moe_count.alloc((size_t)m.n_layers * m.n_experts);
+      c.moe_group_of_block.alloc(c.moe_max_blocks);
+      c.moe_block_begin.alloc(c.moe_max_blocks);
+      c.moe_block_end.alloc(c.moe_max_blocks);
+      c.moe_y.alloc(picks * d);
+      if (r.flags & ROLLOUT_RT_RECORD_ROUTING) c.route_log.alloc((size_t)m.n_layers * R * m.top_k);
+    }
     c.hn_bf16.alloc(2 * (size_t)c.logit_rows * d);
-    c.partial_ld = std::max(c.qkv_dim, (int)d);
+    c.partial_ld = std::max({c.qkv_dim, (int)d, moe ? m.n_experts : 0});
     c.partial_rows = std::max<long long>(R, 2048);
     c.partial.alloc((size_t)c.partial_rows * c.partial_ld);
     c.attn_max_parts = std::max(r.max_live_samples * m.n_kv_heads, 1024);
@@ -344,10 +368,120 @@ static void embed_and_norm(rollout_ctx& c, int R) {
   c.timer.end(c.stream);
 }
 
+// Mixture-of-experts feed-forward block: router projection -> top-k routing -> plan of the
+// expert-sorted row blocks -> grouped gate/up projection with SwiGLU -> grouped down
+// projection -> weighted sum of each row's picks + residual + next norm.
+static void moe_block(rollout_ctx& c, LayerWeights& L, int layer, int R, RowNormArgs rn, const float* next_gain) {
+  const rollout_model_desc& m = c.md;
+  hipStream_t s = c.stream;
+  const int d = m.hidden, fe = m.expert_ffn_dim, E = m.n_experts, k = m.top_k;
+  const int picks = R * k;
+  const int z = project(c, c.h_bf16.p, (long long)(c.h_bf16.n / 2), d, L.router_p.p, R, E, d);
+
+  MoeRouteArgs ra{};
+  ra.partial = c.partial.p;
+  ra.split_stride = (long long)R * E;
+  ra.splits = z;
+  ra.rows = R;
+  ra.n_experts = E;
+  ra.top_k = k;
+  ra.idx = c.moe_idx.p;
+  ra.wt = c.moe_wt.p;
+  ra.pos = c.moe_pos.p;
+  ra.count = c.moe_count.p + (size_t)layer * E;
+  ra.route_log = c.route_log.p ? c.route_log.p + (size_t)layer * c.r_max * k : nullptr;
+  c.timer.begin("moe_route_topk_kernel", (double)R * E * 4 * z, 0, s);
+  launch_moe_route_topk(ra, s);
+  c.timer.end(s);
+
+  MoePlanArgs pa{};
+  pa.count = ra.count;
+  pa.idx = c.moe_idx.p;
+  pa.pos = c.moe_pos.p;
+  pa.rows = R;
+  pa.n_experts = E;
+  pa.top_k = k;
+  pa.max_blocks = std::min(c.moe_max_blocks, std::min(E, picks) + picks / kMoeBlockRows + 1);
+  pa.row_map = c.moe_row_map.p;
+  pa.slot_of = c.moe_slot_of.p;
+  pa.group_of_block = c.moe_group_of_block.p;
+  pa.block_row_begin = c.moe_block_begin.p;
+  pa.block_row_end = c.moe_block_end.p;
+  c.timer.begin("moe_plan_kernel", (double)picks * 16, 0, s);
+  launch_moe_plan(pa, s);
+  c.timer.end(s);
+
+  // Expected number of experts with at least one pick under uniform routing: the weight bytes
+  // of the timing records (the true count stays on the device).
+  const double touched = E * (1.0 - std::pow(1.0 - 1.0 / E, (double)picks));
+  GemmPlan pl{};
+  pl.kind = 1;
+  pl.mt = kMoeBlockRows / 16;
+  pl.nt = 2;
+  pl.nw = 4;
+  pl.splits = 1;
+  pl.kc = 2;
+
+  GemmArgs gu{};
+  gu.a = c.h_bf16.p;
+  gu.a_lo = c.h_bf16.p + c.h_bf16.n / 2;
+  gu.w = L.w_gate_up_p.p;
+  gu.out = c.act_bf16.p;
+  gu.out_lo_offset = (long long)(c.act_bf16.n / 2);
+  gu.M = picks;
+  gu.N = 2 * fe;
+  gu.K = d;
+  gu.lda = d;
+  gu.ldo = fe;
+  gu.group_of_block = pa.group_of_block;
+  gu.block_row_begin = pa.block_row_begin;
+  gu.block_row_end = pa.block_row_end;
+  gu.row_map = pa.row_map;
+  gu.group_stride16 = (long long)2 * fe * d * 2 / 16;
+  gu.n_row_blocks = pa.max_blocks;
+  pl.name = "gemm_tile_kernel<4,2,2,1>";
+  c.timer.begin(pl.name, touched * 2.0 * 2 * fe * d + 4.0 * picks * d + 4.0 * picks * fe, 2.0 * picks * 2 * fe * d, s);
+  launch_gemm_bf16(gu, EPI_SWIGLU_BF16, pl, s);
+  c.timer.end(s);
+
+  GemmArgs dn{};
+  dn.a = c.act_bf16.p;
+  dn.a_lo = c.act_bf16.p + c.act_bf16.n / 2;
+  dn.w = L.w_down_p.p;
+  dn.out = c.moe_y.p;
+  dn.M = picks;
+  dn.N = d;
+  dn.K = fe;
+  dn.lda = fe;
+  dn.ldo = d;
+  dn.split_stride = 0;
+  dn.group_of_block = pa.group_of_block;
+  dn.block_row_begin = pa.block_row_begin;
+  dn.block_row_end = pa.block_row_end;
+  dn.group_stride16 = (long long)d * fe * 2 / 16;
+  dn.n_row_blocks = pa.max_blocks;
+  pl.name = "gemm_tile_kernel<4,2,2,0>";
+  c.timer.begin(pl.name, touched * 2.0 * d * fe + 4.0 * picks * fe + 4.0 * picks * d, 2.0 * picks * d * fe, s);
+  launch_gemm_bf16(dn, EPI_F32, pl, s);
+  c.timer.end(s);
+
+  rn.splits = 0;
+  rn.gain = next_gain;
+  rn.moe_y = c.moe_y.p;
+  rn.moe_slot = c.moe_slot_of.p;
+  rn.moe_wt = c.moe_wt.p;
+  rn.moe_k = k;
+  c.timer.begin("row_norm_kernel", (double)R * d * (4 + 4 + 2 + 2 + 4.0 * k), 0, s);
+  launch_row_norm(rn, s);
+  c.timer.end(s);
+}
+
 static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
   const rollout_model_desc& m = c.md;
   hipStream_t s = c.stream;
   const int d = m.hidden, f = m.ffn_dim;
+  if (m.n_experts > 0)  // the per-layer pick counters of the routing kernels start at zero
+    HIP_TRY(hipMemsetAsync(c.moe_count.p, 0, c.moe_count.n * sizeof(int), s));
   embed_and_norm(c, R);
   RowNormArgs rn{};
   rn.x = c.x.p;
@@ -426,11 +560,16 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
     launch_row_norm(rn, s);
     c.timer.end(s);
 
+    const float* next_gain = l + 1 < m.n_layers ? c.layers[l + 1].norm1.p : c.final_norm.p;
+    if (m.n_experts > 0) {
+      moe_block(c, L, l, R, rn, next_gain);
+      continue;
+    }
     gate_up(c, L, R);
 
     z = project(c, c.act_bf16.p, (long long)(c.act_bf16.n / 2), f, L.w_down_p.p, R, d, f);
     rn.splits = z;
-    rn.gain = l + 1 < m.n_layers ? c.layers[l + 1].norm1.p : c.final_norm.p;
+    rn.gain = next_gain;
     c.timer.begin("row_norm_kernel", rn_bytes + 4.0 * z * R * d, 0, s);
     launch_row_norm(rn, s);
     c.timer.end(s);
@@ -556,7 +695,7 @@ void engine_forward_rows(rollout_ctx& c, int rows, const SeqBatch* seqs) {
   if (rows < 1) return;
   c.last_route_rows = rows;
   if (!c.simple) {
-    if (!seqs && rows <= 32)
+    if (!seqs && rows <= 32 && !c.md.n_experts)
       forward_rows_decode(c, rows);
     else
       forward_rows_tiled(c, rows, seqs);

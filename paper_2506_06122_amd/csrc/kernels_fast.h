@@ -73,6 +73,11 @@ struct RowNormArgs {
   const int* rows_index;
   int rows, hidden;
   float eps;
+  // mixture of experts: x[r] += sum_j moe_wt[r][j] * moe_y[moe_slot[r][j]] (picks in order)
+  const float* moe_y = nullptr;    // [slots][hidden]
+  const int* moe_slot = nullptr;   // [rows][moe_k]
+  const float* moe_wt = nullptr;   // [rows][moe_k]
+  int moe_k = 0;
 };
 void launch_row_norm(const RowNormArgs& a, hipStream_t s);
 
@@ -125,3 +130,35 @@ struct AttnArgs {
 void launch_attention_decode(const AttnArgs& a, hipStream_t s);
 void launch_attention_prefill(const AttnArgs& a, hipStream_t s);
 void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s);
+
+// ---- mixture-of-experts block on the matrix-core path ---------------------------------------
+// Routing: sums the split planes of the router projection, picks the top_k experts of every
+// row by (logit descending, expert index ascending), mixes with the softmax over the picked
+// logits, and takes each pick's position inside its expert's list from an integer counter.
+struct MoeRouteArgs {
+  const float* partial;     // [splits][rows][n_experts] router logits (split planes)
+  long long split_stride;
+  int splits;
+  int rows, n_experts, top_k;
+  int* idx;                 // [rows][top_k] expert of pick j
+  float* wt;                // [rows][top_k] mixing weight of pick j
+  int* pos;                 // [rows][top_k] position of the pick inside its expert's list
+  int* count;               // [n_experts], zero on entry: picks per expert
+  int* route_log;           // optional copy of idx (parity hook)
+};
+void launch_moe_route_topk(const MoeRouteArgs& a, hipStream_t s);
+
+// Plan of the grouped projections: expert-sorted slots, cut into row blocks of 64.
+struct MoePlanArgs {
+  const int* count;         // [n_experts]
+  const int* idx;           // [rows * top_k]
+  const int* pos;           // [rows * top_k]
+  int rows, n_experts, top_k, max_blocks;
+  int* row_map;             // [rows * top_k] slot -> source row
+  int* slot_of;             // [rows * top_k] (row, pick) -> slot
+  int* group_of_block;      // [max_blocks]
+  int* block_row_begin;     // [max_blocks]
+  int* block_row_end;       // [max_blocks]; unused blocks get begin = end = 0
+};
+void launch_moe_plan(const MoePlanArgs& a, hipStream_t s);
+constexpr int kMoeBlockRows = 64;

@@ -231,6 +231,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
     m0 = p.block_row_begin[blockIdx.y];
     m_limit = p.block_row_end[blockIdx.y];
     row_map = p.row_map;
+    if (m0 >= m_limit) return;  // unused block of the plan (uniform over the workgroup)
   }
   const uint16_t* a_base = (const uint16_t*)p.a;
   const long long lo_off = (const uint16_t*)p.a_lo - a_base;
@@ -316,7 +317,8 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
     if (m >= m_limit) continue;
 #pragma unroll
     for (int j = 0; j < NT; j += 2)
-      if (nt0 + j + 1 < n_tiles) store_unit<EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z, true);
+      if (nt0 + j < n_tiles)  // an odd last column tile (fp32 results only) is stored alone
+        store_unit<EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z, nt0 + j + 1 < n_tiles);
   }
 }
 

@@ -30,6 +30,9 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
       if (z + 3 < a.splits) p3 = pp[(long long)(z + 3) * a.split_stride];
       x = (((x + p0) + p1) + p2) + p3;
     }
+    for (int j = 0; j < a.moe_k; ++j)
+      x += a.moe_wt[(long long)r * a.moe_k + j] *
+           a.moe_y[(long long)a.moe_slot[(long long)r * a.moe_k + j] * a.hidden + i];
     row_s[i] = x;
     ss += x * x;
   }
@@ -41,7 +44,7 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
   for (int w = 0; w < ROW_T / WAVE; ++w) total += partial[w];
   const float rinv = a.ssq_out ? 1.0f : 1.0f / sqrtf(total / (float)a.hidden + a.eps);
   if (a.ssq_out && t == 0) a.ssq_out[r] = total;
-  const bool write_x = !a.rows_index && (a.splits || a.tokens);
+  const bool write_x = !a.rows_index && (a.splits || a.tokens || a.moe_k);
   for (int i = t; i < a.hidden; i += ROW_T) {
     const float x = row_s[i];
     if (write_x) a.x[(long long)r * a.hidden + i] = x;

@@ -83,7 +83,7 @@ def test_teacher_forced_logits_match_oracle(name, simple):
         assert regret <= TOL[shape.dtype]
     st = eng.rollout_get_stats()
     assert st["live_samples"] == 0 and st["pages_in_use"] == 0
-    assert st["matrix_core_path"] == int(not simple and shape.dtype == "bf16" and not shape.is_moe)
+    assert st["matrix_core_path"] == int(not simple and shape.dtype == "bf16")
     eng.close()
 
 
@@ -144,8 +144,27 @@ def test_large_config_shapes_reduced_depth(which):
     forced = np.random.default_rng(8).integers(0, shape.vocab, (4, 3)).astype(np.int32)
     worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, 2, forced, 3)
     print(f"{shape.name}: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
-    assert eng.rollout_get_stats()["matrix_core_path"] == int(which == "c3-dense")
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
     assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"]
+    eng.close()
+
+
+@pytest.mark.parametrize("n_prompts,n_samples,lo,hi", [(1, 2, 3, 9), (6, 8, 30, 200)], ids=["few-rows", "many-rows"])
+def test_matrix_core_moe_row_blocks(n_prompts, n_samples, lo, hi):
+    """Grouped expert projections: a handful of rows (most experts untouched, one row each) and
+    hundreds of prompt rows / 48 decode rows (several 64-row blocks per expert)."""
+    shape = workloads.SMALL_MOE_BF16
+    w = scaled_weights(shape, seed=1, scale=1.5)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, max_live_samples=64, max_context=512, max_batch_tokens=2048, flags=2)
+    toks, offs = workloads.make_prompts(n_prompts, lo, hi, shape.vocab, seed=21)
+    steps = 3
+    forced = np.random.default_rng(9).integers(0, shape.vocab, (n_prompts * n_samples, steps)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, n_samples, forced, steps)
+    regret = max(model.routing_regret)
+    print(f"max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}, routing regret {regret:.3e}")
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"] and regret <= TOL["bf16"]
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
     eng.close()
 
 
