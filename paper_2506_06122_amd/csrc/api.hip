@@ -595,11 +595,7 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
         c.attn_flops_this_call += 2.0 * len * (len + 1) * c.q_dim;
       }
       engine_forward_rows(c, rows, &sb);
-      for (int off = 0; off < rows; off += c.logit_rows) {
-        int nr = std::min(c.logit_rows, rows - off);
-        engine_logits(c, nullptr, off, nr, c.logits.p);
-        launch_logprob_gather(c.logits.p, c.row_aux.p + off, inv_t, c.out_logprobs.p + off, nr, m.vocab, c.stream);
-      }
+      engine_target_logprobs(c, rows, c.row_aux.p, inv_t, c.out_logprobs.p);
       d2h(c.h_float.p, c.out_logprobs.p, rows * sizeof(float), c.stream);
       HIP_TRY(hipStreamSynchronize(c.stream));
       c.timer.collect();

@@ -199,6 +199,7 @@ struct rollout_ctx {
   // matrix-core path workspaces
   DevBuf<uint16_t> h_bf16, q_bf16, attn_bf16, act_bf16, hn_bf16;
   DevBuf<float> partial, attn_part_o, attn_part_ml;
+  DevBuf<float> lse_max, lse_sum, lse_tgt;  // log-sum-exp parts of the teacher-forced pass, [parts][r_max]
   long long partial_rows = 0;   // capacity of `partial` in rows of partial_ld floats
   int partial_ld = 0;
   int attn_max_parts = 0;       // capacity of attn_part_* in (row, kv head, split) triples
@@ -235,4 +236,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w);
 void engine_forward_rows(rollout_ctx& c, int rows, const SeqBatch* seqs);
 // logits of `n` rows of c.x selected by rows_index (device, or NULL for rows first..first+n) into out
 void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, float* out);
+// out[r] = log-softmax(logits of row r of c.x * inv_t)[target[r]] for rows 0..n-1 (0 where
+// target[r] < 0); target and out are device arrays
+void engine_target_logprobs(rollout_ctx& c, int n, const int* target, float inv_t, float* out);
 void engine_upload_page_table(rollout_ctx& c);

@@ -221,6 +221,12 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     c.attn_part_o.alloc((size_t)c.attn_max_parts * 16 * 128);
     c.attn_part_ml.alloc((size_t)c.attn_max_parts * 32);
     c.ssq.alloc((size_t)(d / 16 + 1) * 256);
+    {
+      const size_t parts = ceil_div(m.vocab / 16, 8);  // the narrowest tile configuration
+      c.lse_max.alloc(parts * R);
+      c.lse_sum.alloc(parts * R);
+      c.lse_tgt.alloc(R);
+    }
     c.seq_row0.alloc(rollout_ctx::kTempSlots);
     c.seq_len.alloc(rollout_ctx::kTempSlots);
     c.seq_slot.alloc(rollout_ctx::kTempSlots);
@@ -758,4 +764,56 @@ void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, floa
   else
     launch_linear_simple<bf16_t>(c.hn.p, d, (const bf16_t*)c.lm_head.p, out, c.md.vocab, nullptr, 0, n,
                                  c.md.vocab, d, c.stream);
+}
+
+// Teacher-forced log-probs without materialising logits (matrix-core path): final norm into
+// the operand planes, then the logits projection with the log-sum-exp epilogue, then one
+// small pass over the per-workgroup parts.  The plain path stores logits chunk by chunk.
+void engine_target_logprobs(rollout_ctx& c, int n, const int* target, float inv_t, float* out) {
+  if (n < 1) return;
+  const int d = c.md.hidden, V = c.md.vocab;
+  if (c.simple) {
+    for (int off = 0; off < n; off += c.logit_rows) {
+      const int nr = std::min(c.logit_rows, n - off);
+      engine_logits(c, nullptr, off, nr, c.logits.p);
+      launch_logprob_gather(c.logits.p, target + off, inv_t, out + off, nr, V, c.stream);
+    }
+    return;
+  }
+  RowNormArgs rn{};
+  rn.x = c.x.p;
+  rn.h = c.h_bf16.p;  // the layers' operand buffer is free after the forward pass
+  rn.h_lo_offset = (long long)(c.h_bf16.n / 2);
+  rn.gain = c.final_norm.p;
+  rn.rows = n;
+  rn.hidden = d;
+  rn.eps = c.md.rms_eps;
+  c.timer.begin("row_norm_kernel", (double)n * d * (4 + 2 + 2), 0, c.stream);
+  launch_row_norm(rn, c.stream);
+  c.timer.end(c.stream);
+  c.h_is_final = false;
+
+  GemmArgs g{};
+  g.a = c.h_bf16.p;
+  g.a_lo = c.h_bf16.p + c.h_bf16.n / 2;
+  g.w = c.lm_head_p.p;
+  g.M = n;
+  g.N = V;
+  g.K = d;
+  g.lda = d;
+  g.lse_target = target;
+  g.lse_scale = inv_t;
+  g.lse_max = c.lse_max.p;
+  g.lse_sum = c.lse_sum.p;
+  g.lse_tgt = c.lse_tgt.p;
+  g.lse_stride = c.r_max;
+  const GemmPlan pl = gemm_plan(n, V, d, EPI_LSE, 1);
+  const int parts = lse_parts(pl, V);
+  // weights and operand planes once; the parts written and read back are the only result traffic
+  c.timer.begin(pl.name, 2.0 * V * d + 4.0 * n * d + 16.0 * parts * n, 2.0 * n * V * d, c.stream);
+  launch_gemm_bf16(g, EPI_LSE, pl, c.stream);
+  c.timer.end(c.stream);
+  c.timer.begin("lse_finish_kernel", 8.0 * parts * n, 0, c.stream);
+  launch_lse_finish(c.lse_max.p, c.lse_sum.p, c.lse_tgt.p, target, parts, c.r_max, n, out, c.stream);
+  c.timer.end(c.stream);
 }

@@ -13,7 +13,12 @@
 //                    ssq_out[workgroup column][m] = sum of x^2 over the workgroup's columns
 // Any stream-kernel epilogue first scales row m by rsqrt(sum_p rinv_ssq[p][m] / K + eps) when
 // rinv_ssq is given: the second half of the RMSNorm of the projection's input.
-enum { EPI_F32 = 0, EPI_SWIGLU_BF16 = 1, EPI_RESID = 2 };
+//   EPI_LSE          tile kernel only, the teacher-forced log-prob pass: the result z = out *
+//                    lse_scale never reaches memory; per (workgroup column, row) the kernel
+//                    stores max z and sum exp(z - max) over the workgroup's columns, and the
+//                    workgroup that owns column lse_target[m] stores that z (launch_lse_finish
+//                    turns these into log-probs)
+enum { EPI_F32 = 0, EPI_SWIGLU_BF16 = 1, EPI_RESID = 2, EPI_LSE = 3 };
 
 struct GemmArgs {
   const void* a;     // bf16 [rows][K], row stride lda: hi parts of the activations
@@ -44,6 +49,13 @@ struct GemmArgs {
   const int* row_map = nullptr;
   long long group_stride16 = 0;  // 16-byte units between consecutive groups' packed weights
   int n_row_blocks = 0;
+  // EPI_LSE
+  const int* lse_target = nullptr;  // [M] target column of row m, or -1
+  float lse_scale = 1.f;            // 1 / temperature
+  float* lse_max = nullptr;         // [grid columns][lse_stride]
+  float* lse_sum = nullptr;         // [grid columns][lse_stride]
+  float* lse_tgt = nullptr;         // [M]
+  int lse_stride = 0;
 };
 
 // How one projection is launched: kind 0 = gemm_stream_kernel (rows <= 256), 1 = gemm_tile_kernel.
@@ -52,6 +64,12 @@ struct GemmPlan {
   const char* name;  // kernel name as a profiler shows it (without the argument list)
 };
 GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits);
+GemmPlan gemm_plan_tiled(int M, int N, int K, int epi, int max_splits);  // the tile kernel for any M
+// column parts per row that an EPI_LSE launch with this plan writes
+inline int lse_parts(const GemmPlan& pl, int N) { return ceil_div(N >> 4, 4 * pl.nt); }
+// out[m] = lse_tgt[m] - log sum_n exp(z[m][n]) from the parts of an EPI_LSE launch; 0 where target < 0
+void launch_lse_finish(const float* lse_max, const float* lse_sum, const float* lse_tgt, const int* target,
+                       int parts, int stride, int rows, float* out, hipStream_t s);
 // returns the number of split planes written (EPI_F32; <= plan.splits)
 int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& plan, hipStream_t s);
 void launch_pack_weight(const void* src, void* dst, int N, int K, int tile_offset, int tile_stride, hipStream_t s);

@@ -310,6 +310,55 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
     }
     __syncthreads();
   }
+  if constexpr (EPI == EPI_LSE) {
+    // log-sum-exp parts of this workgroup's columns: per wavefront over its NT tiles (the 4
+    // lanes of a row meet by shuffles), then over the 4 wavefronts through LDS
+    __shared__ float part_m[4][MT * 16], part_s[4][MT * 16];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int m = m0 + i * 16 + r;
+      const int tgt = m < m_limit ? p.lse_target[m] : -1;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        if (nt0 + j < n_tiles) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[i][j][e] *= p.lse_scale;
+            mx = fmaxf(mx, acc[i][j][e]);
+            if ((nt0 + j) * 16 + g * 4 + e == tgt) p.lse_tgt[m] = acc[i][j][e];
+          }
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      float sm = 0.f;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        if (nt0 + j < n_tiles) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sm += expf(acc[i][j][e] - mx);
+        }
+      sm += __shfl_xor(sm, 16, WAVE);
+      sm += __shfl_xor(sm, 32, WAVE);
+      if (g == 0) {
+        part_m[wave][i * 16 + r] = mx;
+        part_s[wave][i * 16 + r] = sm;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x < MT * 16 && m0 + (int)threadIdx.x < m_limit) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) mx = fmaxf(mx, part_m[w][threadIdx.x]);
+      float sm = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        if (part_m[w][threadIdx.x] > -INFINITY) sm += part_s[w][threadIdx.x] * expf(part_m[w][threadIdx.x] - mx);
+      p.lse_max[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = mx;
+      p.lse_sum[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = sm;
+    }
+    return;
+  }
   if (nt0 >= n_tiles) return;
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
@@ -318,7 +367,8 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NT; j += 2)
       if (nt0 + j < n_tiles)  // an odd last column tile (fp32 results only) is stored alone
-        store_unit<EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z, nt0 + j + 1 < n_tiles);
+        store_unit<EPI == EPI_LSE ? EPI_F32 : EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z,
+                                                  nt0 + j + 1 < n_tiles);
   }
 }
 
@@ -349,38 +399,43 @@ static const char* stream_name(int mt, int nt, int nw, int epi) {
   return names[mt == 1 ? 0 : mt == 2 ? 1 : 2][nt - 1][nw == 4 ? 0 : 1][epi];
 }
 
-GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
+// tiled kernel: the largest tile that still gives every CU a workgroup, then split-K planes
+GemmPlan gemm_plan_tiled(int M, int N, int K, int epi, int max_splits) {
   GemmPlan pl{};
   const int n_tiles = N >> 4, k_tiles = K >> 5;
-  if (M > 32) {
-    // tiled kernel: the largest tile that still gives every CU a workgroup, then split-K planes
-    pl.kind = 1;
-    pl.nw = 4;
-    static const int cfg[3][2] = {{8, 4}, {4, 4}, {4, 2}};
-    static const char* const names[3][2] = {{"gemm_tile_kernel<8,4,2,0>", "gemm_tile_kernel<8,4,2,1>"},
-                                            {"gemm_tile_kernel<4,4,2,0>", "gemm_tile_kernel<4,4,2,1>"},
-                                            {"gemm_tile_kernel<4,2,2,0>", "gemm_tile_kernel<4,2,2,1>"}};
-    int pick = 2;
-    long long blocks = 0;
-    for (int c = 0; c < 3; ++c) {
-      blocks = (long long)ceil_div(M, 16 * cfg[c][0]) * ceil_div(n_tiles, 4 * cfg[c][1]);
-      if (blocks >= 256 || c == 2) {
-        pick = c;
-        break;
-      }
+  pl.kind = 1;
+  pl.nw = 4;
+  static const int cfg[3][2] = {{8, 4}, {4, 4}, {4, 2}};
+  static const char* const names[3][3] = {
+      {"gemm_tile_kernel<8,4,2,0>", "gemm_tile_kernel<8,4,2,1>", "gemm_tile_kernel<8,4,2,3>"},
+      {"gemm_tile_kernel<4,4,2,0>", "gemm_tile_kernel<4,4,2,1>", "gemm_tile_kernel<4,4,2,3>"},
+      {"gemm_tile_kernel<4,2,2,0>", "gemm_tile_kernel<4,2,2,1>", "gemm_tile_kernel<4,2,2,3>"}};
+  int pick = 2;
+  long long blocks = 0;
+  for (int c = 0; c < 3; ++c) {
+    blocks = (long long)ceil_div(M, 16 * cfg[c][0]) * ceil_div(n_tiles, 4 * cfg[c][1]);
+    if (blocks >= 256 || c == 2) {
+      pick = c;
+      break;
     }
-    pl.mt = cfg[pick][0];
-    pl.nt = cfg[pick][1];
-    pl.kc = 2;
-    pl.splits = 1;
-    if (epi == EPI_F32 && blocks < 256) {
-      int z = (int)((768 + blocks - 1) / blocks);
-      z = std::min(z, std::max(1, k_tiles / 8));
-      pl.splits = std::max(1, std::min(z, max_splits));
-    }
-    pl.name = names[pick][epi == EPI_F32 ? 0 : 1];
-    return pl;
   }
+  pl.mt = cfg[pick][0];
+  pl.nt = cfg[pick][1];
+  pl.kc = 2;
+  pl.splits = 1;
+  if (epi == EPI_F32 && blocks < 256) {
+    int z = (int)((768 + blocks - 1) / blocks);
+    z = std::min(z, std::max(1, k_tiles / 8));
+    pl.splits = std::max(1, std::min(z, max_splits));
+  }
+  pl.name = names[pick][epi == EPI_F32 ? 0 : epi == EPI_SWIGLU_BF16 ? 1 : 2];
+  return pl;
+}
+
+GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
+  if (M > 32 || epi == EPI_LSE) return gemm_plan_tiled(M, N, K, epi, max_splits);
+  GemmPlan pl{};
+  const int n_tiles = N >> 4, k_tiles = K >> 5;
   pl.kind = 0;
   pl.mt = M <= 16 ? 1 : M <= 32 ? 2 : 4;
   const int m_blocks = ceil_div(M, 16 * pl.mt);
@@ -401,6 +456,13 @@ GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
   return pl;
 }
 
+template <int MT, int NT>
+static void launch_tile(const GemmArgs& a, int epi, dim3 grid, hipStream_t s) {
+  if (epi == EPI_F32) gemm_tile_kernel<MT, NT, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
+  else if (epi == EPI_SWIGLU_BF16) gemm_tile_kernel<MT, NT, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+  else gemm_tile_kernel<MT, NT, 2, EPI_LSE><<<grid, 256, 0, s>>>(a);
+}
+
 template <int MT, int KU>
 static void launch_stream_mt(const GemmArgs& a, int epi, const GemmPlan& pl, dim3 grid, hipStream_t s) {
   if (pl.nt == 1 && pl.nw == 4) launch_stream<MT, 1, KU, 4>(a, epi, grid, s);
@@ -418,17 +480,9 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
     a.k_tiles_per_split = per;
     const int m_blocks = a.group_of_block ? a.n_row_blocks : ceil_div(a.M, 16 * pl.mt);
     dim3 grid(ceil_div(n_tiles, 4 * pl.nt), m_blocks, splits);
-    const bool f32 = epi == EPI_F32;
-    if (pl.mt == 8) {
-      if (f32) gemm_tile_kernel<8, 4, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
-      else gemm_tile_kernel<8, 4, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
-    } else if (pl.nt == 4) {
-      if (f32) gemm_tile_kernel<4, 4, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
-      else gemm_tile_kernel<4, 4, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
-    } else {
-      if (f32) gemm_tile_kernel<4, 2, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
-      else gemm_tile_kernel<4, 2, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
-    }
+    if (pl.mt == 8) launch_tile<8, 4>(a, epi, grid, s);
+    else if (pl.nt == 4) launch_tile<4, 4>(a, epi, grid, s);
+    else launch_tile<4, 2>(a, epi, grid, s);
     return splits;
   }
   int per = ceil_div(k_tiles, epi == EPI_F32 ? pl.splits : 1);
@@ -439,6 +493,36 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
   else if (pl.mt == 2) launch_stream_mt<2, 4>(a, epi, pl, grid, s);
   else launch_stream_mt<4, 2>(a, epi, pl, grid, s);
   return splits;
+}
+
+// ---------------------------------------------------------------- log-prob from the parts
+// one thread per row; parts are [part][row], so a wavefront reads 64 consecutive rows
+__global__ __launch_bounds__(256) void lse_finish_kernel(const float* __restrict__ lse_max,
+                                                         const float* __restrict__ lse_sum,
+                                                         const float* __restrict__ lse_tgt,
+                                                         const int* __restrict__ target, int parts, int stride,
+                                                         int rows, float* __restrict__ out) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r >= rows) return;
+  if (target[r] < 0) {
+    out[r] = 0.f;
+    return;
+  }
+  float mx = -INFINITY, sm = 0.f;
+  for (int q = 0; q < parts; ++q) {
+    const float pm = lse_max[(long long)q * stride + r], ps = lse_sum[(long long)q * stride + r];
+    if (pm > mx) {
+      sm = sm * expf(mx - pm) + ps;  // exp(-inf) = 0 on the first part
+      mx = pm;
+    } else if (pm > -INFINITY) {
+      sm += ps * expf(pm - mx);
+    }
+  }
+  out[r] = lse_tgt[r] - mx - logf(sm);
+}
+void launch_lse_finish(const float* lse_max, const float* lse_sum, const float* lse_tgt, const int* target,
+                       int parts, int stride, int rows, float* out, hipStream_t s) {
+  if (rows) lse_finish_kernel<<<ceil_div(rows, 256), 256, 0, s>>>(lse_max, lse_sum, lse_tgt, target, parts, stride, rows, out);
 }
 
 // ---------------------------------------------------------------- weight re-ordering

@@ -208,11 +208,15 @@ def test_c1_full_config_rollout():
 
 
 def test_teacher_forced_logprob_pass_matches_oracle():
-    for shape, scale in ((workloads.C1_TINY, 1.0), (workloads.SMALL_BF16, 1.0), (workloads.TINY_MOE_FP32, 6.0)):
+    cases = ((workloads.C1_TINY, 1.0, 96, (7, 1, 90)), (workloads.SMALL_BF16, 1.0, 96, (7, 1, 90)),
+             (workloads.TINY_MOE_FP32, 6.0, 96, (7, 1, 90)), (workloads.SMALL_MOE_BF16, 1.5, 96, (7, 1, 90)),
+             # one chunk of about 2000 rows: the widest tile configuration of the fused log-sum-exp
+             (workloads.SMALL_BF16, 1.0, 2048, (12, 40, 300)))
+    for shape, scale, chunk, (n_seqs, lo, hi) in cases:
         w = scaled_weights(shape, seed=1, scale=scale)
         model = oracle_model(shape, w)
-        eng = make_engine(shape, w, max_batch_tokens=96)                      # forces several chunks
-        toks, cu = workloads.packed_sequences(7, 1, 90, shape.vocab, seed=6)
+        eng = make_engine(shape, w, max_batch_tokens=chunk)                   # 96 forces several chunks
+        toks, cu = workloads.packed_sequences(n_seqs, lo, hi, shape.vocab, seed=6)
         got = eng.rollout_logprobs(toks, cu, temperature=0.8)
         want = T.packed_log_probs(model, toks, cu, temperature=float(np.float32(1) / sampler.inv_temperature(0.8)))
         err = float(np.max(np.abs(got - want)))
