@@ -1,14 +1,22 @@
 """Rollout throughput on one MI355X.
 
-A "step" is one whole generation job of the workload: prefill of every prompt, then decode
-steps until every sample has finished (inputs and weights already resident in HBM).
-Prints one JSON line: output tokens/s, the roofline of the kernel that took the most time
-(HIP-event timings gathered by the library on its own stream during the timed steps), and
-the CPU oracle timed on a bounded slice of the same workload.
+A "step" is one whole job of the workload with inputs and weights already resident in HBM:
+for the rollout workloads, prefill of every prompt and then decode steps until every sample
+has finished; for the teacher-forced workload, one log-prob pass over the packed batch.
+Prints one JSON line: tokens/s, the roofline of the kernel that took the most time (HIP-event
+timings gathered by the library on its own stream during the timed steps), and the CPU
+oracle timed on a bounded slice of the same workload.
+
+The default workload is the one the headline metric is quoted on (Qwen2.5-1.5B shape, 32
+prompts x 8 samples).  The others measure the remaining parts of the path at their real
+matrix shapes: a 7B-shape dense rollout, a 30B-A3B-shape mixture-of-experts rollout and the
+teacher-forced pass on the 7B shape; --layers and --prompts cut them down for quick runs and
+the JSON line says so.
 """
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -55,6 +63,66 @@ def cpu_baseline(shape, weights, load) -> dict:
             "sample": f"{shape.name}: 1 prompt x 256 tokens prefill, 4 samples x 64 new tokens, fp64, {dt:.1f} s"}
 
 
+def cpu_baseline_logprobs(shape, weights, tokens) -> dict:
+    """The oracle's teacher-forced pass on one 192-token sequence of the same batch."""
+    from threadpoolctl import threadpool_info
+    from oracle import transformer as T
+    model = T.Model(shape, weights)
+    for name in weights:
+        model.w(name)
+    toks = tokens[:192]
+    t0 = time.perf_counter()
+    T.packed_log_probs(model, toks, np.array([0, len(toks)]))
+    dt = time.perf_counter() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": len(toks) / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{shape.name}: one 192-token sequence, fp64, {dt:.1f} s"}
+
+
+def kernel_table(eng, before):
+    """Per-kernel deltas of the library's event timings since `before`; the cost of an empty
+    event bracket (recorded by the library in every timed decode step) is taken off each launch."""
+    kernels = []
+    for k in eng.rollout_kernel_stats():
+        b = before.get(k["name"], dict(launches=0, ms=0.0, bytes=0.0, flops=0.0))
+        n = k["launches"] - b["launches"]
+        if n:
+            kernels.append(dict(name=k["name"], launches=n, ms=k["ms"] - b["ms"], bytes=k["bytes"] - b["bytes"],
+                                flops=k["flops"] - b["flops"]))
+    empty = [k for k in kernels if k["name"] == "(empty bracket)"]
+    kernels = [k for k in kernels if k["name"] != "(empty bracket)"]
+    bracket_ms = empty[0]["ms"] / empty[0]["launches"] if empty else 0.0
+    for k in kernels:
+        k["raw_ms"] = k["ms"]
+        k["ms"] = max(k["ms"] - k["launches"] * bracket_ms, 1e-9)
+    kernels.sort(key=lambda k: -k["ms"])
+    return kernels, bracket_ms
+
+
+def roofline_of(kernels, bracket_ms):
+    if not kernels:
+        return None
+    top = kernels[0]
+    ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if top["flops"] / max(top["bytes"], 1.0) >= ridge:
+        ach = top["flops"] / (top["ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    else:
+        ach = top["bytes"] / (top["ms"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": ach / HBM_PEAK_GBS, "traffic": None}
+    roofline["kernel"] = top["name"]
+    roofline["avg_launch_us"] = 1e3 * top["ms"] / top["launches"]
+    roofline["timed_launches"] = top["launches"]
+    roofline["event_bracket_us"] = 1e3 * bracket_ms
+    roofline["per_kernel"] = [
+        {"name": k["name"], "launches": k["launches"], "avg_us": 1e3 * k["ms"] / k["launches"],
+         "GB/s": k["bytes"] / (k["ms"] * 1e-3) / 1e9, "TFLOP/s": k["flops"] / (k["ms"] * 1e-3) / 1e12}
+        for k in kernels]
+    return roofline
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,7 +131,11 @@ def main() -> int:
     ap.add_argument("--timing-stride", type=int, default=16,
                     help="bracket kernels with HIP events on every n-th library call (0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--prompts", type=int, default=32, help="smaller values only for quick checks")
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5"], default="c2",
+                    help="c2 = headline (1.5B shape); c3 = 7B-shape rollout; c4 = 30B-A3B-shape MoE rollout; "
+                         "c5 = teacher-forced log-prob pass on the 7B shape")
+    ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
+    ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 256 MiB read+write kernels (a known-size reference for byte counters)")
     args = ap.parse_args()
@@ -85,89 +157,86 @@ def main() -> int:
             torch.mul(src, 2.0, out=dst)   # one elementwise kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
-    shape = workloads.C2_1P5B
-    load = workloads.load_c2(n_prompts=args.prompts)
+
+    wl = args.workload
+    shape = {"c2": workloads.C2_1P5B, "c3": workloads.C3_7B, "c4": workloads.C4_30B_A3B, "c5": workloads.C3_7B}[wl]
+    cut = ""
+    if args.layers and args.layers < shape.n_layers:
+        cut = f", cut to {args.layers} of {shape.n_layers} layers"
+        shape = dataclasses.replace(shape, n_layers=args.layers)
     t0 = time.perf_counter()
     weights = workloads.make_weights(shape, seed=1, gains="ones")
     print(f"# weights generated in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
-
-    max_prompt = int(np.diff(load.prompt_offsets).max())
     flags = B.RT_KERNEL_TIMING if args.timing_stride > 0 else 0
-    eng = R.Rollout(shape, weights, kv_pool_bytes=12 << 30, page_tokens=32,
-                    max_live_samples=load.n_prompts * load.n_samples,
-                    max_context=max_prompt + int(load.max_new_tokens.max()),
-                    max_batch_tokens=max(16384, max_prompt), seed=load.sampler_seed, flags=flags,
-                    timing_stride=max(args.timing_stride, 1))
+    kv_bytes_per_token = shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 2
+
+    if wl == "c5":
+        n_seqs = args.prompts or 24
+        tokens, cu = workloads.packed_sequences(n_seqs, 512, 8192, shape.vocab, seed=2)
+        chunk = 16384
+        eng = R.Rollout(shape, weights, kv_pool_bytes=(chunk + 8192 + 64 * 32) * kv_bytes_per_token, page_tokens=32,
+                        max_live_samples=8, max_context=8192, max_batch_tokens=chunk, seed=3, flags=flags,
+                        timing_stride=1)
+        work = lambda: (eng.rollout_logprobs(tokens, cu, temperature=1.0), len(tokens))[1]
+        desc = ("configs[4]: teacher-forced log-prob pass, Qwen2.5-7B-shaped dense decoder, bf16, %d packed sequences "
+                "(of the config's 512), length U{512..8192}, %d tokens%s" % (n_seqs, len(tokens), cut))
+        load = None
+    else:
+        loader = {"c2": workloads.load_c2, "c3": workloads.load_c3, "c4": workloads.load_c4}[wl]
+        load = loader(n_prompts=args.prompts) if args.prompts else loader()
+        max_prompt = int(np.diff(load.prompt_offsets).max())
+        # every sample's pages are taken at admission: prompt pages once per prompt, the rest per sample
+        need = int(np.diff(load.prompt_offsets).sum()) + int(load.max_new_tokens.sum()) + \
+            64 * load.n_prompts * load.n_samples
+        eng = R.Rollout(shape, weights, kv_pool_bytes=max(need * kv_bytes_per_token, 1 << 30), page_tokens=32,
+                        max_live_samples=load.n_prompts * load.n_samples,
+                        max_context=max_prompt + int(load.max_new_tokens.max()),
+                        max_batch_tokens=max(16384, max_prompt), seed=load.sampler_seed, flags=flags,
+                        timing_stride=max(args.timing_stride, 1))
+        work = lambda: run_job(eng, load)
+        names = {"c2": "configs[1]: Qwen2.5-1.5B-shaped dense decoder, bf16, %d prompts x %d samples, prompt 64-512, "
+                       "response geometric(mean 512) capped 2048, T=1.0 top-p=1.0",
+                 "c3": "configs[2]: Qwen2.5-7B-shaped dense decoder, bf16, %d prompts x %d samples, prompt 128-1024, "
+                       "response log-normal(median 1024, sigma 1) capped 8192, T=0.99 top-p=1.0",
+                 "c4": "configs[3]: Qwen3-30B-A3B-shaped mixture of experts (128 experts, top-8), bf16, %d prompts x %d "
+                       "samples, prompt 128-1024, response log-normal(median 2048, sigma 1) capped 16384, T=1.0 top-p=1.0"}
+        desc = names[wl] % (load.n_prompts, load.n_samples) + cut
     assert eng.rollout_get_stats()["matrix_core_path"] == 1
     print("# engine ready", file=sys.stderr, flush=True)
 
     for _ in range(args.warmup):
-        run_job(eng, load)
+        work()
     torch.cuda.synchronize()
     before = {k["name"]: k for k in eng.rollout_kernel_stats()}
+    calls0 = int(eng.rollout_get_stats()["decode_steps"])
     t0 = time.perf_counter()
     emitted = 0
     for _ in range(args.steps):
-        emitted += run_job(eng, load)
+        emitted += work()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     stats = eng.rollout_get_stats()
-
-    kernels = []
-    for k in eng.rollout_kernel_stats():
-        b = before.get(k["name"], dict(launches=0, ms=0.0, bytes=0.0, flops=0.0))
-        n = k["launches"] - b["launches"]
-        if n:
-            kernels.append(dict(name=k["name"], launches=n, ms=k["ms"] - b["ms"], bytes=k["bytes"] - b["bytes"],
-                                flops=k["flops"] - b["flops"]))
-    # Two event records around nothing still measure a few microseconds: the library records
-    # such an empty bracket in every timed decode step, and its mean is taken off every launch.
-    empty = [k for k in kernels if k["name"] == "(empty bracket)"]
-    kernels = [k for k in kernels if k["name"] != "(empty bracket)"]
-    bracket_ms = empty[0]["ms"] / empty[0]["launches"] if empty else 0.0
-    for k in kernels:
-        k["raw_ms"] = k["ms"]
-        k["ms"] = max(k["ms"] - k["launches"] * bracket_ms, 1e-9)
-    kernels.sort(key=lambda k: -k["ms"])
-    roofline = None
-    if kernels:
-        top = kernels[0]
-        ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
-        if top["flops"] / max(top["bytes"], 1.0) >= ridge:
-            ach = top["flops"] / (top["ms"] * 1e-3) / 1e12
-            roofline = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
-        else:
-            ach = top["bytes"] / (top["ms"] * 1e-3) / 1e9
-            roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": ach / HBM_PEAK_GBS, "traffic": None}
-        roofline["kernel"] = top["name"]
-        roofline["avg_launch_us"] = 1e3 * top["ms"] / top["launches"]
-        roofline["timed_launches"] = top["launches"]
-        roofline["event_bracket_us"] = 1e3 * bracket_ms
-        roofline["per_kernel"] = [
-            {"name": k["name"], "launches": k["launches"], "avg_us": 1e3 * k["ms"] / k["launches"],
-             "GB/s": k["bytes"] / (k["ms"] * 1e-3) / 1e9, "TFLOP/s": k["flops"] / (k["ms"] * 1e-3) / 1e12}
-            for k in kernels]
+    kernels, bracket_ms = kernel_table(eng, before)
 
     out = {
-        "metric": "rollout output tokens/sec on 1 MI355X", "value": emitted / dt, "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / args.steps,
+        "metric": "rollout output tokens/sec on 1 MI355X" if wl != "c5" else "teacher-forced tokens/sec on 1 MI355X",
+        "value": emitted / dt, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt / max(args.steps, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "configs[1]: Qwen2.5-1.5B-shaped dense decoder, bf16, %d prompts x %d samples, "
-                               "prompt 64-512, response geometric(mean 512) capped 2048, T=1.0 top-p=1.0"
-                               % (load.n_prompts, load.n_samples),
+        "config": {"workload": desc,
                    "output_tokens_per_step": emitted // max(args.steps, 1),
-                   "decode_calls_per_step": int(stats["decode_steps"]) // (args.steps + args.warmup)},
-        "roofline": roofline,
+                   "decode_calls_per_step": (int(stats["decode_steps"]) - calls0) // max(args.steps, 1)},
+        "roofline": roofline_of(kernels, bracket_ms),
     }
     eng.close()
     del eng
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shape, weights, load)
-    else:
+    if args.no_cpu_baseline:
         out["cpu_baseline"] = None
+    elif wl == "c5":
+        out["cpu_baseline"] = cpu_baseline_logprobs(shape, weights, tokens)
+    else:
+        out["cpu_baseline"] = cpu_baseline(shape, weights, load)
     print(json.dumps(out))
     return 0
 

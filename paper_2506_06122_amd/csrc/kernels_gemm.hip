@@ -205,10 +205,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
 // ------------------------------------------------------------------------------------------
 // Tiled kernel: a workgroup of 4 wavefronts computes MT*16 rows x 4*NT*16 columns; each
 // wavefront owns NT column tiles and reads its weight fragments straight from memory, the
-// activation fragments (hi and lo planes) of KC k-tiles are staged in LDS for all four.
-// Double-buffered: while one stage is multiplied, the next stage's activations and weights
-// are already in flight (registers), and are written to the other LDS buffer afterwards.
-template <int MT, int NT, int KC, int EPI>
+// activation fragments (hi and lo planes) of KC k-tiles (one stage) are staged in LDS for all
+// four.  D stages of loads are kept in flight in a register ring; a stage's activations move to
+// one of two LDS buffers and its weights to the multiply operands just before the ring slot is
+// refilled with the stage D ahead.  (Measured: the small tiles run best with D = 1 and three
+// workgroups per CU, the 128 x 256 tile, alone on its CU, with single k-tile stages and D = 3.)
+// One barrier per stage: a wavefront reaches the barrier of stage s only after its reads of
+// stage s-1's buffer, which stage s+1 overwrites.
+template <int MT, int NT, int KC, int D, int EPI>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
   constexpr int FR = 2 * MT * KC;      // activation fragments per stage: [kk][plane][mt]
   constexpr int PER = (FR + 3) / 4;    // fragments each wavefront stages
@@ -258,57 +262,61 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  uint4 st[PER];
-  Frag bc[KC][NT], bn[KC][NT];
-  auto load_stage = [&](int kt, Frag (&b)[KC][NT]) {
+  struct Stage {
+    uint4 st[PER];
+    Frag b[KC][NT];
+  };
+  Stage ring[D];
+  Frag cur[KC][NT];
+  auto load_stage = [&](int kt, Stage& sg) {
 #pragma unroll
     for (int s = 0; s < PER; ++s) {
       const int kk = (wave + 4 * s) / (2 * MT);
-      st[s] = make_uint4(0, 0, 0, 0);
-      if (st_src[s] && kt + kk < kt_end) st[s] = *(const uint4*)(st_src[s] + (long long)kt * 32);
+      sg.st[s] = make_uint4(0, 0, 0, 0);
+      if (st_src[s] && kt + kk < kt_end) sg.st[s] = *(const uint4*)(st_src[s] + (long long)kt * 32);
     }
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
-        b[kk][j].u = make_uint4(0, 0, 0, 0);
-        if (kt + kk < kt_end && nt0 + j < n_tiles) b[kk][j].u = wp[((long long)(nt0 + j) * k_tiles + kt + kk) * 64 + lane];
+        sg.b[kk][j].u = make_uint4(0, 0, 0, 0);
+        if (kt + kk < kt_end && nt0 + j < n_tiles)
+          sg.b[kk][j].u = wp[((long long)(nt0 + j) * k_tiles + kt + kk) * 64 + lane];
       }
-  };
-  auto store_stage = [&](int buf) {
-#pragma unroll
-    for (int s = 0; s < PER; ++s)
-      if (wave + 4 * s < FR) a_lds[buf][(wave + 4 * s) * 64 + lane] = st[s];
   };
 
-  load_stage(kt_begin, bc);
-  store_stage(0);
-  __syncthreads();
+#pragma unroll
+  for (int d = 0; d < D; ++d) load_stage(kt_begin + d * KC, ring[d]);
   int buf = 0;
-  for (int kt = kt_begin; kt < kt_end; kt += KC, buf ^= 1) {
-    const bool more = kt + KC < kt_end;
-    if (more) load_stage(kt + KC, bn);
+  for (int kt = kt_begin; kt < kt_end; kt += D * KC) {
 #pragma unroll
-    for (int kk = 0; kk < KC; ++kk)
+    for (int d = 0; d < D; ++d) {
+      const int k0 = kt + d * KC;
+      if (k0 >= kt_end) break;  // uniform over the workgroup
 #pragma unroll
-      for (int plane = 1; plane >= 0; --plane) {  // lo parts first, then hi
-        Frag a[MT];
-#pragma unroll
-        for (int i = 0; i < MT; ++i) a[i].u = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + lane];
-#pragma unroll
-        for (int i = 0; i < MT; ++i)
-#pragma unroll
-          for (int j = 0; j < NT; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bc[kk][j].v, a[i].v, acc[i][j], 0, 0, 0);
-      }
-    if (more) {
-      store_stage(buf ^ 1);
+      for (int s = 0; s < PER; ++s)
+        if (wave + 4 * s < FR) a_lds[buf][(wave + 4 * s) * 64 + lane] = ring[d].st[s];
 #pragma unroll
       for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
-        for (int j = 0; j < NT; ++j) bc[kk][j] = bn[kk][j];
+        for (int j = 0; j < NT; ++j) cur[kk][j] = ring[d].b[kk][j];
+      load_stage(k0 + D * KC, ring[d]);
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+        for (int plane = 1; plane >= 0; --plane) {  // lo parts first, then hi
+          Frag a[MT];
+#pragma unroll
+          for (int i = 0; i < MT; ++i) a[i].u = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + lane];
+#pragma unroll
+          for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur[kk][j].v, a[i].v, acc[i][j], 0, 0, 0);
+        }
+      buf ^= 1;
     }
-    __syncthreads();
   }
   if constexpr (EPI == EPI_LSE) {
     // log-sum-exp parts of this workgroup's columns: per wavefront over its NT tiles (the 4
@@ -407,9 +415,9 @@ GemmPlan gemm_plan_tiled(int M, int N, int K, int epi, int max_splits) {
   pl.nw = 4;
   static const int cfg[3][2] = {{8, 4}, {4, 4}, {4, 2}};
   static const char* const names[3][3] = {
-      {"gemm_tile_kernel<8,4,2,0>", "gemm_tile_kernel<8,4,2,1>", "gemm_tile_kernel<8,4,2,3>"},
-      {"gemm_tile_kernel<4,4,2,0>", "gemm_tile_kernel<4,4,2,1>", "gemm_tile_kernel<4,4,2,3>"},
-      {"gemm_tile_kernel<4,2,2,0>", "gemm_tile_kernel<4,2,2,1>", "gemm_tile_kernel<4,2,2,3>"}};
+      {"gemm_tile_kernel<8,4,1,3,0>", "gemm_tile_kernel<8,4,1,3,1>", "gemm_tile_kernel<8,4,1,3,3>"},
+      {"gemm_tile_kernel<4,4,2,1,0>", "gemm_tile_kernel<4,4,2,1,1>", "gemm_tile_kernel<4,4,2,1,3>"},
+      {"gemm_tile_kernel<4,2,2,1,0>", "gemm_tile_kernel<4,2,2,1,1>", "gemm_tile_kernel<4,2,2,1,3>"}};
   int pick = 2;
   long long blocks = 0;
   for (int c = 0; c < 3; ++c) {
@@ -456,11 +464,11 @@ GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
   return pl;
 }
 
-template <int MT, int NT>
+template <int MT, int NT, int KC, int D>
 static void launch_tile(const GemmArgs& a, int epi, dim3 grid, hipStream_t s) {
-  if (epi == EPI_F32) gemm_tile_kernel<MT, NT, 2, EPI_F32><<<grid, 256, 0, s>>>(a);
-  else if (epi == EPI_SWIGLU_BF16) gemm_tile_kernel<MT, NT, 2, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
-  else gemm_tile_kernel<MT, NT, 2, EPI_LSE><<<grid, 256, 0, s>>>(a);
+  if (epi == EPI_F32) gemm_tile_kernel<MT, NT, KC, D, EPI_F32><<<grid, 256, 0, s>>>(a);
+  else if (epi == EPI_SWIGLU_BF16) gemm_tile_kernel<MT, NT, KC, D, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+  else gemm_tile_kernel<MT, NT, KC, D, EPI_LSE><<<grid, 256, 0, s>>>(a);
 }
 
 template <int MT, int KU>
@@ -480,9 +488,9 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
     a.k_tiles_per_split = per;
     const int m_blocks = a.group_of_block ? a.n_row_blocks : ceil_div(a.M, 16 * pl.mt);
     dim3 grid(ceil_div(n_tiles, 4 * pl.nt), m_blocks, splits);
-    if (pl.mt == 8) launch_tile<8, 4>(a, epi, grid, s);
-    else if (pl.nt == 4) launch_tile<4, 4>(a, epi, grid, s);
-    else launch_tile<4, 2>(a, epi, grid, s);
+    if (pl.mt == 8) launch_tile<8, 4, 1, 3>(a, epi, grid, s);
+    else if (pl.nt == 4) launch_tile<4, 4, 2, 1>(a, epi, grid, s);
+    else launch_tile<4, 2, 2, 1>(a, epi, grid, s);
     return splits;
   }
   int per = ceil_div(k_tiles, epi == EPI_F32 ? pl.splits : 1);
