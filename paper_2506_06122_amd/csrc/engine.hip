@@ -445,7 +445,7 @@ static void moe_block(rollout_ctx& c, LayerWeights& L, int layer, int R, RowNorm
   gu.row_map = pa.row_map;
   gu.group_stride16 = (long long)2 * fe * d * 2 / 16;
   gu.n_row_blocks = pa.max_blocks;
-  pl.name = "gemm_tile_kernel<4,2,2,1,1>";
+  pl.name = "gemm_tile_ring_kernel<4,2,2,1,1>";
   c.timer.begin(pl.name, touched * 2.0 * 2 * fe * d + 4.0 * picks * d + 4.0 * picks * fe, 2.0 * picks * 2 * fe * d, s);
   launch_gemm_bf16(gu, EPI_SWIGLU_BF16, pl, s);
   c.timer.end(s);
@@ -466,7 +466,7 @@ static void moe_block(rollout_ctx& c, LayerWeights& L, int layer, int R, RowNorm
   dn.block_row_end = pa.block_row_end;
   dn.group_stride16 = (long long)d * fe * 2 / 16;
   dn.n_row_blocks = pa.max_blocks;
-  pl.name = "gemm_tile_kernel<4,2,2,1,0>";
+  pl.name = "gemm_tile_ring_kernel<4,2,2,1,0>";
   c.timer.begin(pl.name, touched * 2.0 * d * fe + 4.0 * picks * fe + 4.0 * picks * d, 2.0 * picks * d * fe, s);
   launch_gemm_bf16(dn, EPI_F32, pl, s);
   c.timer.end(s);

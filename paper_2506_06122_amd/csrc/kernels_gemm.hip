@@ -30,8 +30,8 @@
 //           commutes with the projection.  No workgroup ever waits for another.
 //         - SwiGLU on interleaved gate/up column tiles (EPI_SWIGLU_BF16).
 //   gemm_tile_kernel    (more than 32 rows: large decode batches, prefill, teacher-forced
-//       pass): up to 128 x 256 output tile per workgroup, activations staged through LDS in
-//       fragment order and double-buffered, weights still read directly.
+//       pass): 64 x 128 or 64 x 256 output tile per workgroup, activations staged through LDS
+//       in fragment order and double-buffered, weights still read directly.
 #include <cstdio>
 
 #include "kernels_fast.h"
@@ -206,14 +206,190 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
 // Tiled kernel: a workgroup of 4 wavefronts computes MT*16 rows x 4*NT*16 columns; each
 // wavefront owns NT column tiles and reads its weight fragments straight from memory, the
 // activation fragments (hi and lo planes) of KC k-tiles (one stage) are staged in LDS for all
-// four.  D stages of loads are kept in flight in a register ring; a stage's activations move to
-// one of two LDS buffers and its weights to the multiply operands just before the ring slot is
-// refilled with the stage D ahead.  (Measured: the small tiles run best with D = 1 and three
-// workgroups per CU, the 128 x 256 tile, alone on its CU, with single k-tile stages and D = 3.)
-// One barrier per stage: a wavefront reaches the barrier of stage s only after its reads of
-// stage s-1's buffer, which stage s+1 overwrites.
-template <int MT, int NT, int KC, int D, int EPI>
+// four.  Software-pipelined over a ring of R register slots: while stage s is multiplied (its
+// weights read in place from slot s % R, its activations from one LDS buffer), the loads of
+// stage s+R-1 are issued into the slot stage s-1 has just left, and stage s+1's activations
+// move from their slot to the other LDS buffer - all in one basic block, so the matrix
+// instructions overlap the memory instructions.  One barrier per stage: a wavefront reaches
+// the barrier that ends stage s only after its reads of stage s's buffer, which the write of
+// stage s+2 is the next to touch.
+// Loads are never predicated: rows, column tiles and k-tiles past the end read the last valid
+// one instead (results of such rows and columns are not stored; the weights of a k-tile past
+// the end are zeroed).
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int MT, int NT, int KC, int R, int EPI>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
+  constexpr int FR = 2 * MT * KC;      // activation fragments per stage: [kk][plane][mt]
+  static_assert(FR % 4 == 0 && (2 * MT) % 4 == 0, "the fragments divide evenly over the wavefronts");
+  constexpr int PER = FR / 4;          // fragments each wavefront stages: f = 4 s + wave
+  __shared__ u32x4 a_lds[2][FR * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = lane & 15, g = lane >> 4;
+  const int n_tiles = p.N >> 4, k_tiles = p.K >> 5;
+  const int nt0 = (blockIdx.x * 4 + wave) * NT;
+  int m0 = blockIdx.y * (MT * 16);
+  const int kt_begin = blockIdx.z * p.k_tiles_per_split;
+  const int kt_end = min(k_tiles, kt_begin + p.k_tiles_per_split);
+
+  // grouped (per-expert) launches: this row block belongs to one group with its own weights
+  const u32x4* wp = (const u32x4*)p.w;
+  const int* row_map = nullptr;
+  int m_limit = p.M;
+  if (p.group_of_block) {
+    int grp = p.group_of_block[blockIdx.y];
+    wp += (long long)grp * p.group_stride16;
+    m0 = p.block_row_begin[blockIdx.y];
+    m_limit = p.block_row_end[blockIdx.y];
+    row_map = p.row_map;
+    if (m0 >= m_limit) return;  // unused block of the plan (uniform over the workgroup)
+  }
+  const uint16_t* a_base = (const uint16_t*)p.a;
+  const long long lo_off = (const uint16_t*)p.a_lo - a_base;
+
+  const uint16_t* st_src[PER];
+#pragma unroll
+  for (int s = 0; s < PER; ++s) {
+    const int f = 4 * s + wave;
+    const int plane = (f / MT) & 1, mt = f % MT;
+    const int m = min(m0 + mt * 16 + r, m_limit - 1);
+    const long long row = row_map ? row_map[m] : m;
+    st_src[s] = a_base + row * p.lda + g * 8 + (plane ? lo_off : 0);
+  }
+  const u32x4* w_src[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) w_src[j] = wp + (long long)min(nt0 + j, n_tiles - 1) * k_tiles * 64 + lane;
+
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u32x4 rst[R][PER];
+  u32x4 rb[R][KC][NT];
+  // fragment f = 4 s + wave belongs to k-tile 4 s / (2 MT) of its stage (2 MT is a multiple of 4)
+#define GEMM_LOAD_STAGE(KT, SLOT)                                                                 \
+  {                                                                                               \
+    _Pragma("unroll") for (int s = 0; s < PER; ++s) {                                             \
+      const int k = min((KT) + (4 * s) / (2 * MT), kt_end - 1);                                   \
+      rst[SLOT][s] = *(const u32x4*)(st_src[s] + (long long)k * 32);                              \
+    }                                                                                             \
+    _Pragma("unroll") for (int kk = 0; kk < KC; ++kk)                                             \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                          \
+      rb[SLOT][kk][j] = w_src[j][(long long)min((KT) + kk, kt_end - 1) * 64];                     \
+      if (kk > 0 && (KT) + kk >= kt_end) rb[SLOT][kk][j] = u32x4{0u, 0u, 0u, 0u};                 \
+    }                                                                                             \
+  }
+#pragma unroll
+  for (int d = 0; d < R - 1; ++d) GEMM_LOAD_STAGE(kt_begin + d * KC, d)
+#pragma unroll
+  for (int s = 0; s < PER; ++s) a_lds[0][(4 * s + wave) * 64 + lane] = rst[0][s];
+  __syncthreads();
+  int buf = 0;
+  for (int kt = kt_begin; kt < kt_end; kt += R * KC) {
+#pragma unroll
+    for (int d = 0; d < R; ++d) {
+      const int k0 = kt + d * KC;
+      if (k0 < kt_end) {  // uniform over the workgroup
+        u32x4 a[KC][2][MT];
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+          for (int plane = 1; plane >= 0; --plane)
+#pragma unroll
+            for (int i = 0; i < MT; ++i) a[kk][plane][i] = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + lane];
+        GEMM_LOAD_STAGE(k0 + (R - 1) * KC, (d + R - 1) % R)
+#pragma unroll
+        for (int kk = 0; kk < KC; ++kk)
+#pragma unroll
+          for (int plane = 1; plane >= 0; --plane)  // lo parts first, then hi
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+              for (int j = 0; j < NT; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, rb[d][kk][j]),
+                                                                    __builtin_bit_cast(bf16x8, a[kk][plane][i]),
+                                                                    acc[i][j], 0, 0, 0);
+        if (k0 + KC < kt_end) {
+#pragma unroll
+          for (int s = 0; s < PER; ++s) a_lds[buf ^ 1][(4 * s + wave) * 64 + lane] = rst[(d + 1) % R][s];
+        }
+        __syncthreads();
+        buf ^= 1;
+      }
+    }
+  }
+#undef GEMM_LOAD_STAGE
+  if constexpr (EPI == EPI_LSE) {
+    // log-sum-exp parts of this workgroup's columns: per wavefront over its NT tiles (the 4
+    // lanes of a row meet by shuffles), then over the 4 wavefronts through LDS
+    __shared__ float part_m[4][MT * 16], part_s[4][MT * 16];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int m = m0 + i * 16 + r;
+      const int tgt = m < m_limit ? p.lse_target[m] : -1;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        if (nt0 + j < n_tiles) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[i][j][e] *= p.lse_scale;
+            mx = fmaxf(mx, acc[i][j][e]);
+            if ((nt0 + j) * 16 + g * 4 + e == tgt) p.lse_tgt[m] = acc[i][j][e];
+          }
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      float sm = 0.f;
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        if (nt0 + j < n_tiles) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) sm += expf(acc[i][j][e] - mx);
+        }
+      sm += __shfl_xor(sm, 16, WAVE);
+      sm += __shfl_xor(sm, 32, WAVE);
+      if (g == 0) {
+        part_m[wave][i * 16 + r] = mx;
+        part_s[wave][i * 16 + r] = sm;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x < MT * 16 && m0 + (int)threadIdx.x < m_limit) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) mx = fmaxf(mx, part_m[w][threadIdx.x]);
+      float sm = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        if (part_m[w][threadIdx.x] > -INFINITY) sm += part_s[w][threadIdx.x] * expf(part_m[w][threadIdx.x] - mx);
+      p.lse_max[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = mx;
+      p.lse_sum[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = sm;
+    }
+    return;
+  }
+  if (nt0 >= n_tiles) return;
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int m = m0 + i * 16 + r;
+    if (m >= m_limit) continue;
+#pragma unroll
+    for (int j = 0; j < NT; j += 2)
+      if (nt0 + j < n_tiles)  // an odd last column tile (fp32 results only) is stored alone
+        store_unit<EPI == EPI_LSE ? EPI_F32 : EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z,
+                                                  nt0 + j + 1 < n_tiles);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// The same tile with predicated loads and a ring of D prefetched stages whose activations go
+// to LDS and whose weights go to the multiply operands at the top of each stage: the leaner
+// variant (fewer registers, rows past the end are not loaded) that the decode-sized
+// projections run best with.
+template <int MT, int NT, int KC, int D, int EPI>
+__global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
   constexpr int FR = 2 * MT * KC;      // activation fragments per stage: [kk][plane][mt]
   constexpr int PER = (FR + 3) / 4;    // fragments each wavefront stages
   __shared__ uint4 a_lds[2][FR * 64];
@@ -413,16 +589,16 @@ GemmPlan gemm_plan_tiled(int M, int N, int K, int epi, int max_splits) {
   const int n_tiles = N >> 4, k_tiles = K >> 5;
   pl.kind = 1;
   pl.nw = 4;
-  static const int cfg[3][2] = {{8, 4}, {4, 4}, {4, 2}};
-  static const char* const names[3][3] = {
-      {"gemm_tile_kernel<8,4,1,3,0>", "gemm_tile_kernel<8,4,1,3,1>", "gemm_tile_kernel<8,4,1,3,3>"},
-      {"gemm_tile_kernel<4,4,2,1,0>", "gemm_tile_kernel<4,4,2,1,1>", "gemm_tile_kernel<4,4,2,1,3>"},
-      {"gemm_tile_kernel<4,2,2,1,0>", "gemm_tile_kernel<4,2,2,1,1>", "gemm_tile_kernel<4,2,2,1,3>"}};
-  int pick = 2;
+  // 64 x 256 tiles when they still give every CU two workgroups, else 64 x 128
+  static const int cfg[2][2] = {{4, 4}, {4, 2}};
+  static const char* const names[2][3] = {
+      {"gemm_tile_kernel<4,4,2,2,0>", "gemm_tile_kernel<4,4,2,2,1>", "gemm_tile_kernel<4,4,2,2,3>"},
+      {"gemm_tile_ring_kernel<4,2,2,1,0>", "gemm_tile_ring_kernel<4,2,2,1,1>", "gemm_tile_ring_kernel<4,2,2,1,3>"}};
+  int pick = 1;
   long long blocks = 0;
-  for (int c = 0; c < 3; ++c) {
+  for (int c = 0; c < 2; ++c) {
     blocks = (long long)ceil_div(M, 16 * cfg[c][0]) * ceil_div(n_tiles, 4 * cfg[c][1]);
-    if (blocks >= 256 || c == 2) {
+    if (blocks >= 576 || c == 1) {
       pick = c;
       break;
     }
@@ -464,11 +640,18 @@ GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
   return pl;
 }
 
-template <int MT, int NT, int KC, int D>
+template <int MT, int NT, int KC, int R>
 static void launch_tile(const GemmArgs& a, int epi, dim3 grid, hipStream_t s) {
-  if (epi == EPI_F32) gemm_tile_kernel<MT, NT, KC, D, EPI_F32><<<grid, 256, 0, s>>>(a);
-  else if (epi == EPI_SWIGLU_BF16) gemm_tile_kernel<MT, NT, KC, D, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
-  else gemm_tile_kernel<MT, NT, KC, D, EPI_LSE><<<grid, 256, 0, s>>>(a);
+  if (epi == EPI_F32) gemm_tile_kernel<MT, NT, KC, R, EPI_F32><<<grid, 256, 0, s>>>(a);
+  else if (epi == EPI_SWIGLU_BF16) gemm_tile_kernel<MT, NT, KC, R, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+  else gemm_tile_kernel<MT, NT, KC, R, EPI_LSE><<<grid, 256, 0, s>>>(a);
+}
+
+template <int MT, int NT, int KC, int D>
+static void launch_tile_ring(const GemmArgs& a, int epi, dim3 grid, hipStream_t s) {
+  if (epi == EPI_F32) gemm_tile_ring_kernel<MT, NT, KC, D, EPI_F32><<<grid, 256, 0, s>>>(a);
+  else if (epi == EPI_SWIGLU_BF16) gemm_tile_ring_kernel<MT, NT, KC, D, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+  else gemm_tile_ring_kernel<MT, NT, KC, D, EPI_LSE><<<grid, 256, 0, s>>>(a);
 }
 
 template <int MT, int KU>
@@ -488,9 +671,8 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
     a.k_tiles_per_split = per;
     const int m_blocks = a.group_of_block ? a.n_row_blocks : ceil_div(a.M, 16 * pl.mt);
     dim3 grid(ceil_div(n_tiles, 4 * pl.nt), m_blocks, splits);
-    if (pl.mt == 8) launch_tile<8, 4, 1, 3>(a, epi, grid, s);
-    else if (pl.nt == 4) launch_tile<4, 4, 2, 1>(a, epi, grid, s);
-    else launch_tile<4, 2, 2, 1>(a, epi, grid, s);
+    if (pl.nt == 4) launch_tile<4, 4, 2, 2>(a, epi, grid, s);
+    else launch_tile_ring<4, 2, 2, 1>(a, epi, grid, s);
     return splits;
   }
   int per = ceil_div(k_tiles, epi == EPI_F32 ? pl.splits : 1);
