@@ -5,37 +5,71 @@
 
 #define ROW_T 256
 
-// One workgroup per row; the row is staged in LDS between the two passes (hidden <= 8192).
+// One workgroup per row; thread t holds the row's float4 chunks t, t + 256, ... (V of them) in
+// registers, so every load of the row is in flight before the first use (hidden <= 1024 V).
+template <int V>
 __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
-  __shared__ float row_s[8192];
   __shared__ float partial[ROW_T / WAVE];
   const int r = blockIdx.x, t = threadIdx.x;
+  const int n4 = a.hidden >> 2;
   const long long src_row = a.rows_index ? a.rows_index[r] : r;
-  const long long tok = a.tokens ? a.tokens[r] : 0;
-  float ss = 0.f;
-  for (int i = t; i < a.hidden; i += ROW_T) {
-    float x;
-    if (a.tokens) {
-      bf16_t e;
-      e.bits = a.embed[tok * a.hidden + i];
-      x = bf16_to_f32(e);
-    } else {
-      x = a.x[src_row * a.hidden + i];
+  float4 x[V];
+  if (a.tokens) {
+    const uint2* e = (const uint2*)(a.embed + (long long)a.tokens[r] * a.hidden);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      const int c = t + ROW_T * v;
+      uint2 u = make_uint2(0, 0);
+      if (c < n4) u = e[c];
+      x[v] = make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                         __uint_as_float(u.y & 0xffff0000u));
     }
-    const float* pp = a.partial + (long long)r * a.hidden + i;
-    for (int z = 0; z < a.splits; z += 4) {  // four planes at a time, loads issued together
-      float p0 = pp[(long long)z * a.split_stride], p1 = 0.f, p2 = 0.f, p3 = 0.f;
-      if (z + 1 < a.splits) p1 = pp[(long long)(z + 1) * a.split_stride];
-      if (z + 2 < a.splits) p2 = pp[(long long)(z + 2) * a.split_stride];
-      if (z + 3 < a.splits) p3 = pp[(long long)(z + 3) * a.split_stride];
-      x = (((x + p0) + p1) + p2) + p3;
+  } else {
+    const float4* xs = (const float4*)(a.x + src_row * a.hidden);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      const int c = t + ROW_T * v;
+      x[v] = c < n4 ? xs[c] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
-    for (int j = 0; j < a.moe_k; ++j)
-      x += a.moe_wt[(long long)r * a.moe_k + j] *
-           a.moe_y[(long long)a.moe_slot[(long long)r * a.moe_k + j] * a.hidden + i];
-    row_s[i] = x;
-    ss += x * x;
   }
+  // split planes in ascending order, two at a time with their loads issued together
+  for (int z = 0; z < a.splits; z += 2) {
+    const float4* p0 = (const float4*)(a.partial + (long long)z * a.split_stride + (long long)r * a.hidden);
+    const float4* p1 = (const float4*)(a.partial + (long long)(z + 1) * a.split_stride + (long long)r * a.hidden);
+    const bool two = z + 1 < a.splits;
+    float4 u[V], w[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      const int c = t + ROW_T * v;
+      u[v] = c < n4 ? p0[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+      w[v] = (two && c < n4) ? p1[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      x[v].x = (x[v].x + u[v].x) + w[v].x;
+      x[v].y = (x[v].y + u[v].y) + w[v].y;
+      x[v].z = (x[v].z + u[v].z) + w[v].z;
+      x[v].w = (x[v].w + u[v].w) + w[v].w;
+    }
+  }
+  for (int j = 0; j < a.moe_k; ++j) {  // the row's expert picks, in pick order
+    const float wt = a.moe_wt[(long long)r * a.moe_k + j];
+    const float4* y = (const float4*)(a.moe_y + (long long)a.moe_slot[(long long)r * a.moe_k + j] * a.hidden);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      const int c = t + ROW_T * v;
+      if (c < n4) {
+        const float4 yv = y[c];
+        x[v].x += wt * yv.x;
+        x[v].y += wt * yv.y;
+        x[v].z += wt * yv.z;
+        x[v].w += wt * yv.w;
+      }
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int v = 0; v < V; ++v) ss += x[v].x * x[v].x + x[v].y * x[v].y + x[v].z * x[v].z + x[v].w * x[v].w;
   ss = wave_sum(ss);
   if ((t & 63) == 0) partial[t >> 6] = ss;
   __syncthreads();
@@ -45,17 +79,30 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
   const float rinv = a.ssq_out ? 1.0f : 1.0f / sqrtf(total / (float)a.hidden + a.eps);
   if (a.ssq_out && t == 0) a.ssq_out[r] = total;
   const bool write_x = !a.rows_index && (a.splits || a.tokens || a.moe_k);
-  for (int i = t; i < a.hidden; i += ROW_T) {
-    const float x = row_s[i];
-    if (write_x) a.x[(long long)r * a.hidden + i] = x;
-    uint16_t hi, lo;
-    split_bf16(x * a.gain[i] * rinv, hi, lo);
-    a.h[(long long)r * a.hidden + i] = hi;
-    a.h[a.h_lo_offset + (long long)r * a.hidden + i] = lo;
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    const int c = t + ROW_T * v;
+    if (c >= n4) continue;
+    if (write_x) ((float4*)(a.x + (long long)r * a.hidden))[c] = x[v];
+    const float4 gn = ((const float4*)a.gain)[c];
+    uint16_t hi[4], lo[4];
+    split_bf16(x[v].x * gn.x * rinv, hi[0], lo[0]);
+    split_bf16(x[v].y * gn.y * rinv, hi[1], lo[1]);
+    split_bf16(x[v].z * gn.z * rinv, hi[2], lo[2]);
+    split_bf16(x[v].w * gn.w * rinv, hi[3], lo[3]);
+    uint16_t* hp = a.h + (long long)r * a.hidden + 4 * c;
+    *(uint2*)hp = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
+    *(uint2*)(hp + a.h_lo_offset) =
+        make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
   }
 }
 void launch_row_norm(const RowNormArgs& a, hipStream_t s) {
-  if (a.rows) row_norm_kernel<<<a.rows, ROW_T, 0, s>>>(a);
+  if (!a.rows) return;
+  const int chunks = ceil_div(a.hidden >> 2, ROW_T);  // hidden is a multiple of 32 and at most 8192
+  if (chunks <= 1) row_norm_kernel<1><<<a.rows, ROW_T, 0, s>>>(a);
+  else if (chunks <= 2) row_norm_kernel<2><<<a.rows, ROW_T, 0, s>>>(a);
+  else if (chunks <= 4) row_norm_kernel<4><<<a.rows, ROW_T, 0, s>>>(a);
+  else row_norm_kernel<8><<<a.rows, ROW_T, 0, s>>>(a);
 }
 
 // One thread per rotary pair (head, i): grid (rows, heads / 4), 4 heads of 64 pairs per block.
