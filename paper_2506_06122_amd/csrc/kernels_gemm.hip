@@ -97,6 +97,29 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
   }
   const long long lo_off = (const uint16_t*)p.a_lo - a_base;
 
+  // Epilogue unit (one row tile, up to two column tiles) of this wavefront, if it has one.  Its
+  // operands - the input rows' partial sums of squares, the residual values and the gain - are
+  // requested now, so that they arrive while the weights stream.
+  constexpr int NU = NT >= 2 ? NT / 2 : 1;  // units per row tile
+  constexpr int TW = NT >= 2 ? 2 : 1;       // column tiles per unit
+  static_assert(MT * NU <= NW, "at most one epilogue unit per wavefront");
+  const bool has_unit = wave < MT * NU;
+  const int ui = wave / NU, uj = (wave % NU) * TW;
+  const int um = m0 + ui * 16 + r;
+  const bool valid = has_unit && um < p.M && nt0 + uj + TW - 1 < n_tiles;
+  float rs = 0.f;
+  float4 xv[TW], gn[TW];
+  if (has_unit && p.rinv_ssq && um < p.M)
+    for (int pp = g; pp < p.rinv_partials; pp += 4) rs += p.rinv_ssq[(long long)pp * p.ssq_stride + um];
+  if (EPI == EPI_RESID && valid) {
+#pragma unroll
+    for (int q = 0; q < TW; ++q) {
+      const int n = (nt0 + uj + q) * 16 + g * 4;
+      xv[q] = *(const float4*)(p.x + (long long)um * p.N + n);
+      gn[q] = *(const float4*)(p.gain + n);
+    }
+  }
+
   for (int kt = kt_begin + wave * KU; kt < kt_end; kt += NW * KU) {
     Frag b[KU][NT], a[KU][MT], al[KU][MT];
 #pragma unroll
@@ -135,70 +158,60 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
     for (int j = 0; j < NT; ++j)
       red[(wave * MT * NT + i * NT + j) * 64 + lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
   __syncthreads();
-  constexpr int NU = NT >= 2 ? NT / 2 : 1;  // units per row tile
-  constexpr int TW = NT >= 2 ? 2 : 1;       // column tiles per unit
-  for (int u = wave; u < MT * NU; u += NW) {
-    const int i = u / NU, j = (u % NU) * TW;
-    const int m = m0 + i * 16 + r;
-    f32x4 t[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+  if (!has_unit) return;
+  f32x4 t[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int q = 0; q < TW; ++q)
+  for (int q = 0; q < TW; ++q)
 #pragma unroll
-      for (int w = 0; w < NW; ++w) {
-        const float4 v = red[(w * MT * NT + i * NT + j + q) * 64 + lane];
-        t[q][0] += v.x;
-        t[q][1] += v.y;
-        t[q][2] += v.z;
-        t[q][3] += v.w;
-      }
-    if (p.rinv_ssq) {
-      // second half of the RMSNorm of this projection's input: scale row m by
-      // rsqrt(mean(x^2) + eps); the 4 lanes of a row share the partial sums
-      float s = 0.f;
-      for (int pp = g; pp < p.rinv_partials; pp += 4) s += m < p.M ? p.rinv_ssq[(long long)pp * p.ssq_stride + m] : 0.f;
-      s += __shfl_xor(s, 16, WAVE);
-      s += __shfl_xor(s, 32, WAVE);
-      const float rinv = 1.0f / sqrtf(s / (float)p.K + p.eps);
+    for (int w = 0; w < NW; ++w) {
+      const float4 v = red[(w * MT * NT + ui * NT + uj + q) * 64 + lane];
+      t[q][0] += v.x;
+      t[q][1] += v.y;
+      t[q][2] += v.z;
+      t[q][3] += v.w;
+    }
+  if (p.rinv_ssq) {
+    // second half of the RMSNorm of this projection's input: scale row m by
+    // rsqrt(mean(x^2) + eps); the 4 lanes of a row share the partial sums
+    rs += __shfl_xor(rs, 16, WAVE);
+    rs += __shfl_xor(rs, 32, WAVE);
+    const float rinv = 1.0f / sqrtf(rs / (float)p.K + p.eps);
+#pragma unroll
+    for (int q = 0; q < TW; ++q) {
+      t[q][0] *= rinv;
+      t[q][1] *= rinv;
+      t[q][2] *= rinv;
+      t[q][3] *= rinv;
+    }
+  }
+  if (EPI == EPI_RESID) {
+    float ss = 0.f;
+    if (valid) {
 #pragma unroll
       for (int q = 0; q < TW; ++q) {
-        t[q][0] *= rinv;
-        t[q][1] *= rinv;
-        t[q][2] *= rinv;
-        t[q][3] *= rinv;
+        const int n = (nt0 + uj + q) * 16 + g * 4;
+        float4 x4 = xv[q];
+        x4.x += t[q][0];
+        x4.y += t[q][1];
+        x4.z += t[q][2];
+        x4.w += t[q][3];
+        *(float4*)(p.x + (long long)um * p.N + n) = x4;
+        ss += x4.x * x4.x + x4.y * x4.y + x4.z * x4.z + x4.w * x4.w;
+        uint16_t hi[4], lo[4];
+        split_bf16(x4.x * gn[q].x, hi[0], lo[0]);
+        split_bf16(x4.y * gn[q].y, hi[1], lo[1]);
+        split_bf16(x4.z * gn[q].z, hi[2], lo[2]);
+        split_bf16(x4.w * gn[q].w, hi[3], lo[3]);
+        uint16_t* hp = p.h + (long long)um * p.N + n;
+        *(uint2*)hp = pack4(hi);
+        *(uint2*)(hp + p.h_lo_offset) = pack4(lo);
       }
     }
-    const bool valid = m < p.M && nt0 + j + TW - 1 < n_tiles;
-    if (EPI == EPI_RESID) {
-      float ss = 0.f;
-      if (valid) {
-#pragma unroll
-        for (int q = 0; q < TW; ++q) {
-          const int n = (nt0 + j + q) * 16 + g * 4;
-          float4* xp = (float4*)(p.x + (long long)m * p.N + n);
-          float4 xv = *xp;
-          xv.x += t[q][0];
-          xv.y += t[q][1];
-          xv.z += t[q][2];
-          xv.w += t[q][3];
-          *xp = xv;
-          ss += xv.x * xv.x + xv.y * xv.y + xv.z * xv.z + xv.w * xv.w;
-          const float4 gn = *(const float4*)(p.gain + n);
-          uint16_t hi[4], lo[4];
-          split_bf16(xv.x * gn.x, hi[0], lo[0]);
-          split_bf16(xv.y * gn.y, hi[1], lo[1]);
-          split_bf16(xv.z * gn.z, hi[2], lo[2]);
-          split_bf16(xv.w * gn.w, hi[3], lo[3]);
-          uint16_t* hp = p.h + (long long)m * p.N + n;
-          *(uint2*)hp = pack4(hi);
-          *(uint2*)(hp + p.h_lo_offset) = pack4(lo);
-        }
-      }
-      ss += __shfl_xor(ss, 16, WAVE);
-      ss += __shfl_xor(ss, 32, WAVE);
-      if (g == 0 && m < p.M) p.ssq_out[(long long)blockIdx.x * p.ssq_stride + m] = ss;
-    } else if (valid) {
-      store_unit<EPI>(p, m, nt0 + j, t[0], t[1], g, blockIdx.z, TW == 2);
-    }
+    ss += __shfl_xor(ss, 16, WAVE);
+    ss += __shfl_xor(ss, 32, WAVE);
+    if (g == 0 && um < p.M) p.ssq_out[(long long)blockIdx.x * p.ssq_stride + um] = ss;
+  } else if (valid) {
+    store_unit<EPI>(p, um, nt0 + uj, t[0], t[1], g, blockIdx.z, TW == 2);
   }
 }
 
@@ -628,6 +641,10 @@ GemmPlan gemm_plan(int M, int N, int K, int epi, int max_splits) {
   const bool wide = (long long)(n_tiles / 2) * m_blocks >= 512;
   pl.nt = (wide || epi == EPI_SWIGLU_BF16) ? 2 : 1;
   pl.nw = wide ? 4 : 16;
+  // narrow but not tiny (the fused QKV projection of 7B-class models): two column tiles per
+  // wide workgroup halve the activation re-reads and still leave more than a hundred
+  // workgroups.  (Measured: the residual epilogue's projections run better with one.)
+  if (!wide && epi == EPI_F32 && n_tiles >= 192 && n_tiles % 2 == 0) pl.nt = 2;
   if (epi == EPI_SWIGLU_BF16 && !wide) pl.nw = 4;
   pl.splits = 1;
   if (epi == EPI_F32 && !wide && max_splits > 1) {
