@@ -29,6 +29,7 @@ struct GemmArgs {
   long long out_lo_offset = 0;  // EPI_SWIGLU_BF16: elements from the hi plane of `out` to its lo plane
   long long split_stride;  // floats between split planes (EPI_F32)
   int k_tiles_per_split;   // filled by the launcher
+  int grid_nx = 0, grid_ny = 0, grid_nz = 0;  // tile kernels: column blocks, row blocks, K splits (launcher)
   // input normalisation (stream kernel)
   const float* rinv_ssq = nullptr;  // [rinv_partials][ssq_stride] partial sums of squares of the input rows
   int rinv_partials = 0;

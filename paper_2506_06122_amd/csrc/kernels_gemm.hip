@@ -215,6 +215,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
   }
 }
 
+// Workgroup -> (column block, row block, K split) of the tile kernels.  The launch is
+// one-dimensional and workgroups go to the 8 XCDs (each with its own L2) round-robin by index,
+// so index % 8 is the XCD and index / 8 the order inside it.  Inside an XCD the row blocks of
+// one (column block, split) pair run back to back: its weight slab is fetched from HBM once,
+// into that XCD's L2, instead of once per row block and XCD.
+__device__ inline bool tile_block(const GemmArgs& p, int& bx, int& by, int& bz) {
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  by = idx % p.grid_ny;
+  const int pair = (idx / p.grid_ny) * 8 + xcd;
+  bx = pair / p.grid_nz;  // splits fastest: with 8 or 16 of them an XCD keeps to a slice of the
+  bz = pair % p.grid_nz;  // K range, and so to a slice of the activations
+  return pair < p.grid_nx * p.grid_nz;
+}
+
 // ------------------------------------------------------------------------------------------
 // Tiled kernel: a workgroup of 4 wavefronts computes MT*16 rows x 4*NT*16 columns; each
 // wavefront owns NT column tiles and reads its weight fragments straight from memory, the
@@ -240,9 +254,11 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int n_tiles = p.N >> 4, k_tiles = p.K >> 5;
-  const int nt0 = (blockIdx.x * 4 + wave) * NT;
-  int m0 = blockIdx.y * (MT * 16);
-  const int kt_begin = blockIdx.z * p.k_tiles_per_split;
+  int bx, by, bz;
+  if (!tile_block(p, bx, by, bz)) return;  // padding of the XCD-aware launch (uniform)
+  const int nt0 = (bx * 4 + wave) * NT;
+  int m0 = by * (MT * 16);
+  const int kt_begin = bz * p.k_tiles_per_split;
   const int kt_end = min(k_tiles, kt_begin + p.k_tiles_per_split);
 
   // grouped (per-expert) launches: this row block belongs to one group with its own weights
@@ -250,10 +266,10 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
   const int* row_map = nullptr;
   int m_limit = p.M;
   if (p.group_of_block) {
-    int grp = p.group_of_block[blockIdx.y];
+    int grp = p.group_of_block[by];
     wp += (long long)grp * p.group_stride16;
-    m0 = p.block_row_begin[blockIdx.y];
-    m_limit = p.block_row_end[blockIdx.y];
+    m0 = p.block_row_begin[by];
+    m_limit = p.block_row_end[by];
     row_map = p.row_map;
     if (m0 >= m_limit) return;  // unused block of the plan (uniform over the workgroup)
   }
@@ -378,8 +394,8 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         if (part_m[w][threadIdx.x] > -INFINITY) sm += part_s[w][threadIdx.x] * expf(part_m[w][threadIdx.x] - mx);
-      p.lse_max[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = mx;
-      p.lse_sum[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = sm;
+      p.lse_max[(long long)bx * p.lse_stride + m0 + threadIdx.x] = mx;
+      p.lse_sum[(long long)bx * p.lse_stride + m0 + threadIdx.x] = sm;
     }
     return;
   }
@@ -391,7 +407,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NT; j += 2)
       if (nt0 + j < n_tiles)  // an odd last column tile (fp32 results only) is stored alone
-        store_unit<EPI == EPI_LSE ? EPI_F32 : EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z,
+        store_unit<EPI == EPI_LSE ? EPI_F32 : EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, bz,
                                                   nt0 + j + 1 < n_tiles);
   }
 }
@@ -409,9 +425,11 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int n_tiles = p.N >> 4, k_tiles = p.K >> 5;
-  const int nt0 = (blockIdx.x * 4 + wave) * NT;
-  int m0 = blockIdx.y * (MT * 16);
-  const int kt_begin = blockIdx.z * p.k_tiles_per_split;
+  int bx, by, bz;
+  if (!tile_block(p, bx, by, bz)) return;  // padding of the XCD-aware launch (uniform)
+  const int nt0 = (bx * 4 + wave) * NT;
+  int m0 = by * (MT * 16);
+  const int kt_begin = bz * p.k_tiles_per_split;
   const int kt_end = min(k_tiles, kt_begin + p.k_tiles_per_split);
 
   // grouped (per-expert) launches: this row block belongs to one group with its own weights
@@ -419,10 +437,10 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
   const int* row_map = nullptr;
   int m_limit = p.M;
   if (p.group_of_block) {
-    int grp = p.group_of_block[blockIdx.y];
+    int grp = p.group_of_block[by];
     wp += (long long)grp * p.group_stride16;
-    m0 = p.block_row_begin[blockIdx.y];
-    m_limit = p.block_row_end[blockIdx.y];
+    m0 = p.block_row_begin[by];
+    m_limit = p.block_row_end[by];
     row_map = p.row_map;
     if (m0 >= m_limit) return;  // unused block of the plan (uniform over the workgroup)
   }
@@ -551,8 +569,8 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         if (part_m[w][threadIdx.x] > -INFINITY) sm += part_s[w][threadIdx.x] * expf(part_m[w][threadIdx.x] - mx);
-      p.lse_max[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = mx;
-      p.lse_sum[(long long)blockIdx.x * p.lse_stride + m0 + threadIdx.x] = sm;
+      p.lse_max[(long long)bx * p.lse_stride + m0 + threadIdx.x] = mx;
+      p.lse_sum[(long long)bx * p.lse_stride + m0 + threadIdx.x] = sm;
     }
     return;
   }
@@ -564,7 +582,7 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NT; j += 2)
       if (nt0 + j < n_tiles)  // an odd last column tile (fp32 results only) is stored alone
-        store_unit<EPI == EPI_LSE ? EPI_F32 : EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, blockIdx.z,
+        store_unit<EPI == EPI_LSE ? EPI_F32 : EPI>(p, m, nt0 + j, acc[i][j], acc[i][j + 1], g, bz,
                                                   nt0 + j + 1 < n_tiles);
   }
 }
@@ -687,7 +705,10 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
     const int splits = ceil_div(k_tiles, per);
     a.k_tiles_per_split = per;
     const int m_blocks = a.group_of_block ? a.n_row_blocks : ceil_div(a.M, 16 * pl.mt);
-    dim3 grid(ceil_div(n_tiles, 4 * pl.nt), m_blocks, splits);
+    a.grid_nx = ceil_div(n_tiles, 4 * pl.nt);
+    a.grid_ny = m_blocks;
+    a.grid_nz = splits;
+    dim3 grid(ceil_div(a.grid_nx * a.grid_nz, 8) * 8 * a.grid_ny);
     if (pl.nt == 4) launch_tile<4, 4, 2, 2>(a, epi, grid, s);
     else launch_tile_ring<4, 2, 2, 1>(a, epi, grid, s);
     return splits;
