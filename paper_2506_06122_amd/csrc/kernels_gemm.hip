@@ -217,16 +217,22 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
 
 // Workgroup -> (column block, row block, K split) of the tile kernels.  The launch is
 // one-dimensional and workgroups go to the 8 XCDs (each with its own L2) round-robin by index,
-// so index % 8 is the XCD and index / 8 the order inside it.  Inside an XCD the row blocks of
-// one (column block, split) pair run back to back: its weight slab is fetched from HBM once,
-// into that XCD's L2, instead of once per row block and XCD.
+// so index % 8 is the XCD and index / 8 the order inside it.  The unit of work handed to an XCD
+// is a group of up to 8 consecutive row blocks of one (column block, split) pair, which run back
+// to back: the pair's weight slab is fetched from HBM once per group, into that XCD's L2,
+// instead of once per row block and XCD.  Units go round the XCDs with the pair (and inside it
+// the split) varying fastest, so the XCDs stay balanced and, with 8 or 16 splits, each keeps to
+// a slice of the K range, i.e. of the activations.
 __device__ inline bool tile_block(const GemmArgs& p, int& bx, int& by, int& bz) {
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-  by = idx % p.grid_ny;
-  const int pair = (idx / p.grid_ny) * 8 + xcd;
-  bx = pair / p.grid_nz;  // splits fastest: with 8 or 16 of them an XCD keeps to a slice of the
-  bz = pair % p.grid_nz;  // K range, and so to a slice of the activations
-  return pair < p.grid_nx * p.grid_nz;
+  const int gm = min(p.grid_ny, 8);
+  const int pairs = p.grid_nx * p.grid_nz;
+  const int unit = (idx / gm) * 8 + xcd;
+  const int pair = unit % pairs;
+  by = (unit / pairs) * gm + idx % gm;
+  bx = pair / p.grid_nz;
+  bz = pair % p.grid_nz;
+  return by < p.grid_ny;  // units past the last one land past the last row block
 }
 
 // ------------------------------------------------------------------------------------------
@@ -708,7 +714,9 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
     a.grid_nx = ceil_div(n_tiles, 4 * pl.nt);
     a.grid_ny = m_blocks;
     a.grid_nz = splits;
-    dim3 grid(ceil_div(a.grid_nx * a.grid_nz, 8) * 8 * a.grid_ny);
+    const int gm = std::min(a.grid_ny, 8);
+    const long long units = (long long)a.grid_nx * a.grid_nz * ceil_div(a.grid_ny, gm);
+    dim3 grid((unsigned)(ceil_div(units, 8) * 8 * gm));
     if (pl.nt == 4) launch_tile<4, 4, 2, 2>(a, epi, grid, s);
     else launch_tile_ring<4, 2, 2, 1>(a, epi, grid, s);
     return splits;
