@@ -218,14 +218,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
 // Workgroup -> (column block, row block, K split) of the tile kernels.  The launch is
 // one-dimensional and workgroups go to the 8 XCDs (each with its own L2) round-robin by index,
 // so index % 8 is the XCD and index / 8 the order inside it.  The unit of work handed to an XCD
-// is a group of up to 8 consecutive row blocks of one (column block, split) pair, which run back
+// is a group of up to 16 consecutive row blocks of one (column block, split) pair, which run back
 // to back: the pair's weight slab is fetched from HBM once per group, into that XCD's L2,
 // instead of once per row block and XCD.  Units go round the XCDs with the pair (and inside it
 // the split) varying fastest, so the XCDs stay balanced and, with 8 or 16 splits, each keeps to
 // a slice of the K range, i.e. of the activations.
 __device__ inline bool tile_block(const GemmArgs& p, int& bx, int& by, int& bz) {
   const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-  const int gm = min(p.grid_ny, 8);
+  const int gm = min(p.grid_ny, 16);
   const int pairs = p.grid_nx * p.grid_nz;
   const int unit = (idx / gm) * 8 + xcd;
   const int pair = unit % pairs;
@@ -714,7 +714,7 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
     a.grid_nx = ceil_div(n_tiles, 4 * pl.nt);
     a.grid_ny = m_blocks;
     a.grid_nz = splits;
-    const int gm = std::min(a.grid_ny, 8);
+    const int gm = std::min(a.grid_ny, 16);
     const long long units = (long long)a.grid_nx * a.grid_nz * ceil_div(a.grid_ny, gm);
     dim3 grid((unsigned)(ceil_div(units, 8) * 8 * gm));
     if (pl.nt == 4) launch_tile<4, 4, 2, 2>(a, epi, grid, s);

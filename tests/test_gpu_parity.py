@@ -334,3 +334,96 @@ def test_admission_control_rejects_without_side_effects():
     ids, t, lp, fin = eng.rollout_prefill(toks, offs, 2, [20, 20])   # 1 + 1 + 2 x 1 = 4 pages: fits
     assert ids.tolist() == [0, 1]
     eng.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "small-bf16"])
+def test_empty_ragged_and_boundary_inputs(name):
+    """Degenerate cases of the path: nothing live, empty prompt lists, one-token prompts and
+    sequences, prompts that end exactly on a page boundary, a response that ends at the
+    prefill, and a context that reaches max_context exactly."""
+    import paper_2506_06122_amd as R
+    shape, scale, _ = CASES[name]
+    w = scaled_weights(shape, seed=1, scale=scale)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, max_live_samples=16, max_context=96, max_batch_tokens=256)
+    assert len(eng.rollout_decode_step()[0]) == 0                       # nothing live: an empty step
+    with pytest.raises(R.RolloutError) as e:                             # no prompts
+        eng.rollout_prefill(np.zeros(0, np.int32), [0], 1, np.zeros(0, np.int32))
+    assert e.value.code == -1
+    with pytest.raises(R.RolloutError) as e:                             # an empty prompt among others
+        eng.rollout_prefill([1, 2], [0, 2, 2], 1, [2, 2])
+    assert e.value.code == -1
+    assert eng.rollout_get_stats()["pages_in_use"] == 0
+    assert len(eng.rollout_logprobs(np.zeros(0, np.int32), [0])) == 0    # no sequences
+    assert eng.rollout_logprobs([7], [0, 1]).tolist() == [0.0]           # a one-token sequence has no target
+
+    # prompt lengths 1, 31, 32, 33, 64 (page size 32); limits 1 (ends at the prefill), 2, and up to max_context
+    lens = [1, 31, 32, 33, 64]
+    rng = np.random.default_rng(17)
+    toks = rng.integers(0, shape.vocab, sum(lens)).astype(np.int32)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    limits = np.array([1, 2, 4, 3, 96 - 64 + 1], np.int32)               # the last one reaches position 95
+    steps = int(limits.max())
+    forced = rng.integers(0, shape.vocab, (5, steps)).astype(np.int32)
+    ids, t, lp, fin = eng.rollout_prefill(toks, offs, 1, limits, forced_first=forced[:, 0])
+    assert fin.tolist() == [True, False, False, False, False]
+    fwd = T.KVForward(model)
+    caches = [fwd.new_cache() for _ in lens]
+    ref = fwd.extend(caches, [toks[offs[i]:offs[i + 1]] for i in range(5)])
+    got = eng.rollout_debug_logits()
+    worst = max(float(np.max(np.abs(got[i] - ref[i][-1]))) for i in range(5))
+    live = [1, 2, 3, 4]
+    for s in range(1, steps):
+        ids, t, lp, fin = eng.rollout_decode_step(forced_tokens=forced[live, s])
+        assert ids.tolist() == live
+        ref = fwd.extend([caches[i] for i in live], [[int(forced[i, s - 1])] for i in live])
+        got = eng.rollout_debug_logits()
+        worst = max([worst] + [float(np.max(np.abs(got[k] - ref[k][0]))) for k in range(len(live))])
+        assert fin.tolist() == [s + 1 == limits[i] for i in live]
+        live = [i for i in live if s + 1 < limits[i]]
+    assert not live and len(eng.rollout_decode_step()[0]) == 0
+    print(f"{name}: max |dlogits| = {worst:.3e}")
+    assert worst <= TOL[shape.dtype]
+    with pytest.raises(R.RolloutError) as e:                             # one position too many
+        eng.rollout_prefill(toks[:64], [0, 64], 1, [96 - 64 + 2])
+    assert e.value.code == -2
+    st = eng.rollout_get_stats()
+    assert st["pages_in_use"] == 0 and st["live_samples"] == 0
+    eng.close()
+
+
+@pytest.mark.parametrize("name", ["c1", "small-bf16"])
+def test_page_size_and_prefix_sharing_do_not_change_results(name):
+    """The same prompts with 32- and 64-token pages, and n samples forked from one prefill
+    against the same sample prefilled alone: paging and prefix sharing are bookkeeping, so
+    logits agree to the last bit when the batch composition is the same, and within the
+    tolerance when it is not."""
+    shape, scale, _ = CASES[name]
+    w = scaled_weights(shape, seed=1, scale=scale)
+    toks, offs = workloads.make_prompts(2, 20, 75, shape.vocab, seed=23)
+    forced = np.random.default_rng(3).integers(0, shape.vocab, (6, 5)).astype(np.int32)
+
+    def run(page_tokens, prompts, n, rows):
+        eng = make_engine(shape, w, page_tokens=page_tokens, max_context=128)
+        t = np.concatenate([toks[offs[p]:offs[p + 1]] for p in prompts])
+        o = np.concatenate([[0], np.cumsum([offs[p + 1] - offs[p] for p in prompts])]).astype(np.int32)
+        f = forced[rows]
+        out = []
+        eng.rollout_prefill(t, o, n, np.full(len(prompts) * n, 5, np.int32), forced_first=f[:, 0])
+        out.append(eng.rollout_debug_logits())
+        for s in range(1, 5):
+            eng.rollout_decode_step(forced_tokens=f[:, s])
+            out.append(eng.rollout_debug_logits())
+        eng.close()
+        return out
+
+    a = run(32, [0, 1], 3, list(range(6)))
+    b = run(64, [0, 1], 3, list(range(6)))
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    alone = run(32, [1], 1, [4])                 # sample 1 of prompt 1, prefilled alone
+    for s in range(1, 5):
+        err = float(np.max(np.abs(alone[s][0] - a[s][4])))
+        assert err <= TOL[shape.dtype]
+        if shape.dtype == "fp32":
+            assert err <= 1e-5
