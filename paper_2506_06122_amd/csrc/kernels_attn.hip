@@ -129,7 +129,7 @@ __device__ inline void store1_split(uint16_t* dst, long long lo_offset, float a)
 }
 
 // ------------------------------------------------------------------------------ decode
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 3) void attn_decode_kernel(AttnArgs a) {
   __shared__ float m_s[4][16];
   __shared__ float l_s[4][16];
   __shared__ float o_s[4][16 * DH];
@@ -227,7 +227,7 @@ void launch_attention_decode(const AttnArgs& a, hipStream_t s) {
 // 0..pos-1 from the pages.  The new position itself is attended from LDS as a one-token
 // group, so nothing written in this launch is read back from memory.  With several KV
 // splits per (sample, KV head) the partial results go to attn_merge_fused_kernel.
-__global__ __launch_bounds__(256) void attn_decode_fused_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t q_s[2][16][DH];  // hi parts, lo parts
   __shared__ __attribute__((aligned(16))) uint16_t kv_s[2][DH];
   __shared__ float m_s[4][16];
