@@ -374,6 +374,13 @@ static void embed_and_norm(rollout_ctx& c, int R) {
   c.timer.end(c.stream);
 }
 
+// KV splits per (sample, KV head) of a decode step: one workgroup per CU, at least 256 cached
+// positions each, at most the 16 the merge kernels take.  (Measured: more, shorter splits lose
+// to the per-workgroup prologue and the longer merge.)
+static int decode_attention_splits(const rollout_ctx& c, int base) {
+  return std::max(1, std::min({ceil_div(256, base), ceil_div(c.decode_max_ctx, 256), c.attn_max_parts / base, 16}));
+}
+
 // Mixture-of-experts feed-forward block: router projection -> top-k routing -> plan of the
 // expert-sorted row blocks -> grouped gate/up projection with SwiGLU -> grouped down
 // projection -> weighted sum of each row's picks + residual + next norm.
@@ -548,8 +555,7 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
       at.row_slot = c.row_slot.p;
       at.rows = R;
       const int base = R * m.n_kv_heads;
-      const int n_splits = std::max(1, std::min({ceil_div(512, base), ceil_div(c.decode_max_ctx, 256),
-                                                 c.attn_max_parts / base, 16}));
+      const int n_splits = decode_attention_splits(c, base);
       at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
       at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
       at.part_o = c.attn_part_o.p;
@@ -673,10 +679,8 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
     at.rows = R;
     at.qkv_raw = c.partial.p;
     at.cos_sin = c.cos_sin.p;
-    // enough workgroups to fill the chip, at least 256 cached positions each, at most 16 splits
     const int base = R * m.n_kv_heads;
-    const int n_splits = std::max(1, std::min({ceil_div(512, base), ceil_div(c.decode_max_ctx, 256),
-                                               c.attn_max_parts / base, 16}));
+    const int n_splits = decode_attention_splits(c, base);
     at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
     at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
     at.part_o = c.attn_part_o.p;
