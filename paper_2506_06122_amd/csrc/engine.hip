@@ -509,29 +509,7 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
   for (int l = 0; l < m.n_layers; ++l) {
     LayerWeights& L = c.layers[l];
     int z = project(c, c.h_bf16.p, (long long)(c.h_bf16.n / 2), d, L.wqkv_p.p, R, c.qkv_dim, d);
-    QkvPostArgs qp{};
-    qp.partial = c.partial.p;
-    qp.split_stride = (long long)R * c.qkv_dim;
-    qp.splits = z;
-    qp.cos_sin = c.cos_sin.p;
-    qp.row_pos = c.row_pos.p;
-    qp.row_slot = c.row_slot.p;
-    qp.page_table = c.d_page_table.p;
-    qp.max_pages = c.max_pages;
-    qp.q_bf16 = c.q_bf16.p;
-    qp.q_lo_offset = (long long)(c.q_bf16.n / 2);
-    qp.kv_pool = (uint16_t*)c.kv_pool.p;
-    qp.geom = c.geom;
-    qp.layer = l;
-    qp.rows = R;
-    qp.n_q_heads = m.n_q_heads;
-    c.timer.begin("qkv_post_kernel", (double)R * c.qkv_dim * (4 + 2), 0, s);
-    launch_qkv_post(qp, s);
-    c.timer.end(s);
-
     AttnArgs at{};
-    at.q = c.q_bf16.p;
-    at.q_lo_offset = (long long)(c.q_bf16.n / 2);
     at.out = c.attn_bf16.p;
     at.out_lo_offset = (long long)(c.attn_bf16.n / 2);
     at.kv_pool = (const uint16_t*)c.kv_pool.p;
@@ -542,6 +520,28 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
     at.n_q_heads = m.n_q_heads;
     const double kv_bytes = c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2;
     if (seqs) {
+      // packed sequences: sum the planes, rotate, write the KV pages, then causal attention
+      QkvPostArgs qp{};
+      qp.partial = c.partial.p;
+      qp.split_stride = (long long)R * c.qkv_dim;
+      qp.splits = z;
+      qp.cos_sin = c.cos_sin.p;
+      qp.row_pos = c.row_pos.p;
+      qp.row_slot = c.row_slot.p;
+      qp.page_table = c.d_page_table.p;
+      qp.max_pages = c.max_pages;
+      qp.q_bf16 = c.q_bf16.p;
+      qp.q_lo_offset = (long long)(c.q_bf16.n / 2);
+      qp.kv_pool = (uint16_t*)c.kv_pool.p;
+      qp.geom = c.geom;
+      qp.layer = l;
+      qp.rows = R;
+      qp.n_q_heads = m.n_q_heads;
+      c.timer.begin("qkv_post_kernel", (double)R * c.qkv_dim * (4 + 2), 0, s);
+      launch_qkv_post(qp, s);
+      c.timer.end(s);
+      at.q = c.q_bf16.p;
+      at.q_lo_offset = (long long)(c.q_bf16.n / 2);
       at.seq_row0 = seqs->row0;
       at.seq_len = seqs->len;
       at.seq_slot = seqs->slot;
@@ -551,17 +551,24 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
       launch_attention_prefill(at, s);
       c.timer.end(s);
     } else {
+      // one row per sample: the fused decode attention sums the projection's planes itself
+      at.kv_pool_w = (uint16_t*)c.kv_pool.p;
       at.row_pos = c.row_pos.p;
       at.row_slot = c.row_slot.p;
       at.rows = R;
+      at.qkv_raw = c.partial.p;
+      at.qkv_planes = z;
+      at.qkv_plane_stride = (long long)R * c.qkv_dim;
+      at.cos_sin = c.cos_sin.p;
       const int base = R * m.n_kv_heads;
       const int n_splits = decode_attention_splits(c, base);
       at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
       at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
       at.part_o = c.attn_part_o.p;
       at.part_ml = c.attn_part_ml.p;
-      c.timer.begin("attn_decode_kernel", kv_bytes + 4.0 * R * c.q_dim, c.attn_flops_this_call, s);
-      launch_attention_decode(at, s);
+      c.timer.begin("attn_decode_fused_kernel",
+                    kv_bytes + (double)R * (4.0 * z * c.qkv_dim + 4.0 * c.q_dim), c.attn_flops_this_call, s);
+      launch_attention_decode_fused(at, s);
       c.timer.end(s);
     }
 
@@ -678,6 +685,7 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
     at.row_slot = c.row_slot.p;
     at.rows = R;
     at.qkv_raw = c.partial.p;
+    at.qkv_planes = 1;
     at.cos_sin = c.cos_sin.p;
     const int base = R * m.n_kv_heads;
     const int n_splits = decode_attention_splits(c, base);

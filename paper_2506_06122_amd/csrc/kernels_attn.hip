@@ -14,8 +14,9 @@
 // probabilities, so P never moves between lanes.
 //
 //   decode  : one workgroup per (KV split, KV head, sample); columns = the G query heads;
-//             its 4 wavefronts interleave over the split's 32-position groups and merge
-//             through LDS; several splits per sample merge in a second small kernel.
+//             the rotary embedding of the new query and key and the KV-page write ride in
+//             the prologue; its 4 wavefronts interleave over the split's 32-position groups
+//             and merge through LDS; several splits per sample merge in a second small kernel.
 //   prefill : one wavefront per (16 query positions, query head); columns = positions;
 //             causal limit per column.
 #include "kernels_fast.h"
@@ -128,97 +129,6 @@ __device__ inline void store1_split(uint16_t* dst, long long lo_offset, float a)
   dst[lo_offset] = lo;
 }
 
-// ------------------------------------------------------------------------------ decode
-__global__ __launch_bounds__(256, 3) void attn_decode_kernel(AttnArgs a) {
-  __shared__ float m_s[4][16];
-  __shared__ float l_s[4][16];
-  __shared__ float o_s[4][16 * DH];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int c = lane & 15, g = lane >> 4;
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int G = a.n_q_heads / a.geom.n_kv_heads;
-  const int ctx = a.row_pos[b] + 1;
-  const int slot = a.row_slot[b];
-  const int t_begin = split * a.split_tokens;
-  const int t_end = min(ctx, t_begin + a.split_tokens);
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-
-  Frag q[8];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {
-    q[ks].u = make_uint4(0, 0, 0, 0);
-    q[4 + ks].u = make_uint4(0, 0, 0, 0);
-    if (c < G) {
-      const uint16_t* src = a.q + ((long long)b * a.n_q_heads + kvh * G + c) * DH + ks * 32 + g * 8;
-      q[ks].u = *(const uint4*)src;
-      q[4 + ks].u = *(const uint4*)(src + a.q_lo_offset);
-    }
-  }
-  float m = -INFINITY, l = 0.f;
-  f32x4 o[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int tok0 = t_begin + wave * 32; tok0 < t_end; tok0 += 128)
-    attend_group(group_block(a, slot, kvh, tok0, 0), group_block(a, slot, kvh, tok0, 1), q, tok0, ctx - 1,
-                 scale_log2, m, l, o, lane);
-
-  // merge the 4 wavefronts: common max, rescale, sum
-  if (g == 0) m_s[wave][c] = m;
-  __syncthreads();
-  const float M = fmaxf(fmaxf(m_s[0][c], m_s[1][c]), fmaxf(m_s[2][c], m_s[3][c]));
-  const float M_use = (M == -INFINITY) ? 0.f : M;
-  const float w = exp2f(m - M_use);
-  if (g == 0) l_s[wave][c] = l * w;
-#pragma unroll
-  for (int j = 0; j < 8; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) o_s[wave][c * DH + 16 * j + 4 * g + i] = o[j][i] * w;
-  __syncthreads();
-  const long long part = ((long long)b * a.geom.n_kv_heads + kvh) * a.n_splits + split;
-  for (int e = threadIdx.x; e < 16 * DH; e += 256) {
-    const int col = e >> 7, dim = e & 127;
-    if (col >= G) continue;
-    const float acc = o_s[0][e] + o_s[1][e] + o_s[2][e] + o_s[3][e];
-    if (a.n_splits == 1) {
-      const float L = l_s[0][col] + l_s[1][col] + l_s[2][col] + l_s[3][col];
-      store1_split(a.out + ((long long)b * a.n_q_heads + kvh * G + col) * DH + dim, a.out_lo_offset, acc / (L * P_SCALE));
-    } else {
-      a.part_o[part * (16 * DH) + e] = acc;
-    }
-  }
-  if (a.n_splits > 1 && threadIdx.x < 16) {
-    const int col = threadIdx.x;
-    a.part_ml[part * 32 + col] = fmaxf(fmaxf(m_s[0][col], m_s[1][col]), fmaxf(m_s[2][col], m_s[3][col]));
-    a.part_ml[part * 32 + 16 + col] = l_s[0][col] + l_s[1][col] + l_s[2][col] + l_s[3][col];
-  }
-}
-
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a) {
-  const int kvh = blockIdx.x, b = blockIdx.y;
-  const int G = a.n_q_heads / a.geom.n_kv_heads;
-  const long long part0 = ((long long)b * a.geom.n_kv_heads + kvh) * a.n_splits;
-  const int ctx = a.row_pos[b] + 1;
-  const int used = min(a.n_splits, (ctx + a.split_tokens - 1) / a.split_tokens);
-  for (int e = threadIdx.x; e < G * DH; e += 256) {
-    const int col = e >> 7;
-    float M = -INFINITY;
-    for (int s = 0; s < used; ++s) M = fmaxf(M, a.part_ml[(part0 + s) * 32 + col]);
-    float L = 0.f, acc = 0.f;
-    for (int s = 0; s < used; ++s) {
-      const float w = exp2f(a.part_ml[(part0 + s) * 32 + col] - M);
-      L += a.part_ml[(part0 + s) * 32 + 16 + col] * w;
-      acc += a.part_o[(part0 + s) * (16 * DH) + e] * w;
-    }
-    store1_split(a.out + ((long long)b * a.n_q_heads + kvh * G) * DH + e, a.out_lo_offset, acc / (L * P_SCALE));
-  }
-}
-
-void launch_attention_decode(const AttnArgs& a, hipStream_t s) {
-  if (!a.rows) return;
-  attn_decode_kernel<<<dim3(a.n_splits, a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
-  if (a.n_splits > 1) attn_merge_kernel<<<dim3(a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
-}
-
 // ------------------------------------------------------------------------------ fused decode
 // One launch per layer for a decode step: sums nothing and stores nothing in between.
 // Prologue: rotary embedding of this sample's G query rows (kept in LDS as hi + lo half-precision parts) and, in the
@@ -254,7 +164,11 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
     if (hc < G) {
       const float* src = row + (kvh * G + hc) * DH;
       const float cc = cs[2 * i], sn = cs[2 * i + 1];
-      const float x0 = src[i], x1 = src[i + 64];
+      float x0 = src[i], x1 = src[i + 64];
+      for (int z = 1; z < a.qkv_planes; ++z) {
+        x0 += src[z * a.qkv_plane_stride + i];
+        x1 += src[z * a.qkv_plane_stride + i + 64];
+      }
       u = x0 * cc - x1 * sn;
       w = x1 * cc + x0 * sn;
     }
@@ -268,7 +182,11 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
     if (tid < 64) {
       const float* src = row + q_dim + kvh * DH;
       const float cc = cs[2 * i], sn = cs[2 * i + 1];
-      const float x0 = src[i], x1 = src[i + 64];
+      float x0 = src[i], x1 = src[i + 64];
+      for (int z = 1; z < a.qkv_planes; ++z) {
+        x0 += src[z * a.qkv_plane_stride + i];
+        x1 += src[z * a.qkv_plane_stride + i + 64];
+      }
       const uint16_t k0 = f32_to_f16(x0 * cc - x1 * sn).bits, k1 = f32_to_f16(x1 * cc + x0 * sn).bits;
       kv_s[0][i] = k0;
       kv_s[0][i + 64] = k1;
@@ -277,7 +195,12 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
       dst[kv_k_offset(a.geom, tok, i + 64)] = k1;
     } else {
       const float* src = row + q_dim + kv_dim + kvh * DH;
-      const uint16_t v0 = f32_to_f16(src[i]).bits, v1 = f32_to_f16(src[i + 64]).bits;
+      float y0 = src[i], y1 = src[i + 64];
+      for (int z = 1; z < a.qkv_planes; ++z) {
+        y0 += src[z * a.qkv_plane_stride + i];
+        y1 += src[z * a.qkv_plane_stride + i + 64];
+      }
+      const uint16_t v0 = f32_to_f16(y0).bits, v1 = f32_to_f16(y1).bits;
       kv_s[1][i] = v0;
       kv_s[1][i + 64] = v1;
       uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, page, kvh, 1);

@@ -124,7 +124,7 @@ void launch_f32_to_bf16(const float* src, uint16_t* dst, long long n, hipStream_
 
 // Paged grouped-query attention on the matrix cores (KV_MATRIX pool, head_dim 128).
 struct AttnArgs {
-  const uint16_t* q;        // bf16 hi plane [rows][n_q_heads][128], rotary applied (unfused kernels)
+  const uint16_t* q;        // prefill: half-precision hi plane [rows][n_q_heads][128], rotary applied
   long long q_lo_offset;    // elements to its lo plane
   uint16_t* out;            // bf16 hi plane [rows][n_q_heads][128]
   long long out_lo_offset;  // elements to its lo plane
@@ -138,15 +138,17 @@ struct AttnArgs {
   int n_splits, split_tokens;      // KV range per workgroup (multiple of 128)
   float* part_o;                   // [rows][n_kv_heads][n_splits][16][128]
   float* part_ml;                  // [rows][n_kv_heads][n_splits][2][16]
-  // fused decode (rotary + KV write + attention + split merge in one launch)
-  const float* qkv_raw;            // fp32 [rows][(n_q_heads + 2 n_kv_heads) * 128], projections before rotary
+  // decode (rotary + KV write + attention in one launch, split merge in a second)
+  const float* qkv_raw;            // fp32 [planes][rows][(n_q_heads + 2 n_kv_heads) * 128], projections before
+                                   // rotary, as split-K planes that the kernel sums in ascending order
+  int qkv_planes;                  // >= 1
+  long long qkv_plane_stride;      // floats between planes
   const float* cos_sin;
   uint16_t* kv_pool_w;
   // prefill: packed sequences
   const int *seq_row0, *seq_len, *seq_slot;
   int n_seqs, max_seq_len;
 };
-void launch_attention_decode(const AttnArgs& a, hipStream_t s);
 void launch_attention_prefill(const AttnArgs& a, hipStream_t s);
 void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s);
 
