@@ -282,15 +282,27 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
   const uint16_t* a_base = (const uint16_t*)p.a;
   const long long lo_off = (const uint16_t*)p.a_lo - a_base;
 
+  // Staging of the activations: one load instruction brings 8 rows x 128 bytes - both k-tiles
+  // of the stage, one plane - as full cache lines (a 16-row x 64-byte fragment load costs the
+  // L2 path twice as much per byte).  Unit u = 4 s + wave -> (plane, group of 8 rows); a lane
+  // holds chunk c = lane % 8 of row lane / 8, i.e. k-tile c / 4, fragment column group c % 4.
+  // In LDS a fragment's sixteen 16-byte slots of one column group are permuted by
+  // row ^ (2 * group + k-tile), which spreads a row's 8 chunks over all banks.
+  static_assert(KC == 2 && FR == 4 * MT, "a stage is two k-tiles");
+  const int st_kk = (lane & 7) >> 2, st_g = lane & 3;
   const uint16_t* st_src[PER];
+  int st_dst[PER];
 #pragma unroll
   for (int s = 0; s < PER; ++s) {
-    const int f = 4 * s + wave;
-    const int plane = (f / MT) & 1, mt = f % MT;
-    const int m = min(m0 + mt * 16 + r, m_limit - 1);
+    const int u = 4 * s + wave;
+    const int plane = u / (2 * MT), rg = u % (2 * MT);
+    const int mt = rg >> 1, rr = (rg & 1) * 8 + (lane >> 3);
+    const int m = min(m0 + mt * 16 + rr, m_limit - 1);
     const long long row = row_map ? row_map[m] : m;
-    st_src[s] = a_base + row * p.lda + g * 8 + (plane ? lo_off : 0);
+    st_src[s] = a_base + row * p.lda + st_g * 8 + (plane ? lo_off : 0);
+    st_dst[s] = ((st_kk * 2 + plane) * MT + mt) * 64 + st_g * 16 + (rr ^ ((2 * st_g + st_kk) & 7));
   }
+  const int rd_off[2] = {g * 16 + (r ^ ((2 * g) & 7)), g * 16 + (r ^ ((2 * g + 1) & 7))};
   const u32x4* w_src[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) w_src[j] = wp + (long long)min(nt0 + j, n_tiles - 1) * k_tiles * 64 + lane;
@@ -303,11 +315,10 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
 
   u32x4 rst[R][PER];
   u32x4 rb[R][KC][NT];
-  // fragment f = 4 s + wave belongs to k-tile 4 s / (2 MT) of its stage (2 MT is a multiple of 4)
 #define GEMM_LOAD_STAGE(KT, SLOT)                                                                 \
   {                                                                                               \
     _Pragma("unroll") for (int s = 0; s < PER; ++s) {                                             \
-      const int k = min((KT) + (4 * s) / (2 * MT), kt_end - 1);                                   \
+      const int k = min((KT) + st_kk, kt_end - 1);                                                \
       rst[SLOT][s] = *(const u32x4*)(st_src[s] + (long long)k * 32);                              \
     }                                                                                             \
     _Pragma("unroll") for (int kk = 0; kk < KC; ++kk)                                             \
@@ -319,7 +330,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
 #pragma unroll
   for (int d = 0; d < R - 1; ++d) GEMM_LOAD_STAGE(kt_begin + d * KC, d)
 #pragma unroll
-  for (int s = 0; s < PER; ++s) a_lds[0][(4 * s + wave) * 64 + lane] = rst[0][s];
+  for (int s = 0; s < PER; ++s) a_lds[0][st_dst[s]] = rst[0][s];
   __syncthreads();
   int buf = 0;
   for (int kt = kt_begin; kt < kt_end; kt += R * KC) {
@@ -333,7 +344,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
 #pragma unroll
           for (int plane = 1; plane >= 0; --plane)
 #pragma unroll
-            for (int i = 0; i < MT; ++i) a[kk][plane][i] = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + lane];
+            for (int i = 0; i < MT; ++i) a[kk][plane][i] = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + rd_off[kk]];
         GEMM_LOAD_STAGE(k0 + (R - 1) * KC, (d + R - 1) % R)
 #pragma unroll
         for (int kk = 0; kk < KC; ++kk)
@@ -348,7 +359,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs p) {
                                                                     acc[i][j], 0, 0, 0);
         if (k0 + KC < kt_end) {
 #pragma unroll
-          for (int s = 0; s < PER; ++s) a_lds[buf ^ 1][(4 * s + wave) * 64 + lane] = rst[(d + 1) % R][s];
+          for (int s = 0; s < PER; ++s) a_lds[buf ^ 1][st_dst[s]] = rst[(d + 1) % R][s];
         }
         __syncthreads();
         buf ^= 1;
@@ -453,21 +464,30 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
   const uint16_t* a_base = (const uint16_t*)p.a;
   const long long lo_off = (const uint16_t*)p.a_lo - a_base;
 
-  // the activation fragments this wavefront stages: f = wave + 4 s -> (kk, plane, mt)
+  // Staging of the activations: one load instruction brings 8 rows x 128 bytes - both k-tiles
+  // of the stage, one plane - as full cache lines (a 16-row x 64-byte fragment load costs the
+  // L2 path twice as much per byte).  Unit u = wave + 4 s -> (plane, group of 8 rows); a lane
+  // holds chunk c = lane % 8 of row lane / 8, i.e. k-tile c / 4, fragment column group c % 4.
+  // In LDS a fragment's sixteen 16-byte slots of one column group are permuted by
+  // row ^ (2 * group + k-tile), which spreads a row's 8 chunks over all banks.
+  static_assert(KC == 2 && FR == 4 * MT, "a stage is two k-tiles");
+  const int st_kk = (lane & 7) >> 2, st_g = lane & 3;
   const uint16_t* st_src[PER];
+  int st_dst[PER];
 #pragma unroll
   for (int s = 0; s < PER; ++s) {
-    const int f = wave + 4 * s;
+    const int u = wave + 4 * s;
+    const int plane = u / (2 * MT), rg = u % (2 * MT);
+    const int mt = rg >> 1, rr = (rg & 1) * 8 + (lane >> 3);
+    const int m = m0 + mt * 16 + rr;
     st_src[s] = nullptr;
-    if (f < FR) {
-      const int kk = f / (2 * MT), plane = (f / MT) & 1, mt = f % MT;
-      const int m = m0 + mt * 16 + r;
-      if (m < m_limit) {
-        const long long row = row_map ? row_map[m] : m;
-        st_src[s] = a_base + row * p.lda + (long long)kk * 32 + g * 8 + (plane ? lo_off : 0);
-      }
+    if (m < m_limit) {
+      const long long row = row_map ? row_map[m] : m;
+      st_src[s] = a_base + row * p.lda + (lane & 7) * 8 + (plane ? lo_off : 0);
     }
+    st_dst[s] = ((st_kk * 2 + plane) * MT + mt) * 64 + st_g * 16 + (rr ^ ((2 * st_g + st_kk) & 7));
   }
+  const int rd_off[2] = {g * 16 + (r ^ ((2 * g) & 7)), g * 16 + (r ^ ((2 * g + 1) & 7))};
 
   f32x4 acc[MT][NT];
 #pragma unroll
@@ -484,9 +504,8 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
   auto load_stage = [&](int kt, Stage& sg) {
 #pragma unroll
     for (int s = 0; s < PER; ++s) {
-      const int kk = (wave + 4 * s) / (2 * MT);
       sg.st[s] = make_uint4(0, 0, 0, 0);
-      if (st_src[s] && kt + kk < kt_end) sg.st[s] = *(const uint4*)(st_src[s] + (long long)kt * 32);
+      if (st_src[s] && kt + st_kk < kt_end) sg.st[s] = *(const uint4*)(st_src[s] + (long long)kt * 32);
     }
 #pragma unroll
     for (int kk = 0; kk < KC; ++kk)
@@ -507,8 +526,7 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
       const int k0 = kt + d * KC;
       if (k0 >= kt_end) break;  // uniform over the workgroup
 #pragma unroll
-      for (int s = 0; s < PER; ++s)
-        if (wave + 4 * s < FR) a_lds[buf][(wave + 4 * s) * 64 + lane] = ring[d].st[s];
+      for (int s = 0; s < PER; ++s) a_lds[buf][st_dst[s]] = ring[d].st[s];
 #pragma unroll
       for (int kk = 0; kk < KC; ++kk)
 #pragma unroll
@@ -521,7 +539,7 @@ __global__ __launch_bounds__(256) void gemm_tile_ring_kernel(GemmArgs p) {
         for (int plane = 1; plane >= 0; --plane) {  // lo parts first, then hi
           Frag a[MT];
 #pragma unroll
-          for (int i = 0; i < MT; ++i) a[i].u = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + lane];
+          for (int i = 0; i < MT; ++i) a[i].u = a_lds[buf][((kk * 2 + plane) * MT + i) * 64 + rd_off[kk]];
 #pragma unroll
           for (int i = 0; i < MT; ++i)
 #pragma unroll
