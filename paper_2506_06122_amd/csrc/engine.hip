@@ -193,11 +193,13 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   const size_t R = c.r_max;
   c.x.alloc(R * d);
   if (!c.simple) {
-    // activation buffers hold two planes each: hi parts, then lo parts
-    c.h_bf16.alloc(2 * R * d);
+    // activation buffers hold two planes each: hi parts, then lo parts; rows padded to whole
+    // 16-row fragments for the small decode steps, which keep them in fragment order
+    const size_t Rp = (R + 31) / 32 * 32;
+    c.h_bf16.alloc(2 * Rp * d);
     c.q_bf16.alloc(2 * R * c.q_dim);
-    c.attn_bf16.alloc(2 * R * c.q_dim);
-    c.act_bf16.alloc(2 * R * (moe ? (size_t)m.top_k * m.expert_ffn_dim : (size_t)m.ffn_dim));
+    c.attn_bf16.alloc(2 * Rp * c.q_dim);
+    c.act_bf16.alloc(2 * Rp * (moe ? (size_t)m.top_k * m.expert_ffn_dim : (size_t)m.ffn_dim));
     if (moe) {
       const size_t picks = R * m.top_k;
       c.moe_max_blocks = (int)(std::min<size_t>(m.n_experts, picks) + picks / kMoeBlockRows + 1);
@@ -620,6 +622,7 @@ static void stream_project(rollout_ctx& c, const DevBuf<uint16_t>& a, int lda, c
   g.K = K;
   g.lda = lda;
   g.ldo = ldo;
+  g.frag = true;  // every operand plane of this path is in fragment order
   g.eps = c.md.rms_eps;
   g.ssq_stride = 256;
   if (normalise_input) {
@@ -662,6 +665,7 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
     rn.embed = (const uint16_t*)c.embed.p;
     rn.gain = c.layers[0].norm1.p;
     rn.ssq_out = c.ssq.p;
+    rn.h_frag = true;
     c.timer.begin("row_norm_kernel", (double)R * d * (2 + 4 + 2 + 2), 0, s);
     launch_row_norm(rn, s);
     c.timer.end(s);
@@ -674,6 +678,7 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
     AttnArgs at{};
     at.out = c.attn_bf16.p;
     at.out_lo_offset = (long long)(c.attn_bf16.n / 2);
+    at.out_frag = true;
     at.kv_pool = (const uint16_t*)c.kv_pool.p;
     at.kv_pool_w = (uint16_t*)c.kv_pool.p;
     at.geom = c.geom;
@@ -730,8 +735,9 @@ void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, floa
   if (!c.simple) {
     const uint16_t* hn = c.hn_bf16.p;
     long long hn_lo = (long long)(c.hn_bf16.n / 2);
-    if (c.h_is_final && !rows_index) {
-      hn = c.h_bf16.p + (size_t)first * d;  // the fused decode path already applied the final norm
+    const bool from_h = c.h_is_final && !rows_index && first == 0;
+    if (from_h) {
+      hn = c.h_bf16.p;  // the fused decode path already applied the final norm's gain
       hn_lo = (long long)(c.h_bf16.n / 2);
     } else {
       RowNormArgs rn{};
@@ -750,7 +756,8 @@ void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, floa
     GemmArgs g{};
     g.a = hn;
     g.a_lo = hn + hn_lo;
-    if (c.h_is_final && !rows_index) {  // h holds x * gain; the rsqrt factor rides in the epilogue
+    if (from_h) {  // h holds x * gain in fragment order; the rsqrt factor rides in the epilogue
+      g.frag = true;
       g.rinv_ssq = c.ssq.p;
       g.rinv_partials = c.ssq_partials;
       g.ssq_stride = 256;

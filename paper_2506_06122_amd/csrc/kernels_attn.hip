@@ -129,6 +129,12 @@ __device__ inline void store1_split(uint16_t* dst, long long lo_offset, float a)
   dst[lo_offset] = lo;
 }
 
+// element (row b, column k) of the decode result
+__device__ inline long long out_offset(const AttnArgs& a, int b, int k) {
+  const int q_dim = a.n_q_heads * DH;
+  return a.out_frag ? frag_offset(b, k, q_dim >> 5) : (long long)b * q_dim + k;
+}
+
 // ------------------------------------------------------------------------------ fused decode
 // One launch per layer for a decode step: sums nothing and stores nothing in between.
 // Prologue: rotary embedding of this sample's G query rows (kept in LDS as hi + lo half-precision parts) and, in the
@@ -255,13 +261,12 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
   __syncthreads();
   const long long pair = (long long)b * n_kv + kvh;
   const long long part = pair * a.n_splits + split;
-  uint16_t* out = a.out + ((long long)b * a.n_q_heads + kvh * G) * DH;
   for (int e = tid; e < G * DH; e += 256) {
     const int col = e >> 7;
     const float acc = o_s[0][e] + o_s[1][e] + o_s[2][e] + o_s[3][e];
     if (used == 1) {
       const float L = l_s[0][col] + l_s[1][col] + l_s[2][col] + l_s[3][col];
-      store1_split(out + e, a.out_lo_offset, acc / (L * P_SCALE));
+      store1_split(a.out + out_offset(a, b, kvh * G * DH + e), a.out_lo_offset, acc / (L * P_SCALE));
     } else {
       a.part_o[part * (16 * DH) + e] = acc;
     }
@@ -305,7 +310,6 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
     w_s[s][col] = w / (L * P_SCALE);
     __syncthreads();
   }
-  uint16_t* out = a.out + ((long long)b * a.n_q_heads + kvh * G) * DH;
   for (int e = tid; e < G * DH; e += 256) {
     const int col = e >> 7;
     float v[16];
@@ -314,7 +318,7 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
     float acc = 0.f;
 #pragma unroll
     for (int s = 0; s < 16; ++s) acc += v[s] * w_s[s][col];
-    store1_split(out + e, a.out_lo_offset, acc);
+    store1_split(a.out + out_offset(a, b, kvh * G * DH + e), a.out_lo_offset, acc);
   }
 }
 

@@ -20,9 +20,20 @@
 //                    turns these into log-probs)
 enum { EPI_F32 = 0, EPI_SWIGLU_BF16 = 1, EPI_RESID = 2, EPI_LSE = 3 };
 
+// Fragment order of an activation plane [rows][K] (decode steps with at most 32 rows): the
+// 16-row x 32-deep operand fragment of the 16x16x32 matrix instruction is stored as one
+// contiguous 1 KiB block [lane][8] with lane = (k % 32 / 8) * 16 + row % 16, fragments ordered
+// [row / 16][k / 32].  A wavefront then reads an operand fragment as whole cache lines, as it
+// reads a weight fragment.  Rows are padded to a multiple of 16 (the pad is never written and
+// what is read from it only reaches output rows that are not stored).
+__host__ __device__ inline long long frag_offset(int m, int k, int k_tiles) {
+  return (((long long)(m >> 4) * k_tiles + (k >> 5)) << 9) + ((((k >> 3) & 3) * 16 + (m & 15)) << 3) + (k & 7);
+}
+
 struct GemmArgs {
   const void* a;     // bf16 [rows][K], row stride lda: hi parts of the activations
   const void* a_lo;  // same shape: lo parts (value = hi + lo)
+  bool frag = false; // stream kernel: `a`, `h` and the EPI_SWIGLU_BF16 result are in fragment order
   const void* w;     // packed bf16 weight, N/16 x K/32 fragments of 1 KiB
   void* out;         // EPI_F32: float [splits][M][ldo]; EPI_SWIGLU_BF16: bf16 [M][ldo] (ldo = N/2)
   int M, N, K, lda, ldo;
@@ -87,6 +98,7 @@ struct RowNormArgs {
   uint16_t* h;              // bf16 [rows][hidden], hi plane
   long long h_lo_offset;    // elements from the hi plane to the lo plane
   float* ssq_out;           // when set: h = x * gain without the rsqrt factor, ssq_out[r] = sum x[r]^2
+  bool h_frag = false;      // h in fragment order
   const int* tokens;
   const uint16_t* embed;
   const int* rows_index;
@@ -128,6 +140,7 @@ struct AttnArgs {
   long long q_lo_offset;    // elements to its lo plane
   uint16_t* out;            // bf16 hi plane [rows][n_q_heads][128]
   long long out_lo_offset;  // elements to its lo plane
+  bool out_frag = false;    // decode: out in fragment order, K = n_q_heads * 128
   const uint16_t* kv_pool;
   KvGeom geom;
   const int* page_table;

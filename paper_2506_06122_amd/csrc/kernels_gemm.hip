@@ -59,7 +59,8 @@ __device__ inline void store_unit(const GemmArgs& p, int m, int nt, const f32x4&
     *(float4*)(out + nt * 16 + g * 4) = make_float4(t0[0], t0[1], t0[2], t0[3]);
     if (two) *(float4*)(out + (nt + 1) * 16 + g * 4) = make_float4(t1[0], t1[1], t1[2], t1[3]);
   } else {  // EPI_SWIGLU_BF16: tile nt = gate, nt + 1 = up; act[m][f] = silu(gate) * up
-    uint16_t* out = (uint16_t*)p.out + (long long)m * p.ldo + (nt >> 1) * 16 + g * 4;
+    const int f = (nt >> 1) * 16 + g * 4;
+    uint16_t* out = (uint16_t*)p.out + (p.frag ? frag_offset(m, f, p.ldo >> 5) : (long long)m * p.ldo + f);
     uint16_t h[4], lo[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) split_bf16(silu_f(t0[e]) * t1[e], h[e], lo[e]);
@@ -88,13 +89,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // activation row pointers of this lane (row m0 + 16 i + r), or null past the last row
+  // activation pointers of this lane (row m0 + 16 i + r, k = 8 g .. 8 g + 7 of k-tile 0), or null
+  // past the last row; a k-tile further on is a_kstep elements away
   const uint16_t* a_row[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i) {
     const int m = m0 + i * 16 + r;
-    a_row[i] = m < p.M ? a_base + (long long)m * p.lda + g * 8 : nullptr;
+    a_row[i] = m >= p.M ? nullptr
+               : p.frag ? a_base + (((long long)(m >> 4) * k_tiles) << 9) + lane * 8
+                        : a_base + (long long)m * p.lda + g * 8;
   }
+  const int a_kstep = p.frag ? 512 : 32;
   const long long lo_off = (const uint16_t*)p.a_lo - a_base;
 
   // Epilogue unit (one row tile, up to two column tiles) of this wavefront, if it has one.  Its
@@ -135,8 +140,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
         a[kk][i].u = make_uint4(0, 0, 0, 0);
         al[kk][i].u = make_uint4(0, 0, 0, 0);
         if (live && a_row[i]) {
-          a[kk][i].u = *(const uint4*)(a_row[i] + (kt + kk) * 32);
-          al[kk][i].u = *(const uint4*)(a_row[i] + lo_off + (kt + kk) * 32);
+          a[kk][i].u = *(const uint4*)(a_row[i] + (kt + kk) * a_kstep);
+          al[kk][i].u = *(const uint4*)(a_row[i] + lo_off + (kt + kk) * a_kstep);
         }
       }
     }
@@ -202,7 +207,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
         split_bf16(x4.y * gn[q].y, hi[1], lo[1]);
         split_bf16(x4.z * gn[q].z, hi[2], lo[2]);
         split_bf16(x4.w * gn[q].w, hi[3], lo[3]);
-        uint16_t* hp = p.h + (long long)um * p.N + n;
+        uint16_t* hp = p.h + (p.frag ? frag_offset(um, n, n_tiles >> 1) : (long long)um * p.N + n);
         *(uint2*)hp = pack4(hi);
         *(uint2*)(hp + p.h_lo_offset) = pack4(lo);
       }

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
     split_bf16(x[v].y * gn.y * rinv, hi[1], lo[1]);
     split_bf16(x[v].z * gn.z * rinv, hi[2], lo[2]);
     split_bf16(x[v].w * gn.w * rinv, hi[3], lo[3]);
-    uint16_t* hp = a.h + (long long)r * a.hidden + 4 * c;
+    uint16_t* hp = a.h + (a.h_frag ? frag_offset(r, 4 * c, a.hidden >> 5) : (long long)r * a.hidden + 4 * c);
     *(uint2*)hp = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
     *(uint2*)(hp + a.h_lo_offset) =
         make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
