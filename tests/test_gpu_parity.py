@@ -125,6 +125,67 @@ def test_c2_shape_slice_matches_oracle(simple):
     eng.close()
 
 
+def test_c2_full_batch_sampled_rows_and_row_invariance():
+    """The benchmark's job as it is launched there - the full model, all 32 prompts x 8 samples
+    (256 live rows: packed prefill of about 9k prompt tokens, 64 x 128 tile projections,
+    one-split attention), teacher-forced for 3 steps - checked two ways.  (1) Rows the oracle
+    can afford, computed one by one: the shortest and the longest prompt, and one sample of each
+    through the decode steps.  (2) A property that holds at any size, on all 256 rows: a row's
+    result does not depend on where it sits in the batch, so samples of one prompt that are fed
+    the same tokens must produce bit-identical logits, and every returned log-prob must be the
+    log-softmax of its own logits row."""
+    shape = workloads.C2_1P5B
+    w = workloads.make_weights(shape, seed=1)
+    load = workloads.load_c2()
+    P, n = load.n_prompts, load.n_samples
+    toks, offs = load.prompt_tokens, load.prompt_offsets
+    lens = np.diff(offs)
+    steps = 3
+    rng = np.random.default_rng(17)
+    forced = rng.integers(0, shape.vocab, (P * n, steps)).astype(np.int32)
+    for p in range(P):  # samples 0..3 of a prompt share their tokens
+        forced[p * n + 1: p * n + 4] = forced[p * n]
+    kv_per_token = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2
+    need = int(lens.sum()) + P * n * (steps + 64)
+    eng = make_engine(shape, w, kv_pool_bytes=max(need * kv_per_token, 1 << 30), max_live_samples=P * n,
+                      max_context=int(lens.max()) + steps + 1, max_batch_tokens=16384)
+    ids, tk, lps, fin = eng.rollout_prefill(toks, offs, n, np.full(P * n, steps, np.int32), forced_first=forced[:, 0])
+    assert len(ids) == P * n and np.array_equal(tk, forced[:, 0])
+    model = oracle_model(shape, w)
+    fwd = T.KVForward(model)
+    picks = [int(np.argmin(lens)), int(np.argmax(lens))]
+    gpu = eng.rollout_debug_logits()
+    caches, worst = {}, 0.0
+    for p in picks:
+        c = fwd.new_cache()
+        ref = fwd.extend([c], [toks[offs[p]:offs[p + 1]]])[0][-1]
+        worst = max(worst, float(np.max(np.abs(gpu[p] - ref))))
+        caches[p] = c
+    inv_t = np.float32(1.0)
+    for i in range(0, P * n, 7):
+        assert abs(sampler.log_prob(gpu[i // n], inv_t, int(forced[i, 0])) - float(lps[i])) < 2e-5
+    for t in range(1, steps):
+        ids2, tk, lps, fin = eng.rollout_decode_step(forced_tokens=forced[:, t])
+        assert np.array_equal(ids2, ids) and np.array_equal(tk, forced[:, t])
+        gpu = eng.rollout_debug_logits()
+        assert gpu.shape == (P * n, shape.vocab)
+        for p in range(P):
+            for j in range(1, 4):
+                assert np.array_equal(gpu[p * n], gpu[p * n + j]), f"prompt {p}: row {j} differs from row 0"
+        for i in range(0, P * n, 7):
+            assert abs(sampler.log_prob(gpu[i], inv_t, int(forced[i, t])) - float(lps[i])) < 2e-5
+        for p in picks:  # sample 5 of the prompt (its own tokens), oracle one row at a time
+            i = p * n + 5
+            if t == 1:
+                caches[p] = caches[p].fork()
+            ref = fwd.extend([caches[p]], [[int(forced[i, t - 1])]])[0][0]
+            worst = max(worst, float(np.max(np.abs(gpu[i] - ref))))
+    print(f"c2 full batch: max |dlogits| on the oracle's rows = {worst:.3e}")
+    assert worst <= TOL["bf16"]
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
+    eng.close()
+
+
 @pytest.mark.parametrize("which", ["c3-dense", "c4-moe"])
 def test_large_config_shapes_reduced_depth(which):
     """Every matrix shape of configs 3/5 (hidden 3584, 28/4 heads, FFN 18944, vocab 152064) and
