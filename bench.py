@@ -99,7 +99,34 @@ def kernel_table(eng, before):
     return kernels, bracket_ms
 
 
-def roofline_of(kernels, bracket_ms):
+def measured_traffic(kernel: str, summary: str):
+    """HBM bytes per launch of `kernel` from the committed counter summary (rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE, in KiB, each scaled by the factor a plain copy kernel of known size
+    gave in the same run), or None when there is no summary for this workload or the kernel
+    sources have changed since the counters were taken."""
+    from paper_2506_06122_amd import build
+    path = os.path.join(ROOT, "profiles", summary)
+    if not os.path.exists(path):
+        return None
+    digest, factor, mean = None, {}, {}
+    want = kernel.replace(" ", "")
+    with open(path) as f:
+        for line in f:
+            if line.startswith("kernel-sources-sha256:"):
+                digest = line.split(":", 1)[1].strip()
+            elif line.startswith("factor "):
+                _, counter, value = line.split()
+                factor[counter] = float(value)
+            elif "\tlaunches=" in line:
+                name, counter, _, m = line.rstrip("\n").split("\t")[:4]
+                if name.replace("void ", "").replace(" ", "") == want:
+                    mean[counter] = float(m.split("=")[1])
+    if digest != build.sources_digest() or set(mean) != {"FETCH_SIZE", "WRITE_SIZE"} or set(factor) != set(mean):
+        return None
+    return 1024.0 * sum(factor[c] * mean[c] for c in mean)
+
+
+def roofline_of(kernels, bracket_ms, traffic_summary=None):
     if not kernels:
         return None
     top = kernels[0]
@@ -113,6 +140,9 @@ def roofline_of(kernels, bracket_ms):
         roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": ach / HBM_PEAK_GBS, "traffic": None}
     roofline["kernel"] = top["name"]
+    roofline["algorithmic_bytes_per_launch"] = top["bytes"] / top["launches"]
+    if traffic_summary:
+        roofline["traffic"] = measured_traffic(top["name"], traffic_summary)
     roofline["avg_launch_us"] = 1e3 * top["ms"] / top["launches"]
     roofline["timed_launches"] = top["launches"]
     roofline["event_bracket_us"] = 1e3 * bracket_ms
@@ -218,6 +248,9 @@ def main() -> int:
     stats = eng.rollout_get_stats()
     kernels, bracket_ms = kernel_table(eng, before)
 
+    # counters exist for the full workloads only, taken over one whole job
+    summary = None if (args.prompts or cut) else {"c2": "rollout_c2_hbm_traffic.txt",
+                                                  "c5": "logprobs_c5_hbm_traffic.txt"}.get(wl)
     out = {
         "metric": "rollout output tokens/sec on 1 MI355X" if wl != "c5" else "teacher-forced tokens/sec on 1 MI355X",
         "value": emitted / dt, "unit": "tokens/s",
@@ -226,7 +259,7 @@ def main() -> int:
         "config": {"workload": desc,
                    "output_tokens_per_step": emitted // max(args.steps, 1),
                    "decode_calls_per_step": (int(stats["decode_steps"]) - calls0) // max(args.steps, 1)},
-        "roofline": roofline_of(kernels, bracket_ms),
+        "roofline": roofline_of(kernels, bracket_ms, summary),
     }
     eng.close()
     del eng

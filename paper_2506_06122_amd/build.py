@@ -24,6 +24,19 @@ def sources() -> list[str]:
     return sorted(f for f in os.listdir(CSRC) if f.endswith(".hip"))
 
 
+def sources_digest() -> str:
+    """SHA-256 over the kernel sources (csrc/*.hip, csrc/*.h, in name order).  Profiler
+    summaries record it, so a reader can tell whether counters were taken on these kernels."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(CSRC)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            with open(os.path.join(CSRC, f), "rb") as fh:
+                h.update(fh.read())
+    return h.hexdigest()
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(BUILD, src.replace(".hip", ".o"))
     cmd = [HIPCC, *FLAGS, *PER_FILE.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
