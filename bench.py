@@ -45,6 +45,19 @@ def run_job(eng, load) -> int:
         emitted += len(ids)
 
 
+def run_queue_job(eng, load) -> int:
+    """The same kind of job fed through the library's prompt queue: every prompt is pushed up
+    front, the scheduler admits them as slots and pages free up.  Returns the tokens emitted."""
+    eng.rollout_queue_push(load.prompt_tokens, load.prompt_offsets, load.n_samples, load.max_new_tokens,
+                           eos_id=-1, temperature=load.temperature, top_p=load.top_p)
+    emitted = 0
+    while True:
+        ids = eng.rollout_queue_step()[0]
+        if not len(ids):
+            return emitted
+        emitted += len(ids)
+
+
 def cpu_baseline(shape, weights, load) -> dict:
     """The oracle, as it stands, on a bounded slice: one 256-token prompt, 4 samples, 64 new
     tokens each (weights widened to fp64 beforehand, not timed)."""
@@ -161,9 +174,10 @@ def main() -> int:
     ap.add_argument("--timing-stride", type=int, default=16,
                     help="bracket kernels with HIP events on every n-th library call (0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5"], default="c2",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue"], default="c2",
                     help="c2 = headline (1.5B shape); c3 = 7B-shape rollout; c4 = 30B-A3B-shape MoE rollout; "
-                         "c5 = teacher-forced log-prob pass on the 7B shape")
+                         "c5 = teacher-forced log-prob pass on the 7B shape; c2-queue = config 2's model and "
+                         "length laws with 4x the prompts fed through the prompt queue into the same 256 live slots")
     ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
     ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -189,7 +203,8 @@ def main() -> int:
         del src, dst
 
     wl = args.workload
-    shape = {"c2": workloads.C2_1P5B, "c3": workloads.C3_7B, "c4": workloads.C4_30B_A3B, "c5": workloads.C3_7B}[wl]
+    shape = {"c2": workloads.C2_1P5B, "c3": workloads.C3_7B, "c4": workloads.C4_30B_A3B, "c5": workloads.C3_7B,
+             "c2-queue": workloads.C2_1P5B}[wl]
     cut = ""
     if args.layers and args.layers < shape.n_layers:
         cut = f", cut to {args.layers} of {shape.n_layers} layers"
@@ -211,6 +226,18 @@ def main() -> int:
         desc = ("configs[4]: teacher-forced log-prob pass, Qwen2.5-7B-shaped dense decoder, bf16, %d packed sequences "
                 "(of the config's 512), length U{512..8192}, %d tokens%s" % (n_seqs, len(tokens), cut))
         load = None
+    elif wl == "c2-queue":
+        live = 256
+        load = workloads.load_c2(n_prompts=args.prompts or 128)
+        max_prompt = int(np.diff(load.prompt_offsets).max())
+        max_ctx = max_prompt + int(load.max_new_tokens.max())
+        # worst case: every live sample at the longest context (pages are taken at admission)
+        eng = R.Rollout(shape, weights, kv_pool_bytes=live * (max_ctx + 64) * kv_bytes_per_token, page_tokens=32,
+                        max_live_samples=live, max_context=max_ctx, max_batch_tokens=max(16384, max_prompt),
+                        seed=load.sampler_seed, flags=flags, timing_stride=max(args.timing_stride, 1))
+        work = lambda: run_queue_job(eng, load)
+        desc = ("configs[1]'s model and length laws, %d prompts x %d samples pushed to the prompt queue, admitted "
+                "into %d live slots as samples finish" % (load.n_prompts, load.n_samples, live)) + cut
     else:
         loader = {"c2": workloads.load_c2, "c3": workloads.load_c3, "c4": workloads.load_c4}[wl]
         load = loader(n_prompts=args.prompts) if args.prompts else loader()

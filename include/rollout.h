@@ -170,6 +170,55 @@ int rollout_logprobs(rollout_ctx *ctx, int32_t n_seqs, const int32_t *tokens, co
  * pages.  Ids that are not live are ignored.  Returns the number aborted. */
 int rollout_abort(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids);
 
+/* ---- Queue-fed continuous rollout ---------------------------------------------------------
+ * The sample-level lifecycle of paper sections 4.1 and 4.3 driven by the library: prompts wait
+ * in a host-side queue, are admitted ("add request") as live-sample slots and KV pages free
+ * up while the other samples keep decoding, and once a target number of prompts has all its
+ * samples finished the still-running samples are aborted ("abort request") and the waiting
+ * prompts dropped - the mechanism that dynamic sampling uses to cut the long tail.  A sample's
+ * tokens still depend only on (weights, prompt, seed, sample id): the queue decides when a
+ * sample runs, never what it emits. */
+typedef struct {
+  uint64_t prompts_pushed, prompts_admitted, prompts_completed; /* completed = every sample finished */
+  uint64_t samples_aborted;                                     /* by the target policy */
+  int32_t prompts_waiting;
+  int32_t closed;                                               /* 1 once the target was reached */
+} rollout_queue_stats;
+
+/* Appends n_prompts prompts (n_samples samples each) to the queue; host arrays as for
+ * rollout_prefill, copied.  Nothing runs on the GPU.  prompt_ids (host int64 [n_prompts], may be
+ * NULL) receives each prompt's counter; its samples will carry the ids counter * n_samples + j.
+ * Counters are taken here, in push order, from the same sequence rollout_prefill uses.
+ * Errors (nothing is queued): E_INVAL (bad arguments; n_samples differs from earlier pushes;
+ * queue closed); E_NOMEM when a prompt could never be admitted, even into an idle context
+ * (longer than max_batch_tokens, prompt + response beyond max_context, more samples than
+ * live-sample slots, more pages than the pool holds). */
+int rollout_queue_push(rollout_ctx *ctx, int32_t n_prompts, const int32_t *tokens, const int32_t *offsets,
+                       int32_t n_samples, const int32_t *max_new_tokens, int32_t eos_id, float temperature,
+                       float top_p, int64_t *prompt_ids);
+
+/* admit_min_prompts >= 1: a step admits waiting prompts only when at least that many of them
+ * (or all that wait) fit, or when no sample is live - fewer, larger prefill calls.
+ * target_prompts: 0 = run everything; otherwise the queue closes when that many admitted
+ * prompts are complete. */
+int rollout_queue_policy(rollout_ctx *ctx, int32_t admit_min_prompts, int32_t target_prompts);
+
+/* One scheduling step: (1) admits the longest run of waiting prompts, in push order, that
+ * fits the free slots, the unreserved pages and one prefill call, subject to the policy -
+ * their prefill runs and response position 0 of their samples is emitted; (2) one decode step
+ * over every live sample, the newly admitted ones included; (3) when the target is reached,
+ * aborts every live sample, drops the waiting prompts and closes the queue.
+ *   n_out       in: capacity of the output arrays; out: entries written
+ *   n_admitted  out: the first *n_admitted entries are position-0 tokens of newly admitted
+ *               samples (ascending id); the rest is the decode step's output (ascending id)
+ * Outputs as for rollout_decode_step.  With nothing waiting and nothing live, or after the
+ * queue closed: *n_out = 0.  Errors: E_INVAL (capacity below live samples + 2 x samples that
+ * would be admitted: nothing happens). */
+int rollout_queue_step(rollout_ctx *ctx, int32_t *n_out, int32_t *n_admitted, int64_t *sample_ids,
+                       int32_t *tokens, float *logprobs, uint8_t *finished);
+
+int rollout_queue_get_stats(rollout_ctx *ctx, rollout_queue_stats *out);
+
 /* Parity hook: copies the fp32 logits rows of the last prefill (one per prompt, prompt
  * order) or decode step (one per stepped sample, ascending id) to host `out`
  * [rows][vocab].  rows: in capacity, out count.  Errors: E_INVAL, E_STATE (none yet). */

@@ -56,6 +56,12 @@ class rollout_stats(C.Structure):
                                          "pages_peak", "matrix_core_path")]
 
 
+class rollout_queue_stats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("prompts_pushed", "prompts_admitted", "prompts_completed",
+                                          "samples_aborted")] + \
+               [("prompts_waiting", C.c_int32), ("closed", C.c_int32)]
+
+
 class rollout_kernel_stat(C.Structure):
     _fields_ = [("name", C.c_char * 64), ("launches", C.c_uint64), ("ms", C.c_double), ("bytes", C.c_double),
                 ("flops", C.c_double)]
@@ -72,6 +78,10 @@ SIGNATURES = {
     "rollout_decode_step": (C.c_int, [_P, _P, _P, C.POINTER(C.c_int32), _P, _P, _P, _P]),
     "rollout_logprobs": (C.c_int, [_P, C.c_int32, _P, _P, C.c_float, _P]),
     "rollout_abort": (C.c_int, [_P, C.c_int32, _P]),
+    "rollout_queue_push": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, C.c_int32, C.c_float, C.c_float, _P]),
+    "rollout_queue_policy": (C.c_int, [_P, C.c_int32, C.c_int32]),
+    "rollout_queue_step": (C.c_int, [_P, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _P, _P, _P, _P]),
+    "rollout_queue_get_stats": (C.c_int, [_P, C.POINTER(rollout_queue_stats)]),
     "rollout_debug_logits": (C.c_int, [_P, C.POINTER(C.c_int32), _P]),
     "rollout_debug_routing": (C.c_int, [_P, C.POINTER(C.c_int32), _P]),
     "rollout_get_stats": (C.c_int, [_P, C.POINTER(rollout_stats)]),
@@ -234,6 +244,34 @@ class Rollout:
     def rollout_abort(self, sample_ids):
         ids = _arr(sample_ids, np.int64)
         return self._check(self.lib.rollout_abort(self.ctx, len(ids), _ptr(ids)))
+
+    def rollout_queue_push(self, tokens, offsets, n_samples, max_new_tokens, eos_id=-1, temperature=1.0,
+                           top_p=1.0):
+        tokens, offsets = _arr(tokens, np.int32), _arr(offsets, np.int32)
+        max_new = _arr(max_new_tokens, np.int32)
+        pids = np.empty(len(offsets) - 1, np.int64)
+        self._check(self.lib.rollout_queue_push(self.ctx, len(offsets) - 1, _ptr(tokens), _ptr(offsets), n_samples,
+                                                _ptr(max_new), eos_id, temperature, top_p, _ptr(pids)))
+        return pids
+
+    def rollout_queue_policy(self, admit_min_prompts=1, target_prompts=0):
+        self._check(self.lib.rollout_queue_policy(self.ctx, admit_min_prompts, target_prompts))
+
+    def rollout_queue_step(self):
+        """Returns (sample_ids, tokens, logprobs, finished, n_admitted)."""
+        cap = 3 * self.max_live
+        ids, toks = np.empty(cap, np.int64), np.empty(cap, np.int32)
+        lps, fin = np.empty(cap, np.float32), np.empty(cap, np.uint8)
+        n, adm = C.c_int32(cap), C.c_int32(0)
+        self._check(self.lib.rollout_queue_step(self.ctx, C.byref(n), C.byref(adm), _ptr(ids), _ptr(toks),
+                                                _ptr(lps), _ptr(fin)))
+        k = n.value
+        return ids[:k], toks[:k], lps[:k], fin[:k].astype(bool), adm.value
+
+    def rollout_queue_get_stats(self) -> dict:
+        st = rollout_queue_stats()
+        self._check(self.lib.rollout_queue_get_stats(self.ctx, C.byref(st)))
+        return {n: getattr(st, n) for n, _ in rollout_queue_stats._fields_}
 
     def rollout_debug_logits(self, max_rows=None):
         rows = C.c_int32(max_rows or max(self.max_live, 1024))

@@ -83,6 +83,328 @@ static void refresh_stats(rollout_ctx& c) {
   c.stats.matrix_core_path = c.simple ? 0 : 1;
 }
 
+// Admission of P prompts with n samples each (all or none), their prefill and response
+// position 0.  prompt_ids: the prompts' counters (sample id = counter * n + j), or NULL to take
+// the next P counters.
+static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* tokens, const int32_t* offsets,
+                         int32_t n_samples, const int32_t* max_new_tokens, int32_t eos_id, float temperature,
+                         float top_p, const int32_t* forced_first, const uint32_t* uniform_override,
+                         const int64_t* prompt_ids, int64_t* sample_ids, int32_t* first_tokens,
+                         float* first_logprobs, uint8_t* finished) {
+  const rollout_model_desc& m = c.md;
+  const int P = n_prompts, n = n_samples, T = c.rd.page_tokens, R = c.r_max;
+  // ---- validation (no state changes before all of it passed) ----
+  if (P < 1 || n < 1 || !tokens || !offsets || !max_new_tokens) fail(ROLLOUT_E_INVAL, "bad prompt arguments");
+  if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
+  if (!(top_p >= 0.f)) fail(ROLLOUT_E_INVAL, "top_p must be >= 0");
+  if (eos_id < -1 || eos_id >= m.vocab) fail(ROLLOUT_E_INVAL, "eos_id out of range");
+  if (offsets[0] != 0) fail(ROLLOUT_E_INVAL, "offsets[0] must be 0");
+  if ((long long)P * n > R) fail(ROLLOUT_E_NOMEM, "n_prompts * n_samples exceeds the workspace rows");
+  if (P > rollout_ctx::kTempSlots || P > c.logit_rows) fail(ROLLOUT_E_NOMEM, "too many prompts in one call");
+  int need_slots = 0;
+  long long need_pages = 0;
+  for (int p = 0; p < P; ++p) {
+    int len = offsets[p + 1] - offsets[p];
+    if (len < 1) fail(ROLLOUT_E_INVAL, "empty prompt");
+    if (len > c.rd.max_batch_tokens) fail(ROLLOUT_E_NOMEM, "prompt longer than max_batch_tokens");
+    for (int j = 0; j < n; ++j) {
+      int mn = max_new_tokens[p * n + j];
+      if (mn < 1) fail(ROLLOUT_E_INVAL, "max_new_tokens must be >= 1");
+      if ((long long)len + mn - 1 > c.rd.max_context) fail(ROLLOUT_E_NOMEM, "prompt + response exceeds max_context");
+      if (mn > 1) ++need_slots;
+      if (forced_first && (forced_first[p * n + j] < 0 || forced_first[p * n + j] >= m.vocab))
+        fail(ROLLOUT_E_INVAL, "forced token out of range");
+    }
+    for (int i = offsets[p]; i < offsets[p + 1]; ++i)
+      if (tokens[i] < 0 || tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "prompt token out of range");
+    need_pages += plan_pages(len, T, n, max_new_tokens + p * n, nullptr, nullptr, nullptr);
+  }
+  if (need_slots > (int)c.free_slots.size()) fail(ROLLOUT_E_NOMEM, "not enough free live-sample slots");
+  if (need_pages > c.pool->unreserved()) fail(ROLLOUT_E_NOMEM, "not enough free KV pages");
+
+  // ---- pages and page tables ----
+  const float inv_t = 1.0f / temperature;
+  struct PromptPages {
+    std::vector<int32_t> shared;
+    int32_t tail = -1;
+  };
+  std::vector<PromptPages> pp(P);
+  std::vector<Sample> fresh((size_t)P * n);
+  std::vector<int> copy_pairs;
+  for (int p = 0; p < P; ++p) {
+    int len = offsets[p + 1] - offsets[p];
+    int full = len / T, has_tail = (len % T) != 0;
+    int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + p) * c.max_pages];
+    for (int i = 0; i < full; ++i) {
+      int32_t pg = c.pool->alloc(false);
+      pp[p].shared.push_back(pg);
+      prow[i] = pg;
+    }
+    if (has_tail) {
+      pp[p].tail = c.pool->alloc(false);
+      prow[full] = pp[p].tail;
+    }
+    for (int j = 0; j < n; ++j) {
+      Sample& s = fresh[(size_t)p * n + j];
+      s.id = (prompt_ids ? prompt_ids[p] : c.prompt_counter + p) * n + j;
+      s.slot = -1;
+      s.prompt_len = len;
+      s.n_emitted = 0;
+      s.max_new = max_new_tokens[p * n + j];
+      s.eos_id = eos_id;
+      if (s.max_new <= 1) continue;
+      s.slot = c.free_slots.back();
+      c.free_slots.pop_back();
+      int* srow = &c.h_page_table[(size_t)s.slot * c.max_pages];
+      for (int i = 0; i < full; ++i) {
+        c.pool->retain(pp[p].shared[i]);
+        s.pages.push_back(pp[p].shared[i]);
+        srow[i] = pp[p].shared[i];
+      }
+      int total = ceil_div((long long)len + s.max_new - 1, T);
+      for (int i = full; i < total; ++i) {
+        int32_t pg = c.pool->alloc(false);
+        s.pages.push_back(pg);
+        srow[i] = pg;
+      }
+      if (has_tail) {
+        copy_pairs.push_back(pp[p].tail);
+        copy_pairs.push_back(srow[full]);
+      }
+    }
+  }
+  engine_upload_page_table(c);
+
+  // ---- forward over the prompts, in chunks of whole prompts ----
+  int p0 = 0;
+  while (p0 < P) {
+    int p1 = p0, rows = 0;
+    while (p1 < P && rows + (offsets[p1 + 1] - offsets[p1]) <= c.rd.max_batch_tokens) {
+      rows += offsets[p1 + 1] - offsets[p1];
+      ++p1;
+    }
+    int* ht = c.h_int.p;
+    int r = 0, max_len = 0;
+    for (int p = p0; p < p1; ++p) {
+      for (int i = offsets[p]; i < offsets[p + 1]; ++i, ++r) {
+        ht[r] = tokens[i];
+        ht[R + r] = i - offsets[p];
+        ht[2 * R + r] = c.temp_slot0 + p;
+      }
+      ht[3 * R + (p - p0)] = r - 1;  // last row of the prompt
+      ht[4 * R + (p - p0)] = r - (offsets[p + 1] - offsets[p]);
+      ht[5 * R + (p - p0)] = offsets[p + 1] - offsets[p];
+      ht[6 * R + (p - p0)] = c.temp_slot0 + p;
+      max_len = std::max(max_len, offsets[p + 1] - offsets[p]);
+    }
+    SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, p1 - p0, max_len};
+    if (!c.simple) {
+      h2d(c.seq_row0.p, ht + 4 * R, (p1 - p0) * sizeof(int), c.stream);
+      h2d(c.seq_len.p, ht + 5 * R, (p1 - p0) * sizeof(int), c.stream);
+      h2d(c.seq_slot.p, ht + 6 * R, (p1 - p0) * sizeof(int), c.stream);
+    }
+    h2d(c.row_token.p, ht, rows * sizeof(int), c.stream);
+    h2d(c.row_pos.p, ht + R, rows * sizeof(int), c.stream);
+    h2d(c.row_slot.p, ht + 2 * R, rows * sizeof(int), c.stream);
+    h2d(c.row_aux.p, ht + 3 * R, (p1 - p0) * sizeof(int), c.stream);
+    c.timer.start_call();
+    c.kv_tokens_this_call = rows;
+    c.attn_flops_this_call = 0;
+    for (int p = p0; p < p1; ++p) {
+      double len = offsets[p + 1] - offsets[p];
+      c.attn_flops_this_call += 2.0 * len * (len + 1) * c.q_dim;
+    }
+    engine_forward_rows(c, rows, &sb);
+    engine_logits(c, c.row_aux.p, 0, p1 - p0, c.logits.p + (size_t)p0 * m.vocab);
+    HIP_TRY(hipStreamSynchronize(c.stream));  // staging buffers are reused by the next chunk
+    c.timer.collect();
+    c.stats.prompt_tokens += rows;
+    p0 = p1;
+  }
+  c.last_logit_rows = P;
+
+  // ---- private copies of each prompt's partial last page ----
+  if (!copy_pairs.empty()) {
+    if (copy_pairs.size() > c.row_aux.n) fail(ROLLOUT_E_STATE, "internal: page copy list too long");
+    std::memcpy(c.h_int.p, copy_pairs.data(), copy_pairs.size() * sizeof(int));
+    h2d(c.row_aux.p, c.h_int.p, copy_pairs.size() * sizeof(int), c.stream);
+    launch_copy_pages(c.kv_pool.p, c.row_aux.p, (int)copy_pairs.size() / 2, m.n_layers,
+                      c.geom.layer_stride * c.elem, c.geom.page_stride * c.elem, c.stream);
+    HIP_TRY(hipStreamSynchronize(c.stream));
+  }
+
+  // ---- response position 0 of every sample ----
+  const int Rs = P * n;
+  int* hi = c.h_int.p;
+  float* hf = c.h_float.p;
+  int n_new = 0;
+  for (int i = 0; i < Rs; ++i) {
+    hi[i] = i / n;                                       // logits row = prompt
+    hi[R + i] = forced_first ? forced_first[i] : -1;
+    hi[2 * R + i] = 0;                                   // response position
+    hi[3 * R + i] = uniform_override ? (int)uniform_override[i] : 0;
+    hf[i] = inv_t;
+    hf[R + i] = top_p;
+    c.h_ll.p[i] = fresh[i].id;
+    if (fresh[i].slot >= 0) {
+      hi[4 * R + n_new] = fresh[i].slot;
+      hi[5 * R + n_new] = i;
+      hi[6 * R + n_new] = fresh[i].prompt_len;
+      ++n_new;
+    }
+  }
+  h2d(c.row_aux.p, hi, Rs * sizeof(int), c.stream);
+  h2d(c.row_forced.p, hi + R, Rs * sizeof(int), c.stream);
+  h2d(c.row_step.p, hi + 2 * R, Rs * sizeof(int), c.stream);
+  h2d(c.row_uniform.p, hi + 3 * R, Rs * sizeof(int), c.stream);
+  h2d(c.row_inv_temp.p, hf, Rs * sizeof(float), c.stream);
+  h2d(c.row_top_p.p, hf + R, Rs * sizeof(float), c.stream);
+  h2d(c.row_sample_id.p, c.h_ll.p, Rs * sizeof(long long), c.stream);
+  SampleRows sr{};
+  sr.logits = c.logits.p;
+  sr.logits_row = c.row_aux.p;
+  sr.inv_temp = c.row_inv_temp.p;
+  sr.top_p = c.row_top_p.p;
+  sr.uniforms = uniform_override ? c.row_uniform.p : nullptr;
+  sr.sample_id = c.row_sample_id.p;
+  sr.step = c.row_step.p;
+  sr.forced = c.row_forced.p;
+  sr.seed = c.rd.seed;
+  sr.tokens = c.out_tokens.p;
+  sr.logprobs = c.out_logprobs.p;
+  sr.weight_sums = nullptr;
+  launch_sample(sr, Rs, m.vocab, c.stream);
+  if (n_new) {
+    h2d(c.row_token.p, hi + 4 * R, n_new * sizeof(int), c.stream);  // slots
+    h2d(c.row_pos.p, hi + 5 * R, n_new * sizeof(int), c.stream);    // sample rows
+    h2d(c.row_slot.p, hi + 6 * R, n_new * sizeof(int), c.stream);   // positions
+    init_slots_kernel<<<ceil_div(n_new, 256), 256, 0, c.stream>>>(c.st, c.row_token.p, c.row_pos.p, c.row_slot.p,
+                                                                  c.out_tokens.p, c.row_sample_id.p,
+                                                                  c.row_inv_temp.p, c.row_top_p.p, n_new);
+  }
+  d2h(hi + 7 * R, c.out_tokens.p, Rs * sizeof(int), c.stream);
+  d2h(hf + 2 * R, c.out_logprobs.p, Rs * sizeof(float), c.stream);
+  HIP_TRY(hipStreamSynchronize(c.stream));
+
+  // ---- host bookkeeping ----
+  for (int i = 0; i < Rs; ++i) {
+    Sample& s = fresh[i];
+    int tok = hi[7 * R + i];
+    s.n_emitted = 1;
+    bool done = s.max_new <= 1 || (eos_id >= 0 && tok == eos_id);
+    if (sample_ids) sample_ids[i] = s.id;
+    if (first_tokens) first_tokens[i] = tok;
+    if (first_logprobs) first_logprobs[i] = hf[2 * R + i];
+    if (finished) finished[i] = done ? 1 : 0;
+    c.stats.tokens_emitted += 1;
+    c.stats.samples_admitted += 1;
+    if (done) {
+      release_sample(c, s);
+      c.stats.samples_finished += 1;
+    } else {
+      c.live.emplace(s.id, std::move(s));
+    }
+  }
+  for (int p = 0; p < P; ++p) {
+    for (int32_t pg : pp[p].shared) c.pool->release(pg);
+    if (pp[p].tail >= 0) c.pool->release(pp[p].tail);
+  }
+  if (!prompt_ids) c.prompt_counter += P;
+  c.stats.prompts_prefilled += P;
+  c.live_dirty = true;
+  refresh_stats(c);
+}
+
+static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint32_t* uniform_override,
+                        int32_t* n_live, int64_t* sample_ids, int32_t* tokens, float* logprobs,
+                        uint8_t* finished) {
+  const rollout_model_desc& m = c.md;
+  if (!n_live) fail(ROLLOUT_E_INVAL, "n_live is null");
+  const int B = (int)c.live.size(), R = c.r_max;
+  if (B == 0) {
+    *n_live = 0;
+    return;
+  }
+  if (*n_live < B) fail(ROLLOUT_E_INVAL, "output capacity smaller than the live-sample count");
+  if (forced_tokens)
+    for (int i = 0; i < B; ++i)
+      if (forced_tokens[i] < 0 || forced_tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "forced token out of range");
+  int* hi = c.h_int.p;
+  if (c.live_dirty) {
+    int i = 0;
+    for (auto& kv : c.live) hi[i++] = kv.second.slot;
+    h2d(c.d_live.p, hi, B * sizeof(int), c.stream);
+    c.live_dirty = false;
+  }
+  launch_gather_decode_rows(c.st, c.d_live.p, B, c.row_token.p, c.row_pos.p, c.row_slot.p, c.row_inv_temp.p,
+                            c.row_top_p.p, c.row_sample_id.p, c.row_step.p, c.stream);
+  c.decode_max_ctx = 1;
+  c.kv_tokens_this_call = 0;
+  for (auto& kv : c.live) {
+    const int ctx = kv.second.prompt_len + kv.second.n_emitted;
+    c.decode_max_ctx = std::max(c.decode_max_ctx, ctx);
+    c.kv_tokens_this_call += ctx;
+  }
+  c.attn_flops_this_call = 4.0 * c.kv_tokens_this_call * c.q_dim;
+  c.timer.start_call();
+  engine_forward_rows(c, B, nullptr);
+  c.timer.empty_bracket(c.stream);
+  engine_logits(c, nullptr, 0, B, c.logits.p);
+  c.last_logit_rows = B;
+  if (forced_tokens) {
+    std::memcpy(hi + R, forced_tokens, B * sizeof(int));
+    h2d(c.row_forced.p, hi + R, B * sizeof(int), c.stream);
+  }
+  if (uniform_override) {
+    std::memcpy(hi + 2 * R, uniform_override, B * sizeof(int));
+    h2d(c.row_uniform.p, hi + 2 * R, B * sizeof(int), c.stream);
+  }
+  SampleRows sr{};
+  sr.logits = c.logits.p;
+  sr.logits_row = nullptr;
+  sr.inv_temp = c.row_inv_temp.p;
+  sr.top_p = c.row_top_p.p;
+  sr.uniforms = uniform_override ? c.row_uniform.p : nullptr;
+  sr.sample_id = c.row_sample_id.p;
+  sr.step = c.row_step.p;
+  sr.forced = forced_tokens ? c.row_forced.p : nullptr;
+  sr.seed = c.rd.seed;
+  sr.tokens = c.out_tokens.p;
+  sr.logprobs = c.out_logprobs.p;
+  c.timer.begin("sample_kernel", 4.0 * B * m.vocab, 0, c.stream);
+  launch_sample(sr, B, m.vocab, c.stream);
+  c.timer.end(c.stream);
+  launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);
+  d2h(hi + 3 * R, c.out_tokens.p, B * sizeof(int), c.stream);
+  d2h(c.h_float.p, c.out_logprobs.p, B * sizeof(float), c.stream);
+  wait_step_done(c);
+  c.timer.collect();
+
+  int i = 0;
+  for (auto it = c.live.begin(); it != c.live.end(); ++i) {
+    Sample& s = it->second;
+    int tok = hi[3 * R + i];
+    s.n_emitted += 1;
+    bool done = s.n_emitted >= s.max_new || (s.eos_id >= 0 && tok == s.eos_id);
+    if (sample_ids) sample_ids[i] = s.id;
+    if (tokens) tokens[i] = tok;
+    if (logprobs) logprobs[i] = c.h_float.p[i];
+    if (finished) finished[i] = done ? 1 : 0;
+    if (done) {
+      release_sample(c, s);
+      it = c.live.erase(it);
+      c.stats.samples_finished += 1;
+      c.live_dirty = true;
+    } else {
+      ++it;
+    }
+  }
+  *n_live = B;
+  c.stats.decode_steps += 1;
+  c.stats.tokens_emitted += B;
+  refresh_stats(c);
+}
+
 extern "C" {
 
 int rollout_abi_version(void) { return ROLLOUT_ABI_VERSION; }
@@ -157,229 +479,8 @@ int rollout_prefill(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, 
                     int64_t* sample_ids, int32_t* first_tokens, float* first_logprobs, uint8_t* finished) {
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
-    rollout_ctx& c = *ctx;
-    const rollout_model_desc& m = c.md;
-    const int P = n_prompts, n = n_samples, T = c.rd.page_tokens, R = c.r_max;
-    // ---- validation (no state changes before all of it passed) ----
-    if (P < 1 || n < 1 || !tokens || !offsets || !max_new_tokens) fail(ROLLOUT_E_INVAL, "bad prompt arguments");
-    if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
-    if (!(top_p >= 0.f)) fail(ROLLOUT_E_INVAL, "top_p must be >= 0");
-    if (eos_id < -1 || eos_id >= m.vocab) fail(ROLLOUT_E_INVAL, "eos_id out of range");
-    if (offsets[0] != 0) fail(ROLLOUT_E_INVAL, "offsets[0] must be 0");
-    if ((long long)P * n > R) fail(ROLLOUT_E_NOMEM, "n_prompts * n_samples exceeds the workspace rows");
-    if (P > rollout_ctx::kTempSlots || P > c.logit_rows) fail(ROLLOUT_E_NOMEM, "too many prompts in one call");
-    int need_slots = 0;
-    long long need_pages = 0;
-    for (int p = 0; p < P; ++p) {
-      int len = offsets[p + 1] - offsets[p];
-      if (len < 1) fail(ROLLOUT_E_INVAL, "empty prompt");
-      if (len > c.rd.max_batch_tokens) fail(ROLLOUT_E_NOMEM, "prompt longer than max_batch_tokens");
-      for (int j = 0; j < n; ++j) {
-        int mn = max_new_tokens[p * n + j];
-        if (mn < 1) fail(ROLLOUT_E_INVAL, "max_new_tokens must be >= 1");
-        if ((long long)len + mn - 1 > c.rd.max_context) fail(ROLLOUT_E_NOMEM, "prompt + response exceeds max_context");
-        if (mn > 1) ++need_slots;
-        if (forced_first && (forced_first[p * n + j] < 0 || forced_first[p * n + j] >= m.vocab))
-          fail(ROLLOUT_E_INVAL, "forced token out of range");
-      }
-      for (int i = offsets[p]; i < offsets[p + 1]; ++i)
-        if (tokens[i] < 0 || tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "prompt token out of range");
-      need_pages += plan_pages(len, T, n, max_new_tokens + p * n, nullptr, nullptr, nullptr);
-    }
-    if (need_slots > (int)c.free_slots.size()) fail(ROLLOUT_E_NOMEM, "not enough free live-sample slots");
-    if (need_pages > c.pool->unreserved()) fail(ROLLOUT_E_NOMEM, "not enough free KV pages");
-
-    // ---- pages and page tables ----
-    const float inv_t = 1.0f / temperature;
-    struct PromptPages {
-      std::vector<int32_t> shared;
-      int32_t tail = -1;
-    };
-    std::vector<PromptPages> pp(P);
-    std::vector<Sample> fresh((size_t)P * n);
-    std::vector<int> copy_pairs;
-    for (int p = 0; p < P; ++p) {
-      int len = offsets[p + 1] - offsets[p];
-      int full = len / T, has_tail = (len % T) != 0;
-      int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + p) * c.max_pages];
-      for (int i = 0; i < full; ++i) {
-        int32_t pg = c.pool->alloc(false);
-        pp[p].shared.push_back(pg);
-        prow[i] = pg;
-      }
-      if (has_tail) {
-        pp[p].tail = c.pool->alloc(false);
-        prow[full] = pp[p].tail;
-      }
-      for (int j = 0; j < n; ++j) {
-        Sample& s = fresh[(size_t)p * n + j];
-        s.id = (c.prompt_counter + p) * n + j;
-        s.slot = -1;
-        s.prompt_len = len;
-        s.n_emitted = 0;
-        s.max_new = max_new_tokens[p * n + j];
-        s.eos_id = eos_id;
-        if (s.max_new <= 1) continue;
-        s.slot = c.free_slots.back();
-        c.free_slots.pop_back();
-        int* srow = &c.h_page_table[(size_t)s.slot * c.max_pages];
-        for (int i = 0; i < full; ++i) {
-          c.pool->retain(pp[p].shared[i]);
-          s.pages.push_back(pp[p].shared[i]);
-          srow[i] = pp[p].shared[i];
-        }
-        int total = ceil_div((long long)len + s.max_new - 1, T);
-        for (int i = full; i < total; ++i) {
-          int32_t pg = c.pool->alloc(false);
-          s.pages.push_back(pg);
-          srow[i] = pg;
-        }
-        if (has_tail) {
-          copy_pairs.push_back(pp[p].tail);
-          copy_pairs.push_back(srow[full]);
-        }
-      }
-    }
-    engine_upload_page_table(c);
-
-    // ---- forward over the prompts, in chunks of whole prompts ----
-    int p0 = 0;
-    while (p0 < P) {
-      int p1 = p0, rows = 0;
-      while (p1 < P && rows + (offsets[p1 + 1] - offsets[p1]) <= c.rd.max_batch_tokens) {
-        rows += offsets[p1 + 1] - offsets[p1];
-        ++p1;
-      }
-      int* ht = c.h_int.p;
-      int r = 0, max_len = 0;
-      for (int p = p0; p < p1; ++p) {
-        for (int i = offsets[p]; i < offsets[p + 1]; ++i, ++r) {
-          ht[r] = tokens[i];
-          ht[R + r] = i - offsets[p];
-          ht[2 * R + r] = c.temp_slot0 + p;
-        }
-        ht[3 * R + (p - p0)] = r - 1;  // last row of the prompt
-        ht[4 * R + (p - p0)] = r - (offsets[p + 1] - offsets[p]);
-        ht[5 * R + (p - p0)] = offsets[p + 1] - offsets[p];
-        ht[6 * R + (p - p0)] = c.temp_slot0 + p;
-        max_len = std::max(max_len, offsets[p + 1] - offsets[p]);
-      }
-      SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, p1 - p0, max_len};
-      if (!c.simple) {
-        h2d(c.seq_row0.p, ht + 4 * R, (p1 - p0) * sizeof(int), c.stream);
-        h2d(c.seq_len.p, ht + 5 * R, (p1 - p0) * sizeof(int), c.stream);
-        h2d(c.seq_slot.p, ht + 6 * R, (p1 - p0) * sizeof(int), c.stream);
-      }
-      h2d(c.row_token.p, ht, rows * sizeof(int), c.stream);
-      h2d(c.row_pos.p, ht + R, rows * sizeof(int), c.stream);
-      h2d(c.row_slot.p, ht + 2 * R, rows * sizeof(int), c.stream);
-      h2d(c.row_aux.p, ht + 3 * R, (p1 - p0) * sizeof(int), c.stream);
-      c.timer.start_call();
-      c.kv_tokens_this_call = rows;
-      c.attn_flops_this_call = 0;
-      for (int p = p0; p < p1; ++p) {
-        double len = offsets[p + 1] - offsets[p];
-        c.attn_flops_this_call += 2.0 * len * (len + 1) * c.q_dim;
-      }
-      engine_forward_rows(c, rows, &sb);
-      engine_logits(c, c.row_aux.p, 0, p1 - p0, c.logits.p + (size_t)p0 * m.vocab);
-      HIP_TRY(hipStreamSynchronize(c.stream));  // staging buffers are reused by the next chunk
-      c.timer.collect();
-      c.stats.prompt_tokens += rows;
-      p0 = p1;
-    }
-    c.last_logit_rows = P;
-
-    // ---- private copies of each prompt's partial last page ----
-    if (!copy_pairs.empty()) {
-      if (copy_pairs.size() > c.row_aux.n) fail(ROLLOUT_E_STATE, "internal: page copy list too long");
-      std::memcpy(c.h_int.p, copy_pairs.data(), copy_pairs.size() * sizeof(int));
-      h2d(c.row_aux.p, c.h_int.p, copy_pairs.size() * sizeof(int), c.stream);
-      launch_copy_pages(c.kv_pool.p, c.row_aux.p, (int)copy_pairs.size() / 2, m.n_layers,
-                        c.geom.layer_stride * c.elem, c.geom.page_stride * c.elem, c.stream);
-      HIP_TRY(hipStreamSynchronize(c.stream));
-    }
-
-    // ---- response position 0 of every sample ----
-    const int Rs = P * n;
-    int* hi = c.h_int.p;
-    float* hf = c.h_float.p;
-    int n_new = 0;
-    for (int i = 0; i < Rs; ++i) {
-      hi[i] = i / n;                                       // logits row = prompt
-      hi[R + i] = forced_first ? forced_first[i] : -1;
-      hi[2 * R + i] = 0;                                   // response position
-      hi[3 * R + i] = uniform_override ? (int)uniform_override[i] : 0;
-      hf[i] = inv_t;
-      hf[R + i] = top_p;
-      c.h_ll.p[i] = fresh[i].id;
-      if (fresh[i].slot >= 0) {
-        hi[4 * R + n_new] = fresh[i].slot;
-        hi[5 * R + n_new] = i;
-        hi[6 * R + n_new] = fresh[i].prompt_len;
-        ++n_new;
-      }
-    }
-    h2d(c.row_aux.p, hi, Rs * sizeof(int), c.stream);
-    h2d(c.row_forced.p, hi + R, Rs * sizeof(int), c.stream);
-    h2d(c.row_step.p, hi + 2 * R, Rs * sizeof(int), c.stream);
-    h2d(c.row_uniform.p, hi + 3 * R, Rs * sizeof(int), c.stream);
-    h2d(c.row_inv_temp.p, hf, Rs * sizeof(float), c.stream);
-    h2d(c.row_top_p.p, hf + R, Rs * sizeof(float), c.stream);
-    h2d(c.row_sample_id.p, c.h_ll.p, Rs * sizeof(long long), c.stream);
-    SampleRows sr{};
-    sr.logits = c.logits.p;
-    sr.logits_row = c.row_aux.p;
-    sr.inv_temp = c.row_inv_temp.p;
-    sr.top_p = c.row_top_p.p;
-    sr.uniforms = uniform_override ? c.row_uniform.p : nullptr;
-    sr.sample_id = c.row_sample_id.p;
-    sr.step = c.row_step.p;
-    sr.forced = c.row_forced.p;
-    sr.seed = c.rd.seed;
-    sr.tokens = c.out_tokens.p;
-    sr.logprobs = c.out_logprobs.p;
-    sr.weight_sums = nullptr;
-    launch_sample(sr, Rs, m.vocab, c.stream);
-    if (n_new) {
-      h2d(c.row_token.p, hi + 4 * R, n_new * sizeof(int), c.stream);  // slots
-      h2d(c.row_pos.p, hi + 5 * R, n_new * sizeof(int), c.stream);    // sample rows
-      h2d(c.row_slot.p, hi + 6 * R, n_new * sizeof(int), c.stream);   // positions
-      init_slots_kernel<<<ceil_div(n_new, 256), 256, 0, c.stream>>>(c.st, c.row_token.p, c.row_pos.p, c.row_slot.p,
-                                                                    c.out_tokens.p, c.row_sample_id.p,
-                                                                    c.row_inv_temp.p, c.row_top_p.p, n_new);
-    }
-    d2h(hi + 7 * R, c.out_tokens.p, Rs * sizeof(int), c.stream);
-    d2h(hf + 2 * R, c.out_logprobs.p, Rs * sizeof(float), c.stream);
-    HIP_TRY(hipStreamSynchronize(c.stream));
-
-    // ---- host bookkeeping ----
-    for (int i = 0; i < Rs; ++i) {
-      Sample& s = fresh[i];
-      int tok = hi[7 * R + i];
-      s.n_emitted = 1;
-      bool done = s.max_new <= 1 || (eos_id >= 0 && tok == eos_id);
-      if (sample_ids) sample_ids[i] = s.id;
-      if (first_tokens) first_tokens[i] = tok;
-      if (first_logprobs) first_logprobs[i] = hf[2 * R + i];
-      if (finished) finished[i] = done ? 1 : 0;
-      c.stats.tokens_emitted += 1;
-      c.stats.samples_admitted += 1;
-      if (done) {
-        release_sample(c, s);
-        c.stats.samples_finished += 1;
-      } else {
-        c.live.emplace(s.id, std::move(s));
-      }
-    }
-    for (int p = 0; p < P; ++p) {
-      for (int32_t pg : pp[p].shared) c.pool->release(pg);
-      if (pp[p].tail >= 0) c.pool->release(pp[p].tail);
-    }
-    c.prompt_counter += P;
-    c.stats.prompts_prefilled += P;
-    c.live_dirty = true;
-    refresh_stats(c);
+    prefill_impl(*ctx, n_prompts, tokens, offsets, n_samples, max_new_tokens, eos_id, temperature, top_p,
+                 forced_first, uniform_override, nullptr, sample_ids, first_tokens, first_logprobs, finished);
   });
 }
 
@@ -388,92 +489,185 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
                         uint8_t* finished) {
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
-    rollout_ctx& c = *ctx;
-    const rollout_model_desc& m = c.md;
-    if (!n_live) fail(ROLLOUT_E_INVAL, "n_live is null");
-    const int B = (int)c.live.size(), R = c.r_max;
-    if (B == 0) {
-      *n_live = 0;
-      return;
-    }
-    if (*n_live < B) fail(ROLLOUT_E_INVAL, "output capacity smaller than the live-sample count");
-    if (forced_tokens)
-      for (int i = 0; i < B; ++i)
-        if (forced_tokens[i] < 0 || forced_tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "forced token out of range");
-    int* hi = c.h_int.p;
-    if (c.live_dirty) {
-      int i = 0;
-      for (auto& kv : c.live) hi[i++] = kv.second.slot;
-      h2d(c.d_live.p, hi, B * sizeof(int), c.stream);
-      c.live_dirty = false;
-    }
-    launch_gather_decode_rows(c.st, c.d_live.p, B, c.row_token.p, c.row_pos.p, c.row_slot.p, c.row_inv_temp.p,
-                              c.row_top_p.p, c.row_sample_id.p, c.row_step.p, c.stream);
-    c.decode_max_ctx = 1;
-    c.kv_tokens_this_call = 0;
-    for (auto& kv : c.live) {
-      const int ctx = kv.second.prompt_len + kv.second.n_emitted;
-      c.decode_max_ctx = std::max(c.decode_max_ctx, ctx);
-      c.kv_tokens_this_call += ctx;
-    }
-    c.attn_flops_this_call = 4.0 * c.kv_tokens_this_call * c.q_dim;
-    c.timer.start_call();
-    engine_forward_rows(c, B, nullptr);
-    c.timer.empty_bracket(c.stream);
-    engine_logits(c, nullptr, 0, B, c.logits.p);
-    c.last_logit_rows = B;
-    if (forced_tokens) {
-      std::memcpy(hi + R, forced_tokens, B * sizeof(int));
-      h2d(c.row_forced.p, hi + R, B * sizeof(int), c.stream);
-    }
-    if (uniform_override) {
-      std::memcpy(hi + 2 * R, uniform_override, B * sizeof(int));
-      h2d(c.row_uniform.p, hi + 2 * R, B * sizeof(int), c.stream);
-    }
-    SampleRows sr{};
-    sr.logits = c.logits.p;
-    sr.logits_row = nullptr;
-    sr.inv_temp = c.row_inv_temp.p;
-    sr.top_p = c.row_top_p.p;
-    sr.uniforms = uniform_override ? c.row_uniform.p : nullptr;
-    sr.sample_id = c.row_sample_id.p;
-    sr.step = c.row_step.p;
-    sr.forced = forced_tokens ? c.row_forced.p : nullptr;
-    sr.seed = c.rd.seed;
-    sr.tokens = c.out_tokens.p;
-    sr.logprobs = c.out_logprobs.p;
-    c.timer.begin("sample_kernel", 4.0 * B * m.vocab, 0, c.stream);
-    launch_sample(sr, B, m.vocab, c.stream);
-    c.timer.end(c.stream);
-    launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);
-    d2h(hi + 3 * R, c.out_tokens.p, B * sizeof(int), c.stream);
-    d2h(c.h_float.p, c.out_logprobs.p, B * sizeof(float), c.stream);
-    wait_step_done(c);
-    c.timer.collect();
+    decode_impl(*ctx, forced_tokens, uniform_override, n_live, sample_ids, tokens, logprobs, finished);
+  });
+}
 
-    int i = 0;
-    for (auto it = c.live.begin(); it != c.live.end(); ++i) {
-      Sample& s = it->second;
-      int tok = hi[3 * R + i];
-      s.n_emitted += 1;
-      bool done = s.n_emitted >= s.max_new || (s.eos_id >= 0 && tok == s.eos_id);
-      if (sample_ids) sample_ids[i] = s.id;
-      if (tokens) tokens[i] = tok;
-      if (logprobs) logprobs[i] = c.h_float.p[i];
-      if (finished) finished[i] = done ? 1 : 0;
-      if (done) {
-        release_sample(c, s);
-        it = c.live.erase(it);
-        c.stats.samples_finished += 1;
-        c.live_dirty = true;
-      } else {
-        ++it;
+// ---- queue-fed continuous rollout -------------------------------------------------------
+// slots and pages one prompt takes at admission
+static void admission_cost(const rollout_ctx& c, const QueuedPrompt& q, int n, int& slots, long long& pages) {
+  slots = 0;
+  for (int j = 0; j < n; ++j) slots += q.max_new[j] > 1;
+  pages = plan_pages((int)q.tokens.size(), c.rd.page_tokens, n, q.max_new.data(), nullptr, nullptr, nullptr);
+}
+
+// a finished sample of an admitted prompt: the prompt is complete when its last one ends
+static void queue_note_finished(PromptQueue& q, int64_t sample_id) {
+  auto it = q.open.find(sample_id / q.n_samples);
+  if (it == q.open.end()) return;  // admitted through rollout_prefill, not through the queue
+  if (--it->second == 0) {
+    q.open.erase(it);
+    q.completed += 1;
+  }
+}
+
+int rollout_queue_push(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, const int32_t* offsets,
+                       int32_t n_samples, const int32_t* max_new_tokens, int32_t eos_id, float temperature,
+                       float top_p, int64_t* prompt_ids) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    PromptQueue& q = c.queue;
+    const int P = n_prompts, n = n_samples;
+    if (P < 1 || n < 1 || !tokens || !offsets || !max_new_tokens) fail(ROLLOUT_E_INVAL, "bad prompt arguments");
+    if (q.closed) fail(ROLLOUT_E_INVAL, "the queue is closed");
+    if (q.n_samples && q.n_samples != n) fail(ROLLOUT_E_INVAL, "n_samples differs from earlier pushes");
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
+    if (!(top_p >= 0.f)) fail(ROLLOUT_E_INVAL, "top_p must be >= 0");
+    if (eos_id < -1 || eos_id >= c.md.vocab) fail(ROLLOUT_E_INVAL, "eos_id out of range");
+    if (offsets[0] != 0) fail(ROLLOUT_E_INVAL, "offsets[0] must be 0");
+    if (n > c.r_max) fail(ROLLOUT_E_NOMEM, "n_samples exceeds the workspace rows");
+    std::vector<QueuedPrompt> fresh(P);
+    for (int p = 0; p < P; ++p) {
+      const int len = offsets[p + 1] - offsets[p];
+      if (len < 1) fail(ROLLOUT_E_INVAL, "empty prompt");
+      if (len > c.rd.max_batch_tokens) fail(ROLLOUT_E_NOMEM, "prompt longer than max_batch_tokens");
+      QueuedPrompt& e = fresh[p];
+      e.tokens.assign(tokens + offsets[p], tokens + offsets[p + 1]);
+      e.max_new.assign(max_new_tokens + (size_t)p * n, max_new_tokens + (size_t)(p + 1) * n);
+      e.eos_id = eos_id;
+      e.temperature = temperature;
+      e.top_p = top_p;
+      for (int t : e.tokens)
+        if (t < 0 || t >= c.md.vocab) fail(ROLLOUT_E_INVAL, "prompt token out of range");
+      for (int mn : e.max_new) {
+        if (mn < 1) fail(ROLLOUT_E_INVAL, "max_new_tokens must be >= 1");
+        if ((long long)len + mn - 1 > c.rd.max_context) fail(ROLLOUT_E_NOMEM, "prompt + response exceeds max_context");
       }
+      int slots;
+      long long pages;
+      admission_cost(c, e, n, slots, pages);
+      if (slots > c.rd.max_live_samples) fail(ROLLOUT_E_NOMEM, "more samples than live-sample slots");
+      if (pages > c.pool->total()) fail(ROLLOUT_E_NOMEM, "more pages than the pool holds");
     }
-    *n_live = B;
-    c.stats.decode_steps += 1;
-    c.stats.tokens_emitted += B;
-    refresh_stats(c);
+    q.n_samples = n;
+    for (int p = 0; p < P; ++p) {
+      fresh[p].prompt_id = c.prompt_counter++;
+      if (prompt_ids) prompt_ids[p] = fresh[p].prompt_id;
+      q.waiting.push_back(std::move(fresh[p]));
+    }
+    q.pushed += P;
+  });
+}
+
+int rollout_queue_policy(rollout_ctx* ctx, int32_t admit_min_prompts, int32_t target_prompts) {
+  if (!ctx || admit_min_prompts < 1 || target_prompts < 0) return ROLLOUT_E_INVAL;
+  ctx->queue.admit_min = admit_min_prompts;
+  ctx->queue.target = target_prompts;
+  return ROLLOUT_OK;
+}
+
+int rollout_queue_get_stats(rollout_ctx* ctx, rollout_queue_stats* out) {
+  if (!ctx || !out) return ROLLOUT_E_INVAL;
+  const PromptQueue& q = ctx->queue;
+  out->prompts_pushed = q.pushed;
+  out->prompts_admitted = q.admitted;
+  out->prompts_completed = q.completed;
+  out->samples_aborted = q.aborted;
+  out->prompts_waiting = (int32_t)q.waiting.size();
+  out->closed = q.closed ? 1 : 0;
+  return ROLLOUT_OK;
+}
+
+int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, int64_t* sample_ids,
+                       int32_t* tokens, float* logprobs, uint8_t* finished) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    PromptQueue& q = c.queue;
+    if (!n_out || !n_admitted) fail(ROLLOUT_E_INVAL, "n_out / n_admitted is null");
+    const int cap = *n_out, n = q.n_samples;
+    *n_out = 0;
+    *n_admitted = 0;
+    if (q.closed) return;
+
+    // (1) the longest run of waiting prompts, in push order, that one prefill call can take
+    int k = 0, slots = 0;
+    long long pages = 0, rows = 0;
+    while (k < (int)q.waiting.size()) {
+      const QueuedPrompt& e = q.waiting[k];
+      const QueuedPrompt& head = q.waiting[0];
+      if (e.eos_id != head.eos_id || e.temperature != head.temperature || e.top_p != head.top_p) break;
+      int s1;
+      long long p1;
+      admission_cost(c, e, n, s1, p1);
+      if (slots + s1 > (int)c.free_slots.size() || pages + p1 > c.pool->unreserved()) break;
+      if (k + 1 > rollout_ctx::kTempSlots || k + 1 > c.logit_rows || (long long)(k + 1) * n > c.r_max) break;
+      slots += s1;
+      pages += p1;
+      rows += (long long)e.tokens.size();
+      ++k;
+    }
+    if (k < std::min<int>(q.admit_min, (int)q.waiting.size()) && !c.live.empty()) k = 0;
+    const int live_before = (int)c.live.size();
+    if (cap < live_before + 2 * k * n) fail(ROLLOUT_E_INVAL, "output capacity smaller than live samples + 2 x admitted samples");
+    std::vector<uint8_t> fin_local;
+    int n_adm = 0;
+    if (k > 0) {
+      std::vector<int32_t> toks, offs(1, 0), max_new;
+      std::vector<int64_t> pids;
+      toks.reserve((size_t)rows);
+      for (int i = 0; i < k; ++i) {
+        const QueuedPrompt& e = q.waiting[i];
+        toks.insert(toks.end(), e.tokens.begin(), e.tokens.end());
+        offs.push_back((int32_t)toks.size());
+        max_new.insert(max_new.end(), e.max_new.begin(), e.max_new.end());
+        pids.push_back(e.prompt_id);
+      }
+      n_adm = k * n;
+      std::vector<int64_t> ids_local(n_adm);
+      fin_local.assign(n_adm, 0);
+      const int eos_id = q.waiting[0].eos_id;
+      const float temperature = q.waiting[0].temperature, top_p = q.waiting[0].top_p;
+      prefill_impl(c, k, toks.data(), offs.data(), n, max_new.data(), eos_id, temperature, top_p,
+                   nullptr, nullptr, pids.data(), ids_local.data(), tokens, logprobs, fin_local.data());
+      for (int i = 0; i < k; ++i) q.open[pids[i]] = n;
+      for (int i = 0; i < n_adm; ++i) {
+        if (sample_ids) sample_ids[i] = ids_local[i];
+        if (finished) finished[i] = fin_local[i];
+        if (fin_local[i]) queue_note_finished(q, ids_local[i]);
+      }
+      q.waiting.erase(q.waiting.begin(), q.waiting.begin() + k);
+      q.admitted += k;
+    }
+
+    // (2) one decode step over everything that is live now
+    int n_dec = cap - n_adm;
+    std::vector<int64_t> ids_dec(c.live.size());
+    std::vector<uint8_t> fin_dec(c.live.size());
+    decode_impl(c, nullptr, nullptr, &n_dec, ids_dec.data(), tokens ? tokens + n_adm : nullptr,
+                logprobs ? logprobs + n_adm : nullptr, fin_dec.data());
+    for (int i = 0; i < n_dec; ++i) {
+      if (sample_ids) sample_ids[n_adm + i] = ids_dec[i];
+      if (finished) finished[n_adm + i] = fin_dec[i];
+      if (fin_dec[i]) queue_note_finished(q, ids_dec[i]);
+    }
+    *n_admitted = n_adm;
+    *n_out = n_adm + n_dec;
+
+    // (3) enough prompts complete: abort what still runs, drop what still waits
+    if (q.target > 0 && q.completed >= (uint64_t)q.target) {
+      const int running = (int)c.live.size();
+      for (auto& kv : c.live) release_sample(c, kv.second);
+      c.live.clear();
+      c.live_dirty = true;
+      c.stats.samples_aborted += running;
+      q.aborted += running;
+      q.waiting.clear();
+      q.open.clear();
+      q.closed = true;
+      refresh_stats(c);
+    }
   });
 }
 

@@ -1,7 +1,9 @@
 // Rollout engine: library-owned weights, paged KV pool, per-slot decode state, the
 // sample table and the forward pass over a batch of rows.  One context = one GPU.
 #pragma once
+#include <deque>
 #include <map>
+#include <unordered_map>
 #include <string>
 #include <vector>
 
@@ -149,6 +151,23 @@ struct Sample {
   std::vector<int32_t> pages;  // one reference held on each
 };
 
+// Prompts waiting for admission and the bookkeeping of the queue-fed rollout (host only).
+struct QueuedPrompt {
+  int64_t prompt_id;
+  std::vector<int32_t> tokens, max_new;  // max_new: one per sample
+  int eos_id;
+  float temperature, top_p;
+};
+struct PromptQueue {
+  std::deque<QueuedPrompt> waiting;
+  int n_samples = 0;      // fixed by the first push
+  int admit_min = 1;      // admit only when this many waiting prompts fit (or nothing is live)
+  int target = 0;         // close the queue once this many prompts are complete; 0 = never
+  bool closed = false;
+  std::unordered_map<int64_t, int> open;  // admitted prompt -> samples not finished yet
+  uint64_t pushed = 0, admitted = 0, completed = 0, aborted = 0;
+};
+
 struct rollout_ctx {
   rollout_model_desc md{};
   rollout_runtime_desc rd{};
@@ -185,6 +204,7 @@ struct rollout_ctx {
   std::map<int64_t, Sample> live;
   std::vector<int> free_slots;
   int64_t prompt_counter = 0;
+  PromptQueue queue;
   bool live_dirty = true;
   DevBuf<int> d_live;
 

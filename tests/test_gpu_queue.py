@@ -1,0 +1,171 @@
+"""GPU tests of the queue-fed continuous rollout (rollout_queue_*): the scheduler decides when
+a sample runs, never what it emits, so every sample is checked against the oracle's
+per-sample rollout, which knows nothing of queues, slots or pages."""
+import numpy as np
+import pytest
+
+import workloads
+from gpu_util import make_engine, oracle_model, scaled_weights
+from oracle import rollout
+
+pytestmark = pytest.mark.gpu
+
+
+def drain(eng, max_live, max_steps=10000):
+    """Steps the queue until nothing waits and nothing is live; returns {sample id: (tokens,
+    logprobs)}, the order in which samples first appeared, and the peak live count."""
+    seqs, order, peak = {}, [], 0
+    for _ in range(max_steps):
+        ids, toks, lps, fin, n_adm = eng.rollout_queue_step()
+        if not len(ids):
+            break
+        assert np.all(np.diff(ids[:n_adm]) > 0) and np.all(np.diff(ids[n_adm:]) > 0)
+        for k, (i, t, lp) in enumerate(zip(ids, toks, lps)):
+            if k < n_adm:
+                assert int(i) not in seqs, "a sample was admitted twice"
+                seqs[int(i)] = ([], [])
+                order.append(int(i))
+            seqs[int(i)][0].append(int(t))
+            seqs[int(i)][1].append(float(lp))
+        st = eng.rollout_get_stats()
+        assert st["live_samples"] <= max_live
+        peak = max(peak, st["live_samples"])
+    else:
+        raise AssertionError("the queue did not drain")
+    return seqs, order, peak
+
+
+def test_queue_fed_rollout_reproduces_per_sample_results():
+    """Tiny fp32 model, 10 prompts x 2 samples with ragged lengths (some samples end at
+    position 0) through 6 live slots and a 14-page pool, so that slots at some steps and pages
+    at others hold prompts back.  (1) Every emitted log-prob equals the oracle's, teacher-forced
+    on the emitted tokens, within the fp32 tolerance: admission order, slot and page reuse leave
+    no trace in a sample's KV cache.  (2) Running free, the oracle draws the same tokens for all
+    but at most one sample.  (3) Prompts are admitted in push order with the ids promised at push
+    time, never more than 6 samples live, every page back in the pool at the end."""
+    shape = workloads.C1_TINY
+    w = scaled_weights(shape, seed=1)
+    P, n, temperature, top_p, seed = 10, 2, 1.0, 0.9, 3
+    toks, offs = workloads.make_prompts(P, 5, 60, shape.vocab, seed=31)
+    max_new = np.random.default_rng(32).integers(1, 25, P * n).astype(np.int32)
+    max_new[3] = 1                                   # ends at position 0, takes no slot
+    page_bytes = 32 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 4
+    eng = make_engine(shape, w, kv_pool_bytes=14 * page_bytes, max_live_samples=6, max_context=128,
+                      max_batch_tokens=256, seed=seed)
+    assert eng.rollout_get_stats()["pages_total"] == 14
+    pids = np.concatenate([
+        eng.rollout_queue_push(toks[:offs[5]], offs[:6], n, max_new[:5 * n], temperature=temperature, top_p=top_p),
+        eng.rollout_queue_push(toks[offs[5]:], offs[5:] - offs[5], n, max_new[5 * n:], temperature=temperature,
+                               top_p=top_p)])
+    assert pids.tolist() == list(range(P))
+    assert eng.rollout_queue_get_stats()["prompts_waiting"] == P
+    seqs, order, peak = drain(eng, max_live=6)
+    qs, st = eng.rollout_queue_get_stats(), eng.rollout_get_stats()
+    assert qs["prompts_waiting"] == 0 and qs["prompts_admitted"] == P and qs["prompts_completed"] == P
+    assert qs["samples_aborted"] == 0 and not qs["closed"]
+    assert st["live_samples"] == 0 and st["pages_in_use"] == 0 and st["pages_reserved"] == 0
+    assert order == sorted(order) == list(range(P * n)) and peak >= 5
+    assert st["prompts_prefilled"] == P and st["decode_steps"] > int(max_new.max()) - 1  # several admissions
+    for sid, (t, _) in seqs.items():
+        assert len(t) == max_new[sid]
+
+    model = oracle_model(shape, w)
+    forced = {sid: t for sid, (t, _) in seqs.items()}
+    ref = rollout.generate(model, toks, offs, n, max_new, -1, temperature, top_p, seed, forced_tokens=forced)
+    worst = max(abs(a - b) for tr in ref for a, b in zip(tr.logprobs, seqs[tr.sample_id][1]))
+    free = rollout.generate(model, toks, offs, n, max_new, -1, temperature, top_p, seed)
+    same = sum(tr.tokens == seqs[tr.sample_id][0] for tr in free)
+    print(f"queue-fed: max |dlogp| = {worst:.3e}; free-running oracle reproduced {same}/{P * n} samples; "
+          f"peak live {peak}, {st['decode_steps']} decode steps")
+    assert worst < 1e-4
+    assert same >= P * n - 1
+    eng.close()
+
+
+def test_queue_results_do_not_depend_on_capacity_or_policy():
+    """bf16 model: the same queue through 4 live slots with single-prompt admissions and through
+    32 slots in one admission gives every sample the same tokens (the sampler is exact on
+    integers; logits differ by rounding between batch shapes, which may flip a draw that sits on
+    a boundary: at most one sample may differ) and log-probs within the bf16 tolerance."""
+    shape = workloads.SMALL_BF16
+    w = scaled_weights(shape, seed=1)
+    P, n = 8, 4
+    toks, offs = workloads.make_prompts(P, 8, 70, shape.vocab, seed=41)
+    max_new = np.random.default_rng(42).integers(3, 14, P * n).astype(np.int32)
+    runs = []
+    for live, admit_min in ((4, 1), (32, 8)):
+        eng = make_engine(shape, w, max_live_samples=live, max_context=128, max_batch_tokens=1024, seed=9)
+        eng.rollout_queue_policy(admit_min_prompts=admit_min)
+        eng.rollout_queue_push(toks, offs, n, max_new, temperature=0.8, top_p=0.95)
+        seqs, order, peak = drain(eng, max_live=live)
+        assert eng.rollout_get_stats()["matrix_core_path"] == 1 and peak == min(live, P * n)
+        assert eng.rollout_get_stats()["pages_in_use"] == 0
+        runs.append(seqs)
+        eng.close()
+    a, b = runs
+    assert a.keys() == b.keys() and len(a) == P * n
+    differ = [sid for sid in a if a[sid][0] != b[sid][0]]
+    assert len(differ) <= 1, differ
+    worst = max(abs(x - y) for sid in a if sid not in differ for x, y in zip(a[sid][1], b[sid][1]))
+    print(f"4 slots vs 32 slots: {len(differ)} samples differ, max |dlogp| = {worst:.3e}")
+    assert worst <= 2e-2
+
+
+def test_queue_target_aborts_the_tail_and_closes():
+    """Dynamic-sampling mechanism: with a target of 3 complete prompts the queue stops as soon
+    as the third prompt has all its samples finished: the running samples are aborted, their
+    pages and slots return, the waiting prompts are dropped, later steps and pushes do nothing."""
+    shape = workloads.C1_TINY
+    w = scaled_weights(shape, seed=1)
+    P, n = 8, 2
+    toks, offs = workloads.make_prompts(P, 4, 30, shape.vocab, seed=51)
+    max_new = np.full(P * n, 40, np.int32)
+    max_new[0:2] = (3, 5)        # prompt 0 completes in step 4 (a step-s token is position s)
+    max_new[4:6] = (2, 9)        # prompt 2 in step 8
+    max_new[6:8] = (12, 4)       # prompt 3 in step 11: the third to complete
+    eng = make_engine(shape, w, max_live_samples=8, max_context=128, max_batch_tokens=256, seed=5)
+    eng.rollout_queue_policy(admit_min_prompts=1, target_prompts=3)
+    eng.rollout_queue_push(toks, offs, n, max_new)
+    emitted = {}
+    steps = 0
+    while True:
+        ids, tk, lps, fin, n_adm = eng.rollout_queue_step()
+        if not len(ids):
+            break
+        steps += 1
+        for i in ids:
+            emitted[int(i)] = emitted.get(int(i), 0) + 1
+    qs, st = eng.rollout_queue_get_stats(), eng.rollout_get_stats()
+    # 8 slots: prompts 0..3 admitted at once; prompt 4 when prompt 0's slots are free, and so on
+    assert qs["closed"] and qs["prompts_completed"] == 3 and qs["prompts_waiting"] == 0
+    assert qs["samples_aborted"] > 0 and st["samples_aborted"] == qs["samples_aborted"]
+    assert st["live_samples"] == 0 and st["pages_in_use"] == 0
+    assert emitted[0] == 3 and emitted[1] == 5 and emitted[6] == 12 and emitted[7] == 4
+    assert emitted[2] == 12 and emitted[3] == 12            # prompt 1 was cut at the closing step
+    assert steps == 11                                      # position 0 and 1 come out of the first step
+    assert len(eng.rollout_queue_step()[0]) == 0
+    with pytest.raises(Exception):
+        eng.rollout_queue_push(toks[:offs[1]], offs[:2], n, max_new[:n])
+    eng.close()
+
+
+def test_queue_push_rejects_what_can_never_run():
+    shape = workloads.C1_TINY
+    w = scaled_weights(shape, seed=1)
+    eng = make_engine(shape, w, max_live_samples=4, max_context=64, max_batch_tokens=48)
+    import paper_2506_06122_amd as R
+    toks, offs = workloads.make_prompts(1, 50, 50, shape.vocab, seed=1)
+    with pytest.raises(R.RolloutError):     # longer than max_batch_tokens
+        eng.rollout_queue_push(toks, offs, 2, np.array([2, 2], np.int32))
+    toks, offs = workloads.make_prompts(1, 40, 40, shape.vocab, seed=1)
+    with pytest.raises(R.RolloutError):     # prompt + response beyond max_context
+        eng.rollout_queue_push(toks, offs, 2, np.array([2, 30], np.int32))
+    with pytest.raises(R.RolloutError):     # 5 running samples, 4 slots
+        eng.rollout_queue_push(toks, offs, 5, np.full(5, 3, np.int32))
+    assert eng.rollout_queue_get_stats()["prompts_waiting"] == 0
+    eng.rollout_queue_push(toks, offs, 2, np.array([2, 3], np.int32))
+    with pytest.raises(R.RolloutError):     # n_samples is fixed by the first push
+        eng.rollout_queue_push(toks, offs, 3, np.full(3, 3, np.int32))
+    ids, tk, lps, fin, n_adm = eng.rollout_queue_step()
+    assert n_adm == 2 and ids.tolist() == [0, 1, 0, 1] and fin.tolist() == [False, False, True, False]
+    eng.close()
