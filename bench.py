@@ -58,6 +58,37 @@ def run_queue_job(eng, load) -> int:
         emitted += len(ids)
 
 
+def run_turns_job(eng, load, turns, turn_tokens, obs_tokens, vocab, clock) -> int:
+    """A multi-turn job: every sample answers `turns` times with `turn_tokens` tokens; between
+    turns `obs_tokens` seeded tokens (an environment's observation) are appended to its context.
+    clock accumulates the seconds spent in rollout_extend and the tokens appended there."""
+    import torch
+    rng = np.random.Generator(np.random.Philox(key=[7, 0x6f6273]))
+    n_live = load.n_prompts * load.n_samples
+    budget = np.full(n_live, turns * turn_tokens, np.int32)
+    ids, toks, lps, fin = eng.rollout_prefill(load.prompt_tokens, load.prompt_offsets, load.n_samples, budget,
+                                              eos_id=-1, temperature=load.temperature, top_p=load.top_p)
+    emitted = len(ids)
+    per_call = max(1, eng.max_batch_tokens // (obs_tokens + 1))
+    for turn in range(turns):
+        for _ in range(turn_tokens - 1):
+            emitted += len(eng.rollout_decode_step()[0])
+        if turn + 1 == turns:
+            break
+        live = eng.rollout_live_samples()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for a in range(0, len(live), per_call):
+            part = live[a:a + per_call]
+            obs = rng.integers(0, vocab, len(part) * obs_tokens).astype(np.int32)
+            eng.rollout_extend(part, obs, np.arange(len(part) + 1, dtype=np.int32) * obs_tokens)
+            emitted += len(part)
+            clock[1] += len(part) * obs_tokens
+        clock[0] += time.perf_counter() - t0
+    assert not len(eng.rollout_live_samples())
+    return emitted
+
+
 def cpu_baseline(shape, weights, load) -> dict:
     """The oracle, as it stands, on a bounded slice: one 256-token prompt, 4 samples, 64 new
     tokens each (weights widened to fp64 beforehand, not timed)."""
@@ -174,10 +205,12 @@ def main() -> int:
     ap.add_argument("--timing-stride", type=int, default=16,
                     help="bracket kernels with HIP events on every n-th library call (0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue"], default="c2",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns"], default="c2",
                     help="c2 = headline (1.5B shape); c3 = 7B-shape rollout; c4 = 30B-A3B-shape MoE rollout; "
                          "c5 = teacher-forced log-prob pass on the 7B shape; c2-queue = config 2's model and "
-                         "length laws with 4x the prompts fed through the prompt queue into the same 256 live slots")
+                         "length laws with 4x the prompts fed through the prompt queue into the same 256 live slots; "
+                         "c2-turns = config 2's model and prompts, 4 turns of 128 response tokens with 256 appended "
+                         "tokens between turns (rollout_extend)")
     ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
     ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -204,7 +237,7 @@ def main() -> int:
 
     wl = args.workload
     shape = {"c2": workloads.C2_1P5B, "c3": workloads.C3_7B, "c4": workloads.C4_30B_A3B, "c5": workloads.C3_7B,
-             "c2-queue": workloads.C2_1P5B}[wl]
+             "c2-queue": workloads.C2_1P5B, "c2-turns": workloads.C2_1P5B}[wl]
     cut = ""
     if args.layers and args.layers < shape.n_layers:
         cut = f", cut to {args.layers} of {shape.n_layers} layers"
@@ -226,6 +259,21 @@ def main() -> int:
         desc = ("configs[4]: teacher-forced log-prob pass, Qwen2.5-7B-shaped dense decoder, bf16, %d packed sequences "
                 "(of the config's 512), length U{512..8192}, %d tokens%s" % (n_seqs, len(tokens), cut))
         load = None
+    elif wl == "c2-turns":
+        turns, turn_tokens, obs_tokens = 4, 128, 256
+        load = workloads.load_c2(n_prompts=args.prompts or 32)
+        max_prompt = int(np.diff(load.prompt_offsets).max())
+        max_ctx = max_prompt + turns * turn_tokens + (turns - 1) * obs_tokens
+        live = load.n_prompts * load.n_samples
+        eng = R.Rollout(shape, weights, kv_pool_bytes=live * (max_ctx + 64) * kv_bytes_per_token, page_tokens=32,
+                        max_live_samples=live, max_context=max_ctx, max_batch_tokens=16384,
+                        seed=load.sampler_seed, flags=flags, timing_stride=max(args.timing_stride, 1))
+        eng.max_batch_tokens = 16384
+        extend_clock = [0.0, 0]
+        work = lambda: run_turns_job(eng, load, turns, turn_tokens, obs_tokens, shape.vocab, extend_clock)
+        desc = ("configs[1]'s model and prompts, %d prompts x %d samples, %d turns of %d response tokens, %d tokens "
+                "appended to every context between turns" % (load.n_prompts, load.n_samples, turns, turn_tokens,
+                                                             obs_tokens)) + cut
     elif wl == "c2-queue":
         live = 256
         load = workloads.load_c2(n_prompts=args.prompts or 128)
@@ -288,6 +336,8 @@ def main() -> int:
                    "decode_calls_per_step": (int(stats["decode_steps"]) - calls0) // max(args.steps, 1)},
         "roofline": roofline_of(kernels, bracket_ms, summary),
     }
+    if wl == "c2-turns" and extend_clock[0] > 0:  # warm-up jobs included: a rate, not a total
+        out["config"]["appended_tokens_per_s"] = extend_clock[1] / extend_clock[0]
     eng.close()
     del eng
     torch.cuda.empty_cache()

@@ -166,6 +166,28 @@ int rollout_decode_step(rollout_ctx *ctx, const int32_t *forced_tokens, const ui
 int rollout_logprobs(rollout_ctx *ctx, int32_t n_seqs, const int32_t *tokens, const int32_t *cu_seqlens,
                      float temperature, float *logprobs);
 
+/* Multi-turn continuation (the agentic pipeline's generate - environment - generate loop,
+ * paper section 2.1 "generation" with environment interaction and section 5.2): appends
+ * tokens the model did not generate - an environment's observation, a tool result - to the
+ * contexts of live samples and emits each sample's next response token.  For sample i the
+ * tokens tokens[offsets[i] .. offsets[i+1]) follow its last emitted token; the next token is
+ * drawn (or forced) from the distribution after the last appended token and counts towards
+ * max_new_tokens; appended tokens do not.  The appended tokens run through the model as one
+ * packed sequence per sample that attends to the sample's cache, so the cost is one forward
+ * pass whatever their number.
+ *   sample_ids   host int64 [n], live and distinct; outputs follow this order
+ *   tokens       host int32, the appended tokens concatenated; offsets host int32 [n+1], each
+ *                sample gets at least one
+ *   forced_next, uniform_override   NULL or host [n], as in rollout_decode_step
+ * Outputs (host [n], any may be NULL): next_tokens, next_logprobs, finished.
+ * rollout_debug_logits then returns the n logits rows the tokens were drawn from.
+ * All or nothing.  Errors: E_INVAL (a sample is not live or listed twice, nothing to append,
+ * token out of range); E_NOMEM (context + remaining response beyond max_context, all rows
+ * beyond max_batch_tokens, not enough free pages for the longer contexts). */
+int rollout_extend(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids, const int32_t *tokens,
+                   const int32_t *offsets, const int32_t *forced_next, const uint32_t *uniform_override,
+                   int32_t *next_tokens, float *next_logprobs, uint8_t *finished);
+
 /* "Abort request" (paper section 4.3): drops the listed live samples and frees their
  * pages.  Ids that are not live are ignored.  Returns the number aborted. */
 int rollout_abort(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids);

@@ -78,6 +78,7 @@ SIGNATURES = {
     "rollout_decode_step": (C.c_int, [_P, _P, _P, C.POINTER(C.c_int32), _P, _P, _P, _P]),
     "rollout_logprobs": (C.c_int, [_P, C.c_int32, _P, _P, C.c_float, _P]),
     "rollout_abort": (C.c_int, [_P, C.c_int32, _P]),
+    "rollout_extend": (C.c_int, [_P, C.c_int32, _P, _P, _P, _P, _P, _P, _P, _P]),
     "rollout_queue_push": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, C.c_int32, C.c_float, C.c_float, _P]),
     "rollout_queue_policy": (C.c_int, [_P, C.c_int32, C.c_int32]),
     "rollout_queue_step": (C.c_int, [_P, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _P, _P, _P, _P]),
@@ -240,6 +241,15 @@ class Rollout:
         out = np.empty(len(tokens), np.float32)
         self._check(self.lib.rollout_logprobs(self.ctx, len(cu) - 1, _ptr(tokens), _ptr(cu), temperature, _ptr(out)))
         return out
+
+    def rollout_extend(self, sample_ids, tokens, offsets, forced_next=None, uniform_override=None):
+        ids, tokens, offsets = _arr(sample_ids, np.int64), _arr(tokens, np.int32), _arr(offsets, np.int32)
+        forced, uni = _arr(forced_next, np.int32), _arr(uniform_override, np.uint32)
+        n = len(ids)
+        toks, lps, fin = np.empty(n, np.int32), np.empty(n, np.float32), np.empty(n, np.uint8)
+        self._check(self.lib.rollout_extend(self.ctx, n, _ptr(ids), _ptr(tokens), _ptr(offsets), _ptr(forced),
+                                            _ptr(uni), _ptr(toks), _ptr(lps), _ptr(fin)))
+        return toks, lps, fin.astype(bool)
 
     def rollout_abort(self, sample_ids):
         ids = _arr(sample_ids, np.int64)

@@ -291,6 +291,7 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
     Sample& s = fresh[i];
     int tok = hi[7 * R + i];
     s.n_emitted = 1;
+    s.last_token = tok;
     bool done = s.max_new <= 1 || (eos_id >= 0 && tok == eos_id);
     if (sample_ids) sample_ids[i] = s.id;
     if (first_tokens) first_tokens[i] = tok;
@@ -385,6 +386,7 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
     Sample& s = it->second;
     int tok = hi[3 * R + i];
     s.n_emitted += 1;
+    s.last_token = tok;
     bool done = s.n_emitted >= s.max_new || (s.eos_id >= 0 && tok == s.eos_id);
     if (sample_ids) sample_ids[i] = s.id;
     if (tokens) tokens[i] = tok;
@@ -402,6 +404,162 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
   *n_live = B;
   c.stats.decode_steps += 1;
   c.stats.tokens_emitted += B;
+  refresh_stats(c);
+}
+
+__global__ void extend_slots_kernel(SlotState st, const int* __restrict__ slots, const int* __restrict__ new_pos,
+                                    const int* __restrict__ tokens, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  int sl = slots[i];
+  st.last_token[sl] = tokens[i];
+  st.pos[sl] = new_pos[i];
+  st.step[sl] += 1;
+}
+
+// Appends tokens that the model did not generate to live samples' contexts and emits each
+// sample's next response token: the sample's last response token and the appended tokens run
+// through the model as one packed sequence that attends to the sample's cache (the same
+// kernels as prefill, with a first position per sequence), and the next token is drawn from the
+// logits of the last appended token.
+static void extend_impl(rollout_ctx& c, int32_t n, const int64_t* sample_ids, const int32_t* tokens,
+                        const int32_t* offsets, const int32_t* forced_next, const uint32_t* uniform_override,
+                        int32_t* next_tokens, float* next_logprobs, uint8_t* finished) {
+  const rollout_model_desc& m = c.md;
+  const int T = c.rd.page_tokens, R = c.r_max;
+  if (n < 1 || !sample_ids || !tokens || !offsets) fail(ROLLOUT_E_INVAL, "bad arguments");
+  if (offsets[0] != 0) fail(ROLLOUT_E_INVAL, "offsets[0] must be 0");
+  if (n > rollout_ctx::kTempSlots || n > c.logit_rows) fail(ROLLOUT_E_NOMEM, "too many samples in one call");
+  // ---- validation (no state changes before all of it passed) ----
+  std::vector<Sample*> ss(n);
+  std::vector<int> extra(n);
+  long long rows = 0, extra_pages = 0;
+  for (int i = 0; i < n; ++i) {
+    auto it = c.live.find(sample_ids[i]);
+    if (it == c.live.end()) fail(ROLLOUT_E_INVAL, "sample " + std::to_string(sample_ids[i]) + " is not live");
+    for (int j = 0; j < i; ++j)
+      if (sample_ids[j] == sample_ids[i]) fail(ROLLOUT_E_INVAL, "sample listed twice");
+    Sample& s = it->second;
+    ss[i] = &s;
+    const int len = offsets[i + 1] - offsets[i];
+    if (len < 1) fail(ROLLOUT_E_INVAL, "nothing to append");
+    for (int k = offsets[i]; k < offsets[i + 1]; ++k)
+      if (tokens[k] < 0 || tokens[k] >= m.vocab) fail(ROLLOUT_E_INVAL, "token out of range");
+    if (forced_next && (forced_next[i] < 0 || forced_next[i] >= m.vocab)) fail(ROLLOUT_E_INVAL, "forced token out of range");
+    const long long cached = (long long)s.prompt_len + len + s.max_new - 1;
+    if (cached > c.rd.max_context) fail(ROLLOUT_E_NOMEM, "context + response exceeds max_context");
+    extra[i] = std::max(0, ceil_div(cached, T) - (int)s.pages.size());
+    extra_pages += extra[i];
+    rows += len + 1;
+  }
+  if (rows > c.rd.max_batch_tokens || rows > R) fail(ROLLOUT_E_NOMEM, "appended tokens exceed max_batch_tokens");
+  if (extra_pages > c.pool->unreserved()) fail(ROLLOUT_E_NOMEM, "not enough free KV pages");
+
+  // ---- pages for the longer contexts ----
+  for (int i = 0; i < n; ++i) {
+    Sample& s = *ss[i];
+    int* srow = &c.h_page_table[(size_t)s.slot * c.max_pages];
+    for (int k = 0; k < extra[i]; ++k) {
+      int32_t pg = c.pool->alloc(false);
+      srow[s.pages.size()] = pg;
+      s.pages.push_back(pg);
+    }
+  }
+  if (extra_pages) engine_upload_page_table(c);
+
+  // ---- rows: [last response token, appended tokens] per sample, positions after its cache ----
+  int* hi = c.h_int.p;
+  int r = 0, max_len = 0;
+  double kv_tokens = 0, flops = 0;
+  for (int i = 0; i < n; ++i) {
+    Sample& s = *ss[i];
+    const int len = offsets[i + 1] - offsets[i] + 1, p0 = s.prompt_len + s.n_emitted - 1;
+    hi[4 * R + i] = r;
+    hi[5 * R + i] = len;
+    hi[6 * R + i] = s.slot;
+    hi[7 * R + i] = p0;
+    for (int k = 0; k < len; ++k, ++r) {
+      hi[r] = k == 0 ? s.last_token : tokens[offsets[i] + k - 1];
+      hi[R + r] = p0 + k;
+      hi[2 * R + r] = s.slot;
+    }
+    hi[3 * R + i] = r - 1;  // last row: its logits give the next token
+    max_len = std::max(max_len, len);
+    kv_tokens += (double)len * p0 + 0.5 * len * (len + 1);
+    flops += 4.0 * ((double)len * p0 + 0.5 * len * (len + 1)) * c.q_dim;
+  }
+  h2d(c.d_live.p, hi + 6 * R, n * sizeof(int), c.stream);
+  c.live_dirty = true;  // d_live no longer holds the live list
+  launch_gather_decode_rows(c.st, c.d_live.p, n, c.row_token.p, c.row_pos.p, c.row_slot.p, c.row_inv_temp.p,
+                            c.row_top_p.p, c.row_sample_id.p, c.row_step.p, c.stream);
+  h2d(c.row_token.p, hi, rows * sizeof(int), c.stream);
+  h2d(c.row_pos.p, hi + R, rows * sizeof(int), c.stream);
+  h2d(c.row_slot.p, hi + 2 * R, rows * sizeof(int), c.stream);
+  h2d(c.row_aux.p, hi + 3 * R, n * sizeof(int), c.stream);
+  SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, n, max_len};
+  if (!c.simple) {
+    h2d(c.seq_row0.p, hi + 4 * R, n * sizeof(int), c.stream);
+    h2d(c.seq_len.p, hi + 5 * R, n * sizeof(int), c.stream);
+    h2d(c.seq_slot.p, hi + 6 * R, n * sizeof(int), c.stream);
+    h2d(c.seq_pos0.p, hi + 7 * R, n * sizeof(int), c.stream);
+    sb.pos0 = c.seq_pos0.p;
+  }
+  c.timer.start_call();
+  c.kv_tokens_this_call = kv_tokens;
+  c.attn_flops_this_call = flops;
+  engine_forward_rows(c, (int)rows, &sb);
+  engine_logits(c, c.row_aux.p, 0, n, c.logits.p);
+  c.last_logit_rows = n;
+  HIP_TRY(hipStreamSynchronize(c.stream));  // the staging buffers are reused below
+  c.timer.collect();
+
+  // ---- the next response token of every sample ----
+  for (int i = 0; i < n; ++i) {
+    Sample& s = *ss[i];
+    hi[i] = s.prompt_len + (offsets[i + 1] - offsets[i]) + s.n_emitted;  // position of the token drawn now
+    hi[R + i] = forced_next ? forced_next[i] : -1;
+    hi[2 * R + i] = uniform_override ? (int)uniform_override[i] : 0;
+  }
+  h2d(c.row_aux.p + R, hi, n * sizeof(int), c.stream);
+  h2d(c.row_forced.p, hi + R, n * sizeof(int), c.stream);
+  h2d(c.row_uniform.p, hi + 2 * R, n * sizeof(int), c.stream);
+  SampleRows sr{};
+  sr.logits = c.logits.p;
+  sr.logits_row = nullptr;
+  sr.inv_temp = c.row_inv_temp.p;
+  sr.top_p = c.row_top_p.p;
+  sr.uniforms = uniform_override ? c.row_uniform.p : nullptr;
+  sr.sample_id = c.row_sample_id.p;
+  sr.step = c.row_step.p;
+  sr.forced = forced_next ? c.row_forced.p : nullptr;
+  sr.seed = c.rd.seed;
+  sr.tokens = c.out_tokens.p;
+  sr.logprobs = c.out_logprobs.p;
+  launch_sample(sr, n, m.vocab, c.stream);
+  extend_slots_kernel<<<ceil_div(n, 256), 256, 0, c.stream>>>(c.st, c.d_live.p, c.row_aux.p + R, c.out_tokens.p, n);
+  d2h(hi + 3 * R, c.out_tokens.p, n * sizeof(int), c.stream);
+  d2h(c.h_float.p, c.out_logprobs.p, n * sizeof(float), c.stream);
+  HIP_TRY(hipStreamSynchronize(c.stream));
+
+  // ---- host bookkeeping ----
+  for (int i = 0; i < n; ++i) {
+    Sample& s = *ss[i];
+    const int tok = hi[3 * R + i];
+    s.prompt_len += offsets[i + 1] - offsets[i];
+    s.n_emitted += 1;
+    s.last_token = tok;
+    const bool done = s.n_emitted >= s.max_new || (s.eos_id >= 0 && tok == s.eos_id);
+    if (next_tokens) next_tokens[i] = tok;
+    if (next_logprobs) next_logprobs[i] = c.h_float.p[i];
+    if (finished) finished[i] = done ? 1 : 0;
+    c.stats.prompt_tokens += offsets[i + 1] - offsets[i];
+    c.stats.tokens_emitted += 1;
+    if (done) {
+      release_sample(c, s);
+      c.live.erase(sample_ids[i]);
+      c.stats.samples_finished += 1;
+    }
+  }
   refresh_stats(c);
 }
 
@@ -668,6 +826,16 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
       q.closed = true;
       refresh_stats(c);
     }
+  });
+}
+
+int rollout_extend(rollout_ctx* ctx, int32_t n, const int64_t* sample_ids, const int32_t* tokens,
+                   const int32_t* offsets, const int32_t* forced_next, const uint32_t* uniform_override,
+                   int32_t* next_tokens, float* next_logprobs, uint8_t* finished) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    extend_impl(*ctx, n, sample_ids, tokens, offsets, forced_next, uniform_override, next_tokens, next_logprobs,
+                finished);
   });
 }
 

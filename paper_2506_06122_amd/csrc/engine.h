@@ -78,6 +78,7 @@ struct LayerWeights {
 struct SeqBatch {
   const int *row0, *len, *slot;
   int n_seqs, max_len;
+  const int* pos0 = nullptr;  // first position of each sequence (NULL = 0)
 };
 
 // HIP-event brackets around kernel launches on sampled calls (ROLLOUT_RT_KERNEL_TIMING),
@@ -147,7 +148,8 @@ struct KernelTimer {
 struct Sample {
   int64_t id;
   int slot;
-  int prompt_len, n_emitted, max_new, eos_id;
+  int prompt_len, n_emitted, max_new, eos_id;  // prompt_len: every cached token that is not a response token
+  int last_token = -1;                         // the response token emitted last (not cached yet)
   std::vector<int32_t> pages;  // one reference held on each
 };
 
@@ -226,7 +228,7 @@ struct rollout_ctx {
   int decode_max_ctx = 0;       // longest context among the rows of the current decode step
   double kv_tokens_this_call = 0;   // cached positions attended by the current forward (for timing records)
   double attn_flops_this_call = 0;
-  DevBuf<int> seq_row0, seq_len, seq_slot;
+  DevBuf<int> seq_row0, seq_len, seq_slot, seq_pos0;
   DevBuf<float> ssq;            // [partials][256] partial sums of squares of the residual rows (decode path)
   int ssq_partials = 0;
   bool h_is_final = false;      // the last forward left x * final gain in h_bf16 (decode path)

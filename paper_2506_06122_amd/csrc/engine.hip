@@ -232,6 +232,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     c.seq_row0.alloc(rollout_ctx::kTempSlots);
     c.seq_len.alloc(rollout_ctx::kTempSlots);
     c.seq_slot.alloc(rollout_ctx::kTempSlots);
+    c.seq_pos0.alloc(rollout_ctx::kTempSlots);
   } else {
     c.h.alloc(R * d);
     c.qkv.alloc(R * c.qkv_dim);
@@ -547,6 +548,7 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
       at.seq_row0 = seqs->row0;
       at.seq_len = seqs->len;
       at.seq_slot = seqs->slot;
+      at.seq_pos0 = seqs->pos0;
       at.n_seqs = seqs->n_seqs;
       at.max_seq_len = seqs->max_len;
       c.timer.begin("attn_prefill_kernel", kv_bytes + 4.0 * R * c.q_dim, c.attn_flops_this_call, s);

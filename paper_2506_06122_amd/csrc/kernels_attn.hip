@@ -337,16 +337,18 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
   const int q0 = blockIdx.x * 64 + wave * 16;
   if (q0 >= len) return;  // wavefronts are independent: no barrier below
   const int row0 = a.seq_row0[seq], slot = a.seq_slot[seq];
+  const int p0 = a.seq_pos0 ? a.seq_pos0[seq] : 0;  // cached positions before the sequence's first row
   const int kvh = head / (a.n_q_heads / a.geom.n_kv_heads);
-  const int pos = q0 + c;
+  const int qi = q0 + c;                             // row of this column inside the sequence
+  const int pos = p0 + qi;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   Frag q[8];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
     q[ks].u = make_uint4(0, 0, 0, 0);
     q[4 + ks].u = make_uint4(0, 0, 0, 0);
-    if (pos < len) {
-      const uint16_t* src = a.q + ((long long)(row0 + pos) * a.n_q_heads + head) * DH + ks * 32 + g * 8;
+    if (qi < len) {
+      const uint16_t* src = a.q + ((long long)(row0 + qi) * a.n_q_heads + head) * DH + ks * 32 + g * 8;
       q[ks].u = *(const uint4*)src;
       q[4 + ks].u = *(const uint4*)(src + a.q_lo_offset);
     }
@@ -355,12 +357,12 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
   f32x4 o[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int last = min(q0 + 15, len - 1);
+  const int last = p0 + min(q0 + 15, len - 1);
   for (int tok0 = 0; tok0 <= last; tok0 += 32)
     attend_group(group_block(a, slot, kvh, tok0, 0), group_block(a, slot, kvh, tok0, 1), q, tok0, pos, scale_log2,
                  m, l, o, lane);
-  if (pos < len) {
-    uint16_t* dst = a.out + ((long long)(row0 + pos) * a.n_q_heads + head) * DH + 4 * g;
+  if (qi < len) {
+    uint16_t* dst = a.out + ((long long)(row0 + qi) * a.n_q_heads + head) * DH + 4 * g;
     const float inv = 1.0f / (l * P_SCALE);
 #pragma unroll
     for (int j = 0; j < 8; ++j)

@@ -160,6 +160,8 @@ struct AttnArgs {
   uint16_t* kv_pool_w;
   // prefill: packed sequences
   const int *seq_row0, *seq_len, *seq_slot;
+  const int* seq_pos0 = nullptr;   // position of each sequence's first row (NULL = 0): rows that
+                                   // continue a cached context attend to it as well
   int n_seqs, max_seq_len;
 };
 void launch_attention_prefill(const AttnArgs& a, hipStream_t s);
