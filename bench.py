@@ -205,12 +205,13 @@ def main() -> int:
     ap.add_argument("--timing-stride", type=int, default=16,
                     help="bracket kernels with HIP events on every n-th library call (0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns"], default="c2",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns", "c2-refresh"], default="c2",
                     help="c2 = headline (1.5B shape); c3 = 7B-shape rollout; c4 = 30B-A3B-shape MoE rollout; "
                          "c5 = teacher-forced log-prob pass on the 7B shape; c2-queue = config 2's model and "
                          "length laws with 4x the prompts fed through the prompt queue into the same 256 live slots; "
                          "c2-turns = config 2's model and prompts, 4 turns of 128 response tokens with 256 appended "
-                         "tokens between turns (rollout_extend)")
+                         "tokens between turns (rollout_extend); c2-refresh = all of config 2's weights replaced in "
+                         "place from device buffers, one bucket per layer (rollout_update_weights)")
     ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
     ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -237,7 +238,7 @@ def main() -> int:
 
     wl = args.workload
     shape = {"c2": workloads.C2_1P5B, "c3": workloads.C3_7B, "c4": workloads.C4_30B_A3B, "c5": workloads.C3_7B,
-             "c2-queue": workloads.C2_1P5B, "c2-turns": workloads.C2_1P5B}[wl]
+             "c2-queue": workloads.C2_1P5B, "c2-turns": workloads.C2_1P5B, "c2-refresh": workloads.C2_1P5B}[wl]
     cut = ""
     if args.layers and args.layers < shape.n_layers:
         cut = f", cut to {args.layers} of {shape.n_layers} layers"
@@ -248,6 +249,38 @@ def main() -> int:
     flags = B.RT_KERNEL_TIMING if args.timing_stride > 0 else 0
     kv_bytes_per_token = shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 2
 
+    if wl == "c2-refresh":
+        from paper_2506_06122_amd.binding import _to_device
+        eng = R.Rollout(shape, weights, kv_pool_bytes=1 << 30, page_tokens=32, max_live_samples=8, max_context=512,
+                        max_batch_tokens=512, seed=1)
+        dev = {k: _to_device(v, True) for k, v in weights.items()}
+        buckets = [{k: dev[k] for k in ("embed", "final_norm", "lm_head")}] + \
+            [{k: v for k, v in dev.items() if k.startswith(f"layers.{i}.")} for i in range(shape.n_layers)]
+        nbytes = sum(v.numel() * v.element_size() for v in dev.values())
+
+        def refresh():
+            for b in buckets:
+                eng.rollout_update_weights(b)
+        for _ in range(args.warmup):
+            refresh()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            refresh()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / max(args.steps, 1)
+        print(json.dumps({"metric": "weight refresh GB/s on 1 MI355X (bytes of the new weights per second)",
+                          "value": nbytes / dt / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": 1e3 * dt, "higher_is_better": True,
+                          "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": "all tensors of configs[1]'s model (%.2f GB) re-ordered into the "
+                                     "library's layout from device buffers, %d buckets" % (nbytes / 1e9, len(buckets))},
+                          "roofline": {"bound": "hbm", "achieved": 2 * nbytes / dt / 1e9, "peak": HBM_PEAK_GBS,
+                                       "unit": "GB/s", "frac": 2 * nbytes / dt / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                                       "kernel": "pack_weight_kernel"},
+                          "cpu_baseline": None}))
+        eng.close()
+        return 0
     if wl == "c5":
         n_seqs = args.prompts or 24
         tokens, cu = workloads.packed_sequences(n_seqs, 512, 8192, shape.vocab, seed=2)

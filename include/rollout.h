@@ -241,6 +241,29 @@ int rollout_queue_step(rollout_ctx *ctx, int32_t *n_out, int32_t *n_admitted, in
 
 int rollout_queue_get_stats(rollout_ctx *ctx, rollout_queue_stats *out);
 
+/* ---- Weight refresh ------------------------------------------------------------------------
+ * The receiving half of the parameter synchronisation between the training and the generation
+ * stage of an iteration (paper section 2.1: the updated actor generates the next iteration's
+ * responses; section 4.3: the model update is sent to the inference workers in buckets).  Each
+ * call takes one bucket: tensors as rollout_init takes them (DEVICE pointers, model dtype,
+ * row-major [out_features][in_features]) and re-orders them into the library's layout in
+ * place.  Returns when the copies are done, so the caller may reuse the bucket's memory.
+ * The KV pool and every other allocation stay as they are.
+ * Errors: E_INVAL (unknown tensor, layer out of range - model-level tensors take layer -1 -,
+ * null pointer; nothing of the bucket is applied); E_STATE while samples are live or prompts
+ * wait in the queue (their cached keys and values belong to the old weights). */
+enum {
+  ROLLOUT_W_EMBED = 0, ROLLOUT_W_FINAL_NORM = 1, ROLLOUT_W_LM_HEAD = 2,                   /* layer -1 */
+  ROLLOUT_W_NORM1 = 3, ROLLOUT_W_WQ = 4, ROLLOUT_W_WK = 5, ROLLOUT_W_WV = 6, ROLLOUT_W_WO = 7,
+  ROLLOUT_W_NORM2 = 8, ROLLOUT_W_GATE = 9, ROLLOUT_W_UP = 10, ROLLOUT_W_DOWN = 11, ROLLOUT_W_ROUTER = 12
+};
+typedef struct {
+  int32_t layer;    /* 0 .. n_layers-1, or -1 for embed / final_norm / lm_head */
+  int32_t tensor;   /* ROLLOUT_W_* */
+  const void *data; /* DEVICE pointer, shape as in rollout_layer_weights / rollout_weights */
+} rollout_tensor_update;
+int rollout_update_weights(rollout_ctx *ctx, int32_t n, const rollout_tensor_update *updates);
+
 /* Parity hook: copies the fp32 logits rows of the last prefill (one per prompt, prompt
  * order) or decode step (one per stepped sample, ascending id) to host `out`
  * [rows][vocab].  rows: in capacity, out count.  Errors: E_INVAL, E_STATE (none yet). */

@@ -62,6 +62,14 @@ class rollout_queue_stats(C.Structure):
                [("prompts_waiting", C.c_int32), ("closed", C.c_int32)]
 
 
+class rollout_tensor_update(C.Structure):
+    _fields_ = [("layer", C.c_int32), ("tensor", C.c_int32), ("data", C.c_void_p)]
+
+
+W_IDS = {"embed": 0, "final_norm": 1, "lm_head": 2, "norm1": 3, "wq": 4, "wk": 5, "wv": 6, "wo": 7, "norm2": 8,
+         "w_gate": 9, "w_up": 10, "w_down": 11, "router": 12}
+
+
 class rollout_kernel_stat(C.Structure):
     _fields_ = [("name", C.c_char * 64), ("launches", C.c_uint64), ("ms", C.c_double), ("bytes", C.c_double),
                 ("flops", C.c_double)]
@@ -78,6 +86,7 @@ SIGNATURES = {
     "rollout_decode_step": (C.c_int, [_P, _P, _P, C.POINTER(C.c_int32), _P, _P, _P, _P]),
     "rollout_logprobs": (C.c_int, [_P, C.c_int32, _P, _P, C.c_float, _P]),
     "rollout_abort": (C.c_int, [_P, C.c_int32, _P]),
+    "rollout_update_weights": (C.c_int, [_P, C.c_int32, C.POINTER(rollout_tensor_update)]),
     "rollout_extend": (C.c_int, [_P, C.c_int32, _P, _P, _P, _P, _P, _P, _P, _P]),
     "rollout_queue_push": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, C.c_int32, C.c_float, C.c_float, _P]),
     "rollout_queue_policy": (C.c_int, [_P, C.c_int32, C.c_int32]),
@@ -250,6 +259,24 @@ class Rollout:
         self._check(self.lib.rollout_extend(self.ctx, n, _ptr(ids), _ptr(tokens), _ptr(offsets), _ptr(forced),
                                             _ptr(uni), _ptr(toks), _ptr(lps), _ptr(fin)))
         return toks, lps, fin.astype(bool)
+
+    def rollout_update_weights(self, tensors: dict):
+        """One bucket: {checkpoint name ("layers.3.wq", "lm_head", "layers.0.experts.w_up", ...): array or
+        device tensor}.  Host arrays are uploaded first; the call returns when the library holds
+        its own copy."""
+        import torch
+        bf16 = self.shape.dtype == "bf16"
+        arr = (rollout_tensor_update * len(tensors))()
+        keep = []
+        for k, (name, w) in enumerate(tensors.items()):
+            t = w if isinstance(w, torch.Tensor) else _to_device(w, bf16)
+            keep.append(t)
+            parts = name.split(".")
+            layer = int(parts[1]) if parts[0] == "layers" else -1
+            arr[k] = rollout_tensor_update(layer, W_IDS[parts[-1]], t.data_ptr())
+        torch.cuda.synchronize()
+        self._check(self.lib.rollout_update_weights(self.ctx, len(tensors), arr))
+        del keep
 
     def rollout_abort(self, sample_ids):
         ids = _arr(sample_ids, np.int64)

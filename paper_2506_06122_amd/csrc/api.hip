@@ -839,6 +839,29 @@ int rollout_extend(rollout_ctx* ctx, int32_t n, const int64_t* sample_ids, const
   });
 }
 
+int rollout_update_weights(rollout_ctx* ctx, int32_t n, const rollout_tensor_update* updates) {
+  if (!ctx) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    rollout_ctx& c = *ctx;
+    if (n < 0 || (n > 0 && !updates)) fail(ROLLOUT_E_INVAL, "bad arguments");
+    if (!c.live.empty() || !c.queue.waiting.empty())
+      fail(ROLLOUT_E_STATE, "weights cannot change while samples are live or prompts wait");
+    const rollout_model_desc& m = c.md;
+    for (int i = 0; i < n; ++i) {  // the whole bucket is checked before any of it is applied
+      const rollout_tensor_update& u = updates[i];
+      const bool model_level = u.tensor >= ROLLOUT_W_EMBED && u.tensor <= ROLLOUT_W_LM_HEAD;
+      if (!u.data) fail(ROLLOUT_E_INVAL, "null weight pointer");
+      if (u.tensor < ROLLOUT_W_EMBED || u.tensor > ROLLOUT_W_ROUTER) fail(ROLLOUT_E_INVAL, "unknown tensor");
+      if (model_level ? u.layer != -1 : (u.layer < 0 || u.layer >= m.n_layers))
+        fail(ROLLOUT_E_INVAL, "layer out of range (model-level tensors take layer -1)");
+      if (u.tensor == ROLLOUT_W_ROUTER && !m.n_experts) fail(ROLLOUT_E_INVAL, "a dense model has no router");
+    }
+    for (int i = 0; i < n; ++i) engine_load_tensor(c, updates[i].layer, updates[i].tensor, updates[i].data);
+    HIP_TRY(hipStreamSynchronize(c.stream));
+    c.h_is_final = false;
+  });
+}
+
 int rollout_abort(rollout_ctx* ctx, int32_t n, const int64_t* sample_ids) {
   if (!ctx || n < 0 || (n > 0 && !sample_ids)) return ROLLOUT_E_INVAL;
   int aborted = 0;

@@ -262,3 +262,5 @@ void engine_logits(rollout_ctx& c, const int* rows_index, int first, int n, floa
 // target[r] < 0); target and out are device arrays
 void engine_target_logprobs(rollout_ctx& c, int n, const int* target, float inv_t, float* out);
 void engine_upload_page_table(rollout_ctx& c);
+// one tensor (ROLLOUT_W_*, device pointer, caller's layout) into the library's layout, on c.stream
+void engine_load_tensor(rollout_ctx& c, int layer, int which, const void* src);

@@ -12,16 +12,103 @@ static void copy_d2d(void* dst, const void* src, size_t bytes, hipStream_t s) {
   if (bytes) HIP_TRY(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s));
 }
 
-static void load_gain(rollout_ctx& c, DevBuf<float>& dst, const void* src, const char* what) {
-  if (!src) fail(ROLLOUT_E_INVAL, std::string("null weight pointer: ") + what);
-  dst.alloc(c.md.hidden);
+static void load_gain(rollout_ctx& c, DevBuf<float>& dst, const void* src) {
   launch_convert_to_f32(src, c.md.dtype, dst.p, c.md.hidden, c.stream);
 }
 
-static void load_matrix(rollout_ctx& c, DevBuf<char>& dst, size_t dst_off_elems, const void* src, size_t elems,
-                        const char* what) {
-  if (!src) fail(ROLLOUT_E_INVAL, std::string("null weight pointer: ") + what);
+static void load_matrix(rollout_ctx& c, DevBuf<char>& dst, size_t dst_off_elems, const void* src, size_t elems) {
   copy_d2d(dst.p + dst_off_elems * c.elem, src, elems * c.elem, c.stream);
+}
+
+// Buffers of every weight in the library's own layout (sizes depend on the shape only).
+static void alloc_weights(rollout_ctx& c) {
+  const rollout_model_desc& m = c.md;
+  const bool moe = m.n_experts > 0;
+  const size_t d = m.hidden;
+  c.embed.alloc((size_t)m.vocab * d * c.elem);
+  if (c.simple) c.lm_head.alloc((size_t)m.vocab * d * c.elem);
+  else c.lm_head_p.alloc((size_t)m.vocab * d * 2);
+  c.final_norm.alloc(d);
+  c.layers.resize(m.n_layers);
+  for (LayerWeights& L : c.layers) {
+    L.norm1.alloc(d);
+    L.norm2.alloc(d);
+    if (!c.simple) {
+      // MoE: the experts' matrices are stacked, [E * Fe][hidden] and [E * hidden][Fe]; Fe is a
+      // multiple of 16, so the stacked gate/up column tiles still alternate inside every expert
+      const size_t f = moe ? (size_t)m.n_experts * m.expert_ffn_dim : (size_t)m.ffn_dim;
+      if (moe) L.router_p.alloc((size_t)m.n_experts * d * 2);
+      L.wqkv_p.alloc((size_t)c.qkv_dim * d * 2);
+      L.wo_p.alloc(d * c.q_dim * 2);
+      L.w_gate_up_p.alloc(2 * f * d * 2);
+      L.w_down_p.alloc(f * d * 2);
+      continue;
+    }
+    L.wqkv.alloc((size_t)c.qkv_dim * d * c.elem);
+    L.wo.alloc(d * c.q_dim * c.elem);
+    const size_t f = moe ? (size_t)m.n_experts * m.expert_ffn_dim : (size_t)m.ffn_dim;
+    if (moe) L.router.alloc((size_t)m.n_experts * d * c.elem);
+    L.w_gate_up.alloc(2 * f * d * c.elem);
+    L.w_down.alloc(d * f * c.elem);
+  }
+}
+
+// One tensor, given as at rollout_init (device pointer, model dtype, row-major), into the
+// library's layout: asynchronous on the context's stream.
+void engine_load_tensor(rollout_ctx& c, int layer, int which, const void* src) {
+  const rollout_model_desc& m = c.md;
+  const bool moe = m.n_experts > 0;
+  const size_t d = m.hidden;
+  if (!src) fail(ROLLOUT_E_INVAL, "null weight pointer");
+  const bool model_level = which == ROLLOUT_W_EMBED || which == ROLLOUT_W_FINAL_NORM || which == ROLLOUT_W_LM_HEAD;
+  if (which < ROLLOUT_W_EMBED || which > ROLLOUT_W_ROUTER) fail(ROLLOUT_E_INVAL, "unknown tensor");
+  if (model_level ? layer != -1 : (layer < 0 || layer >= m.n_layers))
+    fail(ROLLOUT_E_INVAL, "layer out of range (model-level tensors take layer -1)");
+  if (which == ROLLOUT_W_ROUTER && !moe) fail(ROLLOUT_E_INVAL, "a dense model has no router");
+  if (which == ROLLOUT_W_EMBED) return load_matrix(c, c.embed, 0, src, (size_t)m.vocab * d);
+  if (which == ROLLOUT_W_FINAL_NORM) return load_gain(c, c.final_norm, src);
+  if (which == ROLLOUT_W_LM_HEAD) {
+    if (c.simple) return load_matrix(c, c.lm_head, 0, src, (size_t)m.vocab * d);
+    return launch_pack_weight(src, c.lm_head_p.p, m.vocab, (int)d, 0, 1, c.stream);
+  }
+  LayerWeights& L = c.layers[layer];
+  if (which == ROLLOUT_W_NORM1) return load_gain(c, L.norm1, src);
+  if (which == ROLLOUT_W_NORM2) return load_gain(c, L.norm2, src);
+  const size_t fe = m.expert_ffn_dim, E = m.n_experts;
+  if (!c.simple) {
+    const int f = moe ? m.n_experts * m.expert_ffn_dim : m.ffn_dim;
+    const int down_rows = moe ? m.n_experts * (int)d : (int)d;
+    const int down_k = moe ? m.expert_ffn_dim : m.ffn_dim;
+    switch (which) {
+      case ROLLOUT_W_WQ: return launch_pack_weight(src, L.wqkv_p.p, c.q_dim, (int)d, 0, 1, c.stream);
+      case ROLLOUT_W_WK: return launch_pack_weight(src, L.wqkv_p.p, c.kv_dim, (int)d, c.q_dim / 16, 1, c.stream);
+      case ROLLOUT_W_WV:
+        return launch_pack_weight(src, L.wqkv_p.p, c.kv_dim, (int)d, (c.q_dim + c.kv_dim) / 16, 1, c.stream);
+      case ROLLOUT_W_WO: return launch_pack_weight(src, L.wo_p.p, (int)d, c.q_dim, 0, 1, c.stream);
+      case ROLLOUT_W_GATE: return launch_pack_weight(src, L.w_gate_up_p.p, f, (int)d, 0, 2, c.stream);
+      case ROLLOUT_W_UP: return launch_pack_weight(src, L.w_gate_up_p.p, f, (int)d, 1, 2, c.stream);
+      case ROLLOUT_W_DOWN: return launch_pack_weight(src, L.w_down_p.p, down_rows, down_k, 0, 1, c.stream);
+      default: return launch_pack_weight(src, L.router_p.p, m.n_experts, (int)d, 0, 1, c.stream);
+    }
+  }
+  switch (which) {
+    case ROLLOUT_W_WQ: return load_matrix(c, L.wqkv, 0, src, (size_t)c.q_dim * d);
+    case ROLLOUT_W_WK: return load_matrix(c, L.wqkv, (size_t)c.q_dim * d, src, (size_t)c.kv_dim * d);
+    case ROLLOUT_W_WV: return load_matrix(c, L.wqkv, (size_t)(c.q_dim + c.kv_dim) * d, src, (size_t)c.kv_dim * d);
+    case ROLLOUT_W_WO: return load_matrix(c, L.wo, 0, src, d * c.q_dim);
+    case ROLLOUT_W_ROUTER: return load_matrix(c, L.router, 0, src, E * d);
+    case ROLLOUT_W_DOWN: return load_matrix(c, L.w_down, 0, src, moe ? E * d * fe : d * (size_t)m.ffn_dim);
+    default: break;
+  }
+  // gate / up of the plain path: [gate rows; up rows], per expert for MoE
+  const size_t half = which == ROLLOUT_W_UP ? 1 : 0;
+  if (moe) {
+    HIP_TRY(hipMemcpy2DAsync(L.w_gate_up.p + half * fe * d * c.elem, 2 * fe * d * c.elem, src, fe * d * c.elem,
+                             fe * d * c.elem, E, hipMemcpyDeviceToDevice, c.stream));
+  } else {
+    const size_t f = m.ffn_dim;
+    load_matrix(c, L.w_gate_up, half * f * d, src, f * d);
+  }
 }
 
 void engine_init(rollout_ctx& c, const rollout_weights& w) {
@@ -72,74 +159,15 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
 
   // ---- weights ----
   const size_t d = m.hidden;
-  c.embed.alloc((size_t)m.vocab * d * c.elem);
-  load_matrix(c, c.embed, 0, w.embed, (size_t)m.vocab * d, "embed");
-  if (c.simple) {
-    c.lm_head.alloc((size_t)m.vocab * d * c.elem);
-    load_matrix(c, c.lm_head, 0, w.lm_head, (size_t)m.vocab * d, "lm_head");
-  } else {
-    c.lm_head_p.alloc((size_t)m.vocab * d * 2);
-    launch_pack_weight(w.lm_head, c.lm_head_p.p, m.vocab, (int)d, 0, 1, c.stream);
-  }
-  load_gain(c, c.final_norm, w.final_norm, "final_norm");
-  c.layers.resize(m.n_layers);
+  alloc_weights(c);
+  engine_load_tensor(c, -1, ROLLOUT_W_EMBED, w.embed);
+  engine_load_tensor(c, -1, ROLLOUT_W_LM_HEAD, w.lm_head);
+  engine_load_tensor(c, -1, ROLLOUT_W_FINAL_NORM, w.final_norm);
   for (int l = 0; l < m.n_layers; ++l) {
     const rollout_layer_weights& s = w.layers[l];
-    LayerWeights& L = c.layers[l];
-    load_gain(c, L.norm1, s.norm1, "norm1");
-    load_gain(c, L.norm2, s.norm2, "norm2");
-    if (!c.simple) {
-      if (!s.wq || !s.wk || !s.wv || !s.wo || !s.w_gate || !s.w_up || !s.w_down || (moe && !s.router))
-        fail(ROLLOUT_E_INVAL, "null weight pointer in a layer");
-      // MoE: the experts' matrices are stacked, [E * Fe][hidden] and [E * hidden][Fe]; Fe is a
-      // multiple of 16, so the stacked gate/up column tiles still alternate inside every expert
-      const int f = moe ? m.n_experts * m.expert_ffn_dim : m.ffn_dim;
-      const int down_rows = moe ? m.n_experts * (int)d : (int)d;
-      const int down_k = moe ? m.expert_ffn_dim : m.ffn_dim;
-      if (moe) {
-        L.router_p.alloc((size_t)m.n_experts * d * 2);
-        launch_pack_weight(s.router, L.router_p.p, m.n_experts, (int)d, 0, 1, c.stream);
-      }
-      L.wqkv_p.alloc((size_t)c.qkv_dim * d * 2);
-      launch_pack_weight(s.wq, L.wqkv_p.p, c.q_dim, (int)d, 0, 1, c.stream);
-      launch_pack_weight(s.wk, L.wqkv_p.p, c.kv_dim, (int)d, c.q_dim / 16, 1, c.stream);
-      launch_pack_weight(s.wv, L.wqkv_p.p, c.kv_dim, (int)d, (c.q_dim + c.kv_dim) / 16, 1, c.stream);
-      L.wo_p.alloc(d * c.q_dim * 2);
-      launch_pack_weight(s.wo, L.wo_p.p, (int)d, c.q_dim, 0, 1, c.stream);
-      L.w_gate_up_p.alloc((size_t)2 * f * d * 2);
-      launch_pack_weight(s.w_gate, L.w_gate_up_p.p, f, (int)d, 0, 2, c.stream);
-      launch_pack_weight(s.w_up, L.w_gate_up_p.p, f, (int)d, 1, 2, c.stream);
-      L.w_down_p.alloc((size_t)down_rows * down_k * 2);
-      launch_pack_weight(s.w_down, L.w_down_p.p, down_rows, down_k, 0, 1, c.stream);
-      continue;
-    }
-    L.wqkv.alloc((size_t)c.qkv_dim * d * c.elem);
-    load_matrix(c, L.wqkv, 0, s.wq, (size_t)c.q_dim * d, "wq");
-    load_matrix(c, L.wqkv, (size_t)c.q_dim * d, s.wk, (size_t)c.kv_dim * d, "wk");
-    load_matrix(c, L.wqkv, (size_t)(c.q_dim + c.kv_dim) * d, s.wv, (size_t)c.kv_dim * d, "wv");
-    L.wo.alloc(d * c.q_dim * c.elem);
-    load_matrix(c, L.wo, 0, s.wo, d * c.q_dim, "wo");
-    if (!s.w_gate || !s.w_up || !s.w_down) fail(ROLLOUT_E_INVAL, "null weight pointer: feed-forward");
-    if (moe) {
-      const size_t fe = m.expert_ffn_dim, E = m.n_experts;
-      L.router.alloc(E * d * c.elem);
-      load_matrix(c, L.router, 0, s.router, E * d, "router");
-      L.w_gate_up.alloc(E * 2 * fe * d * c.elem);
-      // per expert: gate rows then up rows
-      HIP_TRY(hipMemcpy2DAsync(L.w_gate_up.p, 2 * fe * d * c.elem, s.w_gate, fe * d * c.elem, fe * d * c.elem, E,
-                               hipMemcpyDeviceToDevice, c.stream));
-      HIP_TRY(hipMemcpy2DAsync(L.w_gate_up.p + fe * d * c.elem, 2 * fe * d * c.elem, s.w_up, fe * d * c.elem,
-                               fe * d * c.elem, E, hipMemcpyDeviceToDevice, c.stream));
-      L.w_down.alloc(E * d * fe * c.elem);
-      load_matrix(c, L.w_down, 0, s.w_down, E * d * fe, "w_down");
-    } else {
-      const size_t f = m.ffn_dim;
-      L.w_gate_up.alloc(2 * f * d * c.elem);
-      load_matrix(c, L.w_gate_up, 0, s.w_gate, f * d, "w_gate");
-      load_matrix(c, L.w_gate_up, f * d, s.w_up, f * d, "w_up");
-      L.w_down.alloc(d * f * c.elem);
-      load_matrix(c, L.w_down, 0, s.w_down, d * f, "w_down");
-    }
+    const void* src[] = {s.norm1, s.wq, s.wk, s.wv, s.wo, s.norm2, s.w_gate, s.w_up, s.w_down};
+    for (int t = 0; t < 9; ++t) engine_load_tensor(c, l, ROLLOUT_W_NORM1 + t, src[t]);
+    if (moe) engine_load_tensor(c, l, ROLLOUT_W_ROUTER, s.router);
   }
 
   // ---- rotary table: cos/sin of pos * theta^(-2i/dh), computed in double ----
