@@ -16,6 +16,11 @@ ones:
                weights = softmax of the selected r; output = sum of weight * expert FFN
   logits       W_lm RMSNorm(x)
 
+and, where the shape says so, what tells the named families apart in their public
+definitions: a bias on the q, k and v projections (Qwen2.5), an RMSNorm over head_dim on
+every q and k head before RoPE with gains q_norm, k_norm (Qwen3), logits through the
+embedding matrix instead of a separate W_lm (the small Qwen2.5 models).
+
 Two independent evaluations are kept: `forward_full` recomputes a whole sequence from
 scratch with an explicit causal mask (the brute-force definition), and `KVForward`
 processes rows incrementally against per-sequence key/value caches (what prefill followed
@@ -90,9 +95,14 @@ class Model:
     def qkv(self, layer: int, x: np.ndarray, pos: np.ndarray):
         s, p = self.shape, f"layers.{layer}."
         h = rmsnorm(x, self.w(p + "norm1"), s.rms_eps)
-        q = (h @ self.w(p + "wq").T).reshape(len(x), s.n_q_heads, s.head_dim)
-        k = (h @ self.w(p + "wk").T).reshape(len(x), s.n_kv_heads, s.head_dim)
-        v = (h @ self.w(p + "wv").T).reshape(len(x), s.n_kv_heads, s.head_dim)
+        q, k, v = h @ self.w(p + "wq").T, h @ self.w(p + "wk").T, h @ self.w(p + "wv").T
+        if getattr(s, "qkv_bias", False):
+            q, k, v = q + self.w(p + "bq"), k + self.w(p + "bk"), v + self.w(p + "bv")
+        q = q.reshape(len(x), s.n_q_heads, s.head_dim)
+        k = k.reshape(len(x), s.n_kv_heads, s.head_dim)
+        v = v.reshape(len(x), s.n_kv_heads, s.head_dim)
+        if getattr(s, "qk_norm", False):  # per head, over head_dim
+            q, k = rmsnorm(q, self.w(p + "q_norm"), s.rms_eps), rmsnorm(k, self.w(p + "k_norm"), s.rms_eps)
         return rope(q, pos, s.rope_theta), rope(k, pos, s.rope_theta), v
 
     def ffn(self, layer: int, h: np.ndarray) -> np.ndarray:
@@ -122,7 +132,8 @@ class Model:
         return x + self.ffn(layer, rmsnorm(x, self.w(p + "norm2"), s.rms_eps))
 
     def logits(self, x: np.ndarray) -> np.ndarray:
-        return rmsnorm(x, self.w("final_norm"), self.shape.rms_eps) @ self.w("lm_head").T
+        head = "embed" if getattr(self.shape, "tied_lm_head", False) else "lm_head"
+        return rmsnorm(x, self.w("final_norm"), self.shape.rms_eps) @ self.w(head).T
 
 
 # ----------------------------------------------------------------------------------------

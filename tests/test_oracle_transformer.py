@@ -104,9 +104,14 @@ def torch_forward(shape, w, tokens):
     for i in range(shape.n_layers):
         p = f"layers.{i}."
         h = F.rms_norm(x, (shape.hidden,), tw[p + "norm1"], eps=shape.rms_eps)
-        q = rope(F.linear(h, tw[p + "wq"]).view(n, shape.n_q_heads, dh))
-        k = rope(F.linear(h, tw[p + "wk"]).view(n, shape.n_kv_heads, dh))
-        v = F.linear(h, tw[p + "wv"]).view(n, shape.n_kv_heads, dh)
+        bias = (lambda b: tw[p + b]) if shape.qkv_bias else (lambda b: None)
+        q = F.linear(h, tw[p + "wq"], bias("bq")).view(n, shape.n_q_heads, dh)
+        k = F.linear(h, tw[p + "wk"], bias("bk")).view(n, shape.n_kv_heads, dh)
+        v = F.linear(h, tw[p + "wv"], bias("bv")).view(n, shape.n_kv_heads, dh)
+        if shape.qk_norm:
+            q = F.rms_norm(q, (dh,), tw[p + "q_norm"], eps=shape.rms_eps)
+            k = F.rms_norm(k, (dh,), tw[p + "k_norm"], eps=shape.rms_eps)
+        q, k = rope(q), rope(k)
         o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
                                            v.transpose(0, 1)[None], is_causal=True,
                                            enable_gqa=True)[0].transpose(0, 1).reshape(n, -1)
@@ -115,16 +120,58 @@ def torch_forward(shape, w, tokens):
         x = x + F.linear(F.silu(F.linear(h, tw[p + "w_gate"])) * F.linear(h, tw[p + "w_up"]),
                          tw[p + "w_down"])
     return F.linear(F.rms_norm(x, (shape.hidden,), tw["final_norm"], eps=shape.rms_eps),
-                    tw["lm_head"]).numpy()
+                    tw["embed" if shape.tied_lm_head else "lm_head"]).numpy()
 
 
-def test_forward_full_matches_library_composition():
-    m = make(NANO)
-    tokens = np.random.default_rng(3).integers(0, NANO.vocab, 11)
-    ref = torch_forward(NANO, m._w, tokens)
+FAMILY_VARIANTS = {"plain": {}, "qkv-bias": dict(qkv_bias=True), "qk-norm": dict(qk_norm=True),
+                   "tied": dict(tied_lm_head=True), "all": dict(qkv_bias=True, qk_norm=True, tied_lm_head=True)}
+
+
+@pytest.mark.parametrize("variant", list(FAMILY_VARIANTS))
+def test_forward_full_matches_library_composition(variant):
+    shape = dataclasses.replace(NANO, **FAMILY_VARIANTS[variant])
+    m = make(shape)
+    tokens = np.random.default_rng(3).integers(0, shape.vocab, 11)
+    ref = torch_forward(shape, m._w, tokens)
     got = T.forward_full(m, tokens)
     assert np.std(ref) > 0.05
     assert np.allclose(got, ref, atol=1e-12)
+    if variant not in ("plain", "tied"):   # the option changes the function: it is not silently ignored
+        base = T.forward_full(T.Model(dataclasses.replace(NANO, tied_lm_head=shape.tied_lm_head), m._w), tokens)
+        assert np.max(np.abs(base - got)) > 1e-3
+
+
+def test_family_options_closed_forms():
+    """Zero projection matrices leave q = bq, k = bk, v = bv: every position attends uniformly
+    (all scores equal after the rotation only if bk = 0, so take bk = 0) and the attention
+    output is bv for every head; QK-norm makes the scores invariant to the scale of wq and wk;
+    with a tied head and an identity final norm the logits of a one-hot-free state are x . E^T."""
+    shape = dataclasses.replace(NANO, n_layers=1, qkv_bias=True)
+    w = workloads.make_weights(shape, 5)
+    for k in ("wq", "wk", "wv"):
+        w["layers.0." + k][:] = 0
+    w["layers.0.bk"][:] = 0
+    m = T.Model(shape, w)
+    x = np.random.default_rng(1).standard_normal((5, shape.hidden))
+    q, k, v = m.qkv(0, x, np.arange(5))
+    assert np.allclose(k, 0) and np.allclose(v.reshape(5, -1), w["layers.0.bv"].astype(np.float64))
+    assert np.allclose(np.linalg.norm(q.reshape(5, -1), axis=1), np.linalg.norm(w["layers.0.bq"].astype(np.float64)))
+    shape = dataclasses.replace(NANO, qk_norm=True)
+    m1 = make(shape)
+    w2 = {k: v.copy() for k, v in m1._w.items()}
+    for i in range(shape.n_layers):
+        w2[f"layers.{i}.wq"] *= np.float32(4.0)      # exact in fp32: logits must not move
+        w2[f"layers.{i}.wk"] *= np.float32(0.25)
+    tokens = np.random.default_rng(2).integers(0, shape.vocab, 9)
+    shape0 = dataclasses.replace(shape, rms_eps=0.0)
+    a, b = T.forward_full(T.Model(shape0, m1._w), tokens), T.forward_full(T.Model(shape0, w2), tokens)
+    assert np.allclose(a, b, atol=1e-9)
+    shape = dataclasses.replace(NANO, tied_lm_head=True)
+    m = make(shape)
+    assert "lm_head" not in m._w
+    x = np.random.default_rng(3).standard_normal((4, shape.hidden))
+    want = T.rmsnorm(x, m.w("final_norm"), shape.rms_eps) @ m.w("embed").T
+    assert np.allclose(m.logits(x), want, atol=1e-13)
 
 
 def test_hand_worked_single_layer_example():
@@ -200,6 +247,30 @@ def test_shared_prefix_fork_equals_independent_runs():
         ref = T.forward_full(m, np.concatenate([prompt, tail]))[7:]
         assert np.allclose(got, ref, atol=1e-12, rtol=0)
     assert prefix.length == 7 and prefix.k[0].shape[0] == 7          # forks left the prefix alone
+
+
+@pytest.mark.parametrize("shape", [NANO, NANO_MOE], ids=["dense", "moe"])
+def test_multi_turn_growth_equals_full_recompute(shape):
+    """The multi-turn pattern - prefill, single-token steps, a block of several tokens appended to
+    the grown cache, single-token steps again, two caches of different lengths side by side -
+    gives the logits of one full forward over the concatenated sequence."""
+    m = make(shape, scale=8.0)
+    rng = np.random.default_rng(11)
+    seqs = [rng.integers(0, shape.vocab, n) for n in (17, 12)]
+    cuts = [(5, 7, 13), (3, 4, 10)]          # prefill | steps | block | steps
+    fwd = T.KVForward(m)
+    caches = [fwd.new_cache(), fwd.new_cache()]
+    got = [list(o) for o in fwd.extend(caches, [s[:c[0]] for s, c in zip(seqs, cuts)])]
+    for i, (s, c) in enumerate(zip(seqs, cuts)):
+        for t in range(c[0], c[1]):
+            got[i].append(fwd.extend([caches[i]], [[s[t]]])[0][0])
+    for i, o in enumerate(fwd.extend(caches, [s[c[1]:c[2]] for s, c in zip(seqs, cuts)])):
+        got[i].extend(o)
+    for i, (s, c) in enumerate(zip(seqs, cuts)):
+        for t in range(c[2], len(s)):
+            got[i].append(fwd.extend([caches[i]], [[s[t]]])[0][0])
+    for s, g in zip(seqs, got):
+        assert np.allclose(np.stack(g), T.forward_full(m, s), atol=1e-12, rtol=0)
 
 
 def test_gqa_reduces_to_mha_with_duplicated_kv_heads():

@@ -37,6 +37,10 @@ class ModelShape:
     expert_ffn_dim: int = 0
     rms_eps: float = 1e-6
     rope_theta: float = 1e6
+    # what distinguishes the named model families (all off in the benchmark configurations)
+    qkv_bias: bool = False      # q, k, v projections add a bias
+    qk_norm: bool = False       # RMSNorm over head_dim on every q and k head, before the rotary embedding
+    tied_lm_head: bool = False  # logits = h . embed^T, no separate lm_head
 
     @property
     def is_moe(self) -> bool:
@@ -94,7 +98,7 @@ def bf16_bits(a: np.ndarray) -> np.ndarray:
 # weights
 # ----------------------------------------------------------------------------------------
 def weight_layout(shape: ModelShape) -> list[tuple[str, tuple[int, ...], str]]:
-    """(name, dims, kind) of every tensor in checkpoint order; kind is 'matrix' or 'gain'.
+    """(name, dims, kind) of every tensor in checkpoint order; kind is 'matrix', 'gain' or 'bias'.
 
     Matrices are row-major [out_features][in_features]; a projection is y = W x.
     """
@@ -105,6 +109,10 @@ def weight_layout(shape: ModelShape) -> list[tuple[str, tuple[int, ...], str]]:
         out += [(p + "norm1", (d,), "gain"), (p + "wq", (qd, d), "matrix"),
                 (p + "wk", (kd, d), "matrix"), (p + "wv", (kd, d), "matrix"),
                 (p + "wo", (d, qd), "matrix"), (p + "norm2", (d,), "gain")]
+        if shape.qkv_bias:
+            out += [(p + "bq", (qd,), "bias"), (p + "bk", (kd,), "bias"), (p + "bv", (kd,), "bias")]
+        if shape.qk_norm:
+            out += [(p + "q_norm", (shape.head_dim,), "gain"), (p + "k_norm", (shape.head_dim,), "gain")]
         if shape.is_moe:
             e, fe = shape.n_experts, shape.expert_ffn_dim
             out += [(p + "router", (e, d), "matrix"), (p + "experts.w_gate", (e, fe, d), "matrix"),
@@ -114,7 +122,9 @@ def weight_layout(shape: ModelShape) -> list[tuple[str, tuple[int, ...], str]]:
             f = shape.ffn_dim
             out += [(p + "w_gate", (f, d), "matrix"), (p + "w_up", (f, d), "matrix"),
                     (p + "w_down", (d, f), "matrix")]
-    out += [("final_norm", (d,), "gain"), ("lm_head", (shape.vocab, d), "matrix")]
+    out += [("final_norm", (d,), "gain")]
+    if not shape.tied_lm_head:
+        out += [("lm_head", (shape.vocab, d), "matrix")]
     return out
 
 
@@ -122,7 +132,7 @@ def make_weights(shape: ModelShape, seed: int, gains: str = "varied",
                  threads: int | None = None) -> dict[str, np.ndarray]:
     """Random-init weights as fp32 arrays already rounded to the shape's storage type.
 
-    Matrices and embeddings are N(0, 0.02).  Norm gains are 1 + N(0, 0.1) when
+    Matrices and embeddings are N(0, 0.02), biases N(0, 0.2).  Norm gains are 1 + N(0, 0.1) when
     gains == "varied" (so that a dropped gain shows up in parity) and exactly 1 when
     gains == "ones".  Every tensor has its own stream, derived from (seed, position in
     checkpoint order), so generation can run on several threads with a fixed result.
@@ -140,7 +150,7 @@ def make_weights(shape: ModelShape, seed: int, gains: str = "varied",
                 w = (1.0 + 0.1 * rng.standard_normal(dims, dtype=np.float32)).astype(np.float32)
         else:
             w = rng.standard_normal(dims, dtype=np.float32)
-            w *= np.float32(0.02)
+            w *= np.float32(0.2 if kind == "bias" else 0.02)
         if shape.dtype == "bf16":
             w = round_to_bf16(w)
         return name, w
