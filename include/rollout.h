@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define ROLLOUT_ABI_VERSION 1
+#define ROLLOUT_ABI_VERSION 2
 
 #define ROLLOUT_OK 0
 #define ROLLOUT_E_INVAL (-1) /* bad argument or unsupported shape */
@@ -53,9 +53,17 @@ extern "C" {
 
 typedef struct rollout_ctx rollout_ctx; /* opaque; created by rollout_init, freed by rollout_destroy */
 
-/* Decoder-only transformer shape.  Operators: RMSNorm, bias-free projections, half-split
- * rotary embedding, grouped-query causal attention, SwiGLU feed-forward or (n_experts > 0)
- * a mixture of SwiGLU experts with top_k softmax routing, untied lm_head.  flags must be 0. */
+/* model flags: what tells the named model families apart in their public definitions (the
+ * paper trains Qwen2.5 dense and Qwen3 mixture-of-experts models, section 5.1) */
+#define ROLLOUT_MODEL_QKV_BIAS 1u     /* the q, k and v projections add a bias (Qwen2.5) */
+#define ROLLOUT_MODEL_QK_NORM 2u      /* RMSNorm over head_dim on every q and k head before the rotary
+                                         embedding, gains q_norm / k_norm, eps = rms_eps (Qwen3) */
+#define ROLLOUT_MODEL_TIED_LM_HEAD 4u /* logits = h . embed^T; weights.lm_head is ignored */
+
+/* Decoder-only transformer shape.  Operators: RMSNorm, projections without bias (but see the
+ * flags), half-split rotary embedding, grouped-query causal attention, SwiGLU feed-forward or
+ * (n_experts > 0) a mixture of SwiGLU experts with top_k softmax routing, lm_head.
+ * flags: ROLLOUT_MODEL_*. */
 typedef struct {
   int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
   int32_t n_experts, top_k, expert_ffn_dim; /* 0, 0, 0 = dense */
@@ -74,6 +82,8 @@ typedef struct {
   const void *norm1, *wq, *wk, *wv, *wo, *norm2;
   const void *w_gate, *w_up, *w_down;
   const void *router;
+  const void *bq, *bk, *bv;     /* ROLLOUT_MODEL_QKV_BIAS: [Hq dh], [Hkv dh], [Hkv dh]; else ignored */
+  const void *q_norm, *k_norm;  /* ROLLOUT_MODEL_QK_NORM: [head_dim] gains; else ignored */
 } rollout_layer_weights;
 
 /* embed [vocab][hidden], final_norm [hidden], lm_head [vocab][hidden]: DEVICE pointers.
@@ -255,7 +265,8 @@ int rollout_queue_get_stats(rollout_ctx *ctx, rollout_queue_stats *out);
 enum {
   ROLLOUT_W_EMBED = 0, ROLLOUT_W_FINAL_NORM = 1, ROLLOUT_W_LM_HEAD = 2,                   /* layer -1 */
   ROLLOUT_W_NORM1 = 3, ROLLOUT_W_WQ = 4, ROLLOUT_W_WK = 5, ROLLOUT_W_WV = 6, ROLLOUT_W_WO = 7,
-  ROLLOUT_W_NORM2 = 8, ROLLOUT_W_GATE = 9, ROLLOUT_W_UP = 10, ROLLOUT_W_DOWN = 11, ROLLOUT_W_ROUTER = 12
+  ROLLOUT_W_NORM2 = 8, ROLLOUT_W_GATE = 9, ROLLOUT_W_UP = 10, ROLLOUT_W_DOWN = 11, ROLLOUT_W_ROUTER = 12,
+  ROLLOUT_W_BQ = 13, ROLLOUT_W_BK = 14, ROLLOUT_W_BV = 15, ROLLOUT_W_Q_NORM = 16, ROLLOUT_W_K_NORM = 17
 };
 typedef struct {
   int32_t layer;    /* 0 .. n_layers-1, or -1 for embed / final_norm / lm_head */

@@ -34,7 +34,7 @@ class rollout_model_desc(C.Structure):
 
 class rollout_layer_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("norm1", "wq", "wk", "wv", "wo", "norm2", "w_gate", "w_up",
-                                          "w_down", "router")]
+                                          "w_down", "router", "bq", "bk", "bv", "q_norm", "k_norm")]
 
 
 class rollout_weights(C.Structure):
@@ -67,7 +67,9 @@ class rollout_tensor_update(C.Structure):
 
 
 W_IDS = {"embed": 0, "final_norm": 1, "lm_head": 2, "norm1": 3, "wq": 4, "wk": 5, "wv": 6, "wo": 7, "norm2": 8,
-         "w_gate": 9, "w_up": 10, "w_down": 11, "router": 12}
+         "w_gate": 9, "w_up": 10, "w_down": 11, "router": 12, "bq": 13, "bk": 14, "bv": 15, "q_norm": 16,
+         "k_norm": 17}
+MODEL_QKV_BIAS, MODEL_QK_NORM, MODEL_TIED_LM_HEAD = 1, 2, 4
 
 
 class rollout_kernel_stat(C.Structure):
@@ -145,7 +147,10 @@ def model_desc_from_shape(shape) -> rollout_model_desc:
     return rollout_model_desc(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                               shape.ffn_dim, shape.vocab, shape.n_experts, shape.top_k, shape.expert_ffn_dim,
                               shape.rms_eps, shape.rope_theta,
-                              DTYPE_BF16 if shape.dtype == "bf16" else DTYPE_F32, 0)
+                              DTYPE_BF16 if shape.dtype == "bf16" else DTYPE_F32,
+                              (MODEL_QKV_BIAS if getattr(shape, "qkv_bias", False) else 0) |
+                              (MODEL_QK_NORM if getattr(shape, "qk_norm", False) else 0) |
+                              (MODEL_TIED_LM_HEAD if getattr(shape, "tied_lm_head", False) else 0))
 
 
 def _to_device(a: np.ndarray, bf16: bool):
@@ -180,6 +185,12 @@ class Rollout:
             lw = layers[i]
             for f in ("norm1", "wq", "wk", "wv", "wo", "norm2"):
                 setattr(lw, f, up(p + f))
+            if getattr(shape, "qkv_bias", False):
+                for f in ("bq", "bk", "bv"):
+                    setattr(lw, f, up(p + f))
+            if getattr(shape, "qk_norm", False):
+                for f in ("q_norm", "k_norm"):
+                    setattr(lw, f, up(p + f))
             if shape.n_experts:
                 lw.router = up(p + "router")
                 for f in ("w_gate", "w_up", "w_down"):
@@ -187,7 +198,8 @@ class Rollout:
             else:
                 for f in ("w_gate", "w_up", "w_down"):
                     setattr(lw, f, up(p + f))
-        w = rollout_weights(up("embed"), up("final_norm"), up("lm_head"), layers)
+        tied = getattr(shape, "tied_lm_head", False)
+        w = rollout_weights(up("embed"), up("final_norm"), None if tied else up("lm_head"), layers)
         md = model_desc_from_shape(shape)
         rd = rollout_runtime_desc(kv_pool_bytes, page_tokens, max_live_samples, max_context, max_batch_tokens,
                                   stream, seed, flags, timing_stride)

@@ -846,15 +846,10 @@ int rollout_update_weights(rollout_ctx* ctx, int32_t n, const rollout_tensor_upd
     if (n < 0 || (n > 0 && !updates)) fail(ROLLOUT_E_INVAL, "bad arguments");
     if (!c.live.empty() || !c.queue.waiting.empty())
       fail(ROLLOUT_E_STATE, "weights cannot change while samples are live or prompts wait");
-    const rollout_model_desc& m = c.md;
     for (int i = 0; i < n; ++i) {  // the whole bucket is checked before any of it is applied
       const rollout_tensor_update& u = updates[i];
-      const bool model_level = u.tensor >= ROLLOUT_W_EMBED && u.tensor <= ROLLOUT_W_LM_HEAD;
       if (!u.data) fail(ROLLOUT_E_INVAL, "null weight pointer");
-      if (u.tensor < ROLLOUT_W_EMBED || u.tensor > ROLLOUT_W_ROUTER) fail(ROLLOUT_E_INVAL, "unknown tensor");
-      if (model_level ? u.layer != -1 : (u.layer < 0 || u.layer >= m.n_layers))
-        fail(ROLLOUT_E_INVAL, "layer out of range (model-level tensors take layer -1)");
-      if (u.tensor == ROLLOUT_W_ROUTER && !m.n_experts) fail(ROLLOUT_E_INVAL, "a dense model has no router");
+      engine_check_tensor(c, u.layer, u.tensor);
     }
     for (int i = 0; i < n; ++i) engine_load_tensor(c, updates[i].layer, updates[i].tensor, updates[i].data);
     HIP_TRY(hipStreamSynchronize(c.stream));

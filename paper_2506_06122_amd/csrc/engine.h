@@ -64,6 +64,8 @@ struct PinnedBuf {
 
 struct LayerWeights {
   DevBuf<float> norm1, norm2;
+  DevBuf<float> qkv_bias;        // [q | k | v] biases (ROLLOUT_MODEL_QKV_BIAS)
+  DevBuf<float> q_gain, k_gain;  // [head_dim] gains of the per-head q / k RMSNorm (ROLLOUT_MODEL_QK_NORM)
   DevBuf<char> wqkv;       // [(Hq + 2 Hkv) dh][hidden]
   DevBuf<char> wo;         // [hidden][Hq dh]
   DevBuf<char> w_gate_up;  // dense [2F][hidden] (gate rows, then up rows); MoE [E][2Fe][hidden]
@@ -264,3 +266,5 @@ void engine_target_logprobs(rollout_ctx& c, int n, const int* target, float inv_
 void engine_upload_page_table(rollout_ctx& c);
 // one tensor (ROLLOUT_W_*, device pointer, caller's layout) into the library's layout, on c.stream
 void engine_load_tensor(rollout_ctx& c, int layer, int which, const void* src);
+// throws E_INVAL unless this model has tensor `which` (ROLLOUT_W_*) at `layer`
+void engine_check_tensor(const rollout_ctx& c, int layer, int which);

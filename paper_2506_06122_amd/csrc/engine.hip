@@ -33,6 +33,11 @@ static void alloc_weights(rollout_ctx& c) {
   for (LayerWeights& L : c.layers) {
     L.norm1.alloc(d);
     L.norm2.alloc(d);
+    if (m.flags & ROLLOUT_MODEL_QKV_BIAS) L.qkv_bias.alloc(c.qkv_dim);
+    if (m.flags & ROLLOUT_MODEL_QK_NORM) {
+      L.q_gain.alloc(m.head_dim);
+      L.k_gain.alloc(m.head_dim);
+    }
     if (!c.simple) {
       // MoE: the experts' matrices are stacked, [E * Fe][hidden] and [E * hidden][Fe]; Fe is a
       // multiple of 16, so the stacked gate/up column tiles still alternate inside every expert
@@ -53,6 +58,22 @@ static void alloc_weights(rollout_ctx& c) {
   }
 }
 
+// Does this model have tensor `which` at `layer`?
+void engine_check_tensor(const rollout_ctx& c, int layer, int which) {
+  const rollout_model_desc& m = c.md;
+  const bool model_level = which == ROLLOUT_W_EMBED || which == ROLLOUT_W_FINAL_NORM || which == ROLLOUT_W_LM_HEAD;
+  if (which < ROLLOUT_W_EMBED || which > ROLLOUT_W_K_NORM) fail(ROLLOUT_E_INVAL, "unknown tensor");
+  if (model_level ? layer != -1 : (layer < 0 || layer >= m.n_layers))
+    fail(ROLLOUT_E_INVAL, "layer out of range (model-level tensors take layer -1)");
+  if (which == ROLLOUT_W_ROUTER && !m.n_experts) fail(ROLLOUT_E_INVAL, "a dense model has no router");
+  if (which == ROLLOUT_W_LM_HEAD && (m.flags & ROLLOUT_MODEL_TIED_LM_HEAD))
+    fail(ROLLOUT_E_INVAL, "the lm_head of this model is its embedding matrix");
+  if (which >= ROLLOUT_W_BQ && which <= ROLLOUT_W_BV && !(m.flags & ROLLOUT_MODEL_QKV_BIAS))
+    fail(ROLLOUT_E_INVAL, "this model has no q/k/v bias");
+  if (which >= ROLLOUT_W_Q_NORM && which <= ROLLOUT_W_K_NORM && !(m.flags & ROLLOUT_MODEL_QK_NORM))
+    fail(ROLLOUT_E_INVAL, "this model has no q/k norm");
+}
+
 // One tensor, given as at rollout_init (device pointer, model dtype, row-major), into the
 // library's layout: asynchronous on the context's stream.
 void engine_load_tensor(rollout_ctx& c, int layer, int which, const void* src) {
@@ -61,19 +82,28 @@ void engine_load_tensor(rollout_ctx& c, int layer, int which, const void* src) {
   const size_t d = m.hidden;
   if (!src) fail(ROLLOUT_E_INVAL, "null weight pointer");
   const bool model_level = which == ROLLOUT_W_EMBED || which == ROLLOUT_W_FINAL_NORM || which == ROLLOUT_W_LM_HEAD;
-  if (which < ROLLOUT_W_EMBED || which > ROLLOUT_W_ROUTER) fail(ROLLOUT_E_INVAL, "unknown tensor");
-  if (model_level ? layer != -1 : (layer < 0 || layer >= m.n_layers))
-    fail(ROLLOUT_E_INVAL, "layer out of range (model-level tensors take layer -1)");
-  if (which == ROLLOUT_W_ROUTER && !moe) fail(ROLLOUT_E_INVAL, "a dense model has no router");
-  if (which == ROLLOUT_W_EMBED) return load_matrix(c, c.embed, 0, src, (size_t)m.vocab * d);
+  engine_check_tensor(c, layer, which);
+  const bool tied = (m.flags & ROLLOUT_MODEL_TIED_LM_HEAD) != 0;
+  if (which == ROLLOUT_W_EMBED) {
+    load_matrix(c, c.embed, 0, src, (size_t)m.vocab * d);
+    if (!tied) return;
+    which = ROLLOUT_W_LM_HEAD;  // the embedding matrix is the logits projection as well
+  }
   if (which == ROLLOUT_W_FINAL_NORM) return load_gain(c, c.final_norm, src);
   if (which == ROLLOUT_W_LM_HEAD) {
     if (c.simple) return load_matrix(c, c.lm_head, 0, src, (size_t)m.vocab * d);
     return launch_pack_weight(src, c.lm_head_p.p, m.vocab, (int)d, 0, 1, c.stream);
   }
+  (void)model_level;
   LayerWeights& L = c.layers[layer];
   if (which == ROLLOUT_W_NORM1) return load_gain(c, L.norm1, src);
   if (which == ROLLOUT_W_NORM2) return load_gain(c, L.norm2, src);
+  if (which == ROLLOUT_W_BQ) return launch_convert_to_f32(src, m.dtype, L.qkv_bias.p, c.q_dim, c.stream);
+  if (which == ROLLOUT_W_BK) return launch_convert_to_f32(src, m.dtype, L.qkv_bias.p + c.q_dim, c.kv_dim, c.stream);
+  if (which == ROLLOUT_W_BV)
+    return launch_convert_to_f32(src, m.dtype, L.qkv_bias.p + c.q_dim + c.kv_dim, c.kv_dim, c.stream);
+  if (which == ROLLOUT_W_Q_NORM) return launch_convert_to_f32(src, m.dtype, L.q_gain.p, m.head_dim, c.stream);
+  if (which == ROLLOUT_W_K_NORM) return launch_convert_to_f32(src, m.dtype, L.k_gain.p, m.head_dim, c.stream);
   const size_t fe = m.expert_ffn_dim, E = m.n_experts;
   if (!c.simple) {
     const int f = moe ? m.n_experts * m.expert_ffn_dim : m.ffn_dim;
@@ -121,7 +151,8 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (m.head_dim < 32 || m.head_dim > 256 || m.head_dim % 32)
     fail(ROLLOUT_E_INVAL, "head_dim must be a multiple of 32 in [32, 256]");
   if (m.dtype != ROLLOUT_DTYPE_F32 && m.dtype != ROLLOUT_DTYPE_BF16) fail(ROLLOUT_E_INVAL, "unknown dtype");
-  if (m.flags) fail(ROLLOUT_E_INVAL, "model flags must be 0");
+  if (m.flags & ~(ROLLOUT_MODEL_QKV_BIAS | ROLLOUT_MODEL_QK_NORM | ROLLOUT_MODEL_TIED_LM_HEAD))
+    fail(ROLLOUT_E_INVAL, "unknown model flag");
   const bool moe = m.n_experts > 0;
   if (moe) {
     if (m.top_k < 1 || m.top_k > m.n_experts || m.top_k > 64 || m.n_experts > 256 || m.expert_ffn_dim < 1)
@@ -134,7 +165,8 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (r.max_live_samples < 1 || r.max_context < 2 || r.max_batch_tokens < 1)
     fail(ROLLOUT_E_INVAL, "max_live_samples, max_context, max_batch_tokens must be positive");
   if (r.flags & ~(ROLLOUT_RT_SIMPLE_KERNELS | ROLLOUT_RT_RECORD_ROUTING | ROLLOUT_RT_KERNEL_TIMING)) fail(ROLLOUT_E_INVAL, "unknown runtime flag");
-  if (!w.embed || !w.final_norm || !w.lm_head || !w.layers) fail(ROLLOUT_E_INVAL, "null weight pointer");
+  const bool tied = (m.flags & ROLLOUT_MODEL_TIED_LM_HEAD) != 0;
+  if (!w.embed || !w.final_norm || (!tied && !w.lm_head) || !w.layers) fail(ROLLOUT_E_INVAL, "null weight pointer");
 
   int n_dev = 0;
   if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) fail(ROLLOUT_E_HIP, "no HIP device");
@@ -161,13 +193,22 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   const size_t d = m.hidden;
   alloc_weights(c);
   engine_load_tensor(c, -1, ROLLOUT_W_EMBED, w.embed);
-  engine_load_tensor(c, -1, ROLLOUT_W_LM_HEAD, w.lm_head);
+  if (!tied) engine_load_tensor(c, -1, ROLLOUT_W_LM_HEAD, w.lm_head);
   engine_load_tensor(c, -1, ROLLOUT_W_FINAL_NORM, w.final_norm);
   for (int l = 0; l < m.n_layers; ++l) {
     const rollout_layer_weights& s = w.layers[l];
     const void* src[] = {s.norm1, s.wq, s.wk, s.wv, s.wo, s.norm2, s.w_gate, s.w_up, s.w_down};
     for (int t = 0; t < 9; ++t) engine_load_tensor(c, l, ROLLOUT_W_NORM1 + t, src[t]);
     if (moe) engine_load_tensor(c, l, ROLLOUT_W_ROUTER, s.router);
+    if (m.flags & ROLLOUT_MODEL_QKV_BIAS) {
+      engine_load_tensor(c, l, ROLLOUT_W_BQ, s.bq);
+      engine_load_tensor(c, l, ROLLOUT_W_BK, s.bk);
+      engine_load_tensor(c, l, ROLLOUT_W_BV, s.bv);
+    }
+    if (m.flags & ROLLOUT_MODEL_QK_NORM) {
+      engine_load_tensor(c, l, ROLLOUT_W_Q_NORM, s.q_norm);
+      engine_load_tensor(c, l, ROLLOUT_W_K_NORM, s.k_norm);
+    }
   }
 
   // ---- rotary table: cos/sin of pos * theta^(-2i/dh), computed in double ----
@@ -314,6 +355,8 @@ static void forward_rows_simple(rollout_ctx& c, int R) {
     LayerWeights& L = c.layers[l];
     launch_rmsnorm_f32(c.x.p, L.norm1.p, c.h.p, nullptr, R, d, m.rms_eps, s);
     launch_linear_simple<T>(c.h.p, d, (const T*)L.wqkv.p, c.qkv.p, c.qkv_dim, nullptr, 0, R, c.qkv_dim, d, s);
+    launch_qkv_bias_norm(c.qkv.p, L.qkv_bias.p, L.q_gain.p, L.k_gain.p, m.rms_eps, R, m.n_q_heads, m.n_kv_heads,
+                         m.head_dim, s);
     launch_rope_kvwrite<KT>(c.qkv.p, c.cos_sin.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
                             (KT*)c.kv_pool.p, c.geom, l, R, m.n_q_heads, s);
     launch_attention_simple<KT>(c.qkv.p, c.attn.p, c.row_pos.p, c.row_slot.p, c.d_page_table.p, c.max_pages,
@@ -568,6 +611,7 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
       qp.layer = l;
       qp.rows = R;
       qp.n_q_heads = m.n_q_heads;
+      qp.extra = QkvExtras{L.qkv_bias.p, L.q_gain.p, L.k_gain.p, m.rms_eps};
       c.timer.begin("qkv_post_kernel", (double)R * c.qkv_dim * (4 + 2), 0, s);
       launch_qkv_post(qp, s);
       c.timer.end(s);
@@ -592,13 +636,14 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
       at.qkv_planes = z;
       at.qkv_plane_stride = (long long)R * c.qkv_dim;
       at.cos_sin = c.cos_sin.p;
+      at.extra = QkvExtras{L.qkv_bias.p, L.q_gain.p, L.k_gain.p, m.rms_eps};
       const int base = R * m.n_kv_heads;
       const int n_splits = decode_attention_splits(c, base);
       at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
       at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
       at.part_o = c.attn_part_o.p;
       at.part_ml = c.attn_part_ml.p;
-      c.timer.begin("attn_decode_fused_kernel",
+      c.timer.begin(at.extra.bias || at.extra.q_gain ? "attn_decode_fused_kernel<true>" : "attn_decode_fused_kernel<false>",
                     kv_bytes + (double)R * (4.0 * z * c.qkv_dim + 4.0 * c.q_dim), c.attn_flops_this_call, s);
       launch_attention_decode_fused(at, s);
       c.timer.end(s);
@@ -722,6 +767,7 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
     at.qkv_raw = c.partial.p;
     at.qkv_planes = 1;
     at.cos_sin = c.cos_sin.p;
+    at.extra = QkvExtras{L.qkv_bias.p, L.q_gain.p, L.k_gain.p, m.rms_eps};
     const int base = R * m.n_kv_heads;
     const int n_splits = decode_attention_splits(c, base);
     at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
@@ -729,7 +775,7 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
     at.part_o = c.attn_part_o.p;
     at.part_ml = c.attn_part_ml.p;
     // every cached key and value of every live sample once (no prefix reuse), q in, out
-    c.timer.begin("attn_decode_fused_kernel",
+    c.timer.begin(at.extra.bias || at.extra.q_gain ? "attn_decode_fused_kernel<true>" : "attn_decode_fused_kernel<false>",
                   c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2 + (double)R * (4.0 * c.qkv_dim + 4.0 * c.q_dim),
                   c.attn_flops_this_call, s);
     launch_attention_decode_fused(at, s);

@@ -18,6 +18,9 @@ void launch_linear_simple(const float* a, int lda, const T* w, float* out, int l
                           int ldr, int M, int N, int K, hipStream_t s);
 
 // rotary embedding of q (in place) and k, then k and v of every row go to the row's page
+// plain path: bias and per-head RMSNorm of the fused [q | k | v] rows, in place (NULL parts are skipped)
+void launch_qkv_bias_norm(float* qkv, const float* bias, const float* q_gain, const float* k_gain, float eps,
+                          int rows, int n_q_heads, int n_kv_heads, int dh, hipStream_t s);
 template <typename KT>
 void launch_rope_kvwrite(float* qkv, const float* cos_sin, const int* row_pos, const int* row_slot,
                          const int* page_table, int max_pages, KT* kv_pool, KvGeom geom, int layer, int rows,

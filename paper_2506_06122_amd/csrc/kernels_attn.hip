@@ -143,6 +143,8 @@ __device__ inline long long out_offset(const AttnArgs& a, int b, int k) {
 // 0..pos-1 from the pages.  The new position itself is attended from LDS as a one-token
 // group, so nothing written in this launch is read back from memory.  With several KV
 // splits per (sample, KV head) the partial results go to attn_merge_fused_kernel.
+// EXTRA: the model adds a bias to q, k, v and / or normalises q and k heads (a.extra).
+template <bool EXTRA>
 __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t q_s[2][16][DH];  // hi parts, lo parts
   __shared__ __attribute__((aligned(16))) uint16_t kv_s[2][DH];
@@ -175,6 +177,7 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
         x0 += src[z * a.qkv_plane_stride + i];
         x1 += src[z * a.qkv_plane_stride + i + 64];
       }
+      if (EXTRA) qkv_extras(a.extra, (kvh * G + hc) * DH, i, a.extra.q_gain, x0, x1);  // hc: same in all 64 lanes
       u = x0 * cc - x1 * sn;
       w = x1 * cc + x0 * sn;
     }
@@ -193,6 +196,7 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
         x0 += src[z * a.qkv_plane_stride + i];
         x1 += src[z * a.qkv_plane_stride + i + 64];
       }
+      if (EXTRA) qkv_extras(a.extra, q_dim + kvh * DH, i, a.extra.k_gain, x0, x1);  // wavefront 0
       const uint16_t k0 = f32_to_f16(x0 * cc - x1 * sn).bits, k1 = f32_to_f16(x1 * cc + x0 * sn).bits;
       kv_s[0][i] = k0;
       kv_s[0][i + 64] = k1;
@@ -206,6 +210,7 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
         y0 += src[z * a.qkv_plane_stride + i];
         y1 += src[z * a.qkv_plane_stride + i + 64];
       }
+      if (EXTRA) qkv_extras(a.extra, q_dim + kv_dim + kvh * DH, i, nullptr, y0, y1);  // wavefront 1: bias only
       const uint16_t v0 = f32_to_f16(y0).bits, v1 = f32_to_f16(y1).bits;
       kv_s[1][i] = v0;
       kv_s[1][i + 64] = v1;
@@ -324,7 +329,9 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
 
 void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s) {
   if (!a.rows) return;
-  attn_decode_fused_kernel<<<dim3(a.n_splits, a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
+  const dim3 grid(a.n_splits, a.geom.n_kv_heads, a.rows);
+  if (a.extra.bias || a.extra.q_gain) attn_decode_fused_kernel<true><<<grid, 256, 0, s>>>(a);
+  else attn_decode_fused_kernel<false><<<grid, 256, 0, s>>>(a);
   if (a.n_splits > 1) attn_merge_fused_kernel<<<dim3(a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
 }
 

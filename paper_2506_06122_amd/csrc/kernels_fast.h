@@ -112,6 +112,28 @@ struct RowNormArgs {
 };
 void launch_row_norm(const RowNormArgs& a, hipStream_t s);
 
+// What some model families do to q, k, v between the projection and the rotary embedding
+// (head_dim 128 here: one wavefront holds one head as 64 rotary pairs).
+struct QkvExtras {
+  const float* bias = nullptr;    // [q | k | v] added to the projection, or NULL
+  const float* q_gain = nullptr;  // [128] gains of an RMSNorm over each q head, or NULL
+  const float* k_gain = nullptr;  // [128] the same for each k head
+  float eps = 0.f;
+};
+// x0, x1 = elements i and i + 64 of one head, all 64 lanes of the wavefront taking part:
+// adds the bias (element offset `off` of the fused row) and normalises the head.
+__device__ inline void qkv_extras(const QkvExtras& e, int off, int i, const float* gain, float& x0, float& x1) {
+  if (e.bias) {
+    x0 += e.bias[off + i];
+    x1 += e.bias[off + i + 64];
+  }
+  if (gain) {
+    const float rinv = 1.0f / sqrtf(wave_sum(x0 * x0 + x1 * x1) / 128.0f + e.eps);
+    x0 *= rinv * gain[i];
+    x1 *= rinv * gain[i + 64];
+  }
+}
+
 // Sums the split planes of the fused QKV projection, applies the rotary embedding to q and
 // k, writes q as bf16 [rows][q_dim] (and optionally as fp32 into q_f32 [rows][q_f32_ld]) and
 // stores k, v into the row's KV page (bf16, the pool's element order).
@@ -129,6 +151,7 @@ struct QkvPostArgs {
   uint16_t* kv_pool;
   KvGeom geom;
   int layer, rows, n_q_heads;
+  QkvExtras extra;
 };
 void launch_qkv_post(const QkvPostArgs& a, hipStream_t s);
 
@@ -157,6 +180,7 @@ struct AttnArgs {
   int qkv_planes;                  // >= 1
   long long qkv_plane_stride;      // floats between planes
   const float* cos_sin;
+  QkvExtras extra;                 // decode: bias / per-head norm of the new q, k, v
   uint16_t* kv_pool_w;
   // prefill: packed sequences
   const int *seq_row0, *seq_len, *seq_slot;

@@ -127,6 +127,10 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
     u = (((u + u0) + u1) + u2) + u3;
     w = (((w + w0) + w1) + w2) + w3;
   }
+  // bias and per-head norm: this launch runs with head_dim 128, a wavefront per head
+  if (a.extra.bias || a.extra.q_gain)
+    qkv_extras(a.extra, head * dh, i,
+               head < a.n_q_heads ? a.extra.q_gain : head < a.n_q_heads + g.n_kv_heads ? a.extra.k_gain : nullptr, u, w);
   if (head < a.n_q_heads + g.n_kv_heads) {
     const float* cs = a.cos_sin + (long long)pos * dh;
     float c = cs[2 * i], sn = cs[2 * i + 1];

@@ -83,6 +83,34 @@ template void launch_linear_simple<float>(const float*, int, const float*, float
 template void launch_linear_simple<bf16_t>(const float*, int, const bf16_t*, float*, int, const float*, int,
                                            int, int, int, hipStream_t);
 
+// ---------------------------------------------------------------- q/k/v bias and per-head norm
+// One wavefront per (row, head) of the fused [q | k | v] rows, in place: adds the bias, then
+// normalises q and k heads over head_dim with their gains (either part may be absent).
+__global__ void qkv_bias_norm_kernel(float* __restrict__ qkv, const float* __restrict__ bias,
+                                     const float* __restrict__ q_gain, const float* __restrict__ k_gain, float eps,
+                                     int n_q_heads, int n_kv_heads, int dh) {
+  const int r = blockIdx.x, head = blockIdx.y * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int n_heads = n_q_heads + 2 * n_kv_heads;
+  if (head >= n_heads) return;
+  float* x = qkv + ((long long)r * n_heads + head) * dh;
+  float ss = 0.f;
+  for (int i = lane; i < dh; i += 64) {
+    const float v = x[i] + (bias ? bias[head * dh + i] : 0.f);
+    x[i] = v;
+    ss += v * v;
+  }
+  const float* gain = head < n_q_heads ? q_gain : head < n_q_heads + n_kv_heads ? k_gain : nullptr;
+  if (!gain) return;
+  const float rinv = 1.0f / sqrtf(wave_sum(ss) / (float)dh + eps);
+  for (int i = lane; i < dh; i += 64) x[i] *= rinv * gain[i];
+}
+void launch_qkv_bias_norm(float* qkv, const float* bias, const float* q_gain, const float* k_gain, float eps,
+                          int rows, int n_q_heads, int n_kv_heads, int dh, hipStream_t s) {
+  if (rows && (bias || q_gain))
+    qkv_bias_norm_kernel<<<dim3(rows, ceil_div(n_q_heads + 2 * n_kv_heads, 4)), 256, 0, s>>>(
+        qkv, bias, q_gain, k_gain, eps, n_q_heads, n_kv_heads, dh);
+}
+
 // ---------------------------------------------------------------- RoPE + KV write
 // qkv row = [q heads | k heads | v heads] x head_dim.  Half-split pairing: (u_i, u_{i+dh/2})
 // rotates by pos * theta^(-2i/dh); cos_sin[pos][i] = (cos, sin) interleaved.

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in rollout.h but not exported"
     assert set(names) == set(B.SIGNATURES), "binding and header disagree on the entry points"
-    assert lib.rollout_abi_version() == 1
+    assert lib.rollout_abi_version() == 2
 
 
 def test_init_validates_and_fails_loudly_without_gpu():
@@ -47,7 +47,7 @@ def test_init_validates_and_fails_loudly_without_gpu():
     assert init(head_dim=30)[0] == B.E_INVAL
     assert init(n_q_heads=3)[0] == B.E_INVAL
     assert init(dtype=7)[0] == B.E_INVAL
-    assert init(flags=1)[0] == B.E_INVAL
+    assert init(flags=8)[0] == B.E_INVAL          # 1, 2, 4 are the model-family options
     assert init(n_experts=4, top_k=5, expert_ffn_dim=8)[0] == B.E_INVAL
     rd.page_tokens = 24
     assert init()[0] == B.E_INVAL
