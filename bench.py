@@ -205,13 +205,15 @@ def main() -> int:
     ap.add_argument("--timing-stride", type=int, default=16,
                     help="bracket kernels with HIP events on every n-th library call (0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns", "c2-refresh"], default="c2",
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns", "c2-refresh", "loss"],
+                    default="c2",
                     help="c2 = headline (1.5B shape); c3 = 7B-shape rollout; c4 = 30B-A3B-shape MoE rollout; "
                          "c5 = teacher-forced log-prob pass on the 7B shape; c2-queue = config 2's model and "
                          "length laws with 4x the prompts fed through the prompt queue into the same 256 live slots; "
                          "c2-turns = config 2's model and prompts, 4 turns of 128 response tokens with 256 appended "
                          "tokens between turns (rollout_extend); c2-refresh = all of config 2's weights replaced in "
-                         "place from device buffers, one bucket per layer (rollout_update_weights)")
+                         "place from device buffers, one bucket per layer (rollout_update_weights); loss = the "
+                         "policy-gradient objective over config 5's 512 packed sequences (rollout_policy_loss)")
     ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
     ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -237,6 +239,37 @@ def main() -> int:
         del src, dst
 
     wl = args.workload
+    if wl == "loss":
+        _, cu = workloads.packed_sequences(args.prompts or 512, 512, 8192, 1024, seed=2)
+        total = int(cu[-1])
+        g = torch.Generator(device="cuda").manual_seed(3)
+        old = -torch.rand(total, device="cuda", generator=g) * 4
+        new = old + 0.3 * torch.randn(total, device="cuda", generator=g)
+        ref = old + 0.2 * torch.randn(total, device="cuda", generator=g)
+        mask = (torch.rand(total, device="cuda", generator=g) > 0.3).to(torch.uint8)
+        rewards = np.random.default_rng(4).standard_normal(len(cu) - 1).astype(np.float32) * 15
+        run = lambda: R.rollout_policy_loss(cu, new, old, ref, mask, rewards, gamma=0.99, kl_coef=0.02)
+        for _ in range(args.warmup):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / max(args.steps, 1)
+        nbytes = total * (3 * 4 + 1 + 2 * 4 + 2 * 4)  # three log-probs and the mask in; advantages out; gradient out, scaled in place
+        print(json.dumps({"metric": "policy-loss tokens/sec on 1 MI355X", "value": total / dt, "unit": "tokens/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * dt,
+                          "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+                          "data": "synthetic",
+                          "config": {"workload": "%d packed sequences, length U{512..8192}, %d tokens; the call "
+                                     "includes its own allocations, two small uploads and the loss coming back"
+                                     % (len(cu) - 1, total)},
+                          "roofline": {"bound": "hbm", "achieved": nbytes / dt / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                       "frac": nbytes / dt / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                                       "kernel": "policy_advantage_kernel + policy_scale_kernel (whole call)"},
+                          "cpu_baseline": None}))
+        return 0
     shape = {"c2": workloads.C2_1P5B, "c3": workloads.C3_7B, "c4": workloads.C4_30B_A3B, "c5": workloads.C3_7B,
              "c2-queue": workloads.C2_1P5B, "c2-turns": workloads.C2_1P5B, "c2-refresh": workloads.C2_1P5B}[wl]
     cut = ""

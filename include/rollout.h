@@ -275,6 +275,32 @@ typedef struct {
 } rollout_tensor_update;
 int rollout_update_weights(rollout_ctx *ctx, int32_t n, const rollout_tensor_update *updates);
 
+/* ---- Policy-gradient objective ------------------------------------------------------------
+ * What the training stage does with the log-probs (paper sections 5.1 and 5.2: PPO loss whose
+ * advantage is the REINFORCE return instead of a GAE estimate, rewards clipped at 20 and
+ * advantages at 10; section 2.1: the reference model contributes a KL penalty).  Token by token,
+ * over the tokens with mask = 1 ("counted", t_1 < ... < t_L inside each sequence):
+ *   rho_j = -kl_coef (logp_old - logp_ref) at t_j (0 without logp_ref); the sequence's reward,
+ *           clipped to +-reward_clip, is added to rho_L
+ *   G_L = rho_L, G_j = rho_j + gamma G_{j+1};  A_j = clip(G_j, +-adv_clip)
+ *   r_j = exp(logp_new - logp_old);  s_j = min(r_j A_j, clip(r_j, 1 - eps_low, 1 + eps_high) A_j)
+ *   loss = -(sum of s over all counted tokens) / N, N = their number (0 when N = 0)
+ *   grad = d loss / d logp_new = -(r_j A_j) / N where the unclipped term is the minimum, else 0
+ * Tokens that are not counted get advantage 0 and gradient 0.  The paper fixes neither the
+ * discount nor the KL coefficient nor the ratio bounds: they are parameters.
+ *   cu_seqlens  HOST int32 [n_seqs+1], packed sequences;  rewards HOST float [n_seqs]
+ *   logp_new, logp_old, logp_ref (or NULL), mask (uint8)   DEVICE arrays [cu_seqlens[n_seqs]]
+ *   grad DEVICE [total];  advantages DEVICE [total] or NULL;  loss HOST float
+ * Runs on hip_stream (NULL = the null stream) and returns when the loss has arrived.  Sums are
+ * taken in a fixed order: the result does not depend on scheduling.  Errors: E_INVAL, E_HIP. */
+typedef struct {
+  float gamma, kl_coef, reward_clip, adv_clip, eps_low, eps_high;
+} rollout_loss_params;
+int rollout_policy_loss(int32_t n_seqs, const int32_t *cu_seqlens, const float *logp_new, const float *logp_old,
+                        const float *logp_ref, const uint8_t *mask, const float *rewards,
+                        const rollout_loss_params *params, void *hip_stream, float *loss, float *grad,
+                        float *advantages);
+
 /* Parity hook: copies the fp32 logits rows of the last prefill (one per prompt, prompt
  * order) or decode step (one per stepped sample, ascending id) to host `out`
  * [rows][vocab].  rows: in capacity, out count.  Errors: E_INVAL, E_STATE (none yet). */

@@ -72,6 +72,10 @@ W_IDS = {"embed": 0, "final_norm": 1, "lm_head": 2, "norm1": 3, "wq": 4, "wk": 5
 MODEL_QKV_BIAS, MODEL_QK_NORM, MODEL_TIED_LM_HEAD = 1, 2, 4
 
 
+class rollout_loss_params(C.Structure):
+    _fields_ = [(n, C.c_float) for n in ("gamma", "kl_coef", "reward_clip", "adv_clip", "eps_low", "eps_high")]
+
+
 class rollout_kernel_stat(C.Structure):
     _fields_ = [("name", C.c_char * 64), ("launches", C.c_uint64), ("ms", C.c_double), ("bytes", C.c_double),
                 ("flops", C.c_double)]
@@ -103,6 +107,8 @@ SIGNATURES = {
     "rollout_abi_version": (C.c_int, []),
     "rollout_sample": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_float, C.c_float, _P, _P, _P, _P, _P, _P]),
     "rollout_philox_words": (C.c_int, [C.c_uint64, C.c_int32, _P, _P, _P]),
+    "rollout_policy_loss": (C.c_int, [C.c_int32, _P, _P, _P, _P, _P, _P, C.POINTER(rollout_loss_params), _P,
+                                      C.POINTER(C.c_float), _P, _P]),
     "rollout_pool_create": (_P, [C.c_int32]),
     "rollout_pool_destroy": (None, [_P]),
     "rollout_pool_free_pages": (C.c_int32, [_P]),
@@ -364,6 +370,28 @@ def rollout_sample(logits, temperature, top_p, uniforms, forced=None, stream=Non
     if rc != OK:
         raise RolloutError(rc, lib.rollout_last_error(None).decode())
     return toks, lps, sums
+
+
+def rollout_policy_loss(cu_seqlens, logp_new, logp_old, logp_ref, mask, rewards, *, gamma=1.0, kl_coef=0.0,
+                        reward_clip=20.0, adv_clip=10.0, eps_low=0.2, eps_high=0.2, stream=None):
+    """Per-token arrays are torch CUDA tensors (float32; mask uint8), logp_ref may be None.
+    Returns (loss, grad, advantages) with grad and advantages as new CUDA tensors."""
+    import torch
+    lib = load_library()
+    cu, rw = _arr(cu_seqlens, np.int32), _arr(rewards, np.float32)
+    for t in (logp_new, logp_old, mask) + ((logp_ref,) if logp_ref is not None else ()):
+        assert t.is_cuda and t.is_contiguous() and len(t) == int(cu[-1])
+    assert logp_new.dtype == torch.float32 and logp_old.dtype == torch.float32 and mask.dtype == torch.uint8
+    grad, adv = torch.empty_like(logp_new), torch.empty_like(logp_new)
+    params = rollout_loss_params(gamma, kl_coef, reward_clip, adv_clip, eps_low, eps_high)
+    loss = C.c_float(0)
+    torch.cuda.synchronize()
+    rc = lib.rollout_policy_loss(len(cu) - 1, _ptr(cu), logp_new.data_ptr(), logp_old.data_ptr(),
+                                 logp_ref.data_ptr() if logp_ref is not None else None, mask.data_ptr(), _ptr(rw),
+                                 C.byref(params), stream, C.byref(loss), grad.data_ptr(), adv.data_ptr())
+    if rc != OK:
+        raise RolloutError(rc, lib.rollout_last_error(None).decode())
+    return loss.value, grad, adv
 
 
 def rollout_philox_words(seed, sample_ids, steps):

@@ -1036,6 +1036,58 @@ int rollout_sample(const float* logits, int32_t rows, int32_t vocab, float tempe
   });
 }
 
+int rollout_policy_loss(int32_t n_seqs, const int32_t* cu_seqlens, const float* logp_new, const float* logp_old,
+                        const float* logp_ref, const uint8_t* mask, const float* rewards,
+                        const rollout_loss_params* params, void* hip_stream, float* loss, float* grad,
+                        float* advantages) {
+  return guarded(nullptr, [&] {
+    if (n_seqs < 0 || !cu_seqlens || !params || !loss) fail(ROLLOUT_E_INVAL, "bad argument");
+    if (cu_seqlens[0] != 0) fail(ROLLOUT_E_INVAL, "cu_seqlens[0] must be 0");
+    for (int i = 0; i < n_seqs; ++i)
+      if (cu_seqlens[i + 1] < cu_seqlens[i]) fail(ROLLOUT_E_INVAL, "cu_seqlens must not decrease");
+    const long long total = cu_seqlens[n_seqs];
+    if (total > 0 && (!logp_new || !logp_old || !mask || !grad || !rewards)) fail(ROLLOUT_E_INVAL, "null array");
+    const rollout_loss_params& q = *params;
+    if (!(q.gamma >= 0.f) || !(q.reward_clip >= 0.f) || !(q.adv_clip >= 0.f) || !(q.eps_low >= 0.f) ||
+        !(q.eps_high >= 0.f) || !std::isfinite(q.kl_coef))
+      fail(ROLLOUT_E_INVAL, "bad loss parameters");
+    hipStream_t s = (hipStream_t)hip_stream;
+    DevBuf<int> cu;
+    DevBuf<float> rw, part, result;
+    cu.alloc(n_seqs + 1);
+    rw.alloc(std::max(n_seqs, 1));
+    part.alloc(2 * (size_t)std::max(n_seqs, 1));
+    result.alloc(2);
+    HIP_TRY(hipMemcpyAsync(cu.p, cu_seqlens, (n_seqs + 1) * sizeof(int), hipMemcpyHostToDevice, s));
+    if (n_seqs) HIP_TRY(hipMemcpyAsync(rw.p, rewards, n_seqs * sizeof(float), hipMemcpyHostToDevice, s));
+    PolicyLossArgs p{};
+    p.n_seqs = n_seqs;
+    p.total = total;
+    p.cu_seqlens = cu.p;
+    p.logp_new = logp_new;
+    p.logp_old = logp_old;
+    p.logp_ref = logp_ref;
+    p.mask = mask;
+    p.rewards = rw.p;
+    p.gamma = q.gamma;
+    p.kl_coef = q.kl_coef;
+    p.reward_clip = q.reward_clip;
+    p.adv_clip = q.adv_clip;
+    p.eps_low = q.eps_low;
+    p.eps_high = q.eps_high;
+    p.grad = grad;
+    p.advantages = advantages;
+    p.part_sum = part.p;
+    p.part_cnt = part.p + std::max(n_seqs, 1);
+    p.result = result.p;
+    launch_policy_loss(p, s);
+    float out[2];
+    HIP_TRY(hipMemcpyAsync(out, result.p, sizeof(out), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    *loss = out[0];
+  });
+}
+
 int rollout_philox_words(uint64_t seed, int32_t n, const int64_t* sample_ids, const uint32_t* steps,
                          uint32_t* words) {
   return guarded(nullptr, [&] {

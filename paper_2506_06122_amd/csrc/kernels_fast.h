@@ -191,6 +191,22 @@ struct AttnArgs {
 void launch_attention_prefill(const AttnArgs& a, hipStream_t s);
 void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s);
 
+// ---- policy-gradient objective over packed rollouts (kernels_loss.hip) ----------------------
+struct PolicyLossArgs {
+  int n_seqs;
+  long long total;            // tokens = cu_seqlens[n_seqs]
+  const int* cu_seqlens;      // [n_seqs + 1]
+  const float *logp_new, *logp_old, *logp_ref;  // [total]; logp_ref may be NULL
+  const unsigned char* mask;  // [total] 1 = the token counts
+  const float* rewards;       // [n_seqs]
+  float gamma, kl_coef, reward_clip, adv_clip, eps_low, eps_high;
+  float* grad;                // [total] d loss / d logp_new
+  float* advantages;          // [total] or NULL
+  float *part_sum, *part_cnt; // [n_seqs] scratch
+  float* result;              // [2]: loss, 1 / N
+};
+void launch_policy_loss(const PolicyLossArgs& p, hipStream_t s);
+
 // ---- mixture-of-experts block on the matrix-core path ---------------------------------------
 // Routing: sums the split planes of the router projection, picks the top_k experts of every
 // row by (logit descending, expert index ascending), mixes with the softmax over the picked
