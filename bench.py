@@ -216,6 +216,8 @@ def main() -> int:
                          "policy-gradient objective over config 5's 512 packed sequences (rollout_policy_loss)")
     ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
     ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
+    ap.add_argument("--prompt-groups", action="store_true",
+                    help="decode attention reads shared prompt pages once per group of samples (library flag)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 256 MiB read+write kernels (a known-size reference for byte counters)")
     args = ap.parse_args()
@@ -279,7 +281,7 @@ def main() -> int:
     t0 = time.perf_counter()
     weights = workloads.make_weights(shape, seed=1, gains="ones")
     print(f"# weights generated in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
-    flags = B.RT_KERNEL_TIMING if args.timing_stride > 0 else 0
+    flags = (B.RT_KERNEL_TIMING if args.timing_stride > 0 else 0) | (B.RT_PROMPT_GROUPS if args.prompt_groups else 0)
     kv_bytes_per_token = shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 2
 
     if wl == "c2-refresh":

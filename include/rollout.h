@@ -50,6 +50,9 @@ extern "C" {
 #define ROLLOUT_RT_SIMPLE_KERNELS 1u /* run every operator with the plain one-op-per-kernel path */
 #define ROLLOUT_RT_RECORD_ROUTING 2u /* MoE: keep each forward's expert choices for rollout_debug_routing */
 #define ROLLOUT_RT_KERNEL_TIMING 4u  /* bracket kernels with HIP events on sampled calls, see rollout_kernel_stats */
+#define ROLLOUT_RT_PROMPT_GROUPS 8u   /* decode steps with more than 32 live samples: up to 4 samples of a prompt attend to its
+                                         shared pages together, each key and value fragment read once for all of them (fewer
+                                         bytes, one more launch; off by default: slower at the sizes measured so far) */
 
 typedef struct rollout_ctx rollout_ctx; /* opaque; created by rollout_init, freed by rollout_destroy */
 

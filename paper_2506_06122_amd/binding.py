@@ -18,6 +18,7 @@ DTYPE_F32, DTYPE_BF16 = 0, 1
 RT_SIMPLE_KERNELS = 1
 RT_RECORD_ROUTING = 2
 RT_KERNEL_TIMING = 4
+RT_PROMPT_GROUPS = 8
 
 
 class RolloutError(RuntimeError):

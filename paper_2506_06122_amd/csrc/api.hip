@@ -146,7 +146,9 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
     }
     for (int j = 0; j < n; ++j) {
       Sample& s = fresh[(size_t)p * n + j];
-      s.id = (prompt_ids ? prompt_ids[p] : c.prompt_counter + p) * n + j;
+      s.group = prompt_ids ? prompt_ids[p] : c.prompt_counter + p;
+      s.id = s.group * n + j;
+      s.shared_len = full * T;
       s.slot = -1;
       s.prompt_len = len;
       s.n_emitted = 0;
@@ -335,17 +337,70 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
     int i = 0;
     for (auto& kv : c.live) hi[i++] = kv.second.slot;
     h2d(c.d_live.p, hi, B * sizeof(int), c.stream);
+    // Groups for the decode attention: live samples of one prompt (consecutive in id order), at
+    // least two of them and at least 64 shared positions, in chunks of GROUP_MEMBERS.
+    std::vector<int> grows, glen, gslot;  // pageable: their uploads complete before the call returns
+    c.h_row_t0.assign(B, 0);
+    c.n_groups = 0;
+    c.max_shared = 0;
+    c.shared_saved = 0;
+    c.shared_dup = 0;
+    {
+      const Sample* first = nullptr;
+      for (auto& kv : c.live) {
+        if (first && kv.second.group == first->group) c.shared_dup += first->shared_len;
+        else first = &kv.second;
+      }
+    }
+    if (!c.simple) {
+      std::vector<const Sample*> rows;
+      rows.reserve(B);
+      for (auto& kv : c.live) rows.push_back(&kv.second);
+      for (int r0 = 0; r0 < B;) {
+        int r1 = r0 + 1;
+        while (r1 < B && rows[r1]->group == rows[r0]->group && r1 - r0 < GROUP_MEMBERS) ++r1;
+        const int members = r1 - r0, len = rows[r0]->shared_len;
+        if (members >= 2 && len >= 64) {
+          for (int j = 0; j < GROUP_MEMBERS; ++j) grows.push_back(j < members ? r0 + j : -1);
+          glen.push_back(len);
+          gslot.push_back(rows[r0]->slot);
+          for (int r = r0; r < r1; ++r) c.h_row_t0[r] = len;
+          c.max_shared = std::max(c.max_shared, len);
+          c.shared_saved += (long long)(members - 1) * len;
+          ++c.n_groups;
+        }
+        r0 = r1;
+      }
+      if (c.n_groups) {
+        h2d(c.grp_rows.p, grows.data(), grows.size() * sizeof(int), c.stream);
+        h2d(c.grp_len.p, glen.data(), glen.size() * sizeof(int), c.stream);
+        h2d(c.grp_slot.p, gslot.data(), gslot.size() * sizeof(int), c.stream);
+        h2d(c.row_t0.p, c.h_row_t0.data(), B * sizeof(int), c.stream);
+      }
+    }
     c.live_dirty = false;
   }
   launch_gather_decode_rows(c.st, c.d_live.p, B, c.row_token.p, c.row_pos.p, c.row_slot.p, c.row_inv_temp.p,
                             c.row_top_p.p, c.row_sample_id.p, c.row_step.p, c.stream);
   c.decode_max_ctx = 1;
+  c.decode_max_own = 1;
   c.kv_tokens_this_call = 0;
-  for (auto& kv : c.live) {
-    const int ctx = kv.second.prompt_len + kv.second.n_emitted;
-    c.decode_max_ctx = std::max(c.decode_max_ctx, ctx);
-    c.kv_tokens_this_call += ctx;
+  {
+    int r = 0;
+    for (auto& kv : c.live) {
+      const int ctx = kv.second.prompt_len + kv.second.n_emitted;
+      c.decode_max_ctx = std::max(c.decode_max_ctx, ctx);
+      c.decode_max_own = std::max(c.decode_max_own, ctx - (r < (int)c.h_row_t0.size() ? c.h_row_t0[r] : 0));
+      c.kv_tokens_this_call += ctx;
+      ++r;
+    }
   }
+  // one read of a shared prompt per group instead of one per member (opt-in), when it saves at
+  // least a fifth of the positions
+  c.use_groups = c.n_groups > 0 && B > 32 && c.md.n_q_heads / c.md.n_kv_heads <= 8 &&
+                 (c.rd.flags & ROLLOUT_RT_PROMPT_GROUPS) &&
+                 (double)c.shared_saved >= 0.2 * c.kv_tokens_this_call;
+  c.kv_unique_tokens_this_call = c.kv_tokens_this_call - (double)c.shared_dup;
   c.attn_flops_this_call = 4.0 * c.kv_tokens_this_call * c.q_dim;
   c.timer.start_call();
   engine_forward_rows(c, B, nullptr);

@@ -152,6 +152,8 @@ struct Sample {
   int slot;
   int prompt_len, n_emitted, max_new, eos_id;  // prompt_len: every cached token that is not a response token
   int last_token = -1;                         // the response token emitted last (not cached yet)
+  int64_t group = -1;                          // the prompt's counter: samples of one prompt share its full pages
+  int shared_len = 0;                          // positions held in those shared pages (a multiple of page_tokens)
   std::vector<int32_t> pages;  // one reference held on each
 };
 
@@ -228,6 +230,15 @@ struct rollout_ctx {
   int partial_ld = 0;
   int attn_max_parts = 0;       // capacity of attn_part_* in (row, kv head, split) triples
   int decode_max_ctx = 0;       // longest context among the rows of the current decode step
+  // decode attention with shared prompts: groups of up to 8 live samples of one prompt
+  DevBuf<int> grp_rows, grp_len, grp_slot, row_t0;
+  std::vector<int> h_row_t0;    // per live row (ascending id): start of its own range, 0 = not grouped
+  int n_groups = 0, max_shared = 0;
+  long long shared_saved = 0;   // positions that grouping reads once instead of once per member
+  long long shared_dup = 0;     // positions cached once but attended by several live samples, counted per extra sample
+  bool use_groups = false;      // this decode step attends shared prompts by group
+  int decode_max_own = 0;       // longest own range (context - row_t0) among the rows
+  double kv_unique_tokens_this_call = 0;  // cached positions counted once per group where pages are shared
   double kv_tokens_this_call = 0;   // cached positions attended by the current forward (for timing records)
   double attn_flops_this_call = 0;
   DevBuf<int> seq_row0, seq_len, seq_slot, seq_pos0;

@@ -164,7 +164,9 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (r.page_tokens < 32 || r.page_tokens % 32) fail(ROLLOUT_E_INVAL, "page_tokens must be a positive multiple of 32");
   if (r.max_live_samples < 1 || r.max_context < 2 || r.max_batch_tokens < 1)
     fail(ROLLOUT_E_INVAL, "max_live_samples, max_context, max_batch_tokens must be positive");
-  if (r.flags & ~(ROLLOUT_RT_SIMPLE_KERNELS | ROLLOUT_RT_RECORD_ROUTING | ROLLOUT_RT_KERNEL_TIMING)) fail(ROLLOUT_E_INVAL, "unknown runtime flag");
+  if (r.flags & ~(ROLLOUT_RT_SIMPLE_KERNELS | ROLLOUT_RT_RECORD_ROUTING | ROLLOUT_RT_KERNEL_TIMING |
+                  ROLLOUT_RT_PROMPT_GROUPS))
+    fail(ROLLOUT_E_INVAL, "unknown runtime flag");
   const bool tied = (m.flags & ROLLOUT_MODEL_TIED_LM_HEAD) != 0;
   if (!w.embed || !w.final_norm || (!tied && !w.lm_head) || !w.layers) fail(ROLLOUT_E_INVAL, "null weight pointer");
 
@@ -288,7 +290,11 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     c.partial_ld = std::max({c.qkv_dim, (int)d, moe ? m.n_experts : 0});
     c.partial_rows = std::max<long long>(R, 2048);
     c.partial.alloc((size_t)c.partial_rows * c.partial_ld);
-    c.attn_max_parts = std::max(r.max_live_samples * m.n_kv_heads, 1024);
+    c.attn_max_parts = std::max(8 * r.max_live_samples * m.n_kv_heads, 1024);
+    c.grp_rows.alloc(8 * (size_t)r.max_live_samples);
+    c.grp_len.alloc(r.max_live_samples);
+    c.grp_slot.alloc(r.max_live_samples);
+    c.row_t0.alloc(r.max_live_samples);
     c.attn_part_o.alloc((size_t)c.attn_max_parts * 16 * 128);
     c.attn_part_ml.alloc((size_t)c.attn_max_parts * 32);
     c.ssq.alloc((size_t)(d / 16 + 1) * 256);
@@ -592,7 +598,8 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
     at.max_pages = c.max_pages;
     at.layer = l;
     at.n_q_heads = m.n_q_heads;
-    const double kv_bytes = c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2;
+    // algorithmic bytes: every cached position once, a prompt's shared pages once for all its samples
+    const double kv_bytes = (seqs ? c.kv_tokens_this_call : c.kv_unique_tokens_this_call) * (double)m.n_kv_heads * 128 * 2 * 2;
     if (seqs) {
       // packed sequences: sum the planes, rotate, write the KV pages, then causal attention
       QkvPostArgs qp{};
@@ -638,15 +645,42 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
       at.cos_sin = c.cos_sin.p;
       at.extra = QkvExtras{L.qkv_bias.p, L.q_gain.p, L.k_gain.p, m.rms_eps};
       const int base = R * m.n_kv_heads;
-      const int n_splits = decode_attention_splits(c, base);
-      at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
-      at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
       at.part_o = c.attn_part_o.p;
       at.part_ml = c.attn_part_ml.p;
-      c.timer.begin(at.extra.bias || at.extra.q_gain ? "attn_decode_fused_kernel<true>" : "attn_decode_fused_kernel<false>",
-                    kv_bytes + (double)R * (4.0 * z * c.qkv_dim + 4.0 * c.q_dim), c.attn_flops_this_call, s);
-      launch_attention_decode_fused(at, s);
-      c.timer.end(s);
+      const double qo_bytes = (double)R * (4.0 * z * c.qkv_dim + 4.0 * c.q_dim);
+      if (c.use_groups) {
+        // shared prompts by group, in splits of at least 128 positions that give every CU a
+        // workgroup; own ranges in splits of 1024 or more (few, long-lived workgroups: one round on the chip)
+        at.row_t0 = c.row_t0.p;
+        at.grp_rows = c.grp_rows.p;
+        at.grp_len = c.grp_len.p;
+        at.grp_slot = c.grp_slot.p;
+        at.n_groups = c.n_groups;
+        const int want_a = std::max(1, std::min(4, ceil_div(128, c.n_groups * m.n_kv_heads)));
+        at.split_tokens_a = ceil_div(ceil_div(c.max_shared, want_a), 128) * 128;
+        at.n_splits_a = ceil_div(c.max_shared, at.split_tokens_a);
+        at.slot0 = at.n_splits_a;
+        const int max_own = std::min(16 - at.slot0, std::max(1, c.attn_max_parts / base - at.slot0));
+        at.split_tokens = std::max(1024, ceil_div(ceil_div(c.decode_max_own, max_own), 128) * 128);
+        at.n_splits = ceil_div(c.decode_max_own, at.split_tokens);
+        at.n_slots = at.slot0 + at.n_splits;
+        const int G = m.n_q_heads / m.n_kv_heads;
+        static const char* const names[2][2] = {
+            {"attn_decode_grouped_kernel<1,false>", "attn_decode_grouped_kernel<1,true>"},
+            {"attn_decode_grouped_kernel<2,false>", "attn_decode_grouped_kernel<2,true>"}};
+        c.timer.begin(names[GROUP_MEMBERS * G <= 16 ? 0 : 1][at.extra.bias || at.extra.q_gain ? 1 : 0],
+                      kv_bytes + qo_bytes, c.attn_flops_this_call, s);
+        launch_attention_decode_grouped(at, s);
+        c.timer.end(s);
+      } else {
+        const int n_splits = decode_attention_splits(c, base);
+        at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
+        at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
+        c.timer.begin(at.extra.bias || at.extra.q_gain ? "attn_decode_fused_kernel<true>" : "attn_decode_fused_kernel<false>",
+                      kv_bytes + qo_bytes, c.attn_flops_this_call, s);
+        launch_attention_decode_fused(at, s);
+        c.timer.end(s);
+      }
     }
 
     z = project(c, c.attn_bf16.p, (long long)(c.attn_bf16.n / 2), c.q_dim, L.wo_p.p, R, d, c.q_dim);
@@ -774,9 +808,9 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
     at.n_splits = ceil_div(c.decode_max_ctx, at.split_tokens);
     at.part_o = c.attn_part_o.p;
     at.part_ml = c.attn_part_ml.p;
-    // every cached key and value of every live sample once (no prefix reuse), q in, out
+    // every cached key and value once (a shared prompt once for all its samples), q in, out
     c.timer.begin(at.extra.bias || at.extra.q_gain ? "attn_decode_fused_kernel<true>" : "attn_decode_fused_kernel<false>",
-                  c.kv_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2 + (double)R * (4.0 * c.qkv_dim + 4.0 * c.q_dim),
+                  c.kv_unique_tokens_this_call * (double)m.n_kv_heads * 128 * 2 * 2 + (double)R * (4.0 * c.qkv_dim + 4.0 * c.q_dim),
                   c.attn_flops_this_call, s);
     launch_attention_decode_fused(at, s);
     c.timer.end(s);

@@ -140,49 +140,146 @@ __device__ inline long long out_offset(const AttnArgs& a, int b, int k) {
 // Prologue: rotary embedding of this sample's G query rows (kept in LDS as hi + lo half-precision parts) and, in the
 // workgroup whose split holds the new position, of the new key; that key and the new value
 // are written to the sample's page and also kept in LDS.  Main loop: the cached positions
-// 0..pos-1 from the pages.  The new position itself is attended from LDS as a one-token
-// group, so nothing written in this launch is read back from memory.  With several KV
-// splits per (sample, KV head) the partial results go to attn_merge_fused_kernel.
+// t0..pos-1 from the pages (t0 = 0 unless the sample's prompt is attended by its group, below).
+// The new position itself is attended from LDS as a one-token group, so nothing written in
+// this launch is read back from memory.  With several partial results per (sample, KV head)
+// they go to attn_merge_fused_kernel.
 // EXTRA: the model adds a bias to q, k, v and / or normalises q and k heads (a.extra).
+struct DecodeSmem {
+  uint16_t* q;   // [2][q_cols][DH] hi parts, lo parts
+  int q_cols;
+  uint16_t* kv;  // [2][DH]
+  float* m;      // [4][ml_cols]
+  float* l;      // [4][ml_cols]
+  int ml_cols;
+  float* o;      // [4][16 * DH]
+};
+
+// elements p[0] and p[64] summed over the split-K planes in ascending order, four planes per
+// round of loads
+__device__ __forceinline__ void sum_planes(const AttnArgs& a, const float* p, float& x0, float& x1) {
+  x0 = 0.f;
+  x1 = 0.f;
+  for (int z = 0; z < a.qkv_planes; z += 4) {
+    const float* q = p + (long long)z * a.qkv_plane_stride;
+    const long long st = a.qkv_plane_stride;
+    const int left = a.qkv_planes - z;
+    const float u0 = q[0], w0 = q[64];
+    const float u1 = left > 1 ? q[st] : 0.f, w1 = left > 1 ? q[st + 64] : 0.f;
+    const float u2 = left > 2 ? q[2 * st] : 0.f, w2 = left > 2 ? q[2 * st + 64] : 0.f;
+    const float u3 = left > 3 ? q[3 * st] : 0.f, w3 = left > 3 ? q[3 * st + 64] : 0.f;
+    x0 = (((x0 + u0) + u1) + u2) + u3;
+    x1 = (((x1 + w0) + w1) + w2) + w3;
+  }
+}
+
+// Query staging.  Thread t of the workgroup owns the rotary pairs idx = t + 256 n, n < N:
+// column idx / 64 (the same in all 64 lanes), pair idx % 64.  rows[n] / heads[n] name the
+// sample row and the query head inside its KV group that column holds (row < 0: the column
+// is empty).  The split-K planes of the projection are summed in ascending order, two planes
+// of all N columns per round of loads, then bias / head norm, the rotary embedding, and the
+// hi + lo half-precision parts into sm.q.
+template <bool EXTRA, int N>
+__device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSmem& sm, int kvh, int G,
+                                              const int (&rows)[N], const int (&heads)[N]) {
+  const int tid = threadIdx.x, i = tid & 63;
+  const int q_dim = a.n_q_heads * DH, kv_dim = a.geom.n_kv_heads * DH;
+  const float* src[N];
+  float x0[N], x1[N];
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    const int b = max(rows[n], 0);  // empty columns read row 0 and are zeroed below
+    src[n] = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim) + (kvh * G + heads[n]) * DH + i;
+    x0[n] = 0.f;
+    x1[n] = 0.f;
+  }
+  for (int z = 0; z < a.qkv_planes; z += 2) {
+    const bool two = z + 1 < a.qkv_planes;
+    const long long o0 = (long long)z * a.qkv_plane_stride, o1 = two ? o0 + a.qkv_plane_stride : o0;
+    float u0[N], u1[N], w0[N], w1[N];
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+      u0[n] = src[n][o0];
+      u1[n] = src[n][o0 + 64];
+      w0[n] = src[n][o1];
+      w1[n] = src[n][o1 + 64];
+    }
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+      x0[n] = two ? (x0[n] + u0[n]) + w0[n] : x0[n] + u0[n];
+      x1[n] = two ? (x1[n] + u1[n]) + w1[n] : x1[n] + u1[n];
+    }
+  }
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    const int col = (tid + 256 * n) >> 6;
+    float u = 0.f, w = 0.f;
+    if (rows[n] >= 0) {  // uniform over the wavefront
+      if (EXTRA) qkv_extras(a.extra, (kvh * G + heads[n]) * DH, i, a.extra.q_gain, x0[n], x1[n]);
+      const float* cs = a.cos_sin + (long long)a.row_pos[rows[n]] * DH;
+      const float cc = cs[2 * i], sn = cs[2 * i + 1];
+      u = x0[n] * cc - x1[n] * sn;
+      w = x1[n] * cc + x0[n] * sn;
+    }
+    uint16_t* hi = sm.q + (long long)col * DH;
+    uint16_t* lo = hi + (long long)sm.q_cols * DH;
+    split_f16(u, hi[i], lo[i]);
+    split_f16(w, hi[i + 64], lo[i + 64]);
+  }
+}
+
+// the 4 wavefronts' results of 16 columns -> one (max, sum, unnormalised output) per column in
+// sm.o[0..3], sm.m, sm.l (columns ml0 ..); every thread of the workgroup calls it
+__device__ __forceinline__ void merge_wavefronts(const DecodeSmem& sm, int ml0, float m, float l, const f32x4 (&o)[8],
+                                                 int wave, int c, int g) {
+  if (g == 0) sm.m[wave * sm.ml_cols + ml0 + c] = m;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(sm.m[ml0 + c], sm.m[sm.ml_cols + ml0 + c]),
+                        fmaxf(sm.m[2 * sm.ml_cols + ml0 + c], sm.m[3 * sm.ml_cols + ml0 + c]));
+  const float M_use = (M == -INFINITY) ? 0.f : M;
+  const float w = exp2f(m - M_use);
+  if (g == 0) sm.l[wave * sm.ml_cols + ml0 + c] = l * w;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sm.o[wave * (16 * DH) + c * DH + 16 * j + 4 * g + i] = o[j][i] * w;
+  __syncthreads();
+}
+__device__ __forceinline__ float merged_max(const DecodeSmem& sm, int col) {
+  return fmaxf(fmaxf(sm.m[col], sm.m[sm.ml_cols + col]), fmaxf(sm.m[2 * sm.ml_cols + col], sm.m[3 * sm.ml_cols + col]));
+}
+__device__ __forceinline__ float merged_sum(const DecodeSmem& sm, int col) {
+  return sm.l[col] + sm.l[sm.ml_cols + col] + sm.l[2 * sm.ml_cols + col] + sm.l[3 * sm.ml_cols + col];
+}
+
+// one workgroup = (own-range split, KV head, sample)
 template <bool EXTRA>
-__global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) uint16_t q_s[2][16][DH];  // hi parts, lo parts
-  __shared__ __attribute__((aligned(16))) uint16_t kv_s[2][DH];
-  __shared__ float m_s[4][16];
-  __shared__ float l_s[4][16];
-  __shared__ float o_s[4][16 * DH];
+__device__ __forceinline__ void decode_own_range(const AttnArgs& a, const DecodeSmem& sm, int split, int kvh, int b) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane & 15, g = lane >> 4;
-  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int n_kv = a.geom.n_kv_heads;
   const int G = a.n_q_heads / n_kv;
   const int pos = a.row_pos[b];
-  const int used = pos / a.split_tokens + 1;  // splits that hold at least the new position
+  const int t0 = a.row_t0 ? a.row_t0[b] : 0;
+  const int used = (pos - t0) / a.split_tokens + 1;  // splits that hold at least the new position
   if (split >= used) return;
   const bool owner = split == used - 1;
+  const bool direct = used == 1 && t0 == 0;          // the only partial result of this (sample, KV head)
   const int slot = a.row_slot[b];
   const int q_dim = a.n_q_heads * DH, kv_dim = n_kv * DH;
   const float* row = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim);
   const float* cs = a.cos_sin + (long long)pos * DH;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
 
-  for (int idx = tid; idx < 16 * (DH / 2); idx += 256) {
-    const int hc = idx >> 6, i = idx & 63;
-    float u = 0.f, w = 0.f;
-    if (hc < G) {
-      const float* src = row + (kvh * G + hc) * DH;
-      const float cc = cs[2 * i], sn = cs[2 * i + 1];
-      float x0 = src[i], x1 = src[i + 64];
-      for (int z = 1; z < a.qkv_planes; ++z) {
-        x0 += src[z * a.qkv_plane_stride + i];
-        x1 += src[z * a.qkv_plane_stride + i + 64];
-      }
-      if (EXTRA) qkv_extras(a.extra, (kvh * G + hc) * DH, i, a.extra.q_gain, x0, x1);  // hc: same in all 64 lanes
-      u = x0 * cc - x1 * sn;
-      w = x1 * cc + x0 * sn;
+  {
+    int rows[4], heads[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      heads[n] = (tid >> 6) + 4 * n;  // column = head inside the KV group
+      rows[n] = heads[n] < G ? b : -1;
+      heads[n] = min(heads[n], G - 1);
     }
-    split_f16(u, q_s[0][hc][i], q_s[1][hc][i]);
-    split_f16(w, q_s[0][hc][i + 64], q_s[1][hc][i + 64]);
+    stage_queries<EXTRA, 4>(a, sm, kvh, G, rows, heads);
   }
   if (owner && tid < 128) {
     const int page = a.page_table[(long long)slot * a.max_pages + pos / a.geom.page_tokens];
@@ -191,29 +288,23 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
     if (tid < 64) {
       const float* src = row + q_dim + kvh * DH;
       const float cc = cs[2 * i], sn = cs[2 * i + 1];
-      float x0 = src[i], x1 = src[i + 64];
-      for (int z = 1; z < a.qkv_planes; ++z) {
-        x0 += src[z * a.qkv_plane_stride + i];
-        x1 += src[z * a.qkv_plane_stride + i + 64];
-      }
+      float x0, x1;
+      sum_planes(a, src + i, x0, x1);
       if (EXTRA) qkv_extras(a.extra, q_dim + kvh * DH, i, a.extra.k_gain, x0, x1);  // wavefront 0
       const uint16_t k0 = f32_to_f16(x0 * cc - x1 * sn).bits, k1 = f32_to_f16(x1 * cc + x0 * sn).bits;
-      kv_s[0][i] = k0;
-      kv_s[0][i + 64] = k1;
+      sm.kv[i] = k0;
+      sm.kv[i + 64] = k1;
       uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, page, kvh, 0);
       dst[kv_k_offset(a.geom, tok, i)] = k0;
       dst[kv_k_offset(a.geom, tok, i + 64)] = k1;
     } else {
       const float* src = row + q_dim + kv_dim + kvh * DH;
-      float y0 = src[i], y1 = src[i + 64];
-      for (int z = 1; z < a.qkv_planes; ++z) {
-        y0 += src[z * a.qkv_plane_stride + i];
-        y1 += src[z * a.qkv_plane_stride + i + 64];
-      }
+      float y0, y1;
+      sum_planes(a, src + i, y0, y1);
       if (EXTRA) qkv_extras(a.extra, q_dim + kv_dim + kvh * DH, i, nullptr, y0, y1);  // wavefront 1: bias only
       const uint16_t v0 = f32_to_f16(y0).bits, v1 = f32_to_f16(y1).bits;
-      kv_s[1][i] = v0;
-      kv_s[1][i + 64] = v1;
+      sm.kv[DH + i] = v0;
+      sm.kv[DH + i + 64] = v1;
       uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, page, kvh, 1);
       dst[kv_v_offset(a.geom, tok, i)] = v0;
       dst[kv_v_offset(a.geom, tok, i + 64)] = v1;
@@ -224,14 +315,14 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
   Frag q[8];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    q[ks].u = *(const uint4*)&q_s[0][c][ks * 32 + g * 8];
-    q[4 + ks].u = *(const uint4*)&q_s[1][c][ks * 32 + g * 8];
+    q[ks].u = *(const uint4*)&sm.q[c * DH + ks * 32 + g * 8];
+    q[4 + ks].u = *(const uint4*)&sm.q[(sm.q_cols + c) * DH + ks * 32 + g * 8];
   }
   float m = -INFINITY, l = 0.f;
   f32x4 o[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int t_begin = split * a.split_tokens;
+  const int t_begin = t0 + split * a.split_tokens;
   const int t_end = min(pos, t_begin + a.split_tokens);  // cached positions only
   for (int tok0 = t_begin + wave * 32; tok0 < t_end; tok0 += 128)
     attend_group(group_block(a, slot, kvh, tok0, 0), group_block(a, slot, kvh, tok0, 1), q, tok0, pos - 1,
@@ -242,66 +333,161 @@ __global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
     for (int ks = 0; ks < 4; ++ks) {
       k[0][ks].u = make_uint4(0, 0, 0, 0);
       k[1][ks].u = make_uint4(0, 0, 0, 0);
-      if (c == 0) k[0][ks].u = *(const uint4*)&kv_s[0][ks * 32 + g * 8];
+      if (c == 0) k[0][ks].u = *(const uint4*)&sm.kv[ks * 32 + g * 8];
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       v[j].u = make_uint4(0, 0, 0, 0);
-      if (g == 0) v[j].h[0] = kv_s[1][16 * j + c];
+      if (g == 0) v[j].h[0] = sm.kv[DH + 16 * j + c];
     }
     attend_frags(k, v, q, pos, pos, scale_log2, m, l, o, lane);
   }
 
-  // merge the 4 wavefronts: common max, rescale, sum
-  if (g == 0) m_s[wave][c] = m;
-  __syncthreads();
-  const float M = fmaxf(fmaxf(m_s[0][c], m_s[1][c]), fmaxf(m_s[2][c], m_s[3][c]));
-  const float M_use = (M == -INFINITY) ? 0.f : M;
-  const float w = exp2f(m - M_use);
-  if (g == 0) l_s[wave][c] = l * w;
-#pragma unroll
-  for (int j = 0; j < 8; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) o_s[wave][c * DH + 16 * j + 4 * g + i] = o[j][i] * w;
-  __syncthreads();
-  const long long pair = (long long)b * n_kv + kvh;
-  const long long part = pair * a.n_splits + split;
+  merge_wavefronts(sm, 0, m, l, o, wave, c, g);
+  const int n_slots = a.n_slots ? a.n_slots : a.n_splits;
+  const long long part = ((long long)b * n_kv + kvh) * n_slots + a.slot0 + split;
   for (int e = tid; e < G * DH; e += 256) {
     const int col = e >> 7;
-    const float acc = o_s[0][e] + o_s[1][e] + o_s[2][e] + o_s[3][e];
-    if (used == 1) {
-      const float L = l_s[0][col] + l_s[1][col] + l_s[2][col] + l_s[3][col];
-      store1_split(a.out + out_offset(a, b, kvh * G * DH + e), a.out_lo_offset, acc / (L * P_SCALE));
-    } else {
-      a.part_o[part * (16 * DH) + e] = acc;
-    }
+    const float acc = sm.o[e] + sm.o[16 * DH + e] + sm.o[2 * 16 * DH + e] + sm.o[3 * 16 * DH + e];
+    if (direct) store1_split(a.out + out_offset(a, b, kvh * G * DH + e), a.out_lo_offset, acc / (merged_sum(sm, col) * P_SCALE));
+    else a.part_o[part * (16 * DH) + e] = acc;
   }
-  if (used > 1 && tid < 16) {
-    a.part_ml[part * 32 + tid] = fmaxf(fmaxf(m_s[0][tid], m_s[1][tid]), fmaxf(m_s[2][tid], m_s[3][tid]));
-    a.part_ml[part * 32 + 16 + tid] = l_s[0][tid] + l_s[1][tid] + l_s[2][tid] + l_s[3][tid];
+  if (!direct && tid < 16) {
+    a.part_ml[part * 32 + tid] = merged_max(sm, tid);
+    a.part_ml[part * 32 + 16 + tid] = merged_sum(sm, tid);
   }
 }
 
-// Merge of the KV splits of one (sample, KV head), at most 16 of them: a launch of its own,
-// because a launch boundary is the cheapest way to publish results between workgroups here.
+template <bool EXTRA>
+__global__ __launch_bounds__(256, 3) void attn_decode_fused_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t q_s[2 * 16 * DH];
+  __shared__ __attribute__((aligned(16))) uint16_t kv_s[2 * DH];
+  __shared__ float m_s[4 * 16], l_s[4 * 16];
+  __shared__ float o_s[4 * 16 * DH];
+  decode_own_range<EXTRA>(a, DecodeSmem{q_s, 16, kv_s, m_s, l_s, 16, o_s}, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// ------------------------------------------------------------------------------ shared prompts
+// The n samples of a prompt share the prompt's full pages.  A group workgroup = (split of the
+// shared positions, KV head, up to 4 samples of one prompt): the members' query heads are the
+// columns - 4 G of them in NCT tiles of 16 - so one pass over the shared keys and values serves
+// all members, and each member's partial result lands in its own partial slot [0, slot0).
+// The same launch holds the own-range workgroups of every sample (decode_own_range from
+// row_t0 on); attn_merge_fused_kernel joins the slots.  Every shared position is visible to
+// every member (it precedes their prompts' ends), so no causal limit applies here.
+template <int NCT, bool EXTRA>
+__device__ __forceinline__ void decode_shared_range(const AttnArgs& a, const DecodeSmem& sm, int split, int kvh,
+                                                    int grp) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 15, g = lane >> 4;
+  const int n_kv = a.geom.n_kv_heads;
+  const int G = a.n_q_heads / n_kv;
+  const int len = a.grp_len[grp];
+  const int t_begin = split * a.split_tokens_a;
+  if (t_begin >= len) return;
+  const int t_end = min(len, t_begin + a.split_tokens_a);
+  const int slot = a.grp_slot[grp];
+  const int* members = a.grp_rows + grp * GROUP_MEMBERS;
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+
+  {
+    int rows[4 * NCT], heads[4 * NCT];
+#pragma unroll
+    for (int n = 0; n < 4 * NCT; ++n) {
+      const int col = (tid >> 6) + 4 * n, j = col / G;
+      rows[n] = j < GROUP_MEMBERS ? members[j] : -1;
+      heads[n] = col % G;
+    }
+    stage_queries<EXTRA, 4 * NCT>(a, sm, kvh, G, rows, heads);
+  }
+  __syncthreads();
+
+  // one pass over the range per column tile: the second pass finds the fragments in L2, and the
+  // registers stay those of a single tile (three workgroups per CU)
+  const int n_slots = a.n_slots ? a.n_slots : a.n_splits;
+#pragma unroll 1
+  for (int ct = 0; ct < NCT; ++ct) {
+    Frag q[8];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      q[ks].u = *(const uint4*)&sm.q[(ct * 16 + c) * DH + ks * 32 + g * 8];
+      q[4 + ks].u = *(const uint4*)&sm.q[(sm.q_cols + ct * 16 + c) * DH + ks * 32 + g * 8];
+    }
+    float m = -INFINITY, l = 0.f;
+    f32x4 o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int tok0 = t_begin + wave * 32; tok0 < t_end; tok0 += 128)
+      attend_group(group_block(a, slot, kvh, tok0, 0), group_block(a, slot, kvh, tok0, 1), q, tok0, 0x7fffffff,
+                   scale_log2, m, l, o, lane);
+    merge_wavefronts(sm, ct * 16, m, l, o, wave, c, g);
+    for (int e = tid; e < 16 * DH; e += 256) {
+      const int col = ct * 16 + (e >> 7);
+      const int j = col / G, hc = col % G;
+      const int b = j < GROUP_MEMBERS ? members[j] : -1;
+      if (b < 0) continue;
+      const long long part = ((long long)b * n_kv + kvh) * n_slots + split;
+      a.part_o[part * (16 * DH) + hc * DH + (e & 127)] =
+          sm.o[e] + sm.o[16 * DH + e] + sm.o[2 * 16 * DH + e] + sm.o[3 * 16 * DH + e];
+    }
+    if (tid < 16) {
+      const int col = ct * 16 + tid;
+      const int j = col / G, hc = col % G;
+      const int b = j < GROUP_MEMBERS ? members[j] : -1;
+      if (b >= 0) {
+        const long long part = ((long long)b * n_kv + kvh) * n_slots + split;
+        a.part_ml[part * 32 + hc] = merged_max(sm, col);
+        a.part_ml[part * 32 + 16 + hc] = merged_sum(sm, col);
+      }
+    }
+    __syncthreads();  // sm.o is reused by the next tile
+  }
+}
+
+// workgroups [0, n_groups * n_kv * n_splits_a) take the shared ranges, the rest the own ranges
+template <int NCT, bool EXTRA>
+__global__ __launch_bounds__(256, 3) void attn_decode_grouped_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t q_s[2 * NCT * 16 * DH];
+  __shared__ __attribute__((aligned(16))) uint16_t kv_s[2 * DH];
+  __shared__ float m_s[4 * NCT * 16], l_s[4 * NCT * 16];
+  __shared__ float o_s[4 * 16 * DH];
+  const DecodeSmem sm{q_s, NCT * 16, kv_s, m_s, l_s, NCT * 16, o_s};
+  const int n_kv = a.geom.n_kv_heads;
+  const int n_shared = a.n_groups * n_kv * a.n_splits_a;
+  int w = blockIdx.x;
+  if (w < n_shared) {
+    decode_shared_range<NCT, EXTRA>(a, sm, w % a.n_splits_a, (w / a.n_splits_a) % n_kv, w / (a.n_splits_a * n_kv));
+  } else {
+    w -= n_shared;
+    decode_own_range<EXTRA>(a, sm, w % a.n_splits, (w / a.n_splits) % n_kv, w / (a.n_splits * n_kv));
+  }
+}
+
+// Merge of the partial results of one (sample, KV head), at most 16 slots: a launch of its
+// own, because a launch boundary is the cheapest way to publish results between workgroups here.
 __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
-  __shared__ float w_s[16][16];  // [split][column] weight 2^(m_s - M) / (L 2^10)
+  __shared__ float w_s[16][16];  // [slot][column] weight 2^(m_s - M) / (L 2^10)
   const int tid = threadIdx.x, kvh = blockIdx.x, b = blockIdx.y;
   const int n_kv = a.geom.n_kv_heads;
   const int G = a.n_q_heads / n_kv;
-  const int used = a.row_pos[b] / a.split_tokens + 1;
-  if (used == 1) return;  // the attention kernel wrote the result itself
-  const long long part0 = ((long long)b * n_kv + kvh) * a.n_splits;
+  const int t0 = a.row_t0 ? a.row_t0[b] : 0;
+  const int used_shared = t0 ? (t0 + a.split_tokens_a - 1) / a.split_tokens_a : 0;
+  const int used_own = (a.row_pos[b] - t0) / a.split_tokens + 1;
+  if (used_shared == 0 && used_own == 1) return;  // the attention kernel wrote the result itself
+  const int n_slots = a.n_slots ? a.n_slots : a.n_splits;
+  const unsigned valid = ((1u << used_shared) - 1u) | (((1u << used_own) - 1u) << a.slot0);
+  const long long part0 = ((long long)b * n_kv + kvh) * n_slots;
   {
-    const int s = tid >> 4, col = tid & 15;  // 256 threads = 16 splits x 16 columns
-    const float m = s < used ? a.part_ml[(part0 + s) * 32 + col] : -INFINITY;
-    const float l = s < used ? a.part_ml[(part0 + s) * 32 + 16 + col] : 0.f;
+    const int s = tid >> 4, col = tid & 15;  // 256 threads = 16 slots x 16 columns
+    const bool on = (valid >> s) & 1u;
+    const float m = on ? a.part_ml[(part0 + s) * 32 + col] : -INFINITY;
+    const float l = on ? a.part_ml[(part0 + s) * 32 + 16 + col] : 0.f;
     w_s[s][col] = m;
     __syncthreads();
     float M = -INFINITY;
 #pragma unroll
     for (int q = 0; q < 16; ++q) M = fmaxf(M, w_s[q][col]);
-    const float w = exp2f(m - M);  // 0 for unused splits
+    const float w = exp2f(m - M);  // 0 for unused slots
     __syncthreads();
     w_s[s][col] = w;
     // total weight of the column, same order in every thread
@@ -319,7 +505,7 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
     const int col = e >> 7;
     float v[16];
 #pragma unroll
-    for (int s = 0; s < 16; ++s) v[s] = s < used ? a.part_o[(part0 + s) * (16 * DH) + e] : 0.f;
+    for (int s = 0; s < 16; ++s) v[s] = ((valid >> s) & 1u) ? a.part_o[(part0 + s) * (16 * DH) + e] : 0.f;
     float acc = 0.f;
 #pragma unroll
     for (int s = 0; s < 16; ++s) acc += v[s] * w_s[s][col];
@@ -333,6 +519,20 @@ void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s) {
   if (a.extra.bias || a.extra.q_gain) attn_decode_fused_kernel<true><<<grid, 256, 0, s>>>(a);
   else attn_decode_fused_kernel<false><<<grid, 256, 0, s>>>(a);
   if (a.n_splits > 1) attn_merge_fused_kernel<<<dim3(a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
+}
+
+template <int NCT>
+static void launch_grouped(const AttnArgs& a, unsigned grid, hipStream_t s) {
+  if (a.extra.bias || a.extra.q_gain) attn_decode_grouped_kernel<NCT, true><<<grid, 256, 0, s>>>(a);
+  else attn_decode_grouped_kernel<NCT, false><<<grid, 256, 0, s>>>(a);
+}
+void launch_attention_decode_grouped(const AttnArgs& a, hipStream_t s) {
+  if (!a.rows) return;
+  const int n_kv = a.geom.n_kv_heads, G = a.n_q_heads / n_kv;
+  const unsigned grid = (unsigned)(a.n_groups * n_kv * a.n_splits_a + a.rows * n_kv * a.n_splits);
+  if (GROUP_MEMBERS * G <= 16) launch_grouped<1>(a, grid, s);
+  else launch_grouped<2>(a, grid, s);
+  attn_merge_fused_kernel<<<dim3(n_kv, a.rows), 256, 0, s>>>(a);
 }
 
 // ------------------------------------------------------------------------------ prefill

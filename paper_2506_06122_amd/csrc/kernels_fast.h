@@ -157,6 +157,8 @@ void launch_qkv_post(const QkvPostArgs& a, hipStream_t s);
 
 void launch_f32_to_bf16(const float* src, uint16_t* dst, long long n, hipStream_t s);
 
+constexpr int GROUP_MEMBERS = 4;  // samples of one prompt that attend to its shared pages together
+
 // Paged grouped-query attention on the matrix cores (KV_MATRIX pool, head_dim 128).
 struct AttnArgs {
   const uint16_t* q;        // prefill: half-precision hi plane [rows][n_q_heads][128], rotary applied
@@ -172,8 +174,18 @@ struct AttnArgs {
   const int *row_pos, *row_slot;
   int rows;
   int n_splits, split_tokens;      // KV range per workgroup (multiple of 128)
-  float* part_o;                   // [rows][n_kv_heads][n_splits][16][128]
-  float* part_ml;                  // [rows][n_kv_heads][n_splits][2][16]
+  float* part_o;                   // [rows][n_kv_heads][n_slots][16][128]
+  float* part_ml;                  // [rows][n_kv_heads][n_slots][2][16]
+  int n_slots = 0;                 // partial results per (row, KV head); the launcher sets n_splits when 0
+  // decode with shared prompts (launch_attention_decode_grouped): the samples of one prompt
+  // attend to the prompt's shared pages together - each key and value fragment is read once
+  // for all of them - and every row attends alone only to what follows its row_t0.
+  const int* row_t0 = nullptr;     // [rows] first position of the row's own range (0 = no shared part)
+  int slot0 = 0;                   // partial slots [0, slot0) hold the shared part, [slot0, slot0 + n_splits) the own
+  const int* grp_rows = nullptr;   // [n_groups][GROUP_MEMBERS] rows of a group's members, -1 = none
+  const int* grp_len = nullptr;    // [n_groups] shared positions (a multiple of 32)
+  const int* grp_slot = nullptr;   // [n_groups] page-table row of one member
+  int n_groups = 0, n_splits_a = 0, split_tokens_a = 0;  // shared part: splits of split_tokens_a (multiple of 128)
   // decode (rotary + KV write + attention in one launch, split merge in a second)
   const float* qkv_raw;            // fp32 [planes][rows][(n_q_heads + 2 n_kv_heads) * 128], projections before
                                    // rotary, as split-K planes that the kernel sums in ascending order
@@ -190,6 +202,8 @@ struct AttnArgs {
 };
 void launch_attention_prefill(const AttnArgs& a, hipStream_t s);
 void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s);
+// the same with shared prompts; needs n_q_heads / n_kv_heads <= 8 (4 members x heads <= 32 columns)
+void launch_attention_decode_grouped(const AttnArgs& a, hipStream_t s);
 
 // ---- policy-gradient objective over packed rollouts (kernels_loss.hip) ----------------------
 struct PolicyLossArgs {
