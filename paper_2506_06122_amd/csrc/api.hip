@@ -275,6 +275,10 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
   sr.tokens = c.out_tokens.p;
   sr.logprobs = c.out_logprobs.p;
   sr.weight_sums = nullptr;
+  if (Rs <= c.samp_rows) {
+    sr.part_max = c.samp_part_max.p;
+    sr.seg_sums = c.samp_seg_sums.p;
+  }
   launch_sample(sr, Rs, m.vocab, c.stream);
   if (n_new) {
     h2d(c.row_token.p, hi + 4 * R, n_new * sizeof(int), c.stream);  // slots
@@ -428,6 +432,10 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
   sr.tokens = c.out_tokens.p;
   sr.logprobs = c.out_logprobs.p;
   c.timer.begin("sample_kernel", 4.0 * B * m.vocab, 0, c.stream);
+  if (B <= c.samp_rows) {
+    sr.part_max = c.samp_part_max.p;
+    sr.seg_sums = c.samp_seg_sums.p;
+  }
   launch_sample(sr, B, m.vocab, c.stream);
   c.timer.end(c.stream);
   launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);
@@ -590,6 +598,10 @@ static void extend_impl(rollout_ctx& c, int32_t n, const int64_t* sample_ids, co
   sr.seed = c.rd.seed;
   sr.tokens = c.out_tokens.p;
   sr.logprobs = c.out_logprobs.p;
+  if (n <= c.samp_rows) {
+    sr.part_max = c.samp_part_max.p;
+    sr.seg_sums = c.samp_seg_sums.p;
+  }
   launch_sample(sr, n, m.vocab, c.stream);
   extend_slots_kernel<<<ceil_div(n, 256), 256, 0, c.stream>>>(c.st, c.d_live.p, c.row_aux.p + R, c.out_tokens.p, n);
   d2h(hi + 3 * R, c.out_tokens.p, n * sizeof(int), c.stream);
@@ -1082,6 +1094,12 @@ int rollout_sample(const float* logits, int32_t rows, int32_t vocab, float tempe
     sr.tokens = tok.p;
     sr.logprobs = lp.p;
     sr.weight_sums = ws.p;
+    DevBuf<float> pm;
+    DevBuf<unsigned long long> sg;
+    pm.alloc((size_t)rows * kSampleParts);
+    sg.alloc((size_t)rows * kSampleSegments);
+    sr.part_max = pm.p;
+    sr.seg_sums = sg.p;
     launch_sample(sr, rows, vocab, s);
     HIP_TRY(hipMemcpyAsync(tokens, tok.p, rows * sizeof(int), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipMemcpyAsync(logprobs, lp.p, rows * sizeof(float), hipMemcpyDeviceToHost, s));

@@ -249,6 +249,9 @@ struct rollout_ctx {
   DevBuf<long long> row_sample_id;
   DevBuf<float> row_inv_temp, row_top_p, out_logprobs;
   DevBuf<unsigned> row_uniform;
+  DevBuf<float> samp_part_max;               // sampler scratch, see SampleRows
+  DevBuf<unsigned long long> samp_seg_sums;
+  int samp_rows = 0;                         // rows the sampler scratch holds
   PinnedBuf<int> h_int;      // staging, 8 * r_max ints
   PinnedBuf<float> h_float;  // staging, 4 * r_max floats
   PinnedBuf<long long> h_ll; // staging, r_max

@@ -337,6 +337,9 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   c.row_top_p.alloc(R);
   c.out_logprobs.alloc(R);
   c.row_uniform.alloc(R);
+  c.samp_rows = (int)std::min<size_t>(R, 4096);
+  c.samp_part_max.alloc((size_t)c.samp_rows * kSampleParts);
+  c.samp_seg_sums.alloc((size_t)c.samp_rows * kSampleSegments);
   c.h_int.alloc(8 * R);
   c.h_float.alloc(4 * R);
   c.h_ll.alloc(R);

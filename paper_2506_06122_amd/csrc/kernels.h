@@ -67,7 +67,12 @@ struct SampleRows {
   int* tokens;              // out [rows]
   float* logprobs;          // out [rows]
   unsigned long long* weight_sums;  // out [rows] or NULL
+  // Scratch that lets a row's two sweeps over the vocabulary run on several workgroups (the
+  // sums are integers, so the split changes nothing): both or neither.
+  float* part_max = nullptr;               // [rows][kSampleParts]
+  unsigned long long* seg_sums = nullptr;  // [rows][kSampleSegments]
 };
+constexpr int kSampleParts = 64, kSampleSegments = 1024;
 void launch_sample(const SampleRows& r, int rows, int vocab, hipStream_t s);
 void launch_philox_words(unsigned long long seed, const long long* ids, const unsigned* steps, unsigned* out,
                          int n, hipStream_t s);

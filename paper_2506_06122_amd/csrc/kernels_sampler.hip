@@ -9,6 +9,8 @@
 //   weight reaches theta = max(1, floor(S * floor(top_p 2^24) / 2^24)); R = floor(S_N x / 2^32);
 //   token = first id of the nucleus, ascending, whose running weight exceeds R.
 // Every floating-point step is a single rounded fp32 operation: no contraction allowed.
+#include <algorithm>
+
 #include "kernels.h"
 
 #pragma clang fp contract(off)
@@ -250,17 +252,17 @@ __device__ inline int resolve_in_segment(const unsigned long long (&v)[4], unsig
   return found;
 }
 
-__global__ __launch_bounds__(SAMP_T) void sample_kernel(SampleRows a, int vocab) {
+// First sweep on `parts` workgroups per row: maximum of the scaled logits over tiles
+// blockIdx.x, blockIdx.x + parts, ...
+__global__ __launch_bounds__(SAMP_T) void sample_max_kernel(SampleRows a, int vocab, int parts) {
   __shared__ SampShared sh;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = blockIdx.x;
+  const int tid = threadIdx.x, r = blockIdx.y;
   const float* row = a.logits + (long long)(a.logits_row ? a.logits_row[r] : r) * vocab;
   const float inv_t = a.inv_temp[r];
   const bool vec_ok = (vocab & 3) == 0 && (((unsigned long long)row) & 15ull) == 0;
-  const int n_seg = (vocab + 255) >> 8;
   const int n_tiles = (vocab + 4095) >> 12;
-
   float m = -INFINITY;
-  for (int t = 0; t < n_tiles; ++t) {
+  for (int t = blockIdx.x; t < n_tiles; t += parts) {
     const int i0 = t * 4096 + tid * 4;
     if (vec_ok && i0 + 3 < vocab) {
       const float4 v = *(const float4*)(row + i0);
@@ -272,15 +274,67 @@ __global__ __launch_bounds__(SAMP_T) void sample_kernel(SampleRows a, int vocab)
     }
   }
   m = block_max(m, sh);
+  if (tid == 0) a.part_max[(long long)r * kSampleParts + blockIdx.x] = m;
+}
 
-  // pass: all weights, one sum per segment
-  unsigned long long local = 0;
-  for (int t = 0; t < n_tiles; ++t) {
+// Second sweep on `parts` workgroups per row: the weights of the same tiles, one sum per
+// 256-id segment.
+__global__ __launch_bounds__(SAMP_T) void sample_segments_kernel(SampleRows a, int vocab, int parts) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = blockIdx.y;
+  const float* row = a.logits + (long long)(a.logits_row ? a.logits_row[r] : r) * vocab;
+  const float inv_t = a.inv_temp[r];
+  const bool vec_ok = (vocab & 3) == 0 && (((unsigned long long)row) & 15ull) == 0;
+  const int n_seg = (vocab + 255) >> 8;
+  const int n_tiles = (vocab + 4095) >> 12;
+  float m = -INFINITY;
+  for (int q = 0; q < parts; ++q) m = fmaxf(m, a.part_max[(long long)r * kSampleParts + q]);
+  for (int t = blockIdx.x; t < n_tiles; t += parts) {
     const Seg4 q = load_weights4(row, t * 4096 + tid * 4, vocab, vec_ok, inv_t, m);
-    const unsigned long long mine = q.w[0] + q.w[1] + q.w[2] + q.w[3];
-    local += mine;
-    const unsigned long long ws = wave_sum_u64(mine);
-    if (lane == 0 && t * 16 + wave < n_seg) sh.vals[t * 16 + wave] = ws;
+    const unsigned long long ws = wave_sum_u64(q.w[0] + q.w[1] + q.w[2] + q.w[3]);
+    if (lane == 0 && t * 16 + wave < n_seg) a.seg_sums[(long long)r * kSampleSegments + t * 16 + wave] = ws;
+  }
+}
+
+// parts = 0: this kernel sweeps the row itself; else it starts from what the two kernels above left
+__global__ __launch_bounds__(SAMP_T) void sample_kernel(SampleRows a, int vocab, int parts) {
+  __shared__ SampShared sh;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, r = blockIdx.x;
+  const float* row = a.logits + (long long)(a.logits_row ? a.logits_row[r] : r) * vocab;
+  const float inv_t = a.inv_temp[r];
+  const bool vec_ok = (vocab & 3) == 0 && (((unsigned long long)row) & 15ull) == 0;
+  const int n_seg = (vocab + 255) >> 8;
+  const int n_tiles = (vocab + 4095) >> 12;
+
+  float m = -INFINITY;
+  unsigned long long local = 0;
+  if (parts) {
+    for (int q = 0; q < parts; ++q) m = fmaxf(m, a.part_max[(long long)r * kSampleParts + q]);
+    if (tid < n_seg) {
+      local = a.seg_sums[(long long)r * kSampleSegments + tid];
+      sh.vals[tid] = local;
+    }
+  } else {
+    for (int t = 0; t < n_tiles; ++t) {
+      const int i0 = t * 4096 + tid * 4;
+      if (vec_ok && i0 + 3 < vocab) {
+        const float4 v = *(const float4*)(row + i0);
+        m = fmaxf(fmaxf(m, fmaxf(scaled_logit(v.x, inv_t), scaled_logit(v.y, inv_t))),
+                  fmaxf(scaled_logit(v.z, inv_t), scaled_logit(v.w, inv_t)));
+      } else {
+        for (int e = 0; e < 4; ++e)
+          if (i0 + e < vocab) m = fmaxf(m, scaled_logit(row[i0 + e], inv_t));
+      }
+    }
+    m = block_max(m, sh);
+
+    // pass: all weights, one sum per segment
+    for (int t = 0; t < n_tiles; ++t) {
+      const Seg4 q = load_weights4(row, t * 4096 + tid * 4, vocab, vec_ok, inv_t, m);
+      const unsigned long long mine = q.w[0] + q.w[1] + q.w[2] + q.w[3];
+      local += mine;
+      const unsigned long long ws = wave_sum_u64(mine);
+      if (lane == 0 && t * 16 + wave < n_seg) sh.vals[t * 16 + wave] = ws;
+    }
   }
   const unsigned long long S = block_sum_u64(local, sh);  // also orders the writes to sh.vals
 
@@ -376,7 +430,20 @@ __global__ __launch_bounds__(SAMP_T) void sample_kernel(SampleRows a, int vocab)
 }
 
 void launch_sample(const SampleRows& r, int rows, int vocab, hipStream_t s) {
-  if (rows) sample_kernel<<<rows, SAMP_T, 0, s>>>(r, vocab);
+  if (!rows) return;
+  // Large vocabularies with scratch at hand: the two sweeps of a row on several workgroups
+  // (about 512 in all), then the selection; else everything in one workgroup per row.
+  const int n_tiles = (vocab + 4095) >> 12;
+  int parts = 0;
+  if (r.part_max && r.seg_sums && n_tiles >= 8 && vocab <= 256 * kSampleSegments)
+    parts = std::max(2, std::min({n_tiles, kSampleParts, 512 / rows}));
+  if (parts >= 2) {
+    sample_max_kernel<<<dim3(parts, rows), SAMP_T, 0, s>>>(r, vocab, parts);
+    sample_segments_kernel<<<dim3(parts, rows), SAMP_T, 0, s>>>(r, vocab, parts);
+    sample_kernel<<<rows, SAMP_T, 0, s>>>(r, vocab, parts);
+  } else {
+    sample_kernel<<<rows, SAMP_T, 0, s>>>(r, vocab, 0);
+  }
 }
 
 // ---------------------------------------------------------------- teacher-forced gather
