@@ -134,6 +134,11 @@ def load_library() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with "
                                "`python -c 'import __graft_entry__ as g; g.build()'`")
+        try:   # torch brings its own HIP runtime: when this library starts HIP first, torch finds no GPU later
+            import torch
+            torch.cuda.is_available()
+        except ImportError:
+            pass
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(lib, name)
