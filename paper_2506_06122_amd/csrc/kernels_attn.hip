@@ -17,8 +17,12 @@
 //             the rotary embedding of the new query and key and the KV-page write ride in
 //             the prologue; its 4 wavefronts interleave over the split's 32-position groups
 //             and merge through LDS; several splits per sample merge in a second small kernel.
+//   decode, shared prompts (optional): in the same launch, workgroups of (split, KV head, up
+//             to 4 samples of one prompt) take the prompt's shared pages with the members'
+//             query heads as columns, and the per-sample workgroups start after those pages.
 //   prefill : one wavefront per (16 query positions, query head); columns = positions;
-//             causal limit per column.
+//             causal limit per column; a sequence may continue a cached context (its rows
+//             then attend to that context too).
 #include "kernels_fast.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(_Float16)))) _Float16 f16x8;

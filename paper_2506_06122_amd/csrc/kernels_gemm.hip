@@ -15,23 +15,27 @@
 // exactly, so nothing else is rounded).  That doubles the matrix instructions, which the
 // memory-bound decode step does not notice.
 //
-// Two kernels:
+// Three kernels:
 //   gemm_stream_kernel  (rows <= 32, decoding): the NW wavefronts of a workgroup share NT
 //       column tiles and interleave over the K range in chunks of KU fragments, so one
 //       workgroup walks one contiguous weight stream with NW x KU x NT KiB in flight; the
-//       partial accumulators meet in LDS.  Activations come straight from L2.  Narrow
-//       outputs (few column tiles) use wide workgroups (16 wavefronts) rather than split-K
-//       planes, so every output element is complete inside one workgroup and the epilogue
-//       can carry the neighbouring element-wise work:
+//       partial accumulators meet in LDS.  Activations come straight from L2, stored in
+//       fragment order by their producers (frag_offset, kernels_fast.h) so that an operand
+//       fragment, like a weight fragment, is whole cache lines.  Narrow outputs (few column
+//       tiles) use wide workgroups (16 wavefronts) rather than split-K planes, so every output
+//       element is complete inside one workgroup and the epilogue can carry the neighbouring
+//       element-wise work:
 //         - RMSNorm is split in two.  The producer of the residual stream (EPI_RESID) adds
 //           its result to x, stores x * gain as the next projection's operand and one
 //           partial sum of squares per (workgroup, row); the consumer sums those partials
 //           in a fixed order and scales its output rows by rsqrt(mean + eps) - a row scale
 //           commutes with the projection.  No workgroup ever waits for another.
 //         - SwiGLU on interleaved gate/up column tiles (EPI_SWIGLU_BF16).
-//   gemm_tile_kernel    (more than 32 rows: large decode batches, prefill, teacher-forced
-//       pass): 64 x 128 or 64 x 256 output tile per workgroup, activations staged through LDS
-//       in fragment order and double-buffered, weights still read directly.
+//   gemm_tile_ring_kernel (more than 32 rows, decode-sized): 64 x 128 output tile per
+//       workgroup, activations (row-major) staged through LDS in fragment order as whole cache
+//       lines, weights read directly; split-K planes when the tiles alone do not fill the chip.
+//   gemm_tile_kernel    (prefill, teacher-forced pass, lm_head of large decode batches): 64 x 256
+//       tile, the same staging, software-pipelined over a ring of register slots.
 #include <cstdio>
 
 #include "kernels_fast.h"
@@ -785,18 +789,33 @@ void launch_lse_finish(const float* lse_max, const float* lse_sum, const float* 
 }
 
 // ---------------------------------------------------------------- weight re-ordering
-// dst tile (tile_offset + nt * tile_stride) <- rows nt*16.. of src [N][K] (row-major bf16)
+// dst tile (tile_offset + nt * tile_stride) <- rows nt*16.. of src [N][K] (row-major bf16).
+// A wavefront moves 8 rows x 128 bytes - two k-tiles of half a row tile - so that both its
+// reads and its writes are whole cache lines (lane = row * 8 + chunk; chunk = k-tile * 4 +
+// column group; the 8 rows of one chunk land in 8 consecutive 16-byte slots of a fragment).
+// An odd last k-tile is moved as 16 rows x 64 bytes by the first 64 lanes' worth of pieces.
 __global__ void pack_weight_kernel(const uint16_t* __restrict__ src, uint4* __restrict__ dst, int N, int K,
                                    int tile_offset, int tile_stride) {
-  const int k_tiles = K >> 5;
-  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;  // one 16-byte piece each
-  long long total = (long long)(N >> 4) * k_tiles * 64;
-  if (idx >= total) return;
-  int lane = (int)(idx & 63);
-  long long t = idx >> 6;
-  int kt = (int)(t % k_tiles);
-  int nt = (int)(t / k_tiles);
-  int r = lane & 15, g = lane >> 4;
+  const int k_tiles = K >> 5, k_pairs = k_tiles >> 1;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;  // one 16-byte piece each
+  const long long paired = (long long)(N >> 4) * k_pairs * 128;
+  if (idx < paired) {
+    const int lane = (int)(idx & 63);
+    long long t = idx >> 6;
+    const int half = (int)(t & 1);
+    t >>= 1;
+    const int kp = (int)(t % k_pairs), nt = (int)(t / k_pairs);
+    const int r = half * 8 + (lane >> 3), chunk = lane & 7;
+    const int kt = 2 * kp + (chunk >> 2), g = chunk & 3;
+    const uint4 v = *(const uint4*)(src + (long long)(nt * 16 + r) * K + kt * 32 + g * 8);
+    dst[((long long)(tile_offset + nt * tile_stride) * k_tiles + kt) * 64 + g * 16 + r] = v;
+    return;
+  }
+  if (!(k_tiles & 1)) return;
+  const long long rest = idx - paired;  // the odd last k-tile of every row tile
+  if (rest >= (long long)(N >> 4) * 64) return;
+  const int lane = (int)(rest & 63), nt = (int)(rest >> 6), kt = k_tiles - 1;
+  const int r = lane & 15, g = lane >> 4;
   const uint4 v = *(const uint4*)(src + (long long)(nt * 16 + r) * K + kt * 32 + g * 8);
   dst[((long long)(tile_offset + nt * tile_stride) * k_tiles + kt) * 64 + lane] = v;
 }

@@ -14,6 +14,8 @@ CASES = {
     "tiny-moe-fp32": (workloads.TINY_MOE_FP32, 6.0, 2, 1e-4),
     "small-bf16": (workloads.SMALL_BF16, 1.0, 0, 2e-2),
     "small-moe-bf16": (workloads.SMALL_MOE_BF16, 1.5, 2, 2e-2),
+    # hidden = 17 and FFN = 45 fragments deep: the re-ordering kernel's odd last k-tile
+    "odd-k-tiles-bf16": (workloads.ModelShape("odd-k-bf16", 2, 544, 8, 2, 128, 1440, 2048), 1.0, 0, 2e-2),
 }
 
 
