@@ -671,12 +671,23 @@ GemmPlan gemm_plan_tiled(int M, int N, int K, int epi, int max_splits) {
   pl.nt = cfg[pick][1];
   pl.kc = 2;
   pl.splits = 1;
+  if (pick == 1 && epi == EPI_F32 && M <= 128) {
+    pl.mt = 2;
+    blocks = (long long)ceil_div(M, 32) * ceil_div(n_tiles, 8);
+  }
   if (epi == EPI_F32 && blocks < 256) {
     int z = (int)((768 + blocks - 1) / blocks);
     z = std::min(z, std::max(1, k_tiles / 8));
     pl.splits = std::max(1, std::min(z, max_splits));
   }
   pl.name = names[pick][epi == EPI_F32 ? 0 : epi == EPI_SWIGLU_BF16 ? 1 : 2];
+  // SwiGLU projection (no split-K possible) of at most 128 rows: 32-row blocks give the chip
+  // twice the workgroups - one or two 64-row blocks leave CUs idle or with one long workgroup
+  if (pick == 1 && epi == EPI_SWIGLU_BF16 && M <= 128) {
+    pl.mt = 2;
+    pl.name = "gemm_tile_ring_kernel<2,2,2,1,1>";
+  }
+  if (pick == 1 && epi == EPI_F32 && pl.mt == 2) pl.name = "gemm_tile_ring_kernel<2,2,2,1,0>";
   return pl;
 }
 
@@ -745,6 +756,8 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
     const long long units = (long long)a.grid_nx * a.grid_nz * ceil_div(a.grid_ny, gm);
     dim3 grid((unsigned)(ceil_div(units, 8) * 8 * gm));
     if (pl.nt == 4) launch_tile<4, 4, 2, 2>(a, epi, grid, s);
+    else if (pl.mt == 2 && epi == EPI_SWIGLU_BF16) gemm_tile_ring_kernel<2, 2, 2, 1, EPI_SWIGLU_BF16><<<grid, 256, 0, s>>>(a);
+    else if (pl.mt == 2 && epi == EPI_F32) gemm_tile_ring_kernel<2, 2, 2, 1, EPI_F32><<<grid, 256, 0, s>>>(a);
     else launch_tile_ring<4, 2, 2, 1>(a, epi, grid, s);
     return splits;
   }
