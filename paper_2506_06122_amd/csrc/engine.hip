@@ -722,8 +722,9 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
 // projection reads its operand directly.
 static void stream_project(rollout_ctx& c, const DevBuf<uint16_t>& a, int lda, const void* w, int M, int N, int K,
                            int epi, bool normalise_input, void* out, int ldo, long long out_lo_offset,
-                           const float* resid_gain) {
+                           const float* resid_gain, const TouchRange& touch = TouchRange{}) {
   GemmArgs g{};
+  g.touch = touch;
   g.a = a.p;
   g.a_lo = a.p + a.n / 2;
   g.w = w;
@@ -785,7 +786,19 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
   }
   for (int l = 0; l < m.n_layers; ++l) {
     LayerWeights& L = c.layers[l];
-    stream_project(c, c.h_bf16, d, L.wqkv_p.p, R, c.qkv_dim, d, EPI_F32, true, c.partial.p, c.qkv_dim, 0, nullptr);
+    // The down projection has only hidden/16 workgroups, each streaming a deep slice: it is the
+    // one projection here that gains more from finding its weights in the memory-side cache
+    // (11 -> 7 us at config 2's shape) than walking them costs the launch that hosts the walk
+    // (the QKV projection, which leaves half the CUs idle: +1.6 us).  Hosted by the attention
+    // or O-projection launch, or done for the gate/up weights, the walk cost what it gained.
+    TouchRange down_touch;
+    if (L.w_down_p.n <= ((size_t)64 << 20)) {
+      down_touch.p = L.w_down_p.p;
+      down_touch.lines = (long long)(L.w_down_p.n / 128);
+      down_touch.wgs = 128;
+    }
+    stream_project(c, c.h_bf16, d, L.wqkv_p.p, R, c.qkv_dim, d, EPI_F32, true, c.partial.p, c.qkv_dim, 0, nullptr,
+                   down_touch);
 
     AttnArgs at{};
     at.out = c.attn_bf16.p;

@@ -30,6 +30,34 @@ __host__ __device__ inline long long frag_offset(int m, int k, int k_tiles) {
   return (((long long)(m >> 4) * k_tiles + (k >> 5)) << 9) + ((((k >> 3) & 3) * 16 + (m & 15)) << 3) + (k & 7);
 }
 
+// A read-only range that spare workgroups of a launch walk, one dword per 128-byte line, while
+// the launch's own workgroups wait on memory latency: the projection that streams these weights
+// next then finds them in the memory-side cache (256 MiB) instead of HBM.
+struct TouchRange {
+  const void* p = nullptr;
+  long long lines = 0;  // 128-byte lines
+  int wgs = 0;          // workgroups that share the walk (0 = none)
+};
+#ifdef __HIPCC__
+// Workgroup `wg` of t.wgs reads one dword of every 128-byte line of its share of the range,
+// up to 8 loads in flight per lane; the values go nowhere.
+__device__ inline void touch_range(const TouchRange& t, int wg) {
+  const long long stride = (long long)t.wgs * blockDim.x;
+  const char* p = (const char*)t.p;
+  unsigned acc = 0;
+  long long i = (long long)wg * blockDim.x + threadIdx.x;
+  for (; i + 7 * stride < t.lines; i += 8 * stride) {
+    unsigned v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = *(const unsigned*)(p + (i + u * stride) * 128);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u];
+  }
+  for (; i < t.lines; i += stride) acc ^= *(const unsigned*)(p + i * 128);
+  asm volatile("" ::"v"(acc));  // keeps the loads
+}
+#endif
+
 struct GemmArgs {
   const void* a;     // bf16 [rows][K], row stride lda: hi parts of the activations
   const void* a_lo;  // same shape: lo parts (value = hi + lo)
@@ -46,6 +74,8 @@ struct GemmArgs {
   int rinv_partials = 0;
   int ssq_stride = 0;
   float eps = 0.f;
+  TouchRange touch;   // stream kernel: walked by the workgroups with blockIdx.x >= touch_x0
+  int touch_x0 = 0;   // filled by the launcher
   // EPI_RESID
   float* x = nullptr;            // [M][N] residual stream, updated in place
   const float* gain = nullptr;   // [N] gain of the RMSNorm that follows

@@ -77,6 +77,10 @@ template <int MT, int NT, int KU, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
   static_assert(EPI != EPI_RESID || NT <= 2, "one unit must cover a workgroup's columns");
   __shared__ float4 red[NW * MT * NT * 64];
+  if (p.touch.wgs > 0 && (int)blockIdx.x >= p.touch_x0) {  // uniform over the workgroup
+    touch_range(p.touch, blockIdx.x - p.touch_x0);
+    return;
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = lane & 15, g = lane >> 4;
   const int n_tiles = p.N >> 4, k_tiles = p.K >> 5;
@@ -765,6 +769,12 @@ int launch_gemm_bf16(GemmArgs a, int epi, const GemmPlan& pl, hipStream_t s) {
   const int splits = ceil_div(k_tiles, per);
   a.k_tiles_per_split = per;
   dim3 grid(ceil_div(n_tiles, pl.nt), ceil_div(a.M, 16 * pl.mt), splits);
+  if (a.touch.wgs > 0 && grid.y == 1 && grid.z == 1) {
+    a.touch_x0 = (int)grid.x;
+    grid.x += (unsigned)a.touch.wgs;
+  } else {
+    a.touch.wgs = 0;
+  }
   if (pl.mt == 1) launch_stream_mt<1, 4>(a, epi, pl, grid, s);
   else if (pl.mt == 2) launch_stream_mt<2, 4>(a, epi, pl, grid, s);
   else launch_stream_mt<4, 2>(a, epi, pl, grid, s);
