@@ -32,17 +32,55 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 
-def run_job(eng, load) -> int:
-    """One generation job; returns the number of response tokens emitted."""
+def run_job(eng, load, trace=None) -> int:
+    """One generation job; returns the number of response tokens emitted.  `trace`, a list,
+    receives (live samples, seconds) of every decode call (each call returns after its step has
+    finished on the GPU)."""
+    t0 = time.perf_counter()
     ids, toks, lps, fin = eng.rollout_prefill(load.prompt_tokens, load.prompt_offsets, load.n_samples,
                                               load.max_new_tokens, eos_id=-1, temperature=load.temperature,
                                               top_p=load.top_p)
+    if trace is not None:
+        trace.append((0, time.perf_counter() - t0))   # entry 0: the prefill call
     emitted = len(ids)
     while True:
+        t0 = time.perf_counter()
         ids, toks, lps, fin = eng.rollout_decode_step()
         if not len(ids):
             return emitted
+        if trace is not None:
+            trace.append((len(ids), time.perf_counter() - t0))
         emitted += len(ids)
+
+
+def write_step_trace(path, trace, load, kv_bytes_per_token, weight_bytes, command):
+    """The long-tail regime change of one job as a short table: decode steps binned by the number
+    of live samples B, with the cached positions they attend to (sum of c_i, every sample's
+    own context, shared prompts counted per sample) and the mean step time."""
+    plen = np.repeat(np.diff(load.prompt_offsets), load.n_samples).astype(np.int64)
+    new = load.max_new_tokens.astype(np.int64)
+    rows = []
+    for t, (b, sec) in enumerate(trace[1:], start=1):      # decode call t emits response token t
+        live = new > t
+        assert int(live.sum()) == b, (t, b, int(live.sum()))
+        rows.append((b, int((plen[live] + t).sum()), sec))
+    edges = [1, 2, 3, 5, 9, 17, 33, 65, 129, 257, 513, 1 << 30]
+    with open(path, "w") as f:
+        f.write("Per-step trace of one job, binned by live samples B (host clock around each decode call)\n")
+        f.write(f"command: {command}\n")
+        f.write(f"prefill call: {1e3 * trace[0][1]:.1f} ms; decode steps: {len(rows)}; "
+                f"weights read per step {weight_bytes / 1e9:.3f} GB (experts not counted); KV bytes per cached position {kv_bytes_per_token}\n")
+        f.write("B range    steps  mean B  mean sum c_i  mean step us  tokens/s  weight GB/s  KV GB/s (per-sample positions)  share of decode time\n")
+        total = sum(r[2] for r in rows)
+        for lo, hi in zip(edges[:-1], edges[1:]):
+            sel = [r for r in rows if lo <= r[0] < hi]
+            if not sel:
+                continue
+            n = len(sel)
+            mb, mc, ms = sum(r[0] for r in sel) / n, sum(r[1] for r in sel) / n, sum(r[2] for r in sel) / n
+            f.write(f"{lo:4d}-{min(hi - 1, 99999):<5d} {n:6d} {mb:7.1f} {mc:13.0f} {1e6 * ms:13.1f} {mb / ms:9.0f} "
+                    f"{weight_bytes / ms / 1e9:12.0f} {mc * kv_bytes_per_token / ms / 1e9:8.0f} "
+                    f"{100 * n * ms / total:28.1f} %\n")
 
 
 def run_queue_job(eng, load) -> int:
@@ -170,7 +208,10 @@ def measured_traffic(kernel: str, summary: str):
     return 1024.0 * sum(factor[c] * mean[c] for c in mean)
 
 
-def roofline_of(kernels, bracket_ms, traffic_summary=None):
+def roofline_of(kernels, bracket_ms, traffic_summary=None, copy_ceiling_gbs=None, kv_bytes_per_attn_flop=None):
+    """Roofline object of the kernel with the most time.  Beside the contract's keys: the
+    fraction of a measured plain-copy rate, and for the decode attention the rate counted
+    without prefix reuse (every sample's own context, as the kernel reads it)."""
     if not kernels:
         return None
     top = kernels[0]
@@ -184,6 +225,11 @@ def roofline_of(kernels, bracket_ms, traffic_summary=None):
         roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": ach / HBM_PEAK_GBS, "traffic": None}
     roofline["kernel"] = top["name"]
+    if roofline["bound"] == "hbm" and copy_ceiling_gbs:
+        roofline["copy_ceiling"] = copy_ceiling_gbs
+        roofline["frac_of_copy_ceiling"] = roofline["achieved"] / copy_ceiling_gbs
+    if top["name"].startswith("attn_decode") and kv_bytes_per_attn_flop:
+        roofline["achieved_without_prefix_reuse"] = top["flops"] * kv_bytes_per_attn_flop / (top["ms"] * 1e-3) / 1e9
     roofline["algorithmic_bytes_per_launch"] = top["bytes"] / top["launches"]
     if traffic_summary:
         roofline["traffic"] = measured_traffic(top["name"], traffic_summary)
@@ -219,7 +265,10 @@ def main() -> int:
     ap.add_argument("--prompt-groups", action="store_true",
                     help="decode attention reads shared prompt pages once per group of samples (library flag)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="first run three plain 256 MiB read+write kernels (a known-size reference for byte counters)")
+                    help="accepted for the byte-counter commands that name it: the plain 256 MiB read+write kernels "
+                         "(a known-size reference for byte counters, and the measured copy ceiling) now always run")
+    ap.add_argument("--step-trace", default="",
+                    help="c2/c3/c4: write a table of the last timed job's decode steps, binned by live samples, here")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -232,13 +281,21 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if args.copy_calibration:
-        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 2.0, out=dst)   # one elementwise kernel: reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
+    # A plain elementwise kernel that reads 256 MiB and writes 256 MiB: its rate is the measured
+    # ceiling beside the nominal HBM peak, and under a byte-counter run (--copy-calibration) its
+    # launches are the known-size reference.
+    src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.mul(src, 2.0, out=dst)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        torch.mul(src, 2.0, out=dst)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_ceiling_gbs = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
 
     wl = args.workload
     if wl == "loss":
@@ -366,7 +423,12 @@ def main() -> int:
                         max_context=max_prompt + int(load.max_new_tokens.max()),
                         max_batch_tokens=max(16384, max_prompt), seed=load.sampler_seed, flags=flags,
                         timing_stride=max(args.timing_stride, 1))
-        work = lambda: run_job(eng, load)
+        trace = [] if args.step_trace else None
+
+        def work():
+            if trace is not None:
+                del trace[:]
+            return run_job(eng, load, trace)
         names = {"c2": "configs[1]: Qwen2.5-1.5B-shaped dense decoder, bf16, %d prompts x %d samples, prompt 64-512, "
                        "response geometric(mean 512) capped 2048, T=1.0 top-p=1.0",
                  "c3": "configs[2]: Qwen2.5-7B-shaped dense decoder, bf16, %d prompts x %d samples, prompt 128-1024, "
@@ -402,8 +464,16 @@ def main() -> int:
         "config": {"workload": desc,
                    "output_tokens_per_step": emitted // max(args.steps, 1),
                    "decode_calls_per_step": (int(stats["decode_steps"]) - calls0) // max(args.steps, 1)},
-        "roofline": roofline_of(kernels, bracket_ms, summary),
+        # decode attention: 4 flops per cached position, query column and head dimension; K and V
+        # of that position are n_kv_heads * head_dim * 2 * 2 bytes
+        "roofline": roofline_of(kernels, bracket_ms, summary, copy_ceiling_gbs,
+                                shape.n_kv_heads * shape.head_dim * 4 / (4.0 * shape.n_q_heads * shape.head_dim)),
     }
+    if args.step_trace and wl in ("c2", "c3", "c4"):
+        non_expert = shape.param_count() - shape.vocab * shape.hidden - \
+            shape.n_layers * shape.n_experts * 3 * shape.expert_ffn_dim * shape.hidden
+        write_step_trace(args.step_trace, trace, load, kv_bytes_per_token, 2 * non_expert,
+                         "python bench.py " + " ".join(sys.argv[1:]))
     if wl == "c2-turns" and extend_clock[0] > 0:  # warm-up jobs included: a rate, not a total
         out["config"]["appended_tokens_per_s"] = extend_clock[1] / extend_clock[0]
     eng.close()

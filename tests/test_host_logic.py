@@ -140,3 +140,22 @@ def test_plan_pages_matches_direct_count(prompt_len, page, max_new):
         own = {pos // page for pos in cached} - set(range(shared))
         assert got == len(own)
     assert total == shared + tail + int(priv.sum())
+
+
+def test_bench_step_trace_table(tmp_path):
+    """bench.py's per-step table: bins cover every decode step once, the live-sample counts it
+    derives from the load must equal the ones the calls reported."""
+    import bench
+    import workloads
+    load = workloads.load_c2(n_prompts=3)
+    new = load.max_new_tokens.astype(np.int64)
+    trace = [(0, 0.05)] + [(int((new > t).sum()), 1e-3) for t in range(1, int(new.max()))]
+    out = tmp_path / "trace.txt"
+    bench.write_step_trace(str(out), trace, load, 28 * 1024, 3_000_000_000, "python bench.py --step-trace x")
+    lines = out.read_text().splitlines()
+    assert lines[1] == "command: python bench.py --step-trace x"
+    rows = [l.split() for l in lines[4:]]
+    assert sum(int(r[1]) for r in rows) == len(trace) - 1
+    assert abs(sum(float(r[-2]) for r in rows) - 100.0) < 0.5
+    with pytest.raises(AssertionError):   # a step whose count disagrees with the load's lengths
+        bench.write_step_trace(str(out), trace[:5] + [(trace[5][0] + 1, 1e-3)] + trace[6:], load, 1, 1, "x")
