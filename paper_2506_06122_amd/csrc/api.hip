@@ -438,9 +438,8 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
   }
   launch_sample(sr, B, m.vocab, c.stream);
   c.timer.end(c.stream);
-  launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, B, 1, c.stream);
-  d2h(hi + 3 * R, c.out_tokens.p, B * sizeof(int), c.stream);
-  d2h(c.h_float.p, c.out_logprobs.p, B * sizeof(float), c.stream);
+  // pinned host memory is mapped for the device: the kernel stores the step's results there
+  launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, c.out_logprobs.p, B, 1, hi + 3 * R, c.h_float.p, c.stream);
   wait_step_done(c);
   c.timer.collect();
 

@@ -93,6 +93,7 @@ struct SlotState {
 void launch_gather_decode_rows(SlotState st, const int* live, int rows, int* row_token, int* row_pos,
                                int* row_slot, float* row_inv_temp, float* row_top_p, long long* row_sample_id,
                                int* row_step, hipStream_t s);
-// after a draw: slot's last token, position (+1 when advance_pos) and step (+1)
-void launch_scatter_tokens(SlotState st, const int* row_slot, const int* tokens, int rows, int advance_pos,
-                           hipStream_t s);
+// after a draw: slot's last token, position (+1 when advance_pos) and step (+1); the rows' tokens and
+// log-probs are also stored to host_tokens / host_logprobs (pinned host memory, mapped for the device)
+void launch_scatter_tokens(SlotState st, const int* row_slot, const int* tokens, const float* logprobs, int rows,
+                           int advance_pos, int* host_tokens, float* host_logprobs, hipStream_t s);

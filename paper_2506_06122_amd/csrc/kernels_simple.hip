@@ -413,16 +413,26 @@ void launch_gather_decode_rows(SlotState st, const int* live, int rows, int* row
                                                                    row_step);
 }
 
+// A decode step's last kernel: the drawn tokens go back into the slots and, with the log-probs,
+// straight into pinned host memory, where the host reads them once the step's event has fired
+// (no copy launches).
 __global__ void scatter_tokens_kernel(SlotState st, const int* __restrict__ row_slot,
-                                      const int* __restrict__ tokens, int rows, int advance_pos) {
+                                      const int* __restrict__ tokens, const float* __restrict__ logprobs, int rows,
+                                      int advance_pos, int* __restrict__ host_tokens,
+                                      float* __restrict__ host_logprobs) {
   int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= rows) return;
   int sl = row_slot[r];
-  st.last_token[sl] = tokens[r];
+  const int tok = tokens[r];
+  st.last_token[sl] = tok;
   if (advance_pos) st.pos[sl] += 1;
   st.step[sl] += 1;
+  host_tokens[r] = tok;
+  host_logprobs[r] = logprobs[r];
 }
-void launch_scatter_tokens(SlotState st, const int* row_slot, const int* tokens, int rows, int advance_pos,
-                           hipStream_t s) {
-  if (rows) scatter_tokens_kernel<<<ceil_div(rows, 256), 256, 0, s>>>(st, row_slot, tokens, rows, advance_pos);
+void launch_scatter_tokens(SlotState st, const int* row_slot, const int* tokens, const float* logprobs, int rows,
+                           int advance_pos, int* host_tokens, float* host_logprobs, hipStream_t s) {
+  if (rows)
+    scatter_tokens_kernel<<<ceil_div(rows, 256), 256, 0, s>>>(st, row_slot, tokens, logprobs, rows, advance_pos,
+                                                              host_tokens, host_logprobs);
 }
