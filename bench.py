@@ -248,8 +248,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--timing-stride", type=int, default=16,
-                    help="bracket kernels with HIP events on every n-th library call (0 = never)")
+    ap.add_argument("--timing-stride", type=int, default=61,
+                    help="bracket kernels with HIP events on every n-th library call (0 = never); a prime, so that "
+                         "calls that recur with a job's period (its prefill) are sampled like any other")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns", "c2-refresh", "loss"],
                     default="c2",
@@ -439,6 +440,12 @@ def main() -> int:
     assert eng.rollout_get_stats()["matrix_core_path"] == 1
     print("# engine ready", file=sys.stderr, flush=True)
 
+    if load is not None and args.timing_stride > 1:
+        # The library times the calls whose index is a multiple of the stride, call 0 among them:
+        # a one-token prompt admitted and aborted takes that index, so that a run without warm-up
+        # jobs does not start its sample on the job's prefill.
+        ids = eng.rollout_prefill(np.zeros(1, np.int32), np.array([0, 1], np.int32), 1, np.array([2], np.int32))[0]
+        eng.rollout_abort(ids)
     for _ in range(args.warmup):
         work()
     torch.cuda.synchronize()
