@@ -77,6 +77,7 @@ template <int MT, int NT, int KU, int NW, int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
   static_assert(EPI != EPI_RESID || NT <= 2, "one unit must cover a workgroup's columns");
   __shared__ float4 red[NW * MT * NT * 64];
+  __shared__ float rs_part[NW * MT * 64];
   if (p.touch.wgs > 0 && (int)blockIdx.x >= p.touch_x0) {  // uniform over the workgroup
     touch_range(p.touch, blockIdx.x - p.touch_x0);
     return;
@@ -120,10 +121,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
   const int ui = wave / NU, uj = (wave % NU) * TW;
   const int um = m0 + ui * 16 + r;
   const bool valid = has_unit && um < p.M && nt0 + uj + TW - 1 < n_tiles;
-  float rs = 0.f;
   float4 xv[TW], gn[TW];
-  if (has_unit && p.rinv_ssq && um < p.M)
-    for (int pp = g; pp < p.rinv_partials; pp += 4) rs += p.rinv_ssq[(long long)pp * p.ssq_stride + um];
+  // The input rows' sums of squares come as one partial per workgroup of the producing launch
+  // (hidden/16 of them): every wavefront takes the partials w, w + NW, ... - a lane those of its
+  // group g, for row r of each row tile - so that no wavefront has more than a few loads to wait
+  // for; the shares meet in LDS with the accumulators.
+  float rs_share[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    rs_share[i] = 0.f;
+    const int m = m0 + i * 16 + r;
+    if (p.rinv_ssq && m < p.M)
+      for (int pp = wave * 4 + g; pp < p.rinv_partials; pp += NW * 4)
+        rs_share[i] += p.rinv_ssq[(long long)pp * p.ssq_stride + m];
+  }
   if (EPI == EPI_RESID && valid) {
 #pragma unroll
     for (int q = 0; q < TW; ++q) {
@@ -170,6 +181,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < NT; ++j)
       red[(wave * MT * NT + i * NT + j) * 64 + lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+  if (p.rinv_ssq) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) rs_part[(wave * MT + i) * 64 + lane] = rs_share[i];
+  }
   __syncthreads();
   if (!has_unit) return;
   f32x4 t[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
@@ -186,6 +201,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(GemmArgs p) {
   if (p.rinv_ssq) {
     // second half of the RMSNorm of this projection's input: scale row m by
     // rsqrt(mean(x^2) + eps); the 4 lanes of a row share the partial sums
+    float rs = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) rs += rs_part[(w * MT + ui) * 64 + lane];
     rs += __shfl_xor(rs, 16, WAVE);
     rs += __shfl_xor(rs, 32, WAVE);
     const float rinv = 1.0f / sqrtf(rs / (float)p.K + p.eps);
