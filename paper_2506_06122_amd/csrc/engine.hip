@@ -174,10 +174,11 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (hipGetDeviceCount(&n_dev) != hipSuccess || n_dev < 1) fail(ROLLOUT_E_HIP, "no HIP device");
   HIP_TRY(hipGetDevice(&c.device));
   c.stream = (hipStream_t)r.hip_stream;
-  // The matrix-core path needs bf16 storage, head_dim 128 and fragment-aligned dimensions;
-  // anything else runs the plain path.
+  // The matrix-core path needs bf16 storage, head_dim 128, at most 16 query heads per KV head
+  // (the columns of one attention tile) and fragment-aligned dimensions; anything else runs
+  // the plain path.
   c.simple = (r.flags & ROLLOUT_RT_SIMPLE_KERNELS) || m.dtype != ROLLOUT_DTYPE_BF16 || m.head_dim != 128 ||
-             m.hidden % 32 || m.hidden > 8192 || m.vocab % 16 ||
+             m.n_q_heads / m.n_kv_heads > 16 || m.hidden % 32 || m.hidden > 8192 || m.vocab % 16 ||
              (moe ? (m.n_experts % 16 || m.expert_ffn_dim % 32) : m.ffn_dim % 32);
   c.elem = m.dtype == ROLLOUT_DTYPE_BF16 ? 2 : 4;
   c.timer.enabled = (r.flags & ROLLOUT_RT_KERNEL_TIMING) != 0;

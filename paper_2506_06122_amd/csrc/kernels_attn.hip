@@ -481,6 +481,17 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
   const int n_slots = a.n_slots ? a.n_slots : a.n_splits;
   const unsigned valid = ((1u << used_shared) - 1u) | (((1u << used_own) - 1u) << a.slot0);
   const long long part0 = ((long long)b * n_kv + kvh) * n_slots;
+  // the partial outputs do not depend on the weights: requested first (up to 4 x 16 values per
+  // thread for 8 query heads), they arrive while the weights are worked out
+  constexpr int E_MAX = 4;  // the first 1024 of the G * DH outputs; more than 8 query heads: the rest below
+  float v[E_MAX][16];
+#pragma unroll
+  for (int i = 0; i < E_MAX; ++i) {
+    const int e = tid + 256 * i;
+#pragma unroll
+    for (int s = 0; s < 16; ++s)
+      v[i][s] = (e < G * DH && ((valid >> s) & 1u)) ? a.part_o[(part0 + s) * (16 * DH) + e] : 0.f;
+  }
   {
     const int s = tid >> 4, col = tid & 15;  // 256 threads = 16 slots x 16 columns
     const bool on = (valid >> s) & 1u;
@@ -505,14 +516,24 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
     w_s[s][col] = w / (L * P_SCALE);
     __syncthreads();
   }
-  for (int e = tid; e < G * DH; e += 256) {
-    const int col = e >> 7;
-    float v[16];
 #pragma unroll
-    for (int s = 0; s < 16; ++s) v[s] = ((valid >> s) & 1u) ? a.part_o[(part0 + s) * (16 * DH) + e] : 0.f;
+  for (int i = 0; i < E_MAX; ++i) {
+    const int e = tid + 256 * i;
+    if (e >= G * DH) break;
+    const int col = e >> 7;
     float acc = 0.f;
 #pragma unroll
-    for (int s = 0; s < 16; ++s) acc += v[s] * w_s[s][col];
+    for (int s = 0; s < 16; ++s) acc += v[i][s] * w_s[s][col];
+    store1_split(a.out + out_offset(a, b, kvh * G * DH + e), a.out_lo_offset, acc);
+  }
+  for (int e = tid + 256 * E_MAX; e < G * DH; e += 256) {
+    const int col = e >> 7;
+    float u[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) u[s] = ((valid >> s) & 1u) ? a.part_o[(part0 + s) * (16 * DH) + e] : 0.f;
+    float acc = 0.f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) acc += u[s] * w_s[s][col];
     store1_split(a.out + out_offset(a, b, kvh * G * DH + e), a.out_lo_offset, acc);
   }
 }

@@ -32,25 +32,35 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
       x[v] = c < n4 ? xs[c] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
-  // split planes in ascending order, two at a time with their loads issued together
-  for (int z = 0; z < a.splits; z += 2) {
-    const float4* p0 = (const float4*)(a.partial + (long long)z * a.split_stride + (long long)r * a.hidden);
-    const float4* p1 = (const float4*)(a.partial + (long long)(z + 1) * a.split_stride + (long long)r * a.hidden);
-    const bool two = z + 1 < a.splits;
-    float4 u[V], w[V];
+  // the gain is not needed before the end: requested now, it arrives with the row
+  float4 gn[V];
 #pragma unroll
-    for (int v = 0; v < V; ++v) {
-      const int c = t + ROW_T * v;
-      u[v] = c < n4 ? p0[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-      w[v] = (two && c < n4) ? p1[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int v = 0; v < V; ++v) {
+    const int c = t + ROW_T * v;
+    gn[v] = c < n4 ? ((const float4*)a.gain)[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  // split planes, added in ascending order; the loads of four planes are issued together (a
+  // projection with a deep K leaves up to 16 planes: two at a time were eight round trips)
+  for (int z = 0; z < a.splits; z += 4) {
+    float4 u[4][V];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4* pz = (const float4*)(a.partial + (long long)(z + q) * a.split_stride + (long long)r * a.hidden);
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const int c = t + ROW_T * v;
+        u[q][v] = (z + q < a.splits && c < n4) ? pz[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
 #pragma unroll
-    for (int v = 0; v < V; ++v) {
-      x[v].x = (x[v].x + u[v].x) + w[v].x;
-      x[v].y = (x[v].y + u[v].y) + w[v].y;
-      x[v].z = (x[v].z + u[v].z) + w[v].z;
-      x[v].w = (x[v].w + u[v].w) + w[v].w;
-    }
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        x[v].x += u[q][v].x;
+        x[v].y += u[q][v].y;
+        x[v].z += u[q][v].z;
+        x[v].w += u[q][v].w;
+      }
   }
   for (int j = 0; j < a.moe_k; ++j) {  // the row's expert picks, in pick order
     const float wt = a.moe_wt[(long long)r * a.moe_k + j];
@@ -84,12 +94,11 @@ __global__ __launch_bounds__(ROW_T) void row_norm_kernel(RowNormArgs a) {
     const int c = t + ROW_T * v;
     if (c >= n4) continue;
     if (write_x) ((float4*)(a.x + (long long)r * a.hidden))[c] = x[v];
-    const float4 gn = ((const float4*)a.gain)[c];
     uint16_t hi[4], lo[4];
-    split_bf16(x[v].x * gn.x * rinv, hi[0], lo[0]);
-    split_bf16(x[v].y * gn.y * rinv, hi[1], lo[1]);
-    split_bf16(x[v].z * gn.z * rinv, hi[2], lo[2]);
-    split_bf16(x[v].w * gn.w * rinv, hi[3], lo[3]);
+    split_bf16(x[v].x * gn[v].x * rinv, hi[0], lo[0]);
+    split_bf16(x[v].y * gn[v].y * rinv, hi[1], lo[1]);
+    split_bf16(x[v].z * gn[v].z * rinv, hi[2], lo[2]);
+    split_bf16(x[v].w * gn[v].w * rinv, hi[3], lo[3]);
     uint16_t* hp = a.h + (a.h_frag ? frag_offset(r, 4 * c, a.hidden >> 5) : (long long)r * a.hidden + 4 * c);
     *(uint2*)hp = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
     *(uint2*)(hp + a.h_lo_offset) =

@@ -71,3 +71,23 @@ def test_family_tensors_refresh_and_are_checked():
     with pytest.raises(R.RolloutError):
         plain.rollout_update_weights({"layers.0.q_norm": wb["layers.0.q_norm"]})
     plain.close()
+
+
+@pytest.mark.parametrize("n_q,n_kv,fast", [(32, 2, 1), (32, 1, 0)], ids=["G16", "G32-plain-path"])
+def test_many_query_heads_per_kv_head(n_q, n_kv, fast):
+    """16 query heads per KV head fill the attention tile's 16 columns (and the merge of the KV
+    splits walks 2048 outputs per KV head); 32 do not fit and must take the plain path.  Contexts
+    of 200-330 positions: the decode attention runs split, with 6 rows (streamed projections)
+    and with 40 (tile projections)."""
+    shape = workloads.ModelShape(f"small-{n_q}q{n_kv}kv-bf16", 2, 512, n_q, n_kv, 128, 1024, 2048)
+    w = scaled_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    for prompts, samples in ((3, 2), (5, 8)):
+        eng = make_engine(shape, w, max_live_samples=64, max_context=512, max_batch_tokens=2048)
+        assert eng.rollout_get_stats()["matrix_core_path"] == fast
+        toks, offs = workloads.make_prompts(prompts, 200, 330, shape.vocab, seed=17)
+        forced = np.random.default_rng(18).integers(0, shape.vocab, (prompts * samples, 4)).astype(np.int32)
+        worst = teacher_forced_compare(eng, model, toks, offs, samples, forced, 4)
+        print(f"{n_q} query heads, {n_kv} KV heads, {prompts * samples} rows: max |dlogits|, |dlogp| = {worst[0]:.3e}, {worst[1]:.3e}")
+        assert max(worst) <= 2e-2
+        eng.close()
