@@ -180,7 +180,7 @@ __device__ __forceinline__ void sum_planes(const AttnArgs& a, const float* p, fl
 // Query staging.  Thread t of the workgroup owns the rotary pairs idx = t + 256 n, n < N:
 // column idx / 64 (the same in all 64 lanes), pair idx % 64.  rows[n] / heads[n] name the
 // sample row and the query head inside its KV group that column holds (row < 0: the column
-// is empty).  The split-K planes of the projection are summed in ascending order, two planes
+// is empty).  The split-K planes of the projection are summed in ascending order, four planes
 // of all N columns per round of loads, then bias / head norm, the rotary embedding, and the
 // hi + lo half-precision parts into sm.q.
 template <bool EXTRA, int N>
@@ -190,29 +190,34 @@ __device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSme
   const int q_dim = a.n_q_heads * DH, kv_dim = a.geom.n_kv_heads * DH;
   const float* src[N];
   float x0[N], x1[N];
+  float2 cs[N];  // cos, sin of the row's position: requested with the first planes
 #pragma unroll
   for (int n = 0; n < N; ++n) {
     const int b = max(rows[n], 0);  // empty columns read row 0 and are zeroed below
     src[n] = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim) + (kvh * G + heads[n]) * DH + i;
     x0[n] = 0.f;
     x1[n] = 0.f;
+    cs[n] = *(const float2*)(a.cos_sin + (long long)a.row_pos[b] * DH + 2 * i);
   }
-  for (int z = 0; z < a.qkv_planes; z += 2) {
-    const bool two = z + 1 < a.qkv_planes;
-    const long long o0 = (long long)z * a.qkv_plane_stride, o1 = two ? o0 + a.qkv_plane_stride : o0;
-    float u0[N], u1[N], w0[N], w1[N];
+  for (int z = 0; z < a.qkv_planes; z += 4) {
+    float u0[4][N], u1[4][N];
 #pragma unroll
-    for (int n = 0; n < N; ++n) {
-      u0[n] = src[n][o0];
-      u1[n] = src[n][o0 + 64];
-      w0[n] = src[n][o1];
-      w1[n] = src[n][o1 + 64];
+    for (int q = 0; q < 4; ++q) {
+      const bool on = z + q < a.qkv_planes;
+      const long long o = (long long)(on ? z + q : z) * a.qkv_plane_stride;
+#pragma unroll
+      for (int n = 0; n < N; ++n) {
+        u0[q][n] = on ? src[n][o] : 0.f;
+        u1[q][n] = on ? src[n][o + 64] : 0.f;
+      }
     }
 #pragma unroll
-    for (int n = 0; n < N; ++n) {
-      x0[n] = two ? (x0[n] + u0[n]) + w0[n] : x0[n] + u0[n];
-      x1[n] = two ? (x1[n] + u1[n]) + w1[n] : x1[n] + u1[n];
-    }
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int n = 0; n < N; ++n) {
+        x0[n] += u0[q][n];
+        x1[n] += u1[q][n];
+      }
   }
 #pragma unroll
   for (int n = 0; n < N; ++n) {
@@ -220,8 +225,7 @@ __device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSme
     float u = 0.f, w = 0.f;
     if (rows[n] >= 0) {  // uniform over the wavefront
       if (EXTRA) qkv_extras(a.extra, (kvh * G + heads[n]) * DH, i, a.extra.q_gain, x0[n], x1[n]);
-      const float* cs = a.cos_sin + (long long)a.row_pos[rows[n]] * DH;
-      const float cc = cs[2 * i], sn = cs[2 * i + 1];
+      const float cc = cs[n].x, sn = cs[n].y;
       u = x0[n] * cc - x1[n] * sn;
       w = x1[n] * cc + x0[n] * sn;
     }
