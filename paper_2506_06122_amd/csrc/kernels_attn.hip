@@ -183,9 +183,11 @@ __device__ __forceinline__ void sum_planes(const AttnArgs& a, const float* p, fl
 // is empty).  The split-K planes of the projection are summed in ascending order, four planes
 // of all N columns per round of loads, then bias / head norm, the rotary embedding, and the
 // hi + lo half-precision parts into sm.q.
-template <bool EXTRA, int N>
+// PRE: the caller has already loaded plane 0 (pre0 = the element, pre1 = the one 64 further on).
+template <bool EXTRA, int N, bool PRE = false>
 __device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSmem& sm, int kvh, int G,
-                                              const int (&rows)[N], const int (&heads)[N]) {
+                                              const int (&rows)[N], const int (&heads)[N],
+                                              const float* pre0 = nullptr, const float* pre1 = nullptr) {
   const int tid = threadIdx.x, i = tid & 63;
   const int q_dim = a.n_q_heads * DH, kv_dim = a.geom.n_kv_heads * DH;
   const float* src[N];
@@ -195,11 +197,11 @@ __device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSme
   for (int n = 0; n < N; ++n) {
     const int b = max(rows[n], 0);  // empty columns read row 0 and are zeroed below
     src[n] = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim) + (kvh * G + heads[n]) * DH + i;
-    x0[n] = 0.f;
-    x1[n] = 0.f;
+    x0[n] = PRE ? 0.f + pre0[n] : 0.f;
+    x1[n] = PRE ? 0.f + pre1[n] : 0.f;
     cs[n] = *(const float2*)(a.cos_sin + (long long)a.row_pos[b] * DH + 2 * i);
   }
-  for (int z = 0; z < a.qkv_planes; z += 4) {
+  for (int z = PRE ? 1 : 0; z < a.qkv_planes; z += 4) {
     float u0[4][N], u1[4][N];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -269,26 +271,29 @@ __device__ __forceinline__ void decode_own_range(const AttnArgs& a, const Decode
   const int G = a.n_q_heads / n_kv;
   const int pos = a.row_pos[b];
   const int t0 = a.row_t0 ? a.row_t0[b] : 0;
+  const int slot = a.row_slot[b];
+  const int q_dim = a.n_q_heads * DH, kv_dim = n_kv * DH;
+  const float* row = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim);
+  // The first plane of this workgroup's query columns is requested before the position is
+  // known (which says whether this split has anything to do): one round trip less.
+  int rows[4], heads[4];
+  float pre0[4], pre1[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    heads[n] = (tid >> 6) + 4 * n;  // column = head inside the KV group
+    rows[n] = heads[n] < G ? b : -1;
+    heads[n] = min(heads[n], G - 1);
+    const float* src = row + (kvh * G + heads[n]) * DH + (tid & 63);
+    pre0[n] = src[0];
+    pre1[n] = src[64];
+  }
   const int used = (pos - t0) / a.split_tokens + 1;  // splits that hold at least the new position
   if (split >= used) return;
   const bool owner = split == used - 1;
   const bool direct = used == 1 && t0 == 0;          // the only partial result of this (sample, KV head)
-  const int slot = a.row_slot[b];
-  const int q_dim = a.n_q_heads * DH, kv_dim = n_kv * DH;
-  const float* row = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim);
   const float* cs = a.cos_sin + (long long)pos * DH;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-
-  {
-    int rows[4], heads[4];
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      heads[n] = (tid >> 6) + 4 * n;  // column = head inside the KV group
-      rows[n] = heads[n] < G ? b : -1;
-      heads[n] = min(heads[n], G - 1);
-    }
-    stage_queries<EXTRA, 4>(a, sm, kvh, G, rows, heads);
-  }
+  stage_queries<EXTRA, 4, true>(a, sm, kvh, G, rows, heads, pre0, pre1);
   if (owner && tid < 128) {
     const int page = a.page_table[(long long)slot * a.max_pages + pos / a.geom.page_tokens];
     const int tok = pos % a.geom.page_tokens;
@@ -478,15 +483,17 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
   const int tid = threadIdx.x, kvh = blockIdx.x, b = blockIdx.y;
   const int n_kv = a.geom.n_kv_heads;
   const int G = a.n_q_heads / n_kv;
-  const int t0 = a.row_t0 ? a.row_t0[b] : 0;
-  const int used_shared = t0 ? (t0 + a.split_tokens_a - 1) / a.split_tokens_a : 0;
-  const int used_own = (a.row_pos[b] - t0) / a.split_tokens + 1;
-  if (used_shared == 0 && used_own == 1) return;  // the attention kernel wrote the result itself
   const int n_slots = a.n_slots ? a.n_slots : a.n_splits;
-  const unsigned valid = ((1u << used_shared) - 1u) | (((1u << used_own) - 1u) << a.slot0);
   const long long part0 = ((long long)b * n_kv + kvh) * n_slots;
-  // the partial outputs do not depend on the weights: requested first (up to 4 x 16 values per
-  // thread for 8 query heads), they arrive while the weights are worked out
+  // Every load is requested at once - the row's position, which tells the slots in use, and all
+  // 16 slots' maxima, sums and outputs (up to 4 x 16 values per thread for 8 query heads; slots
+  // past the last one read the last one) - and what an unused slot held is dropped afterwards:
+  // one round trip to memory instead of three.
+  const int t0 = a.row_t0 ? a.row_t0[b] : 0;
+  const int pos = a.row_pos[b];
+  const int ms = min(tid >> 4, n_slots - 1), mcol = tid & 15;
+  const float m_ld = a.part_ml[(part0 + ms) * 32 + mcol];
+  const float l_ld = a.part_ml[(part0 + ms) * 32 + 16 + mcol];
   constexpr int E_MAX = 4;  // the first 1024 of the G * DH outputs; more than 8 query heads: the rest below
   float v[E_MAX][16];
 #pragma unroll
@@ -494,13 +501,22 @@ __global__ __launch_bounds__(256) void attn_merge_fused_kernel(AttnArgs a) {
     const int e = tid + 256 * i;
 #pragma unroll
     for (int s = 0; s < 16; ++s)
-      v[i][s] = (e < G * DH && ((valid >> s) & 1u)) ? a.part_o[(part0 + s) * (16 * DH) + e] : 0.f;
+      v[i][s] = e < G * DH ? a.part_o[(part0 + min(s, n_slots - 1)) * (16 * DH) + e] : 0.f;
   }
+  const int used_shared = t0 ? (t0 + a.split_tokens_a - 1) / a.split_tokens_a : 0;
+  const int used_own = (pos - t0) / a.split_tokens + 1;
+  if (used_shared == 0 && used_own == 1) return;  // the attention kernel wrote the result itself
+  const unsigned valid = ((1u << used_shared) - 1u) | (((1u << used_own) - 1u) << a.slot0);
+#pragma unroll
+  for (int i = 0; i < E_MAX; ++i)
+#pragma unroll
+    for (int s = 0; s < 16; ++s)
+      if (!((valid >> s) & 1u)) v[i][s] = 0.f;
   {
     const int s = tid >> 4, col = tid & 15;  // 256 threads = 16 slots x 16 columns
     const bool on = (valid >> s) & 1u;
-    const float m = on ? a.part_ml[(part0 + s) * 32 + col] : -INFINITY;
-    const float l = on ? a.part_ml[(part0 + s) * 32 + 16 + col] : 0.f;
+    const float m = on ? m_ld : -INFINITY;
+    const float l = on ? l_ld : 0.f;
     w_s[s][col] = m;
     __syncthreads();
     float M = -INFINITY;
