@@ -25,15 +25,19 @@ def sources() -> list[str]:
 
 
 def sources_digest() -> str:
-    """SHA-256 over the kernel sources (csrc/*.hip, csrc/*.h, in name order).  Profiler
-    summaries record it, so a reader can tell whether counters were taken on these kernels."""
+    """SHA-256 over the kernel sources (csrc/*.hip, csrc/*.h, in name order) without their
+    comment-only and blank lines and trailing blanks: what compiles.  Profiler summaries record
+    it, so a reader can tell whether counters were taken on these kernels."""
     import hashlib
     h = hashlib.sha256()
     for f in sorted(os.listdir(CSRC)):
         if f.endswith((".hip", ".h")):
             h.update(f.encode())
-            with open(os.path.join(CSRC, f), "rb") as fh:
-                h.update(fh.read())
+            with open(os.path.join(CSRC, f), "r", encoding="utf-8") as fh:
+                for line in fh:
+                    code = line.rstrip()
+                    if code and not code.lstrip().startswith("//"):
+                        h.update(code.encode() + b"\n")
     return h.hexdigest()
 
 

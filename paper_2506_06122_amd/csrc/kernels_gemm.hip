@@ -28,14 +28,18 @@
 //         - RMSNorm is split in two.  The producer of the residual stream (EPI_RESID) adds
 //           its result to x, stores x * gain as the next projection's operand and one
 //           partial sum of squares per (workgroup, row); the consumer sums those partials
-//           in a fixed order and scales its output rows by rsqrt(mean + eps) - a row scale
-//           commutes with the projection.  No workgroup ever waits for another.
+//           in a fixed order (all its wavefronts share the loads) and scales its output rows
+//           by rsqrt(mean + eps) - a row scale commutes with the projection.  No workgroup
+//           ever waits for another.
 //         - SwiGLU on interleaved gate/up column tiles (EPI_SWIGLU_BF16).
-//   gemm_tile_ring_kernel (more than 32 rows, decode-sized): 64 x 128 output tile per
-//       workgroup, activations (row-major) staged through LDS in fragment order as whole cache
+//       Workgroups past the last column block, if the launcher adds any, walk a later
+//       projection's weights into the memory-side cache (TouchRange, kernels_fast.h).
+//   gemm_tile_ring_kernel (33 to 512 rows, every projection of a decode step, the logits
+//       included): 64 x 128 output tile per workgroup (32 x 128 where that fills the chip
+//       better), activations (row-major) staged through LDS in fragment order as whole cache
 //       lines, weights read directly; split-K planes when the tiles alone do not fill the chip.
-//   gemm_tile_kernel    (prefill, teacher-forced pass, lm_head of large decode batches): 64 x 256
-//       tile, the same staging, software-pipelined over a ring of register slots.
+//   gemm_tile_kernel    (more than 512 rows: prefill, teacher-forced pass): 64 x 256 tile, the
+//       same staging, software-pipelined over a ring of register slots.
 #include <cstdio>
 
 #include "kernels_fast.h"
