@@ -19,8 +19,11 @@
  *     valid when the call returns (the library synchronises its stream once per call).
  *   - A context is bound to the device that was current in rollout_init and is not
  *     thread-safe; calls on one context must not overlap.
- *   - Sample id = (global prompt counter) * n_samples + j.  A sample's tokens depend only
- *     on the weights, its prompt, the seed and its id, never on what else is in flight.
+ *   - Sample ids are handed out consecutively, in call order: a call that adds P prompts with
+ *     n samples each takes the next P * n ids, sample j of its prompt p getting first + p * n + j
+ *     (so with one n throughout, id = prompt counter * n + j; calls may use different n).  A
+ *     sample's tokens depend only on the weights, its prompt, the seed and its id, never on what
+ *     else is in flight.
  *   - Response position t = 0 is emitted by rollout_prefill, position t >= 1 by the t-th
  *     rollout_decode_step after it.  A sample finishes when it emits eos_id (the token is
  *     reported) or its max_new_tokens-th token.
@@ -35,13 +38,13 @@
 extern "C" {
 #endif
 
-#define ROLLOUT_ABI_VERSION 2
+#define ROLLOUT_ABI_VERSION 3
 
 #define ROLLOUT_OK 0
 #define ROLLOUT_E_INVAL (-1) /* bad argument or unsupported shape */
 #define ROLLOUT_E_NOMEM (-2) /* KV pool, live-sample table or workspace too small; nothing admitted */
-#define ROLLOUT_E_HIP (-3)   /* a HIP call failed or no usable GPU */
-#define ROLLOUT_E_STATE (-4) /* call not valid in the context's current state */
+#define ROLLOUT_E_HIP (-3)   /* a HIP call failed, no usable GPU, or a decode step's kernels did not finish in time */
+#define ROLLOUT_E_STATE (-4) /* call not valid in the context's current state (also: every call after a time-out) */
 
 #define ROLLOUT_DTYPE_F32 0
 #define ROLLOUT_DTYPE_BF16 1
@@ -165,7 +168,9 @@ int rollout_live_samples(rollout_ctx *ctx, int32_t capacity, int64_t *ids);
  *   uniform_override  NULL, or host uint32 [live]
  *   n_live            in: capacity of the output arrays; out: samples stepped
  * Outputs (host, ascending sample id, any may be NULL): sample_ids, tokens, logprobs,
- * finished.  Errors: E_INVAL (capacity too small). With no live sample: *n_live = 0, OK. */
+ * finished.  Errors: E_INVAL (capacity too small); E_HIP when the step's kernels do not finish
+ * within five minutes of wall clock (the context then refuses every further call with E_STATE:
+ * destroy it).  With no live sample: *n_live = 0, OK. */
 int rollout_decode_step(rollout_ctx *ctx, const int32_t *forced_tokens, const uint32_t *uniform_override,
                         int32_t *n_live, int64_t *sample_ids, int32_t *tokens, float *logprobs,
                         uint8_t *finished);
@@ -202,7 +207,9 @@ int rollout_extend(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids, const
                    int32_t *next_tokens, float *next_logprobs, uint8_t *finished);
 
 /* "Abort request" (paper section 4.3): drops the listed live samples and frees their
- * pages.  Ids that are not live are ignored.  Returns the number aborted. */
+ * pages.  Ids that are not live are ignored.  Returns the number aborted.  For the queue-fed
+ * rollout an aborted sample counts as ended: its prompt is complete once its other samples
+ * have ended too. */
 int rollout_abort(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids);
 
 /* ---- Queue-fed continuous rollout ---------------------------------------------------------
@@ -214,23 +221,23 @@ int rollout_abort(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids);
  * tokens still depend only on (weights, prompt, seed, sample id): the queue decides when a
  * sample runs, never what it emits. */
 typedef struct {
-  uint64_t prompts_pushed, prompts_admitted, prompts_completed; /* completed = every sample finished */
+  uint64_t prompts_pushed, prompts_admitted, prompts_completed; /* completed = every sample finished or aborted by the caller */
   uint64_t samples_aborted;                                     /* by the target policy */
   int32_t prompts_waiting;
   int32_t closed;                                               /* 1 once the target was reached */
 } rollout_queue_stats;
 
 /* Appends n_prompts prompts (n_samples samples each) to the queue; host arrays as for
- * rollout_prefill, copied.  Nothing runs on the GPU.  prompt_ids (host int64 [n_prompts], may be
- * NULL) receives each prompt's counter; its samples will carry the ids counter * n_samples + j.
- * Counters are taken here, in push order, from the same sequence rollout_prefill uses.
+ * rollout_prefill, copied.  Nothing runs on the GPU.  first_sample_ids (host int64 [n_prompts],
+ * may be NULL) receives the id of each prompt's sample 0; its sample j will carry that id + j.
+ * Ids are taken here, in push order, from the same sequence rollout_prefill uses.
  * Errors (nothing is queued): E_INVAL (bad arguments; n_samples differs from earlier pushes;
  * queue closed); E_NOMEM when a prompt could never be admitted, even into an idle context
  * (longer than max_batch_tokens, prompt + response beyond max_context, more samples than
  * live-sample slots, more pages than the pool holds). */
 int rollout_queue_push(rollout_ctx *ctx, int32_t n_prompts, const int32_t *tokens, const int32_t *offsets,
                        int32_t n_samples, const int32_t *max_new_tokens, int32_t eos_id, float temperature,
-                       float top_p, int64_t *prompt_ids);
+                       float top_p, int64_t *first_sample_ids);
 
 /* admit_min_prompts >= 1: a step admits waiting prompts only when at least that many of them
  * (or all that wait) fit, or when no sample is live - fewer, larger prefill calls.

@@ -74,12 +74,15 @@ def generate(model: Model, prompt_tokens, prompt_offsets, n_samples: int, max_ne
 
 
 def decode_slice_batched(model: Model, prompt, n_samples: int, n_new: int,
-                         temperature: float, top_p: float, seed: int) -> int:
+                         temperature: float, top_p: float, seed: int,
+                         out_tokens: list | None = None) -> int:
     """Prefill one prompt, then decode n_samples samples together for n_new tokens each.
 
     Same arithmetic as `generate` with the samples' rows stacked into one matrix per step
-    (the projections see [n_samples][hidden] instead of one row at a time).  Returns the
-    number of tokens emitted; used to time the oracle on a bounded slice.
+    (the projections see [n_samples][hidden] instead of one row at a time); sample j has id j
+    and runs without an end-of-sequence token.  Returns the number of tokens emitted; used to
+    time the oracle on a bounded slice.  out_tokens, when given, receives one list of emitted
+    token ids per sample (a test compares them with `generate`).
     """
     fwd = KVForward(model)
     inv_t = sampler.inv_temperature(temperature)
@@ -88,6 +91,8 @@ def decode_slice_batched(model: Model, prompt, n_samples: int, n_new: int,
     caches = [prefix.fork() for _ in range(n_samples)]
     rows = [last] * n_samples
     emitted = 0
+    if out_tokens is not None:
+        out_tokens[:] = [[] for _ in range(n_samples)]
     for t in range(n_new):
         toks = []
         for j in range(n_samples):
@@ -95,6 +100,8 @@ def decode_slice_batched(model: Model, prompt, n_samples: int, n_new: int,
                                     philox.rollout_uniform(seed, j, t))
             toks.append([tok])
             emitted += 1
+            if out_tokens is not None:
+                out_tokens[j].append(tok)
         if t + 1 < n_new:
             rows = [r[0] for r in fwd.extend(caches, toks)]
     return emitted

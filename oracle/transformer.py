@@ -69,6 +69,28 @@ def route(r: np.ndarray, top_k: int):
     return order, softmax(r[order])
 
 
+def routing_gaps(r: np.ndarray, chosen, top_k: int):
+    """How far an expert set is from the top-k of the logits r, as two differences:
+
+      below   = (k-th largest logit) - (smallest chosen logit): the weakest member is that much
+                worse than the weakest member of the true top-k;
+      outside = (largest logit not chosen) - (smallest chosen logit): an expert left out beats
+                a member by that much.
+
+    A set of k distinct experts is a valid top-k (up to ties) iff both are <= 0; a set that is
+    the top-k up to a logit tolerance tol has both <= tol.  The second difference is the
+    complete condition (every member >= every non-member); the first is kept because it is
+    what a wrong weakest member alone shows.
+    """
+    chosen = np.asarray(chosen, dtype=np.int64)
+    kth = np.sort(r)[::-1][top_k - 1]
+    low = np.min(r[chosen])
+    rest = np.ones(len(r), dtype=bool)
+    rest[chosen] = False
+    outside = (np.max(r[rest]) - low) if rest.any() else -np.inf
+    return float(kth - low), float(outside)
+
+
 class Model:
     """Shape + weights, widened to fp64 on access (cached when `cache` is true)."""
 
@@ -80,9 +102,13 @@ class Model:
         # lower-precision implementation may legitimately pick another expert on a near-tie.
         # When routing_override[layer] holds an int array [rows][top_k], `ffn` uses those
         # expert sets (mixing weights still come from this model's own router logits) and
-        # appends to routing_regret how far each set is from optimal in those logits.
+        # appends to routing_regret, per row, how far the set is from the top-k of those
+        # logits (`routing_gaps`): both numbers are <= 0 exactly when the set is the top-k.
         self.routing_override = {}
         self.routing_regret = []
+        # Second test hook: when routing_trace is a list, `ffn` appends (layer, router logits of
+        # the row, experts used) for every row it routes, in call order.
+        self.routing_trace = None
 
     def w(self, name: str) -> np.ndarray:
         if self._cache is None:
@@ -119,8 +145,10 @@ class Model:
             if forced is not None:
                 chosen = np.asarray(forced[i], dtype=np.int64)
                 assert len(set(chosen.tolist())) == s.top_k
-                self.routing_regret.append(float(np.min(r[i][experts]) - np.min(r[i][chosen])))
+                self.routing_regret.append(routing_gaps(r[i], chosen, s.top_k))
                 experts, mix = chosen, softmax(r[i][chosen])
+            if self.routing_trace is not None:
+                self.routing_trace.append((layer, r[i].copy(), np.asarray(experts).copy()))
             for e, m in zip(experts, mix):
                 act = silu(wg[e] @ h[i]) * (wu[e] @ h[i])
                 out[i] += m * (wd[e] @ act)

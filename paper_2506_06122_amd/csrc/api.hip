@@ -2,8 +2,11 @@
 // accounting on the host, and the launch sequences of prefill, decode step, teacher-forced
 // log-probs and abort.  See include/rollout.h for the contract of each entry point.
 #include <algorithm>
+#include <chrono>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "engine.h"
 
@@ -57,15 +60,61 @@ __global__ void init_slots_kernel(SlotState st, const int* __restrict__ slots, c
 
 // A decode step ends with a few hundred bytes coming back; polling an event answers within
 // microseconds where a blocking wait costs a scheduler round trip per step.
+// The poll is bounded by wall clock (step_timeout_s): kernels that never finish must not hang the
+// caller for good.  After a time-out the device state is unknown, so the context refuses every
+// further call (E_STATE) and rollout_destroy is what is left to do.
 static void wait_step_done(rollout_ctx& c) {
   if (!c.step_done) HIP_TRY(hipEventCreateWithFlags(&c.step_done, hipEventDisableTiming));
   HIP_TRY(hipEventRecord(c.step_done, c.stream));
-  for (;;) {
+  const auto t0 = std::chrono::steady_clock::now();
+  for (unsigned polls = 0;; ++polls) {
     hipError_t e = hipEventQuery(c.step_done);
     if (e == hipSuccess) return;
     if (e != hipErrorNotReady) throw HipError(e, "hipEventQuery", __FILE__, __LINE__);
+    if (((polls & 1023u) == 1023u || c.step_timeout_s <= 0) &&
+        std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > c.step_timeout_s) {
+      c.broken = true;
+      throw ApiError{ROLLOUT_E_HIP, "the decode step's kernels did not finish within " +
+                                        std::to_string(c.step_timeout_s) + " s; the context is unusable now"};
+    }
   }
 }
+
+static void check_usable(const rollout_ctx& c) {
+  if (c.broken) throw ApiError{ROLLOUT_E_STATE, "an earlier call timed out on the device; destroy this context"};
+}
+
+// Pages and live-sample slots taken by a call that has not completed yet: given back if the
+// call leaves by an exception, so that a failing call changes no state.
+struct Rollback {
+  rollout_ctx& c;
+  std::vector<int32_t> page_refs;  // one entry per reference taken (alloc or retain)
+  std::vector<int> slots;
+  bool armed = true;
+  explicit Rollback(rollout_ctx& ctx) : c(ctx) {}
+  int32_t alloc() {
+    const int32_t pg = c.pool->alloc(false);
+    if (pg < 0) throw ApiError{ROLLOUT_E_NOMEM, "internal: the KV pool ran out after admission was checked"};
+    page_refs.push_back(pg);
+    return pg;
+  }
+  void retain(int32_t pg) {
+    c.pool->retain(pg);
+    page_refs.push_back(pg);
+  }
+  int take_slot() {
+    const int sl = c.free_slots.back();
+    c.free_slots.pop_back();
+    slots.push_back(sl);
+    return sl;
+  }
+  void commit() { armed = false; }
+  ~Rollback() {
+    if (!armed) return;
+    for (int32_t pg : page_refs) c.pool->release(pg);
+    for (auto it = slots.rbegin(); it != slots.rend(); ++it) c.free_slots.push_back(*it);
+  }
+};
 
 static void release_sample(rollout_ctx& c, Sample& s) {
   for (int32_t p : s.pages) c.pool->release(p);
@@ -84,13 +133,14 @@ static void refresh_stats(rollout_ctx& c) {
 }
 
 // Admission of P prompts with n samples each (all or none), their prefill and response
-// position 0.  prompt_ids: the prompts' counters (sample id = counter * n + j), or NULL to take
-// the next P counters.
+// position 0.  prompt_ids / first_ids: the prompts' counters and the ids of their first samples
+// as handed out at push time (sample j of prompt p carries first_ids[p] + j), or both NULL to
+// take the next P counters and the next P * n ids.
 static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* tokens, const int32_t* offsets,
                          int32_t n_samples, const int32_t* max_new_tokens, int32_t eos_id, float temperature,
                          float top_p, const int32_t* forced_first, const uint32_t* uniform_override,
-                         const int64_t* prompt_ids, int64_t* sample_ids, int32_t* first_tokens,
-                         float* first_logprobs, uint8_t* finished) {
+                         const int64_t* prompt_ids, const int64_t* first_ids, int64_t* sample_ids,
+                         int32_t* first_tokens, float* first_logprobs, uint8_t* finished) {
   const rollout_model_desc& m = c.md;
   const int P = n_prompts, n = n_samples, T = c.rd.page_tokens, R = c.r_max;
   // ---- validation (no state changes before all of it passed) ----
@@ -121,8 +171,14 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
   }
   if (need_slots > (int)c.free_slots.size()) fail(ROLLOUT_E_NOMEM, "not enough free live-sample slots");
   if (need_pages > c.pool->unreserved()) fail(ROLLOUT_E_NOMEM, "not enough free KV pages");
+  if ((prompt_ids == nullptr) != (first_ids == nullptr)) fail(ROLLOUT_E_STATE, "internal: ids given in part");
+  for (int p = 0; p < P; ++p)
+    for (int j = 0; j < n; ++j)
+      if (c.live.count((first_ids ? first_ids[p] : c.next_sample_id + (int64_t)p * n) + j))
+        fail(ROLLOUT_E_STATE, "internal: a sample id is live already");
 
-  // ---- pages and page tables ----
+  // ---- pages and page tables (given back by `undo` if anything below throws) ----
+  Rollback undo(c);
   const float inv_t = 1.0f / temperature;
   struct PromptPages {
     std::vector<int32_t> shared;
@@ -136,18 +192,18 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
     int full = len / T, has_tail = (len % T) != 0;
     int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + p) * c.max_pages];
     for (int i = 0; i < full; ++i) {
-      int32_t pg = c.pool->alloc(false);
+      int32_t pg = undo.alloc();
       pp[p].shared.push_back(pg);
       prow[i] = pg;
     }
     if (has_tail) {
-      pp[p].tail = c.pool->alloc(false);
+      pp[p].tail = undo.alloc();
       prow[full] = pp[p].tail;
     }
     for (int j = 0; j < n; ++j) {
       Sample& s = fresh[(size_t)p * n + j];
       s.group = prompt_ids ? prompt_ids[p] : c.prompt_counter + p;
-      s.id = s.group * n + j;
+      s.id = (first_ids ? first_ids[p] : c.next_sample_id + (int64_t)p * n) + j;
       s.shared_len = full * T;
       s.slot = -1;
       s.prompt_len = len;
@@ -155,17 +211,16 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
       s.max_new = max_new_tokens[p * n + j];
       s.eos_id = eos_id;
       if (s.max_new <= 1) continue;
-      s.slot = c.free_slots.back();
-      c.free_slots.pop_back();
+      s.slot = undo.take_slot();
       int* srow = &c.h_page_table[(size_t)s.slot * c.max_pages];
       for (int i = 0; i < full; ++i) {
-        c.pool->retain(pp[p].shared[i]);
+        undo.retain(pp[p].shared[i]);
         s.pages.push_back(pp[p].shared[i]);
         srow[i] = pp[p].shared[i];
       }
       int total = ceil_div((long long)len + s.max_new - 1, T);
       for (int i = full; i < total; ++i) {
-        int32_t pg = c.pool->alloc(false);
+        int32_t pg = undo.alloc();
         s.pages.push_back(pg);
         srow[i] = pg;
       }
@@ -292,7 +347,8 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
   d2h(hf + 2 * R, c.out_logprobs.p, Rs * sizeof(float), c.stream);
   HIP_TRY(hipStreamSynchronize(c.stream));
 
-  // ---- host bookkeeping ----
+  // ---- host bookkeeping (nothing below throws: the pages and slots now belong to the samples) ----
+  undo.commit();
   for (int i = 0; i < Rs; ++i) {
     Sample& s = fresh[i];
     int tok = hi[7 * R + i];
@@ -309,22 +365,32 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
       release_sample(c, s);
       c.stats.samples_finished += 1;
     } else {
-      c.live.emplace(s.id, std::move(s));
+      const int64_t id = s.id;
+      Sample moved = std::move(s);
+      auto res = c.live.emplace(id, std::move(moved));
+      if (!res.second) {  // cannot happen (ids were checked above); never drop pages and a slot silently
+        release_sample(c, moved);
+        c.stats.samples_aborted += 1;
+      }
     }
   }
   for (int p = 0; p < P; ++p) {
     for (int32_t pg : pp[p].shared) c.pool->release(pg);
     if (pp[p].tail >= 0) c.pool->release(pp[p].tail);
   }
-  if (!prompt_ids) c.prompt_counter += P;
+  if (!prompt_ids) {
+    c.prompt_counter += P;
+    c.next_sample_id += (int64_t)P * n;
+  }
   c.stats.prompts_prefilled += P;
   c.live_dirty = true;
   refresh_stats(c);
 }
 
+// groups (optional): the prompt counter of every stepped sample, for the queue's bookkeeping
 static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint32_t* uniform_override,
                         int32_t* n_live, int64_t* sample_ids, int32_t* tokens, float* logprobs,
-                        uint8_t* finished) {
+                        uint8_t* finished, int64_t* groups = nullptr) {
   const rollout_model_desc& m = c.md;
   if (!n_live) fail(ROLLOUT_E_INVAL, "n_live is null");
   const int B = (int)c.live.size(), R = c.r_max;
@@ -451,6 +517,7 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
     s.last_token = tok;
     bool done = s.n_emitted >= s.max_new || (s.eos_id >= 0 && tok == s.eos_id);
     if (sample_ids) sample_ids[i] = s.id;
+    if (groups) groups[i] = s.group;
     if (tokens) tokens[i] = tok;
     if (logprobs) logprobs[i] = c.h_float.p[i];
     if (finished) finished[i] = done ? 1 : 0;
@@ -645,6 +712,7 @@ int rollout_init(rollout_ctx** out, const rollout_model_desc* model, const rollo
     c->md = *model;
     c->rd = *runtime;
     engine_init(*c, *weights);
+    if (const char* t = std::getenv("ROLLOUT_STEP_TIMEOUT_MS")) c->step_timeout_s = std::atof(t) * 1e-3;
     refresh_stats(*c);
   });
   if (rc != ROLLOUT_OK) {
@@ -703,8 +771,10 @@ int rollout_prefill(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, 
                     int64_t* sample_ids, int32_t* first_tokens, float* first_logprobs, uint8_t* finished) {
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
+    check_usable(*ctx);
     prefill_impl(*ctx, n_prompts, tokens, offsets, n_samples, max_new_tokens, eos_id, temperature, top_p,
-                 forced_first, uniform_override, nullptr, sample_ids, first_tokens, first_logprobs, finished);
+                 forced_first, uniform_override, nullptr, nullptr, sample_ids, first_tokens, first_logprobs,
+                 finished);
   });
 }
 
@@ -713,6 +783,7 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
                         uint8_t* finished) {
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
+    check_usable(*ctx);
     decode_impl(*ctx, forced_tokens, uniform_override, n_live, sample_ids, tokens, logprobs, finished);
   });
 }
@@ -725,9 +796,10 @@ static void admission_cost(const rollout_ctx& c, const QueuedPrompt& q, int n, i
   pages = plan_pages((int)q.tokens.size(), c.rd.page_tokens, n, q.max_new.data(), nullptr, nullptr, nullptr);
 }
 
-// a finished sample of an admitted prompt: the prompt is complete when its last one ends
-static void queue_note_finished(PromptQueue& q, int64_t sample_id) {
-  auto it = q.open.find(sample_id / q.n_samples);
+// a sample of prompt `group` has ended (finished, or aborted by the caller): the prompt is
+// complete when its last one ends
+static void queue_note_finished(PromptQueue& q, int64_t group) {
+  auto it = q.open.find(group);
   if (it == q.open.end()) return;  // admitted through rollout_prefill, not through the queue
   if (--it->second == 0) {
     q.open.erase(it);
@@ -737,10 +809,11 @@ static void queue_note_finished(PromptQueue& q, int64_t sample_id) {
 
 int rollout_queue_push(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, const int32_t* offsets,
                        int32_t n_samples, const int32_t* max_new_tokens, int32_t eos_id, float temperature,
-                       float top_p, int64_t* prompt_ids) {
+                       float top_p, int64_t* first_sample_ids) {
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
     rollout_ctx& c = *ctx;
+    check_usable(c);
     PromptQueue& q = c.queue;
     const int P = n_prompts, n = n_samples;
     if (P < 1 || n < 1 || !tokens || !offsets || !max_new_tokens) fail(ROLLOUT_E_INVAL, "bad prompt arguments");
@@ -777,7 +850,9 @@ int rollout_queue_push(rollout_ctx* ctx, int32_t n_prompts, const int32_t* token
     q.n_samples = n;
     for (int p = 0; p < P; ++p) {
       fresh[p].prompt_id = c.prompt_counter++;
-      if (prompt_ids) prompt_ids[p] = fresh[p].prompt_id;
+      fresh[p].first_sample = c.next_sample_id;
+      c.next_sample_id += n;
+      if (first_sample_ids) first_sample_ids[p] = fresh[p].first_sample;
       q.waiting.push_back(std::move(fresh[p]));
     }
     q.pushed += P;
@@ -809,6 +884,7 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
   return guarded(ctx, [&] {
     rollout_ctx& c = *ctx;
     PromptQueue& q = c.queue;
+    check_usable(c);
     if (!n_out || !n_admitted) fail(ROLLOUT_E_INVAL, "n_out / n_admitted is null");
     const int cap = *n_out, n = q.n_samples;
     *n_out = 0;
@@ -839,7 +915,7 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
     int n_adm = 0;
     if (k > 0) {
       std::vector<int32_t> toks, offs(1, 0), max_new;
-      std::vector<int64_t> pids;
+      std::vector<int64_t> pids, firsts;
       toks.reserve((size_t)rows);
       for (int i = 0; i < k; ++i) {
         const QueuedPrompt& e = q.waiting[i];
@@ -847,6 +923,7 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
         offs.push_back((int32_t)toks.size());
         max_new.insert(max_new.end(), e.max_new.begin(), e.max_new.end());
         pids.push_back(e.prompt_id);
+        firsts.push_back(e.first_sample);
       }
       n_adm = k * n;
       std::vector<int64_t> ids_local(n_adm);
@@ -854,12 +931,13 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
       const int eos_id = q.waiting[0].eos_id;
       const float temperature = q.waiting[0].temperature, top_p = q.waiting[0].top_p;
       prefill_impl(c, k, toks.data(), offs.data(), n, max_new.data(), eos_id, temperature, top_p,
-                   nullptr, nullptr, pids.data(), ids_local.data(), tokens, logprobs, fin_local.data());
+                   nullptr, nullptr, pids.data(), firsts.data(), ids_local.data(), tokens, logprobs,
+                   fin_local.data());
       for (int i = 0; i < k; ++i) q.open[pids[i]] = n;
       for (int i = 0; i < n_adm; ++i) {
         if (sample_ids) sample_ids[i] = ids_local[i];
         if (finished) finished[i] = fin_local[i];
-        if (fin_local[i]) queue_note_finished(q, ids_local[i]);
+        if (fin_local[i]) queue_note_finished(q, pids[i / n]);
       }
       q.waiting.erase(q.waiting.begin(), q.waiting.begin() + k);
       q.admitted += k;
@@ -867,14 +945,14 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
 
     // (2) one decode step over everything that is live now
     int n_dec = cap - n_adm;
-    std::vector<int64_t> ids_dec(c.live.size());
+    std::vector<int64_t> ids_dec(c.live.size()), grp_dec(c.live.size());
     std::vector<uint8_t> fin_dec(c.live.size());
     decode_impl(c, nullptr, nullptr, &n_dec, ids_dec.data(), tokens ? tokens + n_adm : nullptr,
-                logprobs ? logprobs + n_adm : nullptr, fin_dec.data());
+                logprobs ? logprobs + n_adm : nullptr, fin_dec.data(), grp_dec.data());
     for (int i = 0; i < n_dec; ++i) {
       if (sample_ids) sample_ids[n_adm + i] = ids_dec[i];
       if (finished) finished[n_adm + i] = fin_dec[i];
-      if (fin_dec[i]) queue_note_finished(q, ids_dec[i]);
+      if (fin_dec[i]) queue_note_finished(q, grp_dec[i]);
     }
     *n_admitted = n_adm;
     *n_out = n_adm + n_dec;
@@ -900,6 +978,7 @@ int rollout_extend(rollout_ctx* ctx, int32_t n, const int64_t* sample_ids, const
                    int32_t* next_tokens, float* next_logprobs, uint8_t* finished) {
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
+    check_usable(*ctx);
     extend_impl(*ctx, n, sample_ids, tokens, offsets, forced_next, uniform_override, next_tokens, next_logprobs,
                 finished);
   });
@@ -909,6 +988,7 @@ int rollout_update_weights(rollout_ctx* ctx, int32_t n, const rollout_tensor_upd
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
     rollout_ctx& c = *ctx;
+    check_usable(c);
     if (n < 0 || (n > 0 && !updates)) fail(ROLLOUT_E_INVAL, "bad arguments");
     if (!c.live.empty() || !c.queue.waiting.empty())
       fail(ROLLOUT_E_STATE, "weights cannot change while samples are live or prompts wait");
@@ -929,6 +1009,7 @@ int rollout_abort(rollout_ctx* ctx, int32_t n, const int64_t* sample_ids) {
   for (int i = 0; i < n; ++i) {
     auto it = ctx->live.find(sample_ids[i]);
     if (it == ctx->live.end()) continue;
+    queue_note_finished(ctx->queue, it->second.group);  // it no longer holds its prompt open
     release_sample(*ctx, it->second);
     ctx->live.erase(it);
     ++aborted;
@@ -973,6 +1054,7 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
   if (!ctx) return ROLLOUT_E_INVAL;
   return guarded(ctx, [&] {
     rollout_ctx& c = *ctx;
+    check_usable(c);
     const rollout_model_desc& m = c.md;
     const int T = c.rd.page_tokens, R = c.r_max;
     if (n_seqs < 0 || !cu_seqlens || (n_seqs > 0 && (!tokens || !logprobs))) fail(ROLLOUT_E_INVAL, "null argument");
@@ -999,7 +1081,7 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
         pages += ceil_div(len, T);
         ++s1;
       }
-      std::vector<int32_t> held;
+      Rollback held(c);  // the chunk's scratch pages: back to the pool however the chunk ends
       int* ht = c.h_int.p;
       int r = 0, max_len = 0;
       for (int s = s0; s < s1; ++s) {
@@ -1009,11 +1091,7 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
         ht[6 * R + (s - s0)] = c.temp_slot0 + (s - s0);
         max_len = std::max(max_len, len);
         int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + (s - s0)) * c.max_pages];
-        for (int i = 0; i < ceil_div(len, T); ++i) {
-          int32_t pg = c.pool->alloc(false);
-          held.push_back(pg);
-          prow[i] = pg;
-        }
+        for (int i = 0; i < ceil_div(len, T); ++i) prow[i] = held.alloc();
         for (int i = 0; i < len; ++i, ++r) {
           int g = cu_seqlens[s] + i;
           ht[r] = tokens[g];
@@ -1053,13 +1131,52 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
         for (int i = 0; i + 1 < len; ++i) logprobs[a + i + 1] = c.h_float.p[r + i];
         r += len;
       }
-      for (int32_t pg : held) c.pool->release(pg);
       c.last_logit_rows = 0;
       s0 = s1;
     }
     refresh_stats(c);
   });
 }
+
+}  // extern "C"
+
+// Device scratch of the two context-free entry points below: one grow-only buffer per device,
+// kept until the process ends, so that a call allocates only when it needs more than any call
+// before it.  The mutex is held for the whole call (both calls return after their stream has
+// drained), so calls on one device take turns.
+namespace {
+struct CallScratch {
+  std::mutex mu;
+  char* p = nullptr;
+  size_t bytes = 0;
+  size_t used = 0;
+  void begin() { used = 0; }
+  void reserve(size_t need) {
+    if (need <= bytes) return;
+    if (p) (void)hipFree(p);
+    p = nullptr;
+    bytes = 0;
+    HIP_TRY(hipMalloc((void**)&p, need));
+    bytes = need;
+  }
+  template <typename T>
+  T* take(size_t count) {  // after reserve(): 256-byte aligned pieces of the buffer
+    T* out = (T*)(p + used);
+    used += (count * sizeof(T) + 255) / 256 * 256;
+    return out;
+  }
+  static size_t piece(size_t bytes_) { return (bytes_ + 255) / 256 * 256; }
+};
+CallScratch& call_scratch() {
+  static CallScratch per_device[64];
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) throw ApiError{ROLLOUT_E_HIP, "device index out of range"};
+  return per_device[dev];
+}
+}  // namespace
+
+extern "C" {
 
 int rollout_sample(const float* logits, int32_t rows, int32_t vocab, float temperature, float top_p,
                    const uint32_t* uniforms, const int32_t* forced, void* hip_stream, int32_t* tokens,
@@ -1073,37 +1190,38 @@ int rollout_sample(const float* logits, int32_t rows, int32_t vocab, float tempe
         if (forced[i] >= vocab) fail(ROLLOUT_E_INVAL, "forced token out of range");
     if (rows == 0) return;
     hipStream_t s = (hipStream_t)hip_stream;
-    DevBuf<float> invt, tp, lp;
-    DevBuf<unsigned> un;
-    DevBuf<int> fo, tok;
-    DevBuf<unsigned long long> ws;
+    CallScratch& cs = call_scratch();
+    std::lock_guard<std::mutex> lock(cs.mu);
+    const size_t R = rows;
+    cs.reserve(4 * CallScratch::piece(R * 4) + 2 * CallScratch::piece(R * 4) + CallScratch::piece(R * 8) +
+               CallScratch::piece(R * kSampleParts * 4) + CallScratch::piece(R * kSampleSegments * 8));
+    cs.begin();
+    float *invt = cs.take<float>(R), *tp = cs.take<float>(R), *lp = cs.take<float>(R);
+    unsigned* un = cs.take<unsigned>(R);
+    int *fo = cs.take<int>(R), *tok = cs.take<int>(R);
+    unsigned long long* ws = cs.take<unsigned long long>(R);
     std::vector<float> hv(rows, 1.0f / temperature), hp(rows, top_p);
-    invt.alloc(rows); tp.alloc(rows); lp.alloc(rows); un.alloc(rows); fo.alloc(rows); tok.alloc(rows); ws.alloc(rows);
-    HIP_TRY(hipMemcpyAsync(invt.p, hv.data(), rows * sizeof(float), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(tp.p, hp.data(), rows * sizeof(float), hipMemcpyHostToDevice, s));
-    HIP_TRY(hipMemcpyAsync(un.p, uniforms, rows * sizeof(unsigned), hipMemcpyHostToDevice, s));
-    if (forced) HIP_TRY(hipMemcpyAsync(fo.p, forced, rows * sizeof(int), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(invt, hv.data(), rows * sizeof(float), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(tp, hp.data(), rows * sizeof(float), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync(un, uniforms, rows * sizeof(unsigned), hipMemcpyHostToDevice, s));
+    if (forced) HIP_TRY(hipMemcpyAsync(fo, forced, rows * sizeof(int), hipMemcpyHostToDevice, s));
     HIP_TRY(hipStreamSynchronize(s));  // host staging vectors are pageable
     SampleRows sr{};
     sr.logits = logits;
-    sr.inv_temp = invt.p;
-    sr.top_p = tp.p;
-    sr.uniforms = un.p;
-    sr.forced = forced ? fo.p : nullptr;
-    sr.tokens = tok.p;
-    sr.logprobs = lp.p;
-    sr.weight_sums = ws.p;
-    DevBuf<float> pm;
-    DevBuf<unsigned long long> sg;
-    pm.alloc((size_t)rows * kSampleParts);
-    sg.alloc((size_t)rows * kSampleSegments);
-    sr.part_max = pm.p;
-    sr.seg_sums = sg.p;
+    sr.inv_temp = invt;
+    sr.top_p = tp;
+    sr.uniforms = un;
+    sr.forced = forced ? fo : nullptr;
+    sr.tokens = tok;
+    sr.logprobs = lp;
+    sr.weight_sums = ws;
+    sr.part_max = cs.take<float>(R * kSampleParts);
+    sr.seg_sums = cs.take<unsigned long long>(R * kSampleSegments);
     launch_sample(sr, rows, vocab, s);
-    HIP_TRY(hipMemcpyAsync(tokens, tok.p, rows * sizeof(int), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipMemcpyAsync(logprobs, lp.p, rows * sizeof(float), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(tokens, tok, rows * sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(logprobs, lp, rows * sizeof(float), hipMemcpyDeviceToHost, s));
     if (weight_sums)
-      HIP_TRY(hipMemcpyAsync(weight_sums, ws.p, rows * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipMemcpyAsync(weight_sums, ws, rows * sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
   });
 }
@@ -1124,12 +1242,14 @@ int rollout_policy_loss(int32_t n_seqs, const int32_t* cu_seqlens, const float* 
         !(q.eps_high >= 0.f) || !std::isfinite(q.kl_coef))
       fail(ROLLOUT_E_INVAL, "bad loss parameters");
     hipStream_t s = (hipStream_t)hip_stream;
-    DevBuf<int> cu;
-    DevBuf<float> rw, part, result;
-    cu.alloc(n_seqs + 1);
-    rw.alloc(std::max(n_seqs, 1));
-    part.alloc(2 * (size_t)std::max(n_seqs, 1));
-    result.alloc(2);
+    CallScratch& cs = call_scratch();
+    std::lock_guard<std::mutex> lock(cs.mu);
+    const size_t S1 = (size_t)std::max(n_seqs, 1);
+    cs.reserve(CallScratch::piece((S1 + 1) * 4) + CallScratch::piece(S1 * 4) + CallScratch::piece(2 * S1 * 4) +
+               CallScratch::piece(2 * 4));
+    cs.begin();
+    struct { int* p; } cu{cs.take<int>(S1 + 1)};
+    struct { float* p; } rw{cs.take<float>(S1)}, part{cs.take<float>(2 * S1)}, result{cs.take<float>(2)};
     HIP_TRY(hipMemcpyAsync(cu.p, cu_seqlens, (n_seqs + 1) * sizeof(int), hipMemcpyHostToDevice, s));
     if (n_seqs) HIP_TRY(hipMemcpyAsync(rw.p, rewards, n_seqs * sizeof(float), hipMemcpyHostToDevice, s));
     PolicyLossArgs p{};

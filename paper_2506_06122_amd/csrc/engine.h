@@ -159,7 +159,8 @@ struct Sample {
 
 // Prompts waiting for admission and the bookkeeping of the queue-fed rollout (host only).
 struct QueuedPrompt {
-  int64_t prompt_id;
+  int64_t prompt_id;     // the prompt's counter (what its samples' `group` will be)
+  int64_t first_sample;  // id of its sample 0; sample j carries first_sample + j
   std::vector<int32_t> tokens, max_new;  // max_new: one per sample
   int eos_id;
   float temperature, top_p;
@@ -209,7 +210,10 @@ struct rollout_ctx {
   // sample table
   std::map<int64_t, Sample> live;
   std::vector<int> free_slots;
-  int64_t prompt_counter = 0;
+  int64_t prompt_counter = 0;   // prompts ever admitted or queued
+  int64_t next_sample_id = 0;   // ids are handed out consecutively, n per prompt, at prefill or push time
+  bool broken = false;          // a step timed out: the device state is unknown, every call is refused
+  double step_timeout_s = 300;  // wall-clock bound of the wait that ends a decode step
   PromptQueue queue;
   bool live_dirty = true;
   DevBuf<int> d_live;

@@ -62,7 +62,7 @@ struct SampleRows {
   const unsigned* uniforms; // [rows] or NULL -> Philox(seed, sample_id, step)
   const long long* sample_id;  // [rows] (Philox only)
   const int* step;             // [rows] (Philox only)
-  const int* forced;        // [rows] or NULL; entries < 0 mean "draw"
+  const int* forced;        // [rows] or NULL; entries outside [0, vocab) mean "draw"
   unsigned long long seed;
   int* tokens;              // out [rows]
   float* logprobs;          // out [rows]

@@ -339,7 +339,7 @@ __global__ __launch_bounds__(SAMP_T) void sample_kernel(SampleRows a, int vocab,
   const unsigned long long S = block_sum_u64(local, sh);  // also orders the writes to sh.vals
 
   int token = a.forced ? a.forced[r] : -1;
-  if (token < 0) {
+  if ((unsigned)token >= (unsigned)vocab) {  // nothing forced (an id outside the vocabulary forces nothing)
     const float top_p = a.top_p[r];
     // nucleus membership: w > tau, or w == tau and id <= tie_cut
     unsigned long long tau = 0, s_n = S;

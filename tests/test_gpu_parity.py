@@ -77,10 +77,11 @@ def test_teacher_forced_logits_match_oracle(name, simple):
     print(f"{name}: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
     assert worst <= TOL[shape.dtype]
     assert worst_lp <= TOL[shape.dtype]
-    if shape.is_moe:      # the GPU's expert sets are optimal up to rounding in the oracle's own router logits
-        regret = max(model.routing_regret)
-        print(f"{name}: worst routing regret = {regret:.3e} over {len(model.routing_regret)} decisions")
-        assert regret <= TOL[shape.dtype]
+    if shape.is_moe:      # the GPU's expert sets are the top-k of the oracle's own router logits up to rounding
+        below, outside = (max(g[i] for g in model.routing_regret) for i in (0, 1))
+        print(f"{name}: worst routing gaps = {below:.3e} (k-th logit above the weakest pick), {outside:.3e} "
+              f"(best expert left out above the weakest pick) over {len(model.routing_regret)} decisions")
+        assert below <= TOL[shape.dtype] and outside <= TOL[shape.dtype]
     st = eng.rollout_get_stats()
     assert st["live_samples"] == 0 and st["pages_in_use"] == 0
     assert st["matrix_core_path"] == int(not simple and shape.dtype == "bf16")
@@ -222,10 +223,75 @@ def test_matrix_core_moe_row_blocks(n_prompts, n_samples, lo, hi):
     steps = 3
     forced = np.random.default_rng(9).integers(0, shape.vocab, (n_prompts * n_samples, steps)).astype(np.int32)
     worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, n_samples, forced, steps)
-    regret = max(model.routing_regret)
-    print(f"max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}, routing regret {regret:.3e}")
-    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"] and regret <= TOL["bf16"]
+    below, outside = (max(g[i] for g in model.routing_regret) for i in (0, 1))
+    print(f"max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}, routing gaps {below:.3e} / {outside:.3e}")
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"] and below <= TOL["bf16"] and outside <= TOL["bf16"]
     assert eng.rollout_get_stats()["matrix_core_path"] == 1
+    eng.close()
+
+
+@pytest.mark.parametrize("name,simple", [("tiny-moe-fp32", True), ("tiny-moe-fp32", False), ("small-moe-bf16", False)],
+                         ids=["fp32-plain", "fp32-default", "bf16-fast"])
+def test_moe_routing_decided_independently(name, simple):
+    """The GPU and the oracle route on their own: no expert set is handed from one to the
+    other.  The GPU's recorded sets must be the oracle's `route()` result wherever the oracle's
+    own gap between the k-th and the (k+1)-th router logit exceeds what rounding can move
+    (1e-5 for the fp32 model, the logits tolerance for the bf16 model); for the fp32 model the
+    logits of the two independent runs must agree as well (a routing difference on a near-tie
+    of that size moves them by less than the tolerance)."""
+    shape, scale, kw = CASES[name]
+    w = scaled_weights(shape, seed=1, scale=scale)
+    model = oracle_model(shape, w)
+    model.routing_trace = []
+    eng = make_engine(shape, w, flags=(1 if simple else 0) | 2, **kw)
+    P, n, steps, k = 3, 2, 5, shape.top_k
+    toks, offs = workloads.make_prompts(P, 5, 70, shape.vocab, seed=2)
+    forced = np.random.default_rng(4).integers(0, shape.vocab, (P * n, steps)).astype(np.int32)
+    margin = 1e-5 if shape.dtype == "fp32" else TOL["bf16"]
+    fwd = T.KVForward(model)
+
+    def compare_routing(gpu_sets, n_rows):
+        """gpu_sets [layers][rows][k] against the oracle's trace of the forward it just ran."""
+        trace, decided, near = model.routing_trace, 0, 0
+        assert len(trace) == shape.n_layers * n_rows
+        for i, (layer, r, experts) in enumerate(trace):
+            row = i % n_rows
+            assert layer == i // n_rows
+            srt = np.sort(r)[::-1]
+            got = set(int(e) for e in gpu_sets[layer][row])
+            assert len(got) == k
+            if srt[k - 1] - srt[k] > margin:
+                assert got == set(int(e) for e in experts), f"layer {layer} row {row}"
+                decided += 1
+            else:
+                near += 1
+        model.routing_trace = []
+        return decided, near
+
+    ids, tk, lps, fin = eng.rollout_prefill(toks, offs, n, np.full(P * n, steps, np.int32), forced_first=forced[:, 0])
+    gpu_logits = eng.rollout_debug_logits()
+    routing = eng.rollout_debug_routing(int(offs[-1]))
+    caches, worst, decided, near = [], 0.0, 0, 0
+    for p in range(P):
+        prefix = fwd.new_cache()
+        ref = fwd.extend([prefix], [toks[offs[p]:offs[p + 1]]])[0][-1]
+        d, m = compare_routing([routing[l][offs[p]:offs[p + 1]] for l in range(shape.n_layers)], int(offs[p + 1] - offs[p]))
+        decided, near = decided + d, near + m
+        worst = max(worst, float(np.max(np.abs(gpu_logits[p] - ref))))
+        caches += [prefix.fork() for _ in range(n)]
+    for t in range(1, steps):
+        eng.rollout_decode_step(forced_tokens=forced[:, t])
+        gpu_logits = eng.rollout_debug_logits()
+        routing = eng.rollout_debug_routing(P * n)
+        ref = fwd.extend(caches, [[int(x)] for x in forced[:, t - 1]])
+        d, m = compare_routing(routing, P * n)
+        decided, near = decided + d, near + m
+        worst = max([worst] + [float(np.max(np.abs(gpu_logits[i] - ref[i][0]))) for i in range(P * n)])
+    print(f"{name}: {decided} routing decisions identical, {near} within the margin and not compared; "
+          f"max |dlogits| without any override = {worst:.3e}")
+    assert decided > 10 * max(near, 1)
+    if shape.dtype == "fp32":
+        assert worst <= TOL["fp32"]
     eng.close()
 
 
@@ -286,6 +352,35 @@ def test_teacher_forced_logprob_pass_matches_oracle():
         assert all(got[a] == 0.0 for a in cu[:-1])
         assert eng.rollout_get_stats()["pages_in_use"] == 0
         eng.close()
+
+
+def test_logprob_pass_at_config5_logits_shape():
+    """The teacher-forced pass as config 5 runs it - the 7B matrix shapes, hidden 3584, the full
+    152064-entry vocabulary (1188 column parts per row in the fused log-sum-exp), chunks of more
+    than 512 packed rows (the 64 x 256 tile plan) - with the layer count cut to 2 so that the
+    fp64 oracle fits: 8 sequences of 1 to 320 tokens in three chunks of up to 640 rows."""
+    import dataclasses
+    shape = dataclasses.replace(workloads.C3_7B, n_layers=2, name="qwen2.5-7b-shape-2-layers")
+    w = workloads.make_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, kv_pool_bytes=64 << 20, max_live_samples=8, max_context=512, max_batch_tokens=640)
+    lens = [200, 150, 260, 300, 320, 17, 1, 280]          # chunks: 610 rows, 620 rows, 298 rows
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    toks = np.random.Generator(np.random.Philox(key=[31, 5])).integers(0, shape.vocab, int(cu[-1])).astype(np.int32)
+    got = eng.rollout_logprobs(toks, cu, temperature=1.0)
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1 and eng.rollout_get_stats()["pages_in_use"] == 0
+    eng.close()
+    want = T.packed_log_probs(model, toks, cu, temperature=1.0)
+    err = float(np.max(np.abs(got - want)))
+    print(f"{shape.name}, vocab {shape.vocab}, {int(cu[-1])} rows in 3 chunks: max |dlogp| = {err:.3e}; "
+          f"mean log-prob {want[want != 0].mean():.3f}")
+    assert err <= TOL["bf16"]
+    assert all(got[a] == 0.0 for a in cu[:-1])
+    # a row's result does not depend on its chunk: the same sequence alone gives the same bits
+    eng = make_engine(shape, w, kv_pool_bytes=64 << 20, max_live_samples=8, max_context=512, max_batch_tokens=640)
+    alone = eng.rollout_logprobs(toks[cu[3]:cu[4]], [0, lens[3]], temperature=1.0)
+    eng.close()
+    assert float(np.max(np.abs(alone - got[cu[3]:cu[4]]))) <= 1e-5
 
 
 def test_lifecycle_add_abort_eos_and_batch_invariance():

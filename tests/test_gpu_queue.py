@@ -57,7 +57,7 @@ def test_queue_fed_rollout_reproduces_per_sample_results():
         eng.rollout_queue_push(toks[:offs[5]], offs[:6], n, max_new[:5 * n], temperature=temperature, top_p=top_p),
         eng.rollout_queue_push(toks[offs[5]:], offs[5:] - offs[5], n, max_new[5 * n:], temperature=temperature,
                                top_p=top_p)])
-    assert pids.tolist() == list(range(P))
+    assert pids.tolist() == [p * n for p in range(P)]      # the id of each prompt's sample 0
     assert eng.rollout_queue_get_stats()["prompts_waiting"] == P
     seqs, order, peak = drain(eng, max_live=6)
     qs, st = eng.rollout_queue_get_stats(), eng.rollout_get_stats()
@@ -169,3 +169,102 @@ def test_queue_push_rejects_what_can_never_run():
     ids, tk, lps, fin, n_adm = eng.rollout_queue_step()
     assert n_adm == 2 and ids.tolist() == [0, 1, 0, 1] and fin.tolist() == [False, False, True, False]
     eng.close()
+
+
+def test_sample_ids_stay_unique_when_calls_use_different_sample_counts():
+    """Ids are handed out consecutively: one prompt with 8 samples takes 0..7, four prompts
+    with 2 samples each take 8..15 (a scheme that multiplied a prompt counter by the call's n
+    would hand out 2..9 and collide).  Every sample is live with its own Philox stream: its
+    first token is the oracle sampler's choice for (seed, its id, position 0)."""
+    from oracle import philox, sampler
+    shape = workloads.C1_TINY
+    w = scaled_weights(shape, seed=1)
+    eng = make_engine(shape, w, max_live_samples=32, max_context=128, max_batch_tokens=256, seed=21)
+    toks, offs = workloads.make_prompts(5, 6, 30, shape.vocab, seed=61)
+    inv_t = sampler.inv_temperature(1.0)
+    ids_a, tk_a, _, _ = eng.rollout_prefill(toks[:offs[1]], offs[:2], 8, np.full(8, 6, np.int32), top_p=0.9)
+    rows_a = eng.rollout_debug_logits()
+    ids_b, tk_b, _, _ = eng.rollout_prefill(toks[offs[1]:], offs[1:] - offs[1], 2, np.full(8, 6, np.int32), top_p=0.9)
+    rows_b = eng.rollout_debug_logits()
+    assert ids_a.tolist() == list(range(8)) and ids_b.tolist() == list(range(8, 16))
+    assert eng.rollout_live_samples().tolist() == list(range(16))
+    for k, sid in enumerate(ids_a):
+        assert sampler.sample(rows_a[0], inv_t, 0.9, philox.rollout_uniform(21, int(sid), 0))[0] == tk_a[k]
+    for k, sid in enumerate(ids_b):
+        assert sampler.sample(rows_b[k // 2], inv_t, 0.9, philox.rollout_uniform(21, int(sid), 0))[0] == tk_b[k]
+    pages = eng.rollout_get_stats()["pages_in_use"]
+    assert pages > 0
+    for t in range(1, 6):
+        ids, tk, lps, fin = eng.rollout_decode_step()
+        assert ids.tolist() == list(range(16)) and fin.all() == (t == 5)
+    st = eng.rollout_get_stats()
+    assert st["live_samples"] == 0 and st["pages_in_use"] == 0 and st["samples_finished"] == 16
+    eng.close()
+
+
+def test_queue_steps_over_plain_prefills_and_counts_caller_aborts():
+    """rollout_queue_step on samples that came in through rollout_prefill before any push (the
+    queue then has no sample count of its own), and a caller's abort of a queued prompt's sample:
+    the prompt is complete once its other sample has ended, so a target still closes the queue."""
+    shape = workloads.C1_TINY
+    w = scaled_weights(shape, seed=1)
+    eng = make_engine(shape, w, max_live_samples=8, max_context=128, max_batch_tokens=256, seed=5)
+    toks, offs = workloads.make_prompts(3, 4, 30, shape.vocab, seed=71)
+    ids, _, _, _ = eng.rollout_prefill(toks[:offs[1]], offs[:2], 3, np.array([3, 2, 4], np.int32))
+    assert ids.tolist() == [0, 1, 2]
+    seen = 0
+    while True:
+        out_ids, tk, lps, fin, n_adm = eng.rollout_queue_step()
+        if not len(out_ids):
+            break
+        assert n_adm == 0
+        seen += len(out_ids)
+    assert seen == (3 - 1) + (2 - 1) + (4 - 1) and eng.rollout_get_stats()["pages_in_use"] == 0
+    assert eng.rollout_queue_get_stats()["prompts_completed"] == 0     # they never were the queue's
+    # two queued prompts x 2 samples, target 1: abort sample 1 of the first prompt by hand
+    eng.rollout_queue_policy(admit_min_prompts=1, target_prompts=1)
+    first = eng.rollout_queue_push(toks[offs[1]:], offs[1:] - offs[1], 2, np.array([4, 30, 30, 30], np.int32))
+    assert first.tolist() == [3, 5]
+    out_ids, tk, lps, fin, n_adm = eng.rollout_queue_step()
+    assert n_adm == 4 and out_ids[:4].tolist() == [3, 4, 5, 6]
+    assert eng.rollout_abort([4]) == 1
+    steps = 1
+    while not eng.rollout_queue_get_stats()["closed"]:
+        out_ids, tk, lps, fin, n_adm = eng.rollout_queue_step()
+        assert len(out_ids) and 4 not in out_ids
+        steps += 1
+        assert steps < 10
+    qs, st = eng.rollout_queue_get_stats(), eng.rollout_get_stats()
+    assert steps == 3                      # sample 3 emits positions 0, 1 in step 1, then 2, 3
+    assert qs["prompts_completed"] == 1 and qs["samples_aborted"] == 2 and st["samples_aborted"] == 3
+    assert st["live_samples"] == 0 and st["pages_in_use"] == 0
+    eng.close()
+
+
+def test_decode_step_wait_is_bounded(monkeypatch):
+    """The wait that ends a decode step gives up after a wall-clock limit instead of polling for
+    ever.  With the limit forced to zero from the host the step's (perfectly healthy) kernels
+    are still running when the first poll comes back: the call returns E_HIP, the context then
+    refuses further calls with E_STATE, and destroying it drains the stream."""
+    import paper_2506_06122_amd as R
+    shape = workloads.C1_TINY
+    w = scaled_weights(shape, seed=1)
+    monkeypatch.setenv("ROLLOUT_STEP_TIMEOUT_MS", "0")
+    eng = make_engine(shape, w)
+    monkeypatch.delenv("ROLLOUT_STEP_TIMEOUT_MS")
+    toks, offs = workloads.make_prompts(2, 10, 20, shape.vocab, seed=81)
+    eng.rollout_prefill(toks, offs, 2, np.full(4, 5, np.int32))
+    with pytest.raises(R.RolloutError) as e:
+        eng.rollout_decode_step()
+    assert e.value.code == -3 and "did not finish" in str(e.value)
+    with pytest.raises(R.RolloutError) as e:
+        eng.rollout_decode_step()
+    assert e.value.code == -4
+    with pytest.raises(R.RolloutError) as e:
+        eng.rollout_prefill(toks, offs, 2, np.full(4, 5, np.int32))
+    assert e.value.code == -4
+    eng.close()
+    ok = make_engine(shape, w)                      # a fresh context works as ever
+    ok.rollout_prefill(toks, offs, 2, np.full(4, 3, np.int32))
+    assert len(ok.rollout_decode_step()[0]) == 4
+    ok.close()

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), f"{n} declared in rollout.h but not exported"
     assert set(names) == set(B.SIGNATURES), "binding and header disagree on the entry points"
-    assert lib.rollout_abi_version() == 2
+    assert lib.rollout_abi_version() == 3
 
 
 def test_init_validates_and_fails_loudly_without_gpu():

@@ -1,5 +1,6 @@
 """Pins for the CPU oracle's generation loop (no GPU)."""
 import numpy as np
+import pytest
 
 import workloads
 from oracle import philox, rollout, sampler
@@ -91,3 +92,20 @@ def test_batched_slice_emits_expected_count():
     m = model()
     toks, offs = prompts()
     assert rollout.decode_slice_batched(m, toks[:offs[1]], 3, 4, 1.0, 1.0, 1) == 12
+
+
+@pytest.mark.parametrize("temperature,top_p", [(1.0, 1.0), (0.7, 0.9)])
+def test_batched_slice_draws_the_tokens_of_the_per_sample_rollout(temperature, top_p):
+    """The function the benchmark times as the CPU baseline stacks the samples' rows into one
+    matrix per step; `generate` runs one sample at a time.  Same prompt, same seed, sample ids
+    0..n-1, no end-of-sequence token: the two must emit the same tokens."""
+    m = model()
+    toks, offs = prompts()
+    prompt = toks[:offs[1]]
+    n, n_new = 4, 9
+    got = []
+    assert rollout.decode_slice_batched(m, prompt, n, n_new, temperature, top_p, 11, out_tokens=got) == n * n_new
+    ref = rollout.generate(m, prompt, [0, len(prompt)], n, np.full(n, n_new, np.int32), -1, temperature, top_p, 11)
+    assert [t.sample_id for t in ref] == list(range(n))
+    assert got == [t.tokens for t in ref]
+    assert len({tuple(g) for g in got}) > 1      # the samples do differ from one another

@@ -86,6 +86,30 @@ def test_route_topk_and_ties():
     assert list(e2) == idx.tolist()
 
 
+def test_routing_gaps_accept_the_top_k_and_nothing_else():
+    """The validity check the GPU's recorded expert sets go through: both gaps are <= 0 for
+    the top-k (whatever member a tie picks) and for no other set; a set that swaps the best
+    expert for the runner-up of a near-tie at the k-th place - which looks harmless to a check
+    of the weakest member alone - shows in the second gap."""
+    import itertools
+    r = np.array([3.0, 2.0, 1.0 + 1e-9, 1.0, -0.5, 0.2])
+    k = 3
+    top = set(T.route(r, k)[0].tolist())
+    assert top == {0, 1, 2}
+    for chosen in itertools.combinations(range(len(r)), k):
+        below, outside = T.routing_gaps(r, chosen, k)
+        assert (max(below, outside) <= 0) == (set(chosen) == top)
+        # brute force of the two definitions
+        worst_member = min(r[list(chosen)])
+        assert below == np.sort(r)[::-1][k - 1] - worst_member
+        assert outside == max(r[i] for i in range(len(r)) if i not in chosen) - worst_member
+    below, outside = T.routing_gaps(r, [1, 2, 3], k)       # dropped the best expert, kept the near-tie pair
+    assert below <= 1e-8 and outside == 3.0 - 1.0
+    tie = np.array([1.0, 2.0, 1.0, 0.0])
+    assert max(T.routing_gaps(tie, [1, 0], 2)) <= 0 and max(T.routing_gaps(tie, [1, 2], 2)) <= 0
+    assert T.routing_gaps(np.array([0.3, 0.1]), [0, 1], 2) == (0.0, -np.inf)   # k = E: nothing is left out
+
+
 # ---------------------------------------------------------------- whole forward vs library routines
 def torch_forward(shape, w, tokens):
     """The same network composed from torch library routines in fp64."""
