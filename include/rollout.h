@@ -345,6 +345,28 @@ int rollout_sample(const float *logits, int32_t rows, int32_t vocab, float tempe
                    const uint32_t *uniforms, const int32_t *forced, void *hip_stream, int32_t *tokens,
                    float *logprobs, uint64_t *weight_sums);
 
+/* rollout_sample for callers that cannot allocate device memory or wait: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels and results as
+ * rollout_sample, but every array is DEVICE memory - logits [rows][vocab], uniforms uint32 [rows],
+ * forced int32 [rows] or NULL (ids outside [0, vocab) are drawn), tokens int32 [rows], logprobs
+ * float [rows], weight_sums uint64 [rows] or NULL - and the call only enqueues kernels on
+ * hip_stream: no allocation, no host-device copy, no synchronisation; outputs are valid once the
+ * stream has reached that point.  The kernels' scratch (per-row parameters and the partial maxima
+ * and segment sums of the two sweeps, about 8.3 KB per row) is a fixed device array inside the
+ * library, one copy per GPU, kept until the process ends: rows <= ROLLOUT_SAMPLE_STATIC_MAX_ROWS,
+ * else E_INVAL.  Every call on a GPU uses that one array, which keeps the last call's contents
+ * (nothing in it has to start at zero: each call writes what it reads): calls that overlap on one
+ * GPU - two streams, two threads - race; serialise them.  The array's address is looked up on
+ * the first call on a device (rollout_init does it too); make that first call, or
+ * rollout_sample_static_prepare(), outside graph capture.  Errors: E_INVAL, E_HIP;
+ * rollout_sample_static_error() gives the calling thread's last error text. */
+#define ROLLOUT_SAMPLE_STATIC_MAX_ROWS 256
+int rollout_sample_static(const float *logits, int32_t rows, int32_t vocab, float temperature, float top_p,
+                          const uint32_t *uniforms, const int32_t *forced, void *hip_stream, int32_t *tokens,
+                          float *logprobs, uint64_t *weight_sums);
+int rollout_sample_static_prepare(void); /* looks the array up for the current device; allocates nothing */
+const char *rollout_sample_static_error(void);
+
 /* Writes words[i] = Philox4x32-10 output word 0 for key (seed lo, seed hi) and counter
  * (sample_ids[i] lo, sample_ids[i] hi, steps[i], 0), computed on the device; all arrays
  * host, length n.  Parity hook for the generator. */

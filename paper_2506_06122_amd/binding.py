@@ -107,6 +107,9 @@ SIGNATURES = {
     "rollout_destroy": (None, [_P]),
     "rollout_abi_version": (C.c_int, []),
     "rollout_sample": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_float, C.c_float, _P, _P, _P, _P, _P, _P]),
+    "rollout_sample_static": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_float, C.c_float, _P, _P, _P, _P, _P, _P]),
+    "rollout_sample_static_prepare": (C.c_int, []),
+    "rollout_sample_static_error": (C.c_char_p, []),
     "rollout_philox_words": (C.c_int, [C.c_uint64, C.c_int32, _P, _P, _P]),
     "rollout_policy_loss": (C.c_int, [C.c_int32, _P, _P, _P, _P, _P, _P, C.POINTER(rollout_loss_params), _P,
                                       C.POINTER(C.c_float), _P, _P]),
@@ -376,6 +379,25 @@ def rollout_sample(logits, temperature, top_p, uniforms, forced=None, stream=Non
     if rc != OK:
         raise RolloutError(rc, lib.rollout_last_error(None).decode())
     return toks, lps, sums
+
+
+SAMPLE_STATIC_MAX_ROWS = 256
+
+
+def rollout_sample_static(logits, temperature, top_p, uniforms, tokens, logprobs, forced=None, weight_sums=None,
+                          stream=None):
+    """Every array is a CUDA tensor the caller owns (logits float32 [rows][vocab]; uniforms int32 or
+    uint32 bits [rows]; forced int32 [rows] or None; tokens int32, logprobs float32, weight_sums int64
+    out).  Only enqueues kernels on `stream`: synchronise before reading the outputs."""
+    lib = load_library()
+    rows, vocab = logits.shape
+    for t in (logits, uniforms, tokens, logprobs) + tuple(x for x in (forced, weight_sums) if x is not None):
+        assert t.is_cuda and t.is_contiguous()
+    rc = lib.rollout_sample_static(logits.data_ptr(), rows, vocab, temperature, top_p, uniforms.data_ptr(),
+                                   forced.data_ptr() if forced is not None else None, stream, tokens.data_ptr(),
+                                   logprobs.data_ptr(), weight_sums.data_ptr() if weight_sums is not None else None)
+    if rc != OK:
+        raise RolloutError(rc, lib.rollout_sample_static_error().decode())
 
 
 def rollout_policy_loss(cu_seqlens, logp_new, logp_old, logp_ref, mask, rewards, *, gamma=1.0, kl_coef=0.0,

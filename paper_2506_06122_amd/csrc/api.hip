@@ -712,6 +712,7 @@ int rollout_init(rollout_ctx** out, const rollout_model_desc* model, const rollo
     c->md = *model;
     c->rd = *runtime;
     engine_init(*c, *weights);
+    (void)rollout_sample_static_prepare();  // address of the static sampler scratch on this device
     if (const char* t = std::getenv("ROLLOUT_STEP_TIMEOUT_MS")) c->step_timeout_s = std::atof(t) * 1e-3;
     refresh_stats(*c);
   });
