@@ -7,11 +7,15 @@ Prints one JSON line: tokens/s, the roofline of the kernel that took the most ti
 timings gathered by the library on its own stream during the timed steps), and the CPU
 oracle timed on a bounded slice of the same workload.
 
-The default workload is the one the headline metric is quoted on (Qwen2.5-1.5B shape, 32
-prompts x 8 samples).  The others measure the remaining parts of the path at their real
-matrix shapes: a 7B-shape dense rollout, a 30B-A3B-shape mixture-of-experts rollout and the
-teacher-forced pass on the 7B shape; --layers and --prompts cut them down for quick runs and
-the JSON line says so.
+The default workload (`value`) is configs[1], the Qwen2.5-1.5B shape with 32 prompts x 8
+samples: the largest configuration whose warm-up and timed jobs (25 in the full test run) fit
+a benchmark run of a few minutes - one job of the 7B-shape rollout alone takes about a minute.
+So that the larger configurations are measured in the same run all the same, the default run
+then adds, under "other_configs" of the same JSON line, one job of configs[2] (7B-shape
+rollout, 64 x 8 samples) and one teacher-forced pass over 24 of configs[4]'s packed sequences,
+each with its tokens/s and the roofline of its dominant kernel (--no-other-configs skips them).
+--workload runs any one of them as the main measurement; --layers and --prompts cut a
+workload down for quick runs and the JSON line says so.
 """
 from __future__ import annotations
 
@@ -233,6 +237,8 @@ def roofline_of(kernels, bracket_ms, traffic_summary=None, copy_ceiling_gbs=None
     roofline["algorithmic_bytes_per_launch"] = top["bytes"] / top["launches"]
     if traffic_summary:
         roofline["traffic"] = measured_traffic(top["name"], traffic_summary)
+        if roofline["traffic"] is not None:  # not measured in this run: read from the committed counter summary
+            roofline["traffic_source"] = "profiles/" + traffic_summary
     roofline["avg_launch_us"] = 1e3 * top["ms"] / top["launches"]
     roofline["timed_launches"] = top["launches"]
     roofline["event_bracket_us"] = 1e3 * bracket_ms
@@ -241,6 +247,83 @@ def roofline_of(kernels, bracket_ms, traffic_summary=None, copy_ceiling_gbs=None
          "GB/s": k["bytes"] / (k["ms"] * 1e-3) / 1e9, "TFLOP/s": k["flops"] / (k["ms"] * 1e-3) / 1e12}
         for k in kernels]
     return roofline
+
+
+def measure_other_configs(args, flags, copy_ceiling_gbs) -> dict:
+    """One job of the 7B-shape rollout (configs[2]) and one teacher-forced pass over 24 of
+    configs[4]'s sequences on the same weights: tokens/s and the dominant kernel's roofline."""
+    import torch
+    import paper_2506_06122_amd as R
+    import workloads
+    shape = workloads.C3_7B
+    out = {}
+    t0 = time.perf_counter()
+    weights = workloads.make_weights(shape, seed=1, gains="ones")
+    print(f"# other configs: 7B-shape weights generated in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+    kv_bytes_per_token = shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 2
+    kv_per_flop = shape.n_kv_heads * shape.head_dim * 4 / (4.0 * shape.n_q_heads * shape.head_dim)
+
+    def brief(roof):
+        keep = ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "avg_launch_us", "timed_launches",
+                "algorithmic_bytes_per_launch", "achieved_without_prefix_reuse", "frac_of_copy_ceiling")
+        r = {k: roof[k] for k in keep if k in roof}
+        r["top_kernels"] = roof["per_kernel"][:6]
+        return r
+
+    # ---- configs[2]: one rollout job
+    load = workloads.load_c3()
+    max_prompt = int(np.diff(load.prompt_offsets).max())
+    need = int(np.diff(load.prompt_offsets).sum()) + int(load.max_new_tokens.sum()) + 64 * load.n_prompts * load.n_samples
+    eng = R.Rollout(shape, weights, kv_pool_bytes=need * kv_bytes_per_token, page_tokens=32,
+                    max_live_samples=load.n_prompts * load.n_samples,
+                    max_context=max_prompt + int(load.max_new_tokens.max()), max_batch_tokens=16384,
+                    seed=load.sampler_seed, flags=flags, timing_stride=max(args.timing_stride, 1))
+    ids = eng.rollout_prefill(load.prompt_tokens[:64], np.array([0, 64], np.int32), 4, np.full(4, 8, np.int32))[0]
+    for _ in range(4):                                    # a short warm-up: first launches, first page faults
+        eng.rollout_decode_step()
+    eng.rollout_abort(ids)
+    torch.cuda.synchronize()
+    before = {k["name"]: k for k in eng.rollout_kernel_stats()}
+    calls0 = int(eng.rollout_get_stats()["decode_steps"])
+    t0 = time.perf_counter()
+    emitted = run_job(eng, load)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernels, bracket_ms = kernel_table(eng, before)
+    out["configs[2]"] = {
+        "workload": "Qwen2.5-7B-shaped dense decoder, bf16, %d prompts x %d samples, prompt 128-1024, response "
+                    "log-normal(median 1024, sigma 1) capped 8192, T=0.99 top-p=1.0; one job, no warm-up job"
+                    % (load.n_prompts, load.n_samples),
+        "value": emitted / dt, "unit": "tokens/s", "ms_per_step": 1e3 * dt, "output_tokens": emitted,
+        "decode_calls": int(eng.rollout_get_stats()["decode_steps"]) - calls0,
+        "roofline": brief(roofline_of(kernels, bracket_ms, None, copy_ceiling_gbs, kv_per_flop))}
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+    print(f"# other configs: configs[2] job done in {dt:.1f} s", file=sys.stderr, flush=True)
+
+    # ---- configs[4]: teacher-forced pass, every call timed
+    tokens, cu = workloads.packed_sequences(24, 512, 8192, shape.vocab, seed=2)
+    chunk = 16384
+    eng = R.Rollout(shape, weights, kv_pool_bytes=(chunk + 8192 + 64 * 32) * kv_bytes_per_token, page_tokens=32,
+                    max_live_samples=8, max_context=8192, max_batch_tokens=chunk, seed=3, flags=flags, timing_stride=1)
+    eng.rollout_logprobs(tokens[:cu[1]], cu[:2], temperature=1.0)      # warm-up: the first sequence
+    torch.cuda.synchronize()
+    before = {k["name"]: k for k in eng.rollout_kernel_stats()}
+    t0 = time.perf_counter()
+    eng.rollout_logprobs(tokens, cu, temperature=1.0)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kernels, bracket_ms = kernel_table(eng, before)
+    out["configs[4]"] = {
+        "workload": "teacher-forced log-prob pass, Qwen2.5-7B-shaped dense decoder, bf16, 24 packed sequences (of the "
+                    "config's 512), length U{512..8192}, %d tokens; one pass after a one-sequence warm-up" % len(tokens),
+        "value": len(tokens) / dt, "unit": "tokens/s", "ms_per_step": 1e3 * dt, "tokens": int(len(tokens)),
+        "roofline": brief(roofline_of(kernels, bracket_ms, None, copy_ceiling_gbs, kv_per_flop))}
+    eng.close()
+    del eng, weights
+    torch.cuda.empty_cache()
+    return out
 
 
 def main() -> int:
@@ -252,6 +335,8 @@ def main() -> int:
                     help="bracket kernels with HIP events on every n-th library call (0 = never); a prime, so that "
                          "calls that recur with a job's period (its prefill) are sampled like any other")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="default workload only: skip the one-job measurements of configs[2] and configs[4]")
     ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns", "c2-refresh", "loss"],
                     default="c2",
                     help="c2 = headline (1.5B shape); c3 = 7B-shape rollout; c4 = 30B-A3B-shape MoE rollout; "
@@ -486,6 +571,8 @@ def main() -> int:
     eng.close()
     del eng
     torch.cuda.empty_cache()
+    if wl == "c2" and not (args.prompts or cut or args.no_other_configs):
+        out["other_configs"] = measure_other_configs(args, flags, copy_ceiling_gbs)
     if args.no_cpu_baseline:
         out["cpu_baseline"] = None
     elif wl == "c5":
