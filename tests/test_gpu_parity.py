@@ -211,6 +211,25 @@ def test_large_config_shapes_reduced_depth(which):
     eng.close()
 
 
+def test_c3_full_depth_slice_matches_oracle():
+    """Configs 3 and 5's model at its full depth - 28 layers, hidden 3584, 28/4 heads, FFN 18944,
+    vocab 152064 - on a slice the fp64 oracle can afford on the GPU host (57 GB of widened
+    weights, about 2 x 10^12 flop): 2 prompts x 2 samples, 3 teacher-forced steps.  This is the
+    depth at which rounding has accumulated most: the 16-bit KV cache alone leaves 1.3e-2 here
+    (4 layers of the same shape: 5e-3)."""
+    shape = workloads.C3_7B
+    w = workloads.make_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, kv_pool_bytes=1 << 30, max_live_samples=8, max_context=512, max_batch_tokens=512)
+    toks, offs = workloads.make_prompts(2, 40, 90, shape.vocab, seed=14)
+    forced = np.random.default_rng(8).integers(0, shape.vocab, (4, 3)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, 2, forced, 3)
+    print(f"{shape.name}, all {shape.n_layers} layers: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"]
+    eng.close()
+
+
 @pytest.mark.parametrize("n_prompts,n_samples,lo,hi", [(1, 2, 3, 9), (6, 8, 30, 200)], ids=["few-rows", "many-rows"])
 def test_matrix_core_moe_row_blocks(n_prompts, n_samples, lo, hi):
     """Grouped expert projections: a handful of rows (most experts untouched, one row each) and
