@@ -47,6 +47,7 @@ def run_job(eng, load, trace=None) -> int:
     if trace is not None:
         trace.append((0, time.perf_counter() - t0))   # entry 0: the prefill call
     emitted = len(ids)
+    steps, t_note = 0, time.perf_counter()
     while True:
         t0 = time.perf_counter()
         ids, toks, lps, fin = eng.rollout_decode_step()
@@ -55,6 +56,10 @@ def run_job(eng, load, trace=None) -> int:
         if trace is not None:
             trace.append((len(ids), time.perf_counter() - t0))
         emitted += len(ids)
+        steps += 1
+        if t0 - t_note > 30.0:        # a long job says where it is twice a minute
+            t_note = t0
+            print(f"# decode step {steps}: {len(ids)} live samples, {emitted} tokens so far", file=sys.stderr, flush=True)
 
 
 def write_step_trace(path, trace, load, kv_bytes_per_token, weight_bytes, command):

@@ -230,6 +230,31 @@ def test_c3_full_depth_slice_matches_oracle():
     eng.close()
 
 
+def test_c4_shape_many_rows_four_layers():
+    """Config 4's mixture-of-experts shape - hidden 2048, 32/4 heads, 128 experts, top-8, expert FFN
+    768, vocab 151936 - with 4 of its 48 layers (the fp64 oracle of more does not fit a test), at
+    a batch the grouped expert projections see in the benchmark: 9 prompts x 8 samples = 72 live
+    rows (about 4.5 picks per expert and step, most experts touched), 3 teacher-forced steps;
+    the oracle computes with the GPU's recorded expert sets, which must be the top-8 of its own
+    router logits up to the tolerance."""
+    import dataclasses
+    shape = dataclasses.replace(workloads.C4_30B_A3B, n_layers=4, name="qwen3-30b-a3b-shape-4-layers")
+    w = workloads.make_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, kv_pool_bytes=1 << 30, max_live_samples=80, max_context=256, max_batch_tokens=1024,
+                      flags=2)
+    P, n, steps = 9, 8, 3
+    toks, offs = workloads.make_prompts(P, 20, 60, shape.vocab, seed=15)
+    forced = np.random.default_rng(9).integers(0, shape.vocab, (P * n, steps)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, n, forced, steps)
+    below, outside = (max(g[i] for g in model.routing_regret) for i in (0, 1))
+    print(f"{shape.name}, {P * n} rows: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}, routing gaps "
+          f"{below:.3e} / {outside:.3e} over {len(model.routing_regret)} decisions")
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"] and below <= TOL["bf16"] and outside <= TOL["bf16"]
+    eng.close()
+
+
 @pytest.mark.parametrize("n_prompts,n_samples,lo,hi", [(1, 2, 3, 9), (6, 8, 30, 200)], ids=["few-rows", "many-rows"])
 def test_matrix_core_moe_row_blocks(n_prompts, n_samples, lo, hi):
     """Grouped expert projections: a handful of rows (most experts untouched, one row each) and
