@@ -57,6 +57,13 @@ extern "C" {
                                          shared pages together, each key and value fragment read once for all of them (fewer
                                          bytes, one more launch; off by default: slower at the sizes measured so far) */
 
+#define ROLLOUT_RT_GROW_PAGES 16u     /* KV pages are taken as contexts grow instead of all at admission: a sample is admitted
+                                         with the pages of its prompt plus the one its first fed token goes to, and every
+                                         decode step takes the pages it is about to write.  For workloads that end by EOS
+                                         long before max_new_tokens, where reserving the worst case would leave most of the
+                                         pool idle.  The pool can then run out: rollout_decode_step returns E_NOMEM (nothing
+                                         changed; abort samples and call again), rollout_queue_step makes room itself, see there */
+
 typedef struct rollout_ctx rollout_ctx; /* opaque; created by rollout_init, freed by rollout_destroy */
 
 /* model flags: what tells the named model families apart in their public definitions (the
@@ -223,6 +230,7 @@ int rollout_abort(rollout_ctx *ctx, int32_t n, const int64_t *sample_ids);
 typedef struct {
   uint64_t prompts_pushed, prompts_admitted, prompts_completed; /* completed = every sample finished or aborted by the caller */
   uint64_t samples_aborted;                                     /* by the target policy */
+  uint64_t prompts_preempted;                                   /* ROLLOUT_RT_GROW_PAGES: sent back to the queue to make room */
   int32_t prompts_waiting;
   int32_t closed;                                               /* 1 once the target was reached */
 } rollout_queue_stats;
@@ -255,7 +263,16 @@ int rollout_queue_policy(rollout_ctx *ctx, int32_t admit_min_prompts, int32_t ta
  *               samples (ascending id); the rest is the decode step's output (ascending id)
  * Outputs as for rollout_decode_step.  With nothing waiting and nothing live, or after the
  * queue closed: *n_out = 0.  Errors: E_INVAL (capacity below live samples + 2 x samples that
- * would be admitted: nothing happens). */
+ * would be admitted: nothing happens).
+ * With ROLLOUT_RT_GROW_PAGES a step first makes sure the pool holds the pages it is about to
+ * write: while it does not, the most recently admitted prompt that still runs gives way - its
+ * live samples are dropped and the prompt returns to the head of the queue (a step that drops
+ * samples admits nothing).  The prompt starts over when it is admitted again: all its samples
+ * appear once more among the newly admitted entries, from response position 0, and - their ids
+ * being the same - emit the same tokens as before; a caller that sees a known id there discards
+ * what it had collected for it.  Prompts are admitted only while the pool keeps one spare page
+ * per live sample.  E_NOMEM when the pool is exhausted by samples that did not come through the
+ * queue (abort some). */
 int rollout_queue_step(rollout_ctx *ctx, int32_t *n_out, int32_t *n_admitted, int64_t *sample_ids,
                        int32_t *tokens, float *logprobs, uint8_t *finished);
 

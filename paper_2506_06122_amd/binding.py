@@ -19,6 +19,7 @@ RT_SIMPLE_KERNELS = 1
 RT_RECORD_ROUTING = 2
 RT_KERNEL_TIMING = 4
 RT_PROMPT_GROUPS = 8
+RT_GROW_PAGES = 16
 
 
 class RolloutError(RuntimeError):
@@ -59,7 +60,7 @@ class rollout_stats(C.Structure):
 
 class rollout_queue_stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("prompts_pushed", "prompts_admitted", "prompts_completed",
-                                          "samples_aborted")] + \
+                                          "samples_aborted", "prompts_preempted")] + \
                [("prompts_waiting", C.c_int32), ("closed", C.c_int32)]
 
 

@@ -84,45 +84,6 @@ static void check_usable(const rollout_ctx& c) {
   if (c.broken) throw ApiError{ROLLOUT_E_STATE, "an earlier call timed out on the device; destroy this context"};
 }
 
-// Pages and live-sample slots taken by a call that has not completed yet: given back if the
-// call leaves by an exception, so that a failing call changes no state.
-struct Rollback {
-  rollout_ctx& c;
-  std::vector<int32_t> page_refs;  // one entry per reference taken (alloc or retain)
-  std::vector<int> slots;
-  bool armed = true;
-  explicit Rollback(rollout_ctx& ctx) : c(ctx) {}
-  int32_t alloc() {
-    const int32_t pg = c.pool->alloc(false);
-    if (pg < 0) throw ApiError{ROLLOUT_E_NOMEM, "internal: the KV pool ran out after admission was checked"};
-    page_refs.push_back(pg);
-    return pg;
-  }
-  void retain(int32_t pg) {
-    c.pool->retain(pg);
-    page_refs.push_back(pg);
-  }
-  int take_slot() {
-    const int sl = c.free_slots.back();
-    c.free_slots.pop_back();
-    slots.push_back(sl);
-    return sl;
-  }
-  void commit() { armed = false; }
-  ~Rollback() {
-    if (!armed) return;
-    for (int32_t pg : page_refs) c.pool->release(pg);
-    for (auto it = slots.rbegin(); it != slots.rend(); ++it) c.free_slots.push_back(*it);
-  }
-};
-
-static void release_sample(rollout_ctx& c, Sample& s) {
-  for (int32_t p : s.pages) c.pool->release(p);
-  s.pages.clear();
-  if (s.slot >= 0) c.free_slots.push_back(s.slot);
-  s.slot = -1;
-}
-
 static void refresh_stats(rollout_ctx& c) {
   c.stats.live_samples = (int32_t)c.live.size();
   c.stats.pages_total = c.pool->total();
@@ -142,7 +103,7 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
                          const int64_t* prompt_ids, const int64_t* first_ids, int64_t* sample_ids,
                          int32_t* first_tokens, float* first_logprobs, uint8_t* finished) {
   const rollout_model_desc& m = c.md;
-  const int P = n_prompts, n = n_samples, T = c.rd.page_tokens, R = c.r_max;
+  const int P = n_prompts, n = n_samples, R = c.r_max;
   // ---- validation (no state changes before all of it passed) ----
   if (P < 1 || n < 1 || !tokens || !offsets || !max_new_tokens) fail(ROLLOUT_E_INVAL, "bad prompt arguments");
   if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
@@ -167,7 +128,7 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
     }
     for (int i = offsets[p]; i < offsets[p + 1]; ++i)
       if (tokens[i] < 0 || tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "prompt token out of range");
-    need_pages += plan_pages(len, T, n, max_new_tokens + p * n, nullptr, nullptr, nullptr);
+    need_pages += admission_pages(c, len, n, max_new_tokens + p * n);
   }
   if (need_slots > (int)c.free_slots.size()) fail(ROLLOUT_E_NOMEM, "not enough free live-sample slots");
   if (need_pages > c.pool->unreserved()) fail(ROLLOUT_E_NOMEM, "not enough free KV pages");
@@ -180,56 +141,14 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
   // ---- pages and page tables (given back by `undo` if anything below throws) ----
   Rollback undo(c);
   const float inv_t = 1.0f / temperature;
-  struct PromptPages {
-    std::vector<int32_t> shared;
-    int32_t tail = -1;
-  };
   std::vector<PromptPages> pp(P);
   std::vector<Sample> fresh((size_t)P * n);
   std::vector<int> copy_pairs;
-  for (int p = 0; p < P; ++p) {
-    int len = offsets[p + 1] - offsets[p];
-    int full = len / T, has_tail = (len % T) != 0;
-    int* prow = &c.h_page_table[(size_t)(c.temp_slot0 + p) * c.max_pages];
-    for (int i = 0; i < full; ++i) {
-      int32_t pg = undo.alloc();
-      pp[p].shared.push_back(pg);
-      prow[i] = pg;
-    }
-    if (has_tail) {
-      pp[p].tail = undo.alloc();
-      prow[full] = pp[p].tail;
-    }
-    for (int j = 0; j < n; ++j) {
-      Sample& s = fresh[(size_t)p * n + j];
-      s.group = prompt_ids ? prompt_ids[p] : c.prompt_counter + p;
-      s.id = (first_ids ? first_ids[p] : c.next_sample_id + (int64_t)p * n) + j;
-      s.shared_len = full * T;
-      s.slot = -1;
-      s.prompt_len = len;
-      s.n_emitted = 0;
-      s.max_new = max_new_tokens[p * n + j];
-      s.eos_id = eos_id;
-      if (s.max_new <= 1) continue;
-      s.slot = undo.take_slot();
-      int* srow = &c.h_page_table[(size_t)s.slot * c.max_pages];
-      for (int i = 0; i < full; ++i) {
-        undo.retain(pp[p].shared[i]);
-        s.pages.push_back(pp[p].shared[i]);
-        srow[i] = pp[p].shared[i];
-      }
-      int total = ceil_div((long long)len + s.max_new - 1, T);
-      for (int i = full; i < total; ++i) {
-        int32_t pg = undo.alloc();
-        s.pages.push_back(pg);
-        srow[i] = pg;
-      }
-      if (has_tail) {
-        copy_pairs.push_back(pp[p].tail);
-        copy_pairs.push_back(srow[full]);
-      }
-    }
-  }
+  for (int p = 0; p < P; ++p)
+    take_prompt_pages(c, undo, offsets[p + 1] - offsets[p], n, max_new_tokens + p * n, eos_id,
+                      prompt_ids ? prompt_ids[p] : c.prompt_counter + p,
+                      first_ids ? first_ids[p] : c.next_sample_id + (int64_t)p * n, c.temp_slot0 + p, pp[p],
+                      &fresh[(size_t)p * n], copy_pairs);
   engine_upload_page_table(c);
 
   // ---- forward over the prompts, in chunks of whole prompts ----
@@ -403,6 +322,18 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
     for (int i = 0; i < B; ++i)
       if (forced_tokens[i] < 0 || forced_tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "forced token out of range");
   int* hi = c.h_int.p;
+  if (c.grow_pages) {  // the pages this step writes to (checked first: a failing call changes nothing)
+    if (pages_missing_for_step(c) > c.pool->unreserved())
+      fail(ROLLOUT_E_NOMEM, "the KV pool is exhausted: abort samples and call again");
+    std::vector<PagePatch> patches;
+    grow_pages_for_step(c, patches);
+    if (!patches.empty()) {
+      static_assert(sizeof(PagePatch) == 3 * sizeof(int), "patches travel as int triples");
+      std::memcpy(hi + 4 * R, patches.data(), patches.size() * sizeof(PagePatch));
+      h2d(c.d_page_patch.p, hi + 4 * R, patches.size() * sizeof(PagePatch), c.stream);
+      launch_patch_page_table(c.d_page_table.p, c.max_pages, c.d_page_patch.p, (int)patches.size(), c.stream);
+    }
+  }
   if (c.live_dirty) {
     int i = 0;
     for (auto& kv : c.live) hi[i++] = kv.second.slot;
@@ -555,7 +486,7 @@ static void extend_impl(rollout_ctx& c, int32_t n, const int64_t* sample_ids, co
                         const int32_t* offsets, const int32_t* forced_next, const uint32_t* uniform_override,
                         int32_t* next_tokens, float* next_logprobs, uint8_t* finished) {
   const rollout_model_desc& m = c.md;
-  const int T = c.rd.page_tokens, R = c.r_max;
+  const int T = c.page_tokens, R = c.r_max;
   if (n < 1 || !sample_ids || !tokens || !offsets) fail(ROLLOUT_E_INVAL, "bad arguments");
   if (offsets[0] != 0) fail(ROLLOUT_E_INVAL, "offsets[0] must be 0");
   if (n > rollout_ctx::kTempSlots || n > c.logit_rows) fail(ROLLOUT_E_NOMEM, "too many samples in one call");
@@ -790,24 +721,6 @@ int rollout_decode_step(rollout_ctx* ctx, const int32_t* forced_tokens, const ui
 }
 
 // ---- queue-fed continuous rollout -------------------------------------------------------
-// slots and pages one prompt takes at admission
-static void admission_cost(const rollout_ctx& c, const QueuedPrompt& q, int n, int& slots, long long& pages) {
-  slots = 0;
-  for (int j = 0; j < n; ++j) slots += q.max_new[j] > 1;
-  pages = plan_pages((int)q.tokens.size(), c.rd.page_tokens, n, q.max_new.data(), nullptr, nullptr, nullptr);
-}
-
-// a sample of prompt `group` has ended (finished, or aborted by the caller): the prompt is
-// complete when its last one ends
-static void queue_note_finished(PromptQueue& q, int64_t group) {
-  auto it = q.open.find(group);
-  if (it == q.open.end()) return;  // admitted through rollout_prefill, not through the queue
-  if (--it->second == 0) {
-    q.open.erase(it);
-    q.completed += 1;
-  }
-}
-
 int rollout_queue_push(rollout_ctx* ctx, int32_t n_prompts, const int32_t* tokens, const int32_t* offsets,
                        int32_t n_samples, const int32_t* max_new_tokens, int32_t eos_id, float temperature,
                        float top_p, int64_t* first_sample_ids) {
@@ -842,11 +755,11 @@ int rollout_queue_push(rollout_ctx* ctx, int32_t n_prompts, const int32_t* token
         if (mn < 1) fail(ROLLOUT_E_INVAL, "max_new_tokens must be >= 1");
         if ((long long)len + mn - 1 > c.rd.max_context) fail(ROLLOUT_E_NOMEM, "prompt + response exceeds max_context");
       }
-      int slots;
-      long long pages;
-      admission_cost(c, e, n, slots, pages);
-      if (slots > c.rd.max_live_samples) fail(ROLLOUT_E_NOMEM, "more samples than live-sample slots");
-      if (pages > c.pool->total()) fail(ROLLOUT_E_NOMEM, "more pages than the pool holds");
+      // alone in an idle context the prompt must fit whatever its samples do, so that it always makes progress
+      if (admission_slots(n, e.max_new.data()) > c.rd.max_live_samples)
+        fail(ROLLOUT_E_NOMEM, "more samples than live-sample slots");
+      if (plan_pages(len, c.page_tokens, n, e.max_new.data(), nullptr, nullptr, nullptr) > c.pool->total())
+        fail(ROLLOUT_E_NOMEM, "more pages than the pool holds");
     }
     q.n_samples = n;
     for (int p = 0; p < P; ++p) {
@@ -871,9 +784,10 @@ int rollout_queue_get_stats(rollout_ctx* ctx, rollout_queue_stats* out) {
   if (!ctx || !out) return ROLLOUT_E_INVAL;
   const PromptQueue& q = ctx->queue;
   out->prompts_pushed = q.pushed;
-  out->prompts_admitted = q.admitted;
+  out->prompts_admitted = q.admitted_count;
   out->prompts_completed = q.completed;
   out->samples_aborted = q.aborted;
+  out->prompts_preempted = q.preempted;
   out->prompts_waiting = (int32_t)q.waiting.size();
   out->closed = q.closed ? 1 : 0;
   return ROLLOUT_OK;
@@ -892,24 +806,20 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
     *n_admitted = 0;
     if (q.closed) return;
 
-    // (1) the longest run of waiting prompts, in push order, that one prefill call can take
-    int k = 0, slots = 0;
-    long long pages = 0, rows = 0;
-    while (k < (int)q.waiting.size()) {
-      const QueuedPrompt& e = q.waiting[k];
-      const QueuedPrompt& head = q.waiting[0];
-      if (e.eos_id != head.eos_id || e.temperature != head.temperature || e.top_p != head.top_p) break;
-      int s1;
-      long long p1;
-      admission_cost(c, e, n, s1, p1);
-      if (slots + s1 > (int)c.free_slots.size() || pages + p1 > c.pool->unreserved()) break;
-      if (k + 1 > rollout_ctx::kTempSlots || k + 1 > c.logit_rows || (long long)(k + 1) * n > c.r_max) break;
-      slots += s1;
-      pages += p1;
-      rows += (long long)e.tokens.size();
-      ++k;
+    // (0) growing pages: make room for this step's new pages - the youngest queued prompt gives way
+    int n_preempted = 0;
+    if (c.grow_pages) {
+      while (pages_missing_for_step(c) > c.pool->unreserved()) {
+        const int dropped = queue_preempt_youngest(c, nullptr);
+        if (!dropped) fail(ROLLOUT_E_NOMEM, "the KV pool is exhausted and no queued prompt can give way: abort samples");
+        c.stats.samples_aborted += dropped;
+        n_preempted += dropped;
+      }
     }
-    if (k < std::min<int>(q.admit_min, (int)q.waiting.size()) && !c.live.empty()) k = 0;
+    // (1) the longest run of waiting prompts, in push order, that one prefill call can take
+    int k = n_preempted ? 0 : queue_select_run(c, AdmissionLimits{std::min(rollout_ctx::kTempSlots, c.logit_rows), (long long)c.r_max});
+    long long rows = 0;
+    for (int i = 0; i < k; ++i) rows += (long long)q.waiting[i].tokens.size();
     const int live_before = (int)c.live.size();
     if (cap < live_before + 2 * k * n) fail(ROLLOUT_E_INVAL, "output capacity smaller than live samples + 2 x admitted samples");
     std::vector<uint8_t> fin_local;
@@ -934,14 +844,17 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
       prefill_impl(c, k, toks.data(), offs.data(), n, max_new.data(), eos_id, temperature, top_p,
                    nullptr, nullptr, pids.data(), firsts.data(), ids_local.data(), tokens, logprobs,
                    fin_local.data());
-      for (int i = 0; i < k; ++i) q.open[pids[i]] = n;
+      for (int i = 0; i < k; ++i) {
+        q.open[pids[i]] = n;
+        if (c.grow_pages) q.admitted.emplace(pids[i], q.waiting[i]);  // kept: it may have to start over
+      }
       for (int i = 0; i < n_adm; ++i) {
         if (sample_ids) sample_ids[i] = ids_local[i];
         if (finished) finished[i] = fin_local[i];
         if (fin_local[i]) queue_note_finished(q, pids[i / n]);
       }
       q.waiting.erase(q.waiting.begin(), q.waiting.begin() + k);
-      q.admitted += k;
+      q.admitted_count += k;
     }
 
     // (2) one decode step over everything that is live now
@@ -968,6 +881,7 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
       q.aborted += running;
       q.waiting.clear();
       q.open.clear();
+      q.admitted.clear();
       q.closed = true;
       refresh_stats(c);
     }
@@ -1057,7 +971,7 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
     rollout_ctx& c = *ctx;
     check_usable(c);
     const rollout_model_desc& m = c.md;
-    const int T = c.rd.page_tokens, R = c.r_max;
+    const int T = c.page_tokens, R = c.r_max;
     if (n_seqs < 0 || !cu_seqlens || (n_seqs > 0 && (!tokens || !logprobs))) fail(ROLLOUT_E_INVAL, "null argument");
     if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
     if (n_seqs && cu_seqlens[0] != 0) fail(ROLLOUT_E_INVAL, "cu_seqlens[0] must be 0");

@@ -9,14 +9,9 @@
 
 #include "../../include/rollout.h"
 #include "common.h"
+#include "host_sched.h"
 #include "kernels.h"
 #include "kernels_fast.h"
-#include "page_pool.h"
-
-struct ApiError {
-  int code;
-  std::string msg;
-};
 
 template <typename T>
 struct DevBuf {
@@ -147,35 +142,8 @@ struct KernelTimer {
   }
 };
 
-struct Sample {
-  int64_t id;
-  int slot;
-  int prompt_len, n_emitted, max_new, eos_id;  // prompt_len: every cached token that is not a response token
-  int last_token = -1;                         // the response token emitted last (not cached yet)
-  int64_t group = -1;                          // the prompt's counter: samples of one prompt share its full pages
-  int shared_len = 0;                          // positions held in those shared pages (a multiple of page_tokens)
-  std::vector<int32_t> pages;  // one reference held on each
-};
-
-// Prompts waiting for admission and the bookkeeping of the queue-fed rollout (host only).
-struct QueuedPrompt {
-  int64_t prompt_id;     // the prompt's counter (what its samples' `group` will be)
-  int64_t first_sample;  // id of its sample 0; sample j carries first_sample + j
-  std::vector<int32_t> tokens, max_new;  // max_new: one per sample
-  int eos_id;
-  float temperature, top_p;
-};
-struct PromptQueue {
-  std::deque<QueuedPrompt> waiting;
-  int n_samples = 0;      // fixed by the first push
-  int admit_min = 1;      // admit only when this many waiting prompts fit (or nothing is live)
-  int target = 0;         // close the queue once this many prompts are complete; 0 = never
-  bool closed = false;
-  std::unordered_map<int64_t, int> open;  // admitted prompt -> samples not finished yet
-  uint64_t pushed = 0, admitted = 0, completed = 0, aborted = 0;
-};
-
-struct rollout_ctx {
+// The host-side scheduler state (sample table, slots, page tables, prompt queue) is HostState.
+struct rollout_ctx : HostState {
   rollout_model_desc md{};
   rollout_runtime_desc rd{};
   hipStream_t stream = nullptr;
@@ -185,7 +153,7 @@ struct rollout_ctx {
 
   // derived sizes
   int q_dim = 0, kv_dim = 0, qkv_dim = 0, elem = 4;
-  int max_pages = 0, n_slots = 0, temp_slot0 = 0, r_max = 0, logit_rows = 0;
+  int n_slots = 0, temp_slot0 = 0, r_max = 0, logit_rows = 0;
   static constexpr int kTempSlots = 1024;
 
   // weights
@@ -197,9 +165,8 @@ struct rollout_ctx {
   // KV cache
   DevBuf<char> kv_pool;
   KvGeom geom{};
-  rollout_pool* pool = nullptr;
   DevBuf<int> d_page_table;
-  std::vector<int> h_page_table;
+  DevBuf<int> d_page_patch;     // growing pages: (slot, index, page) triples of a step's new pages
 
   // per-slot decode state
   DevBuf<int> st_last_token, st_pos, st_step;
@@ -207,15 +174,8 @@ struct rollout_ctx {
   DevBuf<float> st_inv_temp, st_top_p;
   SlotState st{};
 
-  // sample table
-  std::map<int64_t, Sample> live;
-  std::vector<int> free_slots;
-  int64_t prompt_counter = 0;   // prompts ever admitted or queued
-  int64_t next_sample_id = 0;   // ids are handed out consecutively, n per prompt, at prefill or push time
   bool broken = false;          // a step timed out: the device state is unknown, every call is refused
   double step_timeout_s = 300;  // wall-clock bound of the wait that ends a decode step
-  PromptQueue queue;
-  bool live_dirty = true;
   DevBuf<int> d_live;
 
   // workspaces

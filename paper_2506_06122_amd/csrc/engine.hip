@@ -165,7 +165,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   if (r.max_live_samples < 1 || r.max_context < 2 || r.max_batch_tokens < 1)
     fail(ROLLOUT_E_INVAL, "max_live_samples, max_context, max_batch_tokens must be positive");
   if (r.flags & ~(ROLLOUT_RT_SIMPLE_KERNELS | ROLLOUT_RT_RECORD_ROUTING | ROLLOUT_RT_KERNEL_TIMING |
-                  ROLLOUT_RT_PROMPT_GROUPS))
+                  ROLLOUT_RT_PROMPT_GROUPS | ROLLOUT_RT_GROW_PAGES))
     fail(ROLLOUT_E_INVAL, "unknown runtime flag");
   const bool tied = (m.flags & ROLLOUT_MODEL_TIED_LM_HEAD) != 0;
   if (!w.embed || !w.final_norm || (!tied && !w.lm_head) || !w.layers) fail(ROLLOUT_E_INVAL, "null weight pointer");
@@ -186,6 +186,9 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   c.q_dim = m.n_q_heads * m.head_dim;
   c.kv_dim = m.n_kv_heads * m.head_dim;
   c.qkv_dim = c.q_dim + 2 * c.kv_dim;
+  c.page_tokens = r.page_tokens;
+  c.max_context = r.max_context;
+  c.grow_pages = (r.flags & ROLLOUT_RT_GROW_PAGES) != 0;
   c.max_pages = ceil_div(r.max_context, r.page_tokens);
   c.temp_slot0 = r.max_live_samples;
   c.n_slots = r.max_live_samples + rollout_ctx::kTempSlots;
@@ -259,6 +262,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   c.st_top_p.alloc(c.n_slots);
   c.st = SlotState{c.st_last_token.p, c.st_pos.p, c.st_step.p, c.st_sample_id.p, c.st_inv_temp.p, c.st_top_p.p};
   c.d_live.alloc(r.max_live_samples);
+  if (c.grow_pages) c.d_page_patch.alloc(3 * (size_t)r.max_live_samples);
   for (int s = r.max_live_samples - 1; s >= 0; --s) c.free_slots.push_back(s);
 
   // ---- workspaces ----

@@ -51,6 +51,10 @@ void launch_moe_down_simple(const float* act, const T* w_down, const int* idx, c
 void launch_copy_pages(void* kv_pool, const int* pairs, int n_pairs, int n_layers, long long layer_stride_bytes,
                        long long page_stride_bytes, hipStream_t s);
 
+// page_table[slot * max_pages + index] = page for n (slot, index, page) triples: the entries that
+// changed on the host since the table was uploaded
+void launch_patch_page_table(int* page_table, int max_pages, const int* triples, int n, hipStream_t s);
+
 void launch_convert_to_f32(const void* src, int dtype, float* dst, long long n, hipStream_t s);
 
 // ---- sampling ---------------------------------------------------------------------------

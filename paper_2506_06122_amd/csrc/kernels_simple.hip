@@ -436,3 +436,13 @@ void launch_scatter_tokens(SlotState st, const int* row_slot, const int* tokens,
     scatter_tokens_kernel<<<ceil_div(rows, 256), 256, 0, s>>>(st, row_slot, tokens, logprobs, rows, advance_pos,
                                                               host_tokens, host_logprobs);
 }
+
+// ---------------------------------------------------------------- page-table patches
+__global__ void patch_page_table_kernel(int* __restrict__ page_table, int max_pages, const int* __restrict__ triples,
+                                        int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) page_table[(long long)triples[3 * i] * max_pages + triples[3 * i + 1]] = triples[3 * i + 2];
+}
+void launch_patch_page_table(int* page_table, int max_pages, const int* triples, int n, hipStream_t s) {
+  if (n) patch_page_table_kernel<<<ceil_div(n, 256), 256, 0, s>>>(page_table, max_pages, triples, n);
+}

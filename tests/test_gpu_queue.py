@@ -268,3 +268,98 @@ def test_decode_step_wait_is_bounded(monkeypatch):
     ok.rollout_prefill(toks, offs, 2, np.full(4, 3, np.int32))
     assert len(ok.rollout_decode_step()[0]) == 4
     ok.close()
+
+
+def drain_restartable(eng, max_live, max_steps=20000):
+    """Steps a queue with growing pages until nothing waits and nothing is live.  A sample that
+    shows up again among the newly admitted entries was preempted and starts over: what was
+    collected for it is discarded.  Returns {sample id: (tokens, logprobs)}, the number of
+    restarts seen and the peak number of live samples."""
+    seqs, restarts, peak = {}, 0, 0
+    for _ in range(max_steps):
+        ids, toks, lps, fin, n_adm = eng.rollout_queue_step()
+        for k, (i, t, lp) in enumerate(zip(ids, toks, lps)):
+            if k < n_adm:
+                restarts += int(i) in seqs
+                seqs[int(i)] = ([], [])
+            seqs[int(i)][0].append(int(t))
+            seqs[int(i)][1].append(float(lp))
+        st = eng.rollout_get_stats()
+        assert st["live_samples"] <= max_live and st["pages_in_use"] <= st["pages_total"]
+        peak = max(peak, st["live_samples"])
+        if not st["live_samples"] and not eng.rollout_queue_get_stats()["prompts_waiting"]:
+            return seqs, restarts, peak
+    raise AssertionError("the queue did not drain")
+
+
+@pytest.mark.parametrize("scenario", ["eos", "exhaustion"])
+def test_growing_pages_admit_by_need_and_survive_exhaustion(scenario):
+    """ROLLOUT_RT_GROW_PAGES: pages are taken as contexts grow.  The worst case of the queued
+    samples (every one running to max_new_tokens) is several times the pool, which would keep
+    most of them waiting under worst-case reservation.
+      eos         24 samples with limits of 100 tokens, some ended early by an end-of-sequence
+                  token, through 16 slots and 24 pages: more samples are live at once than
+                  worst-case reservation could ever admit (5 pages each: 4 samples);
+      exhaustion  no end-of-sequence token, 6 slots and 10 pages: the pool runs out again and
+                  again, the youngest prompts give way and start over later.
+    Either way every sample's final tokens and log-probs are those of the oracle's per-sample
+    rollout, which knows nothing of pages, queues or restarts."""
+    from collections import Counter
+    import paper_2506_06122_amd as R
+    shape = workloads.C1_TINY
+    w = scaled_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    temperature, top_p, seed = 1.0, 0.9, 7
+    page_bytes = 32 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 4
+    if scenario == "eos":
+        P, n, limit, pool_pages, slots = 12, 2, 100, 24, 16
+        toks, offs = workloads.make_prompts(P, 5, 40, shape.vocab, seed=91)
+        max_new = np.full(P * n, limit, np.int32)
+        free = rollout.generate(model, toks, offs, n, np.full(P * n, 30, np.int32), -1, temperature, top_p, seed)
+        eos = Counter(t for tr in free for t in tr.tokens[2:]).most_common(1)[0][0]   # ends many samples early
+    else:
+        P, n, limit, pool_pages, slots = 8, 1, 90, 10, 6
+        toks, offs = workloads.make_prompts(P, 20, 40, shape.vocab, seed=92)
+        max_new = np.full(P * n, limit, np.int32)
+        eos = -1
+    worst_case = sum(int(R.rollout_plan_pages(int(offs[p + 1] - offs[p]), 32, max_new[p * n:(p + 1) * n])[0]) for p in range(P))
+    assert worst_case > 2 * pool_pages
+    eng = make_engine(shape, w, kv_pool_bytes=pool_pages * page_bytes, max_live_samples=slots, max_context=160,
+                      max_batch_tokens=256, seed=seed, flags=R.binding.RT_GROW_PAGES)
+    assert eng.rollout_get_stats()["pages_total"] == pool_pages
+    eng.rollout_queue_push(toks, offs, n, max_new, eos_id=eos, temperature=temperature, top_p=top_p)
+    seqs, restarts, peak = drain_restartable(eng, max_live=slots)
+    qs, st = eng.rollout_queue_get_stats(), eng.rollout_get_stats()
+    assert st["live_samples"] == 0 and st["pages_in_use"] == 0 and qs["prompts_completed"] == P
+    assert sorted(seqs) == list(range(P * n))
+    assert restarts == qs["prompts_preempted"] * n and st["pages_peak"] <= pool_pages
+    if scenario == "eos":
+        assert sum(len(t) < limit for t, _ in seqs.values()) >= 2          # the token did end some early
+        assert all(t[-1] == eos or len(t) == limit for t, _ in seqs.values())
+        assert peak > pool_pages // 5      # worst-case reservation: 5 pages per sample at its limit
+    else:
+        assert qs["prompts_preempted"] > 0
+        assert all(len(t) == limit for t, _ in seqs.values())
+    forced = {sid: t for sid, (t, _) in seqs.items()}
+    limits = np.array([len(seqs[i][0]) for i in range(P * n)], np.int32)
+    ref = rollout.generate(model, toks, offs, n, limits, -1, temperature, top_p, seed, forced_tokens=forced)
+    worst = max(abs(a - b) for tr in ref for a, b in zip(tr.logprobs, seqs[tr.sample_id][1]))
+    free = rollout.generate(model, toks, offs, n, max_new, eos, temperature, top_p, seed)
+    same = sum(tr.tokens == seqs[tr.sample_id][0] for tr in free)
+    print(f"{scenario}: pool {pool_pages} pages, worst case {worst_case}; peak {st['pages_peak']} pages, {peak} live; "
+          f"{qs['prompts_preempted']} preemptions; max |dlogp| = {worst:.3e}; free-running oracle reproduced {same}/{P * n}")
+    assert worst < 1e-4
+    assert same >= P * n - 1
+    if scenario == "exhaustion":
+        # outside the queue the pool's exhaustion is the caller's to resolve: the step fails, nothing changes
+        ids, _, _, _ = eng.rollout_prefill(toks[:offs[1]], offs[:2], 4, np.full(4, 150 - int(offs[1]), np.int32))
+        with pytest.raises(R.RolloutError) as e:
+            for _ in range(200):
+                eng.rollout_decode_step()
+        assert e.value.code == -2 and len(eng.rollout_live_samples()) == 4
+        before = eng.rollout_get_stats()["pages_in_use"]
+        assert eng.rollout_abort(ids[2:]) == 2 and eng.rollout_get_stats()["pages_in_use"] < before
+        eng.rollout_decode_step()                                # room again
+        eng.rollout_abort(ids[:2])
+        assert eng.rollout_get_stats()["pages_in_use"] == 0
+    eng.close()
