@@ -108,6 +108,28 @@ def test_matrix_core_decode_shapes(n_prompts, n_samples, lo, hi):
     eng.close()
 
 
+def test_decode_attention_of_a_long_tailed_large_batch():
+    """128 live rows x 2 KV heads (a workgroup per row and head already fills the chip: no KV
+    splits) with contexts of 6 to 700 positions, mean about 60, as a long-tailed rollout leaves
+    them: a few workgroups walk hundreds of positions while most are done after one group.
+    Every row against the oracle."""
+    shape = workloads.SMALL_BF16
+    w = scaled_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    eng = make_engine(shape, w, max_live_samples=128, max_context=1024, max_batch_tokens=4096)
+    rng = np.random.default_rng(23)
+    lens = rng.integers(6, 40, 16)
+    lens[3], lens[11] = 700, 333
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    toks = rng.integers(0, shape.vocab, int(offs[-1])).astype(np.int32)
+    steps, n = 3, 8
+    forced = rng.integers(0, shape.vocab, (16 * n, steps)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, n, forced, steps)
+    print(f"long-tailed batch of 128 rows: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"]
+    eng.close()
+
+
 @pytest.mark.parametrize("simple", [False, True], ids=["fast", "plain"])
 def test_c2_shape_slice_matches_oracle(simple):
     """The benchmark's model shape (28 layers, hidden 1536, 12/2 heads, FFN 8960, vocab 151936,
