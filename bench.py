@@ -92,15 +92,19 @@ def write_step_trace(path, trace, load, kv_bytes_per_token, weight_bytes, comman
                     f"{100 * n * ms / total:28.1f} %\n")
 
 
-def run_queue_job(eng, load) -> int:
+def run_queue_job(eng, load, step_ms=None) -> int:
     """The same kind of job fed through the library's prompt queue: every prompt is pushed up
-    front, the scheduler admits them as slots and pages free up.  Returns the tokens emitted."""
+    front, the scheduler admits them as slots and pages free up.  Returns the tokens emitted;
+    step_ms (a list) receives the host-clock duration of every queue step."""
     eng.rollout_queue_push(load.prompt_tokens, load.prompt_offsets, load.n_samples, load.max_new_tokens,
                            eos_id=-1, temperature=load.temperature, top_p=load.top_p)
     emitted = 0
     while True:
+        t0 = time.perf_counter()
         ids = eng.rollout_queue_step()[0]
-        if not len(ids):
+        if step_ms is not None:
+            step_ms.append(1e3 * (time.perf_counter() - t0))
+        if not len(ids) and not eng.rollout_queue_busy():   # (a step that only caches prompt rows emits nothing)
             return emitted
         emitted += len(ids)
 
@@ -353,6 +357,9 @@ def main() -> int:
                          "policy-gradient objective over config 5's 512 packed sequences (rollout_policy_loss)")
     ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
     ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
+    ap.add_argument("--chunk-rows", type=int, default=0,
+                    help="c2-queue: chunked prefill, at most this many prompt rows ride along with each decode step "
+                         "(0 = whole prompts before the step)")
     ap.add_argument("--prompt-groups", action="store_true",
                     help="decode attention reads shared prompt pages once per group of samples (library flag)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -499,9 +506,14 @@ def main() -> int:
         eng = R.Rollout(shape, weights, kv_pool_bytes=live * (max_ctx + 64) * kv_bytes_per_token, page_tokens=32,
                         max_live_samples=live, max_context=max_ctx, max_batch_tokens=max(16384, max_prompt),
                         seed=load.sampler_seed, flags=flags, timing_stride=max(args.timing_stride, 1))
-        work = lambda: run_queue_job(eng, load)
+        if args.chunk_rows:
+            eng.rollout_queue_chunking(args.chunk_rows)
+        queue_step_ms = []
+        work = lambda: run_queue_job(eng, load, queue_step_ms)
         desc = ("configs[1]'s model and length laws, %d prompts x %d samples pushed to the prompt queue, admitted "
-                "into %d live slots as samples finish" % (load.n_prompts, load.n_samples, live)) + cut
+                "into %d live slots as samples finish%s" % (
+                    load.n_prompts, load.n_samples, live,
+                    ", at most %d prompt rows per step (chunked prefill)" % args.chunk_rows if args.chunk_rows else "")) + cut
     else:
         loader = {"c2": workloads.load_c2, "c3": workloads.load_c3, "c4": workloads.load_c4}[wl]
         load = loader(n_prompts=args.prompts) if args.prompts else loader()
@@ -538,6 +550,8 @@ def main() -> int:
         eng.rollout_abort(ids)
     for _ in range(args.warmup):
         work()
+    if wl == "c2-queue":
+        del queue_step_ms[:]
     torch.cuda.synchronize()
     before = {k["name"]: k for k in eng.rollout_kernel_stats()}
     calls0 = int(eng.rollout_get_stats()["decode_steps"])
@@ -571,6 +585,10 @@ def main() -> int:
             shape.n_layers * shape.n_experts * 3 * shape.expert_ffn_dim * shape.hidden
         write_step_trace(args.step_trace, trace, load, kv_bytes_per_token, 2 * non_expert,
                          "python bench.py " + " ".join(sys.argv[1:]))
+    if wl == "c2-queue" and queue_step_ms:  # how long the live samples wait between two of their tokens
+        q = np.sort(np.array(queue_step_ms))
+        out["config"]["queue_steps"] = {"steps": len(q), "mean_ms": float(q.mean()), "p99_ms": float(q[int(0.99 * (len(q) - 1))]),
+                                        "max_ms": float(q[-1]), "chunk_rows": args.chunk_rows}
     if wl == "c2-turns" and extend_clock[0] > 0:  # warm-up jobs included: a rate, not a total
         out["config"]["appended_tokens_per_s"] = extend_clock[1] / extend_clock[0]
     eng.close()

@@ -233,6 +233,7 @@ typedef struct {
   uint64_t prompts_preempted;                                   /* ROLLOUT_RT_GROW_PAGES: sent back to the queue to make room */
   int32_t prompts_waiting;
   int32_t closed;                                               /* 1 once the target was reached */
+  int32_t prompts_pending;                                      /* chunked prefill: admitted, prompt not fully cached yet */
 } rollout_queue_stats;
 
 /* Appends n_prompts prompts (n_samples samples each) to the queue; host arrays as for
@@ -275,6 +276,25 @@ int rollout_queue_policy(rollout_ctx *ctx, int32_t admit_min_prompts, int32_t ta
  * queue (abort some). */
 int rollout_queue_step(rollout_ctx *ctx, int32_t *n_out, int32_t *n_admitted, int64_t *sample_ids,
                        int32_t *tokens, float *logprobs, uint8_t *finished);
+
+/* Chunked prefill for the queue-fed rollout (paper section 4.3: requests are added while the
+ * other samples keep decoding).  chunk_rows = 0 (default): rollout_queue_step runs the whole
+ * prefill of the prompts it admits before its decode step, as described above.  chunk_rows > 0:
+ * a step is ONE forward pass that carries a decode row for every live sample and at most
+ * chunk_rows rows of admitted prompts, in push order, a prompt being cut where the budget ends
+ * and continued in the next step (its rows attend to what earlier steps cached).  A prompt
+ * takes its pages and its samples' slots and pages when it is admitted; its samples emit
+ * response position 0 in the step that caches its last rows - they are that step's first
+ * *n_admitted entries - and decode from the next step on, so a sample appears at most once per
+ * step and the capacity needed is live samples + samples of the prompts that end.  A step can
+ * return *n_out = 0 while prompts are still being cached: the queue is drained when
+ * rollout_queue_get_stats shows nothing waiting and nothing pending and no sample is live.
+ * With ROLLOUT_RT_GROW_PAGES the prompts that are only partly cached give way first when the pool
+ * runs out (they return to the head of the queue and count as preempted).  A sample's tokens do
+ * not depend on the setting beyond rounding: the chunks change which rows share a matrix tile.
+ * Matrix-core path only.  Errors: E_INVAL (chunk_rows < 0), E_STATE (plain path; a prompt is
+ * partly cached right now). */
+int rollout_queue_chunking(rollout_ctx *ctx, int32_t chunk_rows);
 
 int rollout_queue_get_stats(rollout_ctx *ctx, rollout_queue_stats *out);
 

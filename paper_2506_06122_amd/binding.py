@@ -61,7 +61,7 @@ class rollout_stats(C.Structure):
 class rollout_queue_stats(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("prompts_pushed", "prompts_admitted", "prompts_completed",
                                           "samples_aborted", "prompts_preempted")] + \
-               [("prompts_waiting", C.c_int32), ("closed", C.c_int32)]
+               [("prompts_waiting", C.c_int32), ("closed", C.c_int32), ("prompts_pending", C.c_int32)]
 
 
 class rollout_tensor_update(C.Structure):
@@ -98,6 +98,7 @@ SIGNATURES = {
     "rollout_extend": (C.c_int, [_P, C.c_int32, _P, _P, _P, _P, _P, _P, _P, _P]),
     "rollout_queue_push": (C.c_int, [_P, C.c_int32, _P, _P, C.c_int32, _P, C.c_int32, C.c_float, C.c_float, _P]),
     "rollout_queue_policy": (C.c_int, [_P, C.c_int32, C.c_int32]),
+    "rollout_queue_chunking": (C.c_int, [_P, C.c_int32]),
     "rollout_queue_step": (C.c_int, [_P, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _P, _P, _P, _P]),
     "rollout_queue_get_stats": (C.c_int, [_P, C.POINTER(rollout_queue_stats)]),
     "rollout_debug_logits": (C.c_int, [_P, C.POINTER(C.c_int32), _P]),
@@ -321,6 +322,15 @@ class Rollout:
 
     def rollout_queue_policy(self, admit_min_prompts=1, target_prompts=0):
         self._check(self.lib.rollout_queue_policy(self.ctx, admit_min_prompts, target_prompts))
+
+    def rollout_queue_chunking(self, chunk_rows):
+        self._check(self.lib.rollout_queue_chunking(self.ctx, chunk_rows))
+
+    def rollout_queue_busy(self) -> bool:
+        """True while the queue still has work: prompts waiting or partly cached, or live samples."""
+        qs = self.rollout_queue_get_stats()
+        return not qs["closed"] and (qs["prompts_waiting"] > 0 or qs["prompts_pending"] > 0 or
+                                     self.rollout_get_stats()["live_samples"] > 0)
 
     def rollout_queue_step(self):
         """Returns (sample_ids, tokens, logprobs, finished, n_admitted)."""

@@ -306,18 +306,33 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
   refresh_stats(c);
 }
 
+// Prompt rows that ride along with a decode step (chunked prefill): the rows of `seqs`, cut from
+// the queue's pending prompts, go through the same forward pass behind the decode rows.  The
+// prompts that end in the step sample response position 0 of their samples; `first_*` receive
+// those results, n samples per finishing prompt in the order of `seqs`.
+struct StepChunk {
+  std::vector<ChunkSeq> seqs;
+  int rows = 0;
+  std::vector<int64_t> first_ids, first_groups;
+  std::vector<int32_t> first_tokens;
+  std::vector<float> first_logprobs;
+  std::vector<uint8_t> first_finished;
+};
+
 // groups (optional): the prompt counter of every stepped sample, for the queue's bookkeeping
 static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint32_t* uniform_override,
                         int32_t* n_live, int64_t* sample_ids, int32_t* tokens, float* logprobs,
-                        uint8_t* finished, int64_t* groups = nullptr) {
+                        uint8_t* finished, int64_t* groups = nullptr, StepChunk* chunk = nullptr) {
   const rollout_model_desc& m = c.md;
   if (!n_live) fail(ROLLOUT_E_INVAL, "n_live is null");
   const int B = (int)c.live.size(), R = c.r_max;
-  if (B == 0) {
+  const int Rq = chunk ? chunk->rows : 0;
+  if (B == 0 && Rq == 0) {
     *n_live = 0;
     return;
   }
   if (*n_live < B) fail(ROLLOUT_E_INVAL, "output capacity smaller than the live-sample count");
+  if (Rq && (c.simple || B + Rq > R)) fail(ROLLOUT_E_STATE, "internal: the step cannot carry these prompt rows");
   if (forced_tokens)
     for (int i = 0; i < B; ++i)
       if (forced_tokens[i] < 0 || forced_tokens[i] >= m.vocab) fail(ROLLOUT_E_INVAL, "forced token out of range");
@@ -403,11 +418,60 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
                  (double)c.shared_saved >= 0.2 * c.kv_tokens_this_call;
   c.kv_unique_tokens_this_call = c.kv_tokens_this_call - (double)c.shared_dup;
   c.attn_flops_this_call = 4.0 * c.kv_tokens_this_call * c.q_dim;
+  PromptQueue& q = c.queue;
+  const int n = q.n_samples;
+  int n_fin = 0;  // prompts that end in this step: their last rows' logits follow the decode rows'
   c.timer.start_call();
-  engine_forward_rows(c, B, nullptr);
-  c.timer.empty_bracket(c.stream);
-  engine_logits(c, nullptr, 0, B, c.logits.p);
-  c.last_logit_rows = B;
+  if (!Rq) {
+    engine_forward_rows(c, B, nullptr);
+    c.timer.empty_bracket(c.stream);
+    engine_logits(c, nullptr, 0, B, c.logits.p);
+    c.last_logit_rows = B;
+  } else {
+    // pageable staging: each of these uploads is complete when its call returns
+    const int ns = (int)chunk->seqs.size();
+    std::vector<int> tok(Rq), pos(Rq), slot(Rq), row0(ns), len(ns), srow(ns), pos0(ns), want(B);
+    for (int i = 0; i < B; ++i) want[i] = i;
+    int r = 0, max_len = 0;
+    c.chunk_kv_tokens = 0;
+    for (int k = 0; k < ns; ++k) {
+      const ChunkSeq& cs = chunk->seqs[k];
+      const PendingPrompt& pp = q.pending[cs.pending_index];
+      row0[k] = B + r;
+      len[k] = cs.len;
+      srow[k] = pp.table_row;
+      pos0[k] = cs.begin;
+      for (int i = 0; i < cs.len; ++i, ++r) {
+        tok[r] = pp.prompt.tokens[cs.begin + i];
+        pos[r] = cs.begin + i;
+        slot[r] = pp.table_row;
+      }
+      if (cs.last) {
+        want.push_back(B + r - 1);
+        ++n_fin;
+      }
+      max_len = std::max(max_len, cs.len);
+      c.chunk_kv_tokens += (double)cs.len * cs.begin + 0.5 * cs.len * (cs.len + 1.0);
+    }
+    if (ns > rollout_ctx::kTempSlots || B + n_fin > c.logit_rows || (long long)B + (long long)n_fin * n > R)
+      fail(ROLLOUT_E_STATE, "internal: the chunk plan exceeds the workspaces");
+    c.chunk_attn_flops = 4.0 * c.chunk_kv_tokens * c.q_dim;
+    h2d(c.row_token.p + B, tok.data(), Rq * sizeof(int), c.stream);
+    h2d(c.row_pos.p + B, pos.data(), Rq * sizeof(int), c.stream);
+    h2d(c.row_slot.p + B, slot.data(), Rq * sizeof(int), c.stream);
+    h2d(c.seq_row0.p, row0.data(), ns * sizeof(int), c.stream);
+    h2d(c.seq_len.p, len.data(), ns * sizeof(int), c.stream);
+    h2d(c.seq_slot.p, srow.data(), ns * sizeof(int), c.stream);
+    h2d(c.seq_pos0.p, pos0.data(), ns * sizeof(int), c.stream);
+    h2d(c.chunk_ints.p, want.data(), want.size() * sizeof(int), c.stream);
+    SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, ns, max_len};
+    sb.pos0 = c.seq_pos0.p;
+    sb.decode_rows = B;
+    engine_forward_rows(c, B + Rq, &sb);
+    engine_logits(c, c.chunk_ints.p, 0, B + n_fin, c.logits.p);
+    c.last_logit_rows = B + n_fin;
+    c.stats.prompt_tokens += Rq;
+  }
   if (forced_tokens) {
     std::memcpy(hi + R, forced_tokens, B * sizeof(int));
     h2d(c.row_forced.p, hi + R, B * sizeof(int), c.stream);
@@ -437,6 +501,76 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
   c.timer.end(c.stream);
   // pinned host memory is mapped for the device: the kernel stores the step's results there
   launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, c.out_logprobs.p, B, 1, hi + 3 * R, c.h_float.p, c.stream);
+
+  // ---- prompts that end in this step: response position 0 of their samples (rows B .. of the row arrays) ----
+  const int Rs = n_fin * n;
+  std::vector<PendingPrompt*> fin;
+  if (n_fin) {
+    std::vector<int> pairs, lrow(Rs), step0(Rs, 0), forced(Rs, -1), slots, srows, spos;
+    std::vector<float> inv_t(Rs), top_p(Rs);
+    std::vector<long long> ids(Rs);
+    for (const ChunkSeq& cs : chunk->seqs)
+      if (cs.last) fin.push_back(&q.pending[cs.pending_index]);
+    for (int k = 0; k < n_fin; ++k) {
+      const PendingPrompt& pp = *fin[k];
+      pairs.insert(pairs.end(), pp.copy_pairs.begin(), pp.copy_pairs.end());
+      for (int j = 0; j < n; ++j) {
+        const int i = k * n + j;
+        lrow[i] = B + k;
+        inv_t[i] = 1.0f / pp.prompt.temperature;
+        top_p[i] = pp.prompt.top_p;
+        ids[i] = pp.samples[j].id;
+        if (pp.samples[j].slot >= 0) {
+          slots.push_back(pp.samples[j].slot);
+          srows.push_back(i);
+          spos.push_back(pp.samples[j].prompt_len);
+        }
+      }
+    }
+    if (pairs.size() > 2 * (size_t)R) fail(ROLLOUT_E_STATE, "internal: page copy list too long");
+    if (!pairs.empty()) {  // private copies of each prompt's partial last page
+      h2d(c.chunk_ints.p + R, pairs.data(), pairs.size() * sizeof(int), c.stream);
+      launch_copy_pages(c.kv_pool.p, c.chunk_ints.p + R, (int)pairs.size() / 2, m.n_layers,
+                        c.geom.layer_stride * c.elem, c.geom.page_stride * c.elem, c.stream);
+    }
+    h2d(c.row_aux.p + B, lrow.data(), Rs * sizeof(int), c.stream);
+    h2d(c.row_forced.p + B, forced.data(), Rs * sizeof(int), c.stream);
+    h2d(c.row_step.p + B, step0.data(), Rs * sizeof(int), c.stream);
+    h2d(c.row_inv_temp.p + B, inv_t.data(), Rs * sizeof(float), c.stream);
+    h2d(c.row_top_p.p + B, top_p.data(), Rs * sizeof(float), c.stream);
+    h2d(c.row_sample_id.p + B, ids.data(), Rs * sizeof(long long), c.stream);
+    SampleRows fr{};
+    fr.logits = c.logits.p;
+    fr.logits_row = c.row_aux.p + B;
+    fr.inv_temp = c.row_inv_temp.p + B;
+    fr.top_p = c.row_top_p.p + B;
+    fr.uniforms = nullptr;
+    fr.sample_id = c.row_sample_id.p + B;
+    fr.step = c.row_step.p + B;
+    fr.forced = c.row_forced.p + B;
+    fr.seed = c.rd.seed;
+    fr.tokens = c.out_tokens.p + B;
+    fr.logprobs = c.out_logprobs.p + B;
+    fr.weight_sums = nullptr;
+    if (Rs <= c.samp_rows) {
+      fr.part_max = c.samp_part_max.p;
+      fr.seg_sums = c.samp_seg_sums.p;
+    }
+    launch_sample(fr, Rs, m.vocab, c.stream);
+    const int n_new = (int)slots.size();
+    if (n_new) {  // the slot state of the samples that go on: the lists sit behind the page pairs
+      int* lists = c.chunk_ints.p + R + pairs.size();
+      if (pairs.size() + 3 * (size_t)n_new > 2 * (size_t)R) fail(ROLLOUT_E_STATE, "internal: slot lists too long");
+      h2d(lists, slots.data(), n_new * sizeof(int), c.stream);
+      h2d(lists + n_new, srows.data(), n_new * sizeof(int), c.stream);
+      h2d(lists + 2 * n_new, spos.data(), n_new * sizeof(int), c.stream);
+      init_slots_kernel<<<ceil_div(n_new, 256), 256, 0, c.stream>>>(c.st, lists, lists + n_new, lists + 2 * n_new,
+                                                                    c.out_tokens.p + B, c.row_sample_id.p + B,
+                                                                    c.row_inv_temp.p + B, c.row_top_p.p + B, n_new);
+    }
+    d2h(hi + 7 * R, c.out_tokens.p + B, Rs * sizeof(int), c.stream);
+    d2h(c.h_float.p + R, c.out_logprobs.p + B, Rs * sizeof(float), c.stream);
+  }
   wait_step_done(c);
   c.timer.collect();
 
@@ -462,8 +596,58 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
     }
   }
   *n_live = B;
-  c.stats.decode_steps += 1;
+  if (B) c.stats.decode_steps += 1;
   c.stats.tokens_emitted += B;
+
+  // ---- chunk bookkeeping: progress of the pending prompts; the finished ones hand over to their samples ----
+  if (chunk) {
+    for (const ChunkSeq& cs : chunk->seqs) q.pending[cs.pending_index].done += cs.len;
+    chunk->first_ids.resize(Rs);
+    chunk->first_groups.resize(Rs);
+    chunk->first_tokens.resize(Rs);
+    chunk->first_logprobs.resize(Rs);
+    chunk->first_finished.resize(Rs);
+    for (int k = 0; k < n_fin; ++k) {
+      PendingPrompt& pp = *fin[k];
+      q.open[pp.prompt.prompt_id] = n;
+      for (int j = 0; j < n; ++j) {
+        const int i = k * n + j;
+        Sample& s = pp.samples[j];
+        const int tok = hi[7 * R + i];
+        s.n_emitted = 1;
+        s.last_token = tok;
+        const bool done = s.max_new <= 1 || (s.eos_id >= 0 && tok == s.eos_id);
+        chunk->first_ids[i] = s.id;
+        chunk->first_groups[i] = s.group;
+        chunk->first_tokens[i] = tok;
+        chunk->first_logprobs[i] = c.h_float.p[R + i];
+        chunk->first_finished[i] = done ? 1 : 0;
+        c.stats.tokens_emitted += 1;
+        c.stats.samples_admitted += 1;
+        if (done) {
+          release_sample(c, s);
+          c.stats.samples_finished += 1;
+        } else {
+          const int64_t id = s.id;
+          Sample moved = std::move(s);
+          auto res = c.live.emplace(id, std::move(moved));
+          if (!res.second) {  // cannot happen: ids are handed out once
+            release_sample(c, moved);
+            c.stats.samples_aborted += 1;
+          }
+        }
+      }
+      // the prefill's own references; the samples hold theirs
+      for (int32_t pg : pp.pages.shared) c.pool->release(pg);
+      if (pp.pages.tail >= 0) c.pool->release(pp.pages.tail);
+      q.free_rows.push_back(pp.table_row);
+      if (c.grow_pages) q.admitted.emplace(pp.prompt.prompt_id, std::move(pp.prompt));  // kept: it may have to start over
+      c.stats.prompts_prefilled += 1;
+      c.live_dirty = true;
+    }
+    // finished prompts sit at the front of the pending list (prompts are cached in order)
+    for (int k = 0; k < n_fin; ++k) q.pending.pop_front();
+  }
   refresh_stats(c);
 }
 
@@ -627,6 +811,90 @@ static void extend_impl(rollout_ctx& c, int32_t n, const int64_t* sample_ids, co
   refresh_stats(c);
 }
 
+// The target is reached: abort what still runs, drop what still waits or is half cached.
+static void close_queue(rollout_ctx& c) {
+  PromptQueue& q = c.queue;
+  const int running = (int)c.live.size();
+  for (auto& kv : c.live) release_sample(c, kv.second);
+  c.live.clear();
+  c.live_dirty = true;
+  c.stats.samples_aborted += running;
+  q.aborted += running;
+  for (PendingPrompt& pp : q.pending) release_pending(c, pp);
+  q.pending.clear();
+  q.waiting.clear();
+  q.open.clear();
+  q.admitted.clear();
+  q.closed = true;
+  refresh_stats(c);
+}
+
+// One step of the queue-fed rollout with chunked prefill (paper section 4.3, "add request" while
+// the other samples keep decoding): a single forward pass carries one decode row per live sample
+// and up to chunk_rows rows of the pending prompts.  A prompt's samples emit response position 0
+// in the step that caches its last rows and take part in the decode rows from the next step on.
+static void queue_step_chunked(rollout_ctx& c, int cap, int32_t* n_out, int32_t* n_admitted, int64_t* sample_ids,
+                               int32_t* tokens, float* logprobs, uint8_t* finished) {
+  PromptQueue& q = c.queue;
+  const int n = q.n_samples;
+  // (0) growing pages: make room for the pages this step writes - first the prompts that are only
+  // half cached (nothing of theirs is lost but the work), then the youngest running prompt
+  int n_preempted = 0;
+  if (c.grow_pages) {
+    while (pages_missing_for_step(c) > c.pool->unreserved()) {
+      if (queue_preempt_pending(c)) {
+        ++n_preempted;
+        continue;
+      }
+      const int dropped = queue_preempt_youngest(c, nullptr);
+      if (!dropped) fail(ROLLOUT_E_NOMEM, "the KV pool is exhausted and no queued prompt can give way: abort samples");
+      c.stats.samples_aborted += dropped;
+      n_preempted += dropped;
+    }
+  }
+  // (1) admission: keep about one step's worth of prompt rows pending
+  bool admitted_any = false;
+  if (!n_preempted && !q.waiting.empty() && pending_rows_left(q) < q.chunk_rows) {
+    int k = queue_select_run(c, AdmissionLimits{(int)q.free_rows.size(), (long long)c.r_max});
+    while (k-- > 0 && pending_rows_left(q) < q.chunk_rows) {
+      queue_admit_pending(c);
+      admitted_any = true;
+    }
+  }
+  if (admitted_any) engine_upload_page_table(c);
+  // (2) the step's rows
+  const int B = (int)c.live.size();
+  StepChunk chunk;
+  const long long budget = std::min<long long>({(long long)q.chunk_rows, (long long)c.r_max - B, (long long)rollout_ctx::kTempSlots});
+  const int max_fin = (int)std::min<long long>(c.logit_rows - B, ((long long)c.r_max - B) / std::max(n, 1));
+  chunk.rows = plan_chunk(q, budget, std::max(max_fin, 0), chunk.seqs);
+  int n_adm = 0;
+  for (const ChunkSeq& cs : chunk.seqs) n_adm += cs.last ? n : 0;
+  if (cap < B + n_adm) fail(ROLLOUT_E_INVAL, "output capacity smaller than live samples + samples of the prompts that end");
+  // (3) one forward pass for both
+  int n_dec = cap - n_adm;
+  std::vector<int64_t> ids_dec(B), grp_dec(B);
+  std::vector<uint8_t> fin_dec(B);
+  decode_impl(c, nullptr, nullptr, &n_dec, ids_dec.data(), tokens ? tokens + n_adm : nullptr,
+              logprobs ? logprobs + n_adm : nullptr, fin_dec.data(), grp_dec.data(), &chunk);
+  for (int i = 0; i < n_adm; ++i) {
+    if (sample_ids) sample_ids[i] = chunk.first_ids[i];
+    if (tokens) tokens[i] = chunk.first_tokens[i];
+    if (logprobs) logprobs[i] = chunk.first_logprobs[i];
+    if (finished) finished[i] = chunk.first_finished[i];
+    if (chunk.first_finished[i]) queue_note_finished(q, chunk.first_groups[i]);
+  }
+  for (int i = 0; i < n_dec; ++i) {
+    if (sample_ids) sample_ids[n_adm + i] = ids_dec[i];
+    if (finished) finished[n_adm + i] = fin_dec[i];
+    if (fin_dec[i]) queue_note_finished(q, grp_dec[i]);
+  }
+  *n_admitted = n_adm;
+  *n_out = n_adm + n_dec;
+  // (4) enough prompts complete
+  if (q.target > 0 && q.completed >= (uint64_t)q.target) close_queue(c);
+}
+
 extern "C" {
 
 int rollout_abi_version(void) { return ROLLOUT_ABI_VERSION; }
@@ -780,6 +1048,15 @@ int rollout_queue_policy(rollout_ctx* ctx, int32_t admit_min_prompts, int32_t ta
   return ROLLOUT_OK;
 }
 
+int rollout_queue_chunking(rollout_ctx* ctx, int32_t chunk_rows) {
+  if (!ctx || chunk_rows < 0) return ROLLOUT_E_INVAL;
+  return guarded(ctx, [&] {
+    if (chunk_rows > 0 && ctx->simple) fail(ROLLOUT_E_STATE, "chunked prefill runs on the matrix-core path only");
+    if (!ctx->queue.pending.empty()) fail(ROLLOUT_E_STATE, "a prompt's prefill is under way");
+    ctx->queue.chunk_rows = chunk_rows;
+  });
+}
+
 int rollout_queue_get_stats(rollout_ctx* ctx, rollout_queue_stats* out) {
   if (!ctx || !out) return ROLLOUT_E_INVAL;
   const PromptQueue& q = ctx->queue;
@@ -789,6 +1066,7 @@ int rollout_queue_get_stats(rollout_ctx* ctx, rollout_queue_stats* out) {
   out->samples_aborted = q.aborted;
   out->prompts_preempted = q.preempted;
   out->prompts_waiting = (int32_t)q.waiting.size();
+  out->prompts_pending = (int32_t)q.pending.size();
   out->closed = q.closed ? 1 : 0;
   return ROLLOUT_OK;
 }
@@ -805,6 +1083,10 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
     *n_out = 0;
     *n_admitted = 0;
     if (q.closed) return;
+    if (q.chunk_rows > 0) {
+      queue_step_chunked(c, cap, n_out, n_admitted, sample_ids, tokens, logprobs, finished);
+      return;
+    }
 
     // (0) growing pages: make room for this step's new pages - the youngest queued prompt gives way
     int n_preempted = 0;
@@ -872,19 +1154,7 @@ int rollout_queue_step(rollout_ctx* ctx, int32_t* n_out, int32_t* n_admitted, in
     *n_out = n_adm + n_dec;
 
     // (3) enough prompts complete: abort what still runs, drop what still waits
-    if (q.target > 0 && q.completed >= (uint64_t)q.target) {
-      const int running = (int)c.live.size();
-      for (auto& kv : c.live) release_sample(c, kv.second);
-      c.live.clear();
-      c.live_dirty = true;
-      c.stats.samples_aborted += running;
-      q.aborted += running;
-      q.waiting.clear();
-      q.open.clear();
-      q.admitted.clear();
-      q.closed = true;
-      refresh_stats(c);
-    }
+    if (q.target > 0 && q.completed >= (uint64_t)q.target) close_queue(c);
   });
 }
 
@@ -905,7 +1175,7 @@ int rollout_update_weights(rollout_ctx* ctx, int32_t n, const rollout_tensor_upd
     rollout_ctx& c = *ctx;
     check_usable(c);
     if (n < 0 || (n > 0 && !updates)) fail(ROLLOUT_E_INVAL, "bad arguments");
-    if (!c.live.empty() || !c.queue.waiting.empty())
+    if (!c.live.empty() || !c.queue.waiting.empty() || !c.queue.pending.empty())
       fail(ROLLOUT_E_STATE, "weights cannot change while samples are live or prompts wait");
     for (int i = 0; i < n; ++i) {  // the whole bucket is checked before any of it is applied
       const rollout_tensor_update& u = updates[i];

@@ -76,6 +76,7 @@ struct SeqBatch {
   const int *row0, *len, *slot;
   int n_seqs, max_len;
   const int* pos0 = nullptr;  // first position of each sequence (NULL = 0)
+  int decode_rows = 0;        // rows [0, decode_rows) before the sequences: one decode row per live sample
 };
 
 // HIP-event brackets around kernel launches on sampled calls (ROLLOUT_RT_KERNEL_TIMING),
@@ -155,6 +156,7 @@ struct rollout_ctx : HostState {
   int q_dim = 0, kv_dim = 0, qkv_dim = 0, elem = 4;
   int n_slots = 0, temp_slot0 = 0, r_max = 0, logit_rows = 0;
   static constexpr int kTempSlots = 1024;
+  static constexpr int kPendingRows = 64;  // page-table rows behind the temporary ones: prompts whose prefill is under way
 
   // weights
   DevBuf<char> embed, lm_head, lm_head_p;
@@ -206,6 +208,9 @@ struct rollout_ctx : HostState {
   double kv_tokens_this_call = 0;   // cached positions attended by the current forward (for timing records)
   double attn_flops_this_call = 0;
   DevBuf<int> seq_row0, seq_len, seq_slot, seq_pos0;
+  // a decode step that carries a chunk of prompt rows (chunked prefill)
+  DevBuf<int> chunk_ints;        // [3 r_max]: rows whose logits are wanted, then (source, destination) page pairs
+  double chunk_kv_tokens = 0, chunk_attn_flops = 0;  // the chunk's share of the attention, for the timing records
   DevBuf<float> ssq;            // [partials][256] partial sums of squares of the residual rows (decode path)
   int ssq_partials = 0;
   bool h_is_final = false;      // the last forward left x * final gain in h_bf16 (decode path)

@@ -191,7 +191,9 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
   c.grow_pages = (r.flags & ROLLOUT_RT_GROW_PAGES) != 0;
   c.max_pages = ceil_div(r.max_context, r.page_tokens);
   c.temp_slot0 = r.max_live_samples;
-  c.n_slots = r.max_live_samples + rollout_ctx::kTempSlots;
+  c.n_slots = r.max_live_samples + rollout_ctx::kTempSlots + rollout_ctx::kPendingRows;
+  c.queue.free_rows.clear();
+  for (int i = rollout_ctx::kPendingRows - 1; i >= 0; --i) c.queue.free_rows.push_back(c.temp_slot0 + rollout_ctx::kTempSlots + i);
   c.r_max = std::max(r.max_batch_tokens, r.max_live_samples);
   c.logit_rows = std::max(r.max_live_samples, std::min(c.r_max, 1024));
 
@@ -313,6 +315,7 @@ void engine_init(rollout_ctx& c, const rollout_weights& w) {
     c.seq_len.alloc(rollout_ctx::kTempSlots);
     c.seq_slot.alloc(rollout_ctx::kTempSlots);
     c.seq_pos0.alloc(rollout_ctx::kTempSlots);
+    c.chunk_ints.alloc(3 * R);
   } else {
     c.h.alloc(R * d);
     c.qkv.alloc(R * c.qkv_dim);
@@ -607,27 +610,31 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
     at.layer = l;
     at.n_q_heads = m.n_q_heads;
     // algorithmic bytes: every cached position once, a prompt's shared pages once for all its samples
-    const double kv_bytes = (seqs ? c.kv_tokens_this_call : c.kv_unique_tokens_this_call) * (double)m.n_kv_heads * 128 * 2 * 2;
-    if (seqs) {
+    // Rows [0, Bd) are decode rows (one per live sample), rows [Bd, R) packed sequences; a step of
+    // the queue-fed rollout with a chunk of prompt rows has both.
+    const int Bd = seqs ? seqs->decode_rows : R, Rq = R - Bd;
+    const double kv_unit = (double)m.n_kv_heads * 128 * 2 * 2;
+    if (Rq > 0) {
       // packed sequences: sum the planes, rotate, write the KV pages, then causal attention
+      const double kv_bytes = (Bd ? c.chunk_kv_tokens : c.kv_tokens_this_call) * kv_unit;
       QkvPostArgs qp{};
-      qp.partial = c.partial.p;
+      qp.partial = c.partial.p + (size_t)Bd * c.qkv_dim;
       qp.split_stride = (long long)R * c.qkv_dim;
       qp.splits = z;
       qp.cos_sin = c.cos_sin.p;
-      qp.row_pos = c.row_pos.p;
-      qp.row_slot = c.row_slot.p;
+      qp.row_pos = c.row_pos.p + Bd;
+      qp.row_slot = c.row_slot.p + Bd;
       qp.page_table = c.d_page_table.p;
       qp.max_pages = c.max_pages;
-      qp.q_bf16 = c.q_bf16.p;
+      qp.q_bf16 = c.q_bf16.p + (size_t)Bd * c.q_dim;
       qp.q_lo_offset = (long long)(c.q_bf16.n / 2);
       qp.kv_pool = (uint16_t*)c.kv_pool.p;
       qp.geom = c.geom;
       qp.layer = l;
-      qp.rows = R;
+      qp.rows = Rq;
       qp.n_q_heads = m.n_q_heads;
       qp.extra = QkvExtras{L.qkv_bias.p, L.q_gain.p, L.k_gain.p, m.rms_eps};
-      c.timer.begin("qkv_post_kernel", (double)R * c.qkv_dim * (4 + 2), 0, s);
+      c.timer.begin("qkv_post_kernel", (double)Rq * c.qkv_dim * (4 + 2), 0, s);
       launch_qkv_post(qp, s);
       c.timer.end(s);
       at.q = c.q_bf16.p;
@@ -638,24 +645,26 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
       at.seq_pos0 = seqs->pos0;
       at.n_seqs = seqs->n_seqs;
       at.max_seq_len = seqs->max_len;
-      c.timer.begin("attn_prefill_kernel", kv_bytes + 4.0 * R * c.q_dim, c.attn_flops_this_call, s);
+      c.timer.begin("attn_prefill_kernel", kv_bytes + 4.0 * Rq * c.q_dim, Bd ? c.chunk_attn_flops : c.attn_flops_this_call, s);
       launch_attention_prefill(at, s);
       c.timer.end(s);
-    } else {
+    }
+    if (Bd > 0) {
       // one row per sample: the fused decode attention sums the projection's planes itself
+      const double kv_bytes = c.kv_unique_tokens_this_call * kv_unit;
       at.kv_pool_w = (uint16_t*)c.kv_pool.p;
       at.row_pos = c.row_pos.p;
       at.row_slot = c.row_slot.p;
-      at.rows = R;
+      at.rows = Bd;
       at.qkv_raw = c.partial.p;
       at.qkv_planes = z;
       at.qkv_plane_stride = (long long)R * c.qkv_dim;
       at.cos_sin = c.cos_sin.p;
       at.extra = QkvExtras{L.qkv_bias.p, L.q_gain.p, L.k_gain.p, m.rms_eps};
-      const int base = R * m.n_kv_heads;
+      const int base = Bd * m.n_kv_heads;
       at.part_o = c.attn_part_o.p;
       at.part_ml = c.attn_part_ml.p;
-      const double qo_bytes = (double)R * (4.0 * z * c.qkv_dim + 4.0 * c.q_dim);
+      const double qo_bytes = (double)Bd * (4.0 * z * c.qkv_dim + 4.0 * c.q_dim);
       if (c.use_groups) {
         // shared prompts by group, in splits of at least 128 positions that give every CU a
         // workgroup; own ranges in splits of 1024 or more (few, long-lived workgroups: one round on the chip)

@@ -42,8 +42,30 @@ struct QueuedPrompt {
   int eos_id;
   float temperature, top_p;
 };
+// The shared pages of one admitted prompt while its prefill runs (the caller releases these
+// references when the samples hold their own).
+struct PromptPages {
+  std::vector<int32_t> shared;
+  int32_t tail = -1;
+};
+// A prompt whose prefill is spread over several queue steps (chunked prefill).  Everything it will
+// hold is taken when it is admitted - the prompt's pages, its samples' slots and pages - so that a
+// prompt once begun can always finish; its samples go live when its last chunk is cached.
+struct PendingPrompt {
+  QueuedPrompt prompt;
+  int table_row = -1;          // the page-table row its prefill writes through
+  int done = 0;                // prompt positions cached so far
+  PromptPages pages;
+  std::vector<Sample> samples;
+  std::vector<int> copy_pairs;     // (source, destination) pages: private copies of the partial last page
+  std::vector<int32_t> page_refs;  // every page reference taken at admission
+  std::vector<int> slots;          // every live-sample slot taken at admission
+};
 struct PromptQueue {
   std::deque<QueuedPrompt> waiting;
+  int chunk_rows = 0;               // > 0: chunked prefill, at most this many prompt rows per step
+  std::deque<PendingPrompt> pending;  // admitted, prefill not complete (push order)
+  std::vector<int> free_rows;       // page-table rows for pending prompts
   int n_samples = 0;      // fixed by the first push
   int admit_min = 1;      // admit only when this many waiting prompts fit (or nothing is live)
   int target = 0;         // close the queue once this many prompts are complete; 0 = never
@@ -124,13 +146,6 @@ inline int admission_slots(int n, const int32_t* max_new) {
   for (int j = 0; j < n; ++j) s += max_new[j] > 1;
   return s;
 }
-
-// The shared pages of one admitted prompt while its prefill runs (the caller releases these
-// references when the samples hold their own).
-struct PromptPages {
-  std::vector<int32_t> shared;
-  int32_t tail = -1;
-};
 
 // Takes the pages and slots of prompt p (length len, counter `group`, first sample id `first`) and
 // fills fresh[0..n): the prompt's full pages once, shared by reference; a private copy target for
@@ -289,4 +304,90 @@ inline int queue_preempt_youngest(HostState& c, std::vector<int64_t>* dropped_id
   q.preempted += 1;
   c.live_dirty = true;
   return dropped;
+}
+
+// ---- chunked prefill ------------------------------------------------------------------------------
+inline long long pending_rows_left(const PromptQueue& q) {
+  long long rows = 0;
+  for (const PendingPrompt& p : q.pending) rows += (long long)p.prompt.tokens.size() - p.done;
+  return rows;
+}
+
+// The head of the queue becomes a pending prompt: its pages and its samples' slots and pages are
+// taken now (the caller has checked with queue_select_run that they are there).  Leaves the queue
+// untouched when it throws.
+inline void queue_admit_pending(HostState& c) {
+  PromptQueue& q = c.queue;
+  if (q.waiting.empty() || q.free_rows.empty()) throw ApiError{ROLLOUT_E_STATE, "internal: nothing to admit"};
+  const QueuedPrompt& e = q.waiting.front();
+  const int n = q.n_samples;
+  PendingPrompt pp;
+  pp.table_row = q.free_rows.back();
+  pp.samples.resize((size_t)n);
+  {
+    Rollback undo(c);
+    take_prompt_pages(c, undo, (int)e.tokens.size(), n, e.max_new.data(), e.eos_id, e.prompt_id, e.first_sample,
+                      pp.table_row, pp.pages, pp.samples.data(), pp.copy_pairs);
+    pp.page_refs = std::move(undo.page_refs);
+    pp.slots = std::move(undo.slots);
+    undo.commit();
+  }
+  pp.prompt = std::move(q.waiting.front());
+  q.waiting.pop_front();
+  q.free_rows.pop_back();
+  q.pending.push_back(std::move(pp));
+  q.admitted_count += 1;
+}
+
+// Gives back everything a pending prompt holds (it never went live).
+inline void release_pending(HostState& c, PendingPrompt& pp) {
+  for (int32_t pg : pp.page_refs) c.pool->release(pg);
+  for (auto it = pp.slots.rbegin(); it != pp.slots.rend(); ++it) c.free_slots.push_back(*it);
+  pp.page_refs.clear();
+  pp.slots.clear();
+  for (Sample& s : pp.samples) {
+    s.pages.clear();
+    s.slot = -1;
+  }
+  c.queue.free_rows.push_back(pp.table_row);
+  pp.table_row = -1;
+}
+
+// Growing pages, the pool is exhausted: the youngest pending prompt returns to the head of the
+// queue and starts over later.  False when nothing is pending.
+inline bool queue_preempt_pending(HostState& c) {
+  PromptQueue& q = c.queue;
+  if (q.pending.empty()) return false;
+  PendingPrompt& pp = q.pending.back();
+  release_pending(c, pp);
+  q.waiting.push_front(std::move(pp.prompt));
+  q.pending.pop_back();
+  q.admitted_count -= 1;
+  q.preempted += 1;
+  return true;
+}
+
+// The prompt rows of one step: pending prompts in order, `budget` rows in all, the last one cut
+// where the budget ends.  At most max_finishing prompts may reach their end in this step (each
+// needs a logits row); one more is cut one row short.
+struct ChunkSeq {
+  int pending_index, begin, len;
+  bool last;  // the chunk ends the prompt
+};
+inline int plan_chunk(const PromptQueue& q, long long budget, int max_finishing, std::vector<ChunkSeq>& out) {
+  int rows = 0, finishing = 0;
+  for (int i = 0; i < (int)q.pending.size() && budget > 0; ++i) {
+    const PendingPrompt& p = q.pending[i];
+    const int left = (int)p.prompt.tokens.size() - p.done;
+    int take = (int)std::min<long long>(left, budget);
+    if (take == left && finishing == max_finishing) --take;
+    if (take <= 0) break;
+    const bool last = take == left;
+    finishing += last;
+    out.push_back(ChunkSeq{i, p.done, take, last});
+    rows += take;
+    budget -= take;
+    if (!last) break;  // prompts are cached in order: nothing starts behind an unfinished one
+  }
+  return rows;
 }

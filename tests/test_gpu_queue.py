@@ -17,7 +17,7 @@ def drain(eng, max_live, max_steps=10000):
     seqs, order, peak = {}, [], 0
     for _ in range(max_steps):
         ids, toks, lps, fin, n_adm = eng.rollout_queue_step()
-        if not len(ids):
+        if not len(ids) and not eng.rollout_queue_busy():   # (with chunked prefill a step can emit nothing)
             break
         assert np.all(np.diff(ids[:n_adm]) > 0) and np.all(np.diff(ids[n_adm:]) > 0)
         for k, (i, t, lp) in enumerate(zip(ids, toks, lps)):
@@ -287,7 +287,7 @@ def drain_restartable(eng, max_live, max_steps=20000):
         st = eng.rollout_get_stats()
         assert st["live_samples"] <= max_live and st["pages_in_use"] <= st["pages_total"]
         peak = max(peak, st["live_samples"])
-        if not st["live_samples"] and not eng.rollout_queue_get_stats()["prompts_waiting"]:
+        if not eng.rollout_queue_busy():
             return seqs, restarts, peak
     raise AssertionError("the queue did not drain")
 
@@ -363,3 +363,91 @@ def test_growing_pages_admit_by_need_and_survive_exhaustion(scenario):
         eng.rollout_abort(ids[:2])
         assert eng.rollout_get_stats()["pages_in_use"] == 0
     eng.close()
+
+
+@pytest.mark.parametrize("chunk_rows,grow", [(48, False), (13, False), (40, True)],
+                         ids=["chunks-of-48", "chunks-of-13", "chunks-of-40-growing-pages"])
+def test_chunked_prefill_rides_along_with_decode_steps(chunk_rows, grow):
+    """rollout_queue_chunking: a step is one forward pass over a decode row per live sample plus
+    at most chunk_rows prompt rows; prompts are cut where the budget ends and go on in the next
+    step.  bf16 model on the matrix-core path, 8 prompts x 3 samples through 8 live slots; prompt
+    lengths below, at and above the chunk size, at page boundaries and one past them.
+      (1) no step carries more prompt rows than the budget, samples keep stepping while prompts
+          are cached, and every prompt row is cached exactly once (unless its prompt starts over);
+      (2) every sample's log-probs equal the oracle's per-sample rollout, teacher-forced on the
+          emitted tokens, within the bf16 tolerance - the oracle knows nothing of chunks;
+      (3) the same queue without chunking emits the same tokens for all but at most two samples
+          (rounding differs between batch shapes and may flip a draw on a boundary).
+    With growing pages, responses of 80 to 110 tokens and a pool of 20 pages, prompts - half cached ones first -
+    give way when the pool runs out and start over; the final results are checked the same way."""
+    import paper_2506_06122_amd as R
+    shape = workloads.SMALL_BF16
+    w = scaled_weights(shape, seed=1)
+    lens = [5, 48, 49, 130, 96, 33, 150, 64]
+    P, n, temperature, top_p, seed, slots = len(lens), 3, 0.8, 0.95, 11, 8
+    rng = np.random.default_rng(77)
+    toks = rng.integers(0, shape.vocab, sum(lens)).astype(np.int32)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    max_new = (rng.integers(80, 110, P * n) if grow else rng.integers(2, 16, P * n)).astype(np.int32)
+    max_new[4] = 1                                                  # ends at position 0, takes no slot
+    page_bytes = 32 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2 * 2
+    kw = dict(max_live_samples=slots, max_context=288, max_batch_tokens=512, seed=seed)
+    if grow:  # contexts grow by three or four pages: 20 pages are the worst case of the longest prompt alone
+        kw.update(kv_pool_bytes=20 * page_bytes, flags=R.binding.RT_GROW_PAGES)
+
+    def run(chunk):
+        eng = make_engine(shape, w, **kw)
+        assert eng.rollout_get_stats()["matrix_core_path"] == 1
+        eng.rollout_queue_chunking(chunk)
+        eng.rollout_queue_push(toks, offs, n, max_new, temperature=temperature, top_p=top_p)
+        seqs, restarts, peak, trace = {}, 0, 0, []
+        cached = 0
+        for _ in range(5000):
+            ids, tk, lps, fin, n_adm = eng.rollout_queue_step()
+            for k, (i, t, lp) in enumerate(zip(ids, tk, lps)):
+                if k < n_adm:
+                    restarts += int(i) in seqs
+                    seqs[int(i)] = ([], [])
+                seqs[int(i)][0].append(int(t))
+                seqs[int(i)][1].append(float(lp))
+            st, qs = eng.rollout_get_stats(), eng.rollout_queue_get_stats()
+            assert len(set(ids.tolist())) == len(ids) or not chunk     # chunked: a sample at most once per step
+            trace.append((st["prompt_tokens"] - cached, len(ids) - n_adm, qs["prompts_pending"]))
+            cached = st["prompt_tokens"]
+            assert st["live_samples"] <= slots
+            peak = max(peak, st["live_samples"])
+            if not eng.rollout_queue_busy():
+                break
+        else:
+            raise AssertionError("the queue did not drain")
+        st, qs = eng.rollout_get_stats(), eng.rollout_queue_get_stats()
+        assert st["pages_in_use"] == 0 and st["live_samples"] == 0 and qs["prompts_completed"] == P
+        assert qs["prompts_pending"] == 0 and qs["prompts_waiting"] == 0
+        eng.close()
+        return seqs, restarts, peak, trace, st, qs
+
+    seqs, restarts, peak, trace, st, qs = run(chunk_rows)
+    assert sorted(seqs) == list(range(P * n))
+    for sid, (t, _) in seqs.items():
+        assert len(t) == max_new[sid]
+    rows = [r for r, _, _ in trace]
+    assert max(rows) <= chunk_rows and sum(r > 0 for r in rows) >= sum(lens) // chunk_rows
+    assert any(r > 0 and d > 0 for r, d, _ in trace)               # prompt rows and decode rows in one step
+    assert any(p > 0 for _, _, p in trace)                         # a prompt was cut and went on in the next step
+    if grow:
+        assert qs["prompts_preempted"] > 0 and sum(rows) >= sum(lens) and restarts <= qs["prompts_preempted"] * n
+        assert st["pages_peak"] <= 20
+    else:
+        assert sum(rows) == sum(lens) and restarts == 0 and qs["prompts_preempted"] == 0
+
+    model = oracle_model(shape, w)
+    forced = {sid: t for sid, (t, _) in seqs.items()}
+    ref = rollout.generate(model, toks, offs, n, max_new, -1, temperature, top_p, seed, forced_tokens=forced)
+    worst = max(abs(a - b) for tr in ref for a, b in zip(tr.logprobs, seqs[tr.sample_id][1]))
+    whole = run(0)[0]
+    differ = [sid for sid in seqs if seqs[sid][0] != whole[sid][0]]
+    print(f"chunks of {chunk_rows}{' with growing pages' if grow else ''}: {len(trace)} steps, at most {max(rows)} prompt "
+          f"rows in one, peak {peak} live, {qs['prompts_preempted']} preemptions; max |dlogp| vs oracle = {worst:.3e}; "
+          f"{len(differ)} samples differ from the unchunked run")
+    assert worst <= 2e-2
+    assert len(differ) <= 2, differ
