@@ -124,6 +124,10 @@ typedef struct {
       samples_finished, samples_aborted;
   int32_t live_samples, pages_total, pages_in_use, pages_reserved, pages_peak;
   int32_t matrix_core_path; /* 1 when the bf16 matrix-core kernels run, 0 for the plain path */
+  /* host wall clock spent inside the calls of each phase, the wait for the device included (ms):
+   * rollout_prefill (and the whole-prompt prefills of the queue), decode steps (chunked queue steps
+   * as a whole), rollout_extend, rollout_logprobs */
+  double prefill_ms, decode_ms, extend_ms, logprobs_ms;
 } rollout_stats;
 
 /* Accumulated HIP-event timings of one kernel on the context's stream (sampled calls only):

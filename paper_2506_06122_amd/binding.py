@@ -55,7 +55,8 @@ class rollout_stats(C.Structure):
                                           "prompt_tokens", "samples_admitted", "samples_finished",
                                           "samples_aborted")] + \
                [(n, C.c_int32) for n in ("live_samples", "pages_total", "pages_in_use", "pages_reserved",
-                                         "pages_peak", "matrix_core_path")]
+                                         "pages_peak", "matrix_core_path")] + \
+               [(n, C.c_double) for n in ("prefill_ms", "decode_ms", "extend_ms", "logprobs_ms")]
 
 
 class rollout_queue_stats(C.Structure):

@@ -80,6 +80,15 @@ static void wait_step_done(rollout_ctx& c) {
   }
 }
 
+// Host wall clock of a phase (the wait for the device included), added to the statistics when the
+// phase ends, by an exception too.
+struct PhaseClock {
+  double& total_ms;
+  std::chrono::steady_clock::time_point t0 = std::chrono::steady_clock::now();
+  explicit PhaseClock(double& slot) : total_ms(slot) {}
+  ~PhaseClock() { total_ms += std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count(); }
+};
+
 static void check_usable(const rollout_ctx& c) {
   if (c.broken) throw ApiError{ROLLOUT_E_STATE, "an earlier call timed out on the device; destroy this context"};
 }
@@ -104,6 +113,7 @@ static void prefill_impl(rollout_ctx& c, int32_t n_prompts, const int32_t* token
                          int32_t* first_tokens, float* first_logprobs, uint8_t* finished) {
   const rollout_model_desc& m = c.md;
   const int P = n_prompts, n = n_samples, R = c.r_max;
+  PhaseClock clock(c.stats.prefill_ms);
   // ---- validation (no state changes before all of it passed) ----
   if (P < 1 || n < 1 || !tokens || !offsets || !max_new_tokens) fail(ROLLOUT_E_INVAL, "bad prompt arguments");
   if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
@@ -327,6 +337,7 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
   if (!n_live) fail(ROLLOUT_E_INVAL, "n_live is null");
   const int B = (int)c.live.size(), R = c.r_max;
   const int Rq = chunk ? chunk->rows : 0;
+  PhaseClock clock(c.stats.decode_ms);
   if (B == 0 && Rq == 0) {
     *n_live = 0;
     return;
@@ -671,6 +682,7 @@ static void extend_impl(rollout_ctx& c, int32_t n, const int64_t* sample_ids, co
                         int32_t* next_tokens, float* next_logprobs, uint8_t* finished) {
   const rollout_model_desc& m = c.md;
   const int T = c.page_tokens, R = c.r_max;
+  PhaseClock clock(c.stats.extend_ms);
   if (n < 1 || !sample_ids || !tokens || !offsets) fail(ROLLOUT_E_INVAL, "bad arguments");
   if (offsets[0] != 0) fail(ROLLOUT_E_INVAL, "offsets[0] must be 0");
   if (n > rollout_ctx::kTempSlots || n > c.logit_rows) fail(ROLLOUT_E_NOMEM, "too many samples in one call");
@@ -1242,6 +1254,7 @@ int rollout_logprobs(rollout_ctx* ctx, int32_t n_seqs, const int32_t* tokens, co
     check_usable(c);
     const rollout_model_desc& m = c.md;
     const int T = c.page_tokens, R = c.r_max;
+    PhaseClock clock(c.stats.logprobs_ms);
     if (n_seqs < 0 || !cu_seqlens || (n_seqs > 0 && (!tokens || !logprobs))) fail(ROLLOUT_E_INVAL, "null argument");
     if (!(temperature > 0.f) || !std::isfinite(temperature)) fail(ROLLOUT_E_INVAL, "temperature must be > 0");
     if (n_seqs && cu_seqlens[0] != 0) fail(ROLLOUT_E_INVAL, "cu_seqlens[0] must be 0");

@@ -657,3 +657,50 @@ def test_page_size_and_prefix_sharing_do_not_change_results(name):
         assert err <= TOL[shape.dtype]
         if shape.dtype == "fp32":
             assert err <= 1e-5
+
+
+@pytest.mark.parametrize("name", ["c1", "small-bf16", "small-moe-bf16"])
+def test_results_are_repeatable_and_independent_of_physical_pages_and_slots(name):
+    """A race or a read of memory that nobody wrote shows as run-to-run noise, so: the same
+    prompts and forced tokens (a) in a fresh context, (b) in a context whose pages and slots were
+    used before by other, longer samples that were aborted in a shuffled order - the free lists
+    hand everything out in another order and every page holds stale keys and values - and (c)
+    once more in that context.  The logits of every step must agree to the last bit in all three."""
+    shape, scale, _ = CASES[name]
+    w = scaled_weights(shape, seed=1, scale=scale)
+    toks, offs = workloads.make_prompts(3, 10, 90, shape.vocab, seed=29)
+    P, n, steps = 3, 2, 6
+    forced = np.random.default_rng(5).integers(0, shape.vocab, (P * n, steps)).astype(np.int32)
+    # a pool just large enough that the second use must take over pages of the first
+    eng_kw = dict(max_live_samples=16, max_context=160, max_batch_tokens=512)
+
+    def job(eng):
+        out = []
+        ids = eng.rollout_prefill(toks, offs, n, np.full(P * n, steps + 1, np.int32), forced_first=forced[:, 0])[0]
+        out.append(eng.rollout_debug_logits())
+        for s in range(1, steps):
+            eng.rollout_decode_step(forced_tokens=forced[:, s])
+            out.append(eng.rollout_debug_logits())
+        assert eng.rollout_abort(ids) == P * n and eng.rollout_get_stats()["pages_in_use"] == 0
+        return out
+
+    fresh = make_engine(shape, w, **eng_kw)
+    a = job(fresh)
+    fresh.close()
+    used = make_engine(shape, w, **eng_kw)
+    d_toks, d_offs = workloads.make_prompts(4, 40, 120, shape.vocab, seed=30)
+    d_ids = used.rollout_prefill(d_toks, d_offs, 3, np.full(12, 20, np.int32))[0]
+    for _ in range(5):
+        used.rollout_decode_step()
+    np.random.default_rng(6).shuffle(d_ids)
+    for i in d_ids:                                    # one by one: pages and slots return in this order
+        assert used.rollout_abort([i]) == 1
+    assert used.rollout_get_stats()["pages_in_use"] == 0
+    b = job(used)
+    c = job(used)
+    st = used.rollout_get_stats()                      # the phase clocks: host time inside the calls
+    assert st["prefill_ms"] > 0 and st["decode_ms"] > 0 and st["extend_ms"] == 0 and st["logprobs_ms"] == 0
+    used.close()
+    for s in range(steps):
+        assert np.array_equal(a[s], b[s]), f"step {s}: a used context gives other logits than a fresh one"
+        assert np.array_equal(b[s], c[s]), f"step {s}: a second run in the same context gives other logits"
