@@ -96,24 +96,33 @@ __device__ inline void attend_frags(const Frag (&k)[2][4], const Frag (&v)[8], c
   }
 }
 
-// The same, with the group's key and value fragments streamed from a KV page.
-__device__ inline void attend_group(const uint4* __restrict__ kblk, const uint4* __restrict__ vblk,
-                                    const Frag (&q)[8], int tok0, int limit, float scale_log2, float& m,
-                                    float& l, f32x4 (&o)[8], int lane) {
-  Frag k[2][4], v[8];
+// key and value fragments of one 32-position group from its KV page
+__device__ __forceinline__ void load_group(const uint4* __restrict__ kblk, const uint4* __restrict__ vblk,
+                                           Frag (&k)[2][4], Frag (&v)[8], int lane) {
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) k[t][ks].u = kblk[(t * 4 + ks) * 64 + lane];
 #pragma unroll
   for (int j = 0; j < 8; ++j) v[j].u = vblk[j * 64 + lane];
+}
+
+// The same, with the group's key and value fragments streamed from a KV page.
+__device__ inline void attend_group(const uint4* __restrict__ kblk, const uint4* __restrict__ vblk,
+                                    const Frag (&q)[8], int tok0, int limit, float scale_log2, float& m,
+                                    float& l, f32x4 (&o)[8], int lane) {
+  Frag k[2][4], v[8];
+  load_group(kblk, vblk, k, v, lane);
   attend_frags(k, v, q, tok0, limit, scale_log2, m, l, o, lane);
 }
 
-__device__ inline const uint4* group_block(const AttnArgs& a, int slot, int kv_head, int tok0, int is_v) {
-  const int page = a.page_table[(long long)slot * a.max_pages + tok0 / a.geom.page_tokens];
+// the 32-position group that starts at position tok0, inside page `page`
+__device__ inline const uint4* page_block(const AttnArgs& a, int page, int kv_head, int tok0, int is_v) {
   const int gip = (tok0 % a.geom.page_tokens) >> 5;
   return (const uint4*)(a.kv_pool + kv_block_base(a.geom, a.layer, page, kv_head, is_v)) + gip * GROUP_U4;
+}
+__device__ inline const uint4* group_block(const AttnArgs& a, int slot, int kv_head, int tok0, int is_v) {
+  return page_block(a, a.page_table[(long long)slot * a.max_pages + tok0 / a.geom.page_tokens], kv_head, tok0, is_v);
 }
 
 // four consecutive values as hi + lo bf16 parts into the two planes of an activation buffer
@@ -164,47 +173,47 @@ struct DecodeSmem {
 __device__ __forceinline__ void sum_planes(const AttnArgs& a, const float* p, float& x0, float& x1) {
   x0 = 0.f;
   x1 = 0.f;
-  for (int z = 0; z < a.qkv_planes; z += 4) {
-    const float* q = p + (long long)z * a.qkv_plane_stride;
+  constexpr int ZR = 8;
+  for (int z = 0; z < a.qkv_planes; z += ZR) {
     const long long st = a.qkv_plane_stride;
+    const float* q = p + (long long)z * st;
     const int left = a.qkv_planes - z;
-    const float u0 = q[0], w0 = q[64];
-    const float u1 = left > 1 ? q[st] : 0.f, w1 = left > 1 ? q[st + 64] : 0.f;
-    const float u2 = left > 2 ? q[2 * st] : 0.f, w2 = left > 2 ? q[2 * st + 64] : 0.f;
-    const float u3 = left > 3 ? q[3 * st] : 0.f, w3 = left > 3 ? q[3 * st + 64] : 0.f;
-    x0 = (((x0 + u0) + u1) + u2) + u3;
-    x1 = (((x1 + w0) + w1) + w2) + w3;
+    float u[ZR], w[ZR];
+#pragma unroll
+    for (int i = 0; i < ZR; ++i) {
+      u[i] = i < left ? q[i * st] : 0.f;
+      w[i] = i < left ? q[i * st + 64] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < ZR; ++i) {
+      x0 += u[i];
+      x1 += w[i];
+    }
   }
 }
 
-// Query staging.  Thread t of the workgroup owns the rotary pairs idx = t + 256 n, n < N:
-// column idx / 64 (the same in all 64 lanes), pair idx % 64.  rows[n] / heads[n] name the
-// sample row and the query head inside its KV group that column holds (row < 0: the column
-// is empty).  The split-K planes of the projection are summed in ascending order, four planes
-// of all N columns per round of loads, then bias / head norm, the rotary embedding, and the
-// hi + lo half-precision parts into sm.q.
-// PRE: the caller has already loaded plane 0 (pre0 = the element, pre1 = the one 64 further on).
-template <bool EXTRA, int N, bool PRE = false>
-__device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSmem& sm, int kvh, int G,
-                                              const int (&rows)[N], const int (&heads)[N],
-                                              const float* pre0 = nullptr, const float* pre1 = nullptr) {
-  const int tid = threadIdx.x, i = tid & 63;
-  const int q_dim = a.n_q_heads * DH, kv_dim = a.geom.n_kv_heads * DH;
-  const float* src[N];
-  float x0[N], x1[N];
-  float2 cs[N];  // cos, sin of the row's position: requested with the first planes
+// Sum over the split-K planes of this thread's N query elements (x0 = element i, x1 = element
+// i + 64 of each column's head), planes in ascending order.  The loads of up to eight planes (four
+// with more than four columns) of all columns are in flight together: under load a round trip to memory costs more than
+// anything else this kernel does before its main loop.
+template <int N>
+__device__ __forceinline__ void sum_query_planes(const AttnArgs& a, const float* const (&src)[N], float (&x0)[N],
+                                                 float (&x1)[N]) {
+  if (a.qkv_planes == 1) {
 #pragma unroll
-  for (int n = 0; n < N; ++n) {
-    const int b = max(rows[n], 0);  // empty columns read row 0 and are zeroed below
-    src[n] = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim) + (kvh * G + heads[n]) * DH + i;
-    x0[n] = PRE ? 0.f + pre0[n] : 0.f;
-    x1[n] = PRE ? 0.f + pre1[n] : 0.f;
-    cs[n] = *(const float2*)(a.cos_sin + (long long)a.row_pos[b] * DH + 2 * i);
+    for (int n = 0; n < N; ++n) {
+      x0[n] = 0.f + src[n][0];
+      x1[n] = 0.f + src[n][64];
+    }
+    return;
   }
-  for (int z = PRE ? 1 : 0; z < a.qkv_planes; z += 4) {
-    float u0[4][N], u1[4][N];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+  for (int n = 0; n < N; ++n) x0[n] = x1[n] = 0.f;
+  constexpr int ZR = N <= 4 ? 8 : 4;  // planes per round: 64 values in flight per thread
+  for (int z = 0; z < a.qkv_planes; z += ZR) {
+    float u0[ZR][N], u1[ZR][N];
+#pragma unroll
+    for (int q = 0; q < ZR; ++q) {
       const bool on = z + q < a.qkv_planes;
       const long long o = (long long)(on ? z + q : z) * a.qkv_plane_stride;
 #pragma unroll
@@ -214,16 +223,28 @@ __device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSme
       }
     }
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < ZR; ++q)
 #pragma unroll
       for (int n = 0; n < N; ++n) {
         x0[n] += u0[q][n];
         x1[n] += u1[q][n];
       }
   }
+}
+
+// Query staging.  Thread t of the workgroup (THREADS threads) owns the rotary pairs idx = t + THREADS n, n < N:
+// column idx / 64 (the same in all 64 lanes), pair idx % 64.  rows[n] / heads[n] name the
+// sample row and the query head inside its KV group that column holds (row < 0: the column
+// is empty).  x0 / x1: the projection's elements, planes summed; cs: cos, sin of the row's position.
+// Bias / head norm, the rotary embedding, and the hi + lo half-precision parts into sm.q.
+template <bool EXTRA, int N, int THREADS = 256>
+__device__ __forceinline__ void rotate_and_stage(const AttnArgs& a, const DecodeSmem& sm, int kvh, int G,
+                                                 const int (&rows)[N], const int (&heads)[N], float (&x0)[N],
+                                                 float (&x1)[N], const float2 (&cs)[N]) {
+  const int tid = threadIdx.x, i = tid & 63;
 #pragma unroll
   for (int n = 0; n < N; ++n) {
-    const int col = (tid + 256 * n) >> 6;
+    const int col = (tid + THREADS * n) >> 6;
     float u = 0.f, w = 0.f;
     if (rows[n] >= 0) {  // uniform over the wavefront
       if (EXTRA) qkv_extras(a.extra, (kvh * G + heads[n]) * DH, i, a.extra.q_gain, x0[n], x1[n]);
@@ -237,15 +258,47 @@ __device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSme
     split_f16(w, hi[i + 64], lo[i + 64]);
   }
 }
+// the two together, positions read from row_pos (columns of several rows)
+template <bool EXTRA, int N>
+__device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSmem& sm, int kvh, int G,
+                                              const int (&rows)[N], const int (&heads)[N]) {
+  const int i = threadIdx.x & 63;
+  const int q_dim = a.n_q_heads * DH, kv_dim = a.geom.n_kv_heads * DH;
+  const float* src[N];
+  float x0[N], x1[N];
+  float2 cs[N];  // requested with the planes
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    const int b = max(rows[n], 0);  // empty columns read row 0 and are zeroed below
+    src[n] = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim) + (kvh * G + heads[n]) * DH + i;
+    cs[n] = *(const float2*)(a.cos_sin + (long long)a.row_pos[b] * DH + 2 * i);
+  }
+  sum_query_planes<N>(a, src, x0, x1);
+  rotate_and_stage<EXTRA, N>(a, sm, kvh, G, rows, heads, x0, x1, cs);
+}
 
-// the 4 wavefronts' results of 16 columns -> one (max, sum, unnormalised output) per column in
-// sm.o[0..3], sm.m, sm.l (columns ml0 ..); every thread of the workgroup calls it
+// the W wavefronts' results of 16 columns -> one (max, sum, unnormalised output) per column in
+// sm.o[0..W-1], sm.m, sm.l (columns ml0 ..); every thread of the workgroup calls it
+template <int W = 4>
+__device__ __forceinline__ float merged_max(const DecodeSmem& sm, int col) {
+  float M = sm.m[col];
+#pragma unroll
+  for (int w = 1; w < W; ++w) M = fmaxf(M, sm.m[w * sm.ml_cols + col]);
+  return M;
+}
+template <int W = 4>
+__device__ __forceinline__ float merged_sum(const DecodeSmem& sm, int col) {
+  float L = sm.l[col];
+#pragma unroll
+  for (int w = 1; w < W; ++w) L += sm.l[w * sm.ml_cols + col];
+  return L;
+}
+template <int W = 4>
 __device__ __forceinline__ void merge_wavefronts(const DecodeSmem& sm, int ml0, float m, float l, const f32x4 (&o)[8],
                                                  int wave, int c, int g) {
   if (g == 0) sm.m[wave * sm.ml_cols + ml0 + c] = m;
   __syncthreads();
-  const float M = fmaxf(fmaxf(sm.m[ml0 + c], sm.m[sm.ml_cols + ml0 + c]),
-                        fmaxf(sm.m[2 * sm.ml_cols + ml0 + c], sm.m[3 * sm.ml_cols + ml0 + c]));
+  const float M = merged_max<W>(sm, ml0 + c);
   const float M_use = (M == -INFINITY) ? 0.f : M;
   const float w = exp2f(m - M_use);
   if (g == 0) sm.l[wave * sm.ml_cols + ml0 + c] = l * w;
@@ -255,70 +308,86 @@ __device__ __forceinline__ void merge_wavefronts(const DecodeSmem& sm, int ml0, 
     for (int i = 0; i < 4; ++i) sm.o[wave * (16 * DH) + c * DH + 16 * j + 4 * g + i] = o[j][i] * w;
   __syncthreads();
 }
-__device__ __forceinline__ float merged_max(const DecodeSmem& sm, int col) {
-  return fmaxf(fmaxf(sm.m[col], sm.m[sm.ml_cols + col]), fmaxf(sm.m[2 * sm.ml_cols + col], sm.m[3 * sm.ml_cols + col]));
-}
-__device__ __forceinline__ float merged_sum(const DecodeSmem& sm, int col) {
-  return sm.l[col] + sm.l[sm.ml_cols + col] + sm.l[2 * sm.ml_cols + col] + sm.l[3 * sm.ml_cols + col];
+// element e of the merged, unnormalised output: the wavefronts' parts in ascending order
+template <int W = 4>
+__device__ __forceinline__ float merged_out(const DecodeSmem& sm, int e) {
+  float acc = sm.o[e];
+#pragma unroll
+  for (int w = 1; w < W; ++w) acc += sm.o[w * 16 * DH + e];
+  return acc;
 }
 
-// one workgroup = (own-range split, KV head, sample)
+// one workgroup = (own-range split, KV head, sample); wavefront w takes the groups w, w + 4, ...
+// of the split.  What the workgroup needs before its main loop comes in three rounds of loads:
+// (1) the row's position and page-table row, and - they depend on neither - every split-K plane
+// of its query columns and of the new key and value; (2) what depends on the position: cos and
+// sin, the page of the new position and the page of the wavefront's first group; (3) that
+// group's keys and values, in flight while the queries are rotated and staged.
 template <bool EXTRA>
 __device__ __forceinline__ void decode_own_range(const AttnArgs& a, const DecodeSmem& sm, int split, int kvh, int b) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int c = lane & 15, g = lane >> 4;
+  const int c = lane & 15, g = lane >> 4, i = lane;
   const int n_kv = a.geom.n_kv_heads;
   const int G = a.n_q_heads / n_kv;
+  const int T = a.geom.page_tokens;
   const int pos = a.row_pos[b];
   const int t0 = a.row_t0 ? a.row_t0[b] : 0;
   const int slot = a.row_slot[b];
   const int q_dim = a.n_q_heads * DH, kv_dim = n_kv * DH;
   const float* row = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim);
-  // The first plane of this workgroup's query columns is requested before the position is
-  // known (which says whether this split has anything to do): one round trip less.
+  // ---- round 1 (does not wait for the position)
   int rows[4], heads[4];
-  float pre0[4], pre1[4];
+  const float* src[4];
+  float x0[4], x1[4];
 #pragma unroll
   for (int n = 0; n < 4; ++n) {
-    heads[n] = (tid >> 6) + 4 * n;  // column = head inside the KV group
+    heads[n] = wave + 4 * n;  // column = head inside the KV group
     rows[n] = heads[n] < G ? b : -1;
     heads[n] = min(heads[n], G - 1);
-    const float* src = row + (kvh * G + heads[n]) * DH + (tid & 63);
-    pre0[n] = src[0];
-    pre1[n] = src[64];
+    src[n] = row + (kvh * G + heads[n]) * DH + i;
   }
+  // the new key (even wavefronts) or value (odd ones); wavefronts 0 and 1 of the split that owns
+  // the new position use theirs
+  const bool is_v = wave & 1;
+  float n0, n1;
+  sum_planes(a, row + q_dim + (is_v ? kv_dim : 0) + kvh * DH + i, n0, n1);
+  sum_query_planes<4>(a, src, x0, x1);
   const int used = (pos - t0) / a.split_tokens + 1;  // splits that hold at least the new position
   if (split >= used) return;
   const bool owner = split == used - 1;
   const bool direct = used == 1 && t0 == 0;          // the only partial result of this (sample, KV head)
-  const float* cs = a.cos_sin + (long long)pos * DH;
+  const bool writer = owner && wave < 2;
+  const int t_begin = t0 + split * a.split_tokens;
+  const int t_end = min(pos, t_begin + a.split_tokens);  // cached positions only
+  int tok0 = t_begin + wave * 32;
+  // ---- round 2
+  const int* pt = a.page_table + (long long)slot * a.max_pages;
+  const float2 rot = *(const float2*)(a.cos_sin + (long long)pos * DH + 2 * i);
+  const int new_page = writer ? pt[pos / T] : 0;
+  const int first_page = tok0 < t_end ? pt[tok0 / T] : 0;
+  // ---- round 3
+  Frag k[2][4], v[8];
+  if (tok0 < t_end)
+    load_group(page_block(a, first_page, kvh, tok0, 0), page_block(a, first_page, kvh, tok0, 1), k, v, lane);
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  stage_queries<EXTRA, 4, true>(a, sm, kvh, G, rows, heads, pre0, pre1);
-  if (owner && tid < 128) {
-    const int page = a.page_table[(long long)slot * a.max_pages + pos / a.geom.page_tokens];
-    const int tok = pos % a.geom.page_tokens;
-    const int i = tid & 63;
-    if (tid < 64) {
-      const float* src = row + q_dim + kvh * DH;
-      const float cc = cs[2 * i], sn = cs[2 * i + 1];
-      float x0, x1;
-      sum_planes(a, src + i, x0, x1);
-      if (EXTRA) qkv_extras(a.extra, q_dim + kvh * DH, i, a.extra.k_gain, x0, x1);  // wavefront 0
-      const uint16_t k0 = f32_to_f16(x0 * cc - x1 * sn).bits, k1 = f32_to_f16(x1 * cc + x0 * sn).bits;
+  const float2 cs[4] = {rot, rot, rot, rot};
+  rotate_and_stage<EXTRA, 4>(a, sm, kvh, G, rows, heads, x0, x1, cs);
+  if (writer) {
+    const int tok = pos % T;
+    if (!is_v) {
+      if (EXTRA) qkv_extras(a.extra, q_dim + kvh * DH, i, a.extra.k_gain, n0, n1);  // wavefront 0
+      const uint16_t k0 = f32_to_f16(n0 * rot.x - n1 * rot.y).bits, k1 = f32_to_f16(n1 * rot.x + n0 * rot.y).bits;
       sm.kv[i] = k0;
       sm.kv[i + 64] = k1;
-      uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, page, kvh, 0);
+      uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, new_page, kvh, 0);
       dst[kv_k_offset(a.geom, tok, i)] = k0;
       dst[kv_k_offset(a.geom, tok, i + 64)] = k1;
     } else {
-      const float* src = row + q_dim + kv_dim + kvh * DH;
-      float y0, y1;
-      sum_planes(a, src + i, y0, y1);
-      if (EXTRA) qkv_extras(a.extra, q_dim + kv_dim + kvh * DH, i, nullptr, y0, y1);  // wavefront 1: bias only
-      const uint16_t v0 = f32_to_f16(y0).bits, v1 = f32_to_f16(y1).bits;
+      if (EXTRA) qkv_extras(a.extra, q_dim + kv_dim + kvh * DH, i, nullptr, n0, n1);  // wavefront 1: bias only
+      const uint16_t v0 = f32_to_f16(n0).bits, v1 = f32_to_f16(n1).bits;
       sm.kv[DH + i] = v0;
       sm.kv[DH + i + 64] = v1;
-      uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, page, kvh, 1);
+      uint16_t* dst = a.kv_pool_w + kv_block_base(a.geom, a.layer, new_page, kvh, 1);
       dst[kv_v_offset(a.geom, tok, i)] = v0;
       dst[kv_v_offset(a.geom, tok, i + 64)] = v1;
     }
@@ -335,13 +404,14 @@ __device__ __forceinline__ void decode_own_range(const AttnArgs& a, const Decode
   f32x4 o[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int t_begin = t0 + split * a.split_tokens;
-  const int t_end = min(pos, t_begin + a.split_tokens);  // cached positions only
-  for (int tok0 = t_begin + wave * 32; tok0 < t_end; tok0 += 128)
+  if (tok0 < t_end) {  // the group that is in registers already
+    attend_frags(k, v, q, tok0, pos - 1, scale_log2, m, l, o, lane);
+    tok0 += 128;
+  }
+  for (; tok0 < t_end; tok0 += 128)
     attend_group(group_block(a, slot, kvh, tok0, 0), group_block(a, slot, kvh, tok0, 1), q, tok0, pos - 1,
                  scale_log2, m, l, o, lane);
   if (owner && wave == 3) {  // the new position, from LDS: token 0 of a group that starts at pos
-    Frag k[2][4], v[8];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       k[0][ks].u = make_uint4(0, 0, 0, 0);
@@ -361,7 +431,7 @@ __device__ __forceinline__ void decode_own_range(const AttnArgs& a, const Decode
   const long long part = ((long long)b * n_kv + kvh) * n_slots + a.slot0 + split;
   for (int e = tid; e < G * DH; e += 256) {
     const int col = e >> 7;
-    const float acc = sm.o[e] + sm.o[16 * DH + e] + sm.o[2 * 16 * DH + e] + sm.o[3 * 16 * DH + e];
+    const float acc = merged_out(sm, e);
     if (direct) store1_split(a.out + out_offset(a, b, kvh * G * DH + e), a.out_lo_offset, acc / (merged_sum(sm, col) * P_SCALE));
     else a.part_o[part * (16 * DH) + e] = acc;
   }
