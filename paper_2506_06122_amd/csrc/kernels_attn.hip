@@ -168,8 +168,8 @@ struct DecodeSmem {
   float* o;      // [4][16 * DH]
 };
 
-// elements p[0] and p[64] summed over the split-K planes in ascending order, four planes per
-// round of loads
+// elements p[0] and p[64] summed over the split-K planes in ascending order, eight planes'
+// loads in flight together
 __device__ __forceinline__ void sum_planes(const AttnArgs& a, const float* p, float& x0, float& x1) {
   x0 = 0.f;
   x1 = 0.f;
@@ -318,7 +318,7 @@ __device__ __forceinline__ float merged_out(const DecodeSmem& sm, int e) {
 }
 
 // one workgroup = (own-range split, KV head, sample); wavefront w takes the groups w, w + 4, ...
-// of the split.  What the workgroup needs before its main loop comes in three rounds of loads:
+// of the split.  What the workgroup needs before its main loop comes in three sets of loads:
 // (1) the row's position and page-table row, and - they depend on neither - every split-K plane
 // of its query columns and of the new key and value; (2) what depends on the position: cos and
 // sin, the page of the new position and the page of the wavefront's first group; (3) that
@@ -335,7 +335,7 @@ __device__ __forceinline__ void decode_own_range(const AttnArgs& a, const Decode
   const int slot = a.row_slot[b];
   const int q_dim = a.n_q_heads * DH, kv_dim = n_kv * DH;
   const float* row = a.qkv_raw + (long long)b * (q_dim + 2 * kv_dim);
-  // ---- round 1 (does not wait for the position)
+  // ---- first set of loads (does not wait for the position)
   int rows[4], heads[4];
   const float* src[4];
   float x0[4], x1[4];
@@ -360,12 +360,12 @@ __device__ __forceinline__ void decode_own_range(const AttnArgs& a, const Decode
   const int t_begin = t0 + split * a.split_tokens;
   const int t_end = min(pos, t_begin + a.split_tokens);  // cached positions only
   int tok0 = t_begin + wave * 32;
-  // ---- round 2
+  // ---- second set: what depends on the position
   const int* pt = a.page_table + (long long)slot * a.max_pages;
   const float2 rot = *(const float2*)(a.cos_sin + (long long)pos * DH + 2 * i);
   const int new_page = writer ? pt[pos / T] : 0;
   const int first_page = tok0 < t_end ? pt[tok0 / T] : 0;
-  // ---- round 3
+  // ---- third set: the first group's keys and values
   Frag k[2][4], v[8];
   if (tok0 < t_end)
     load_group(page_block(a, first_page, kvh, tok0, 0), page_block(a, first_page, kvh, tok0, 1), k, v, lane);
