@@ -108,6 +108,27 @@ def test_matrix_core_decode_shapes(n_prompts, n_samples, lo, hi):
     eng.close()
 
 
+@pytest.mark.parametrize("lens,n_samples", [([3000, 1536], 2), ([2900], 40)], ids=["4rows-12-splits", "40rows-4-splits"])
+def test_long_contexts_over_many_pages_and_splits(lens, n_samples):
+    """Contexts of thousands of positions, as the long tail of configs 3 and 4 has them: prefill
+    attention over 94 pages of one sequence, then decode attention with every wavefront walking
+    several groups per split and up to twelve splits to merge - on the streamed path (4 rows)
+    and on the tile path (40 rows, the prompt's pages shared by all of them)."""
+    shape = workloads.SMALL_BF16
+    w = scaled_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    rng = np.random.default_rng(23)
+    toks = rng.integers(0, shape.vocab, sum(lens)).astype(np.int32)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rows = len(lens) * n_samples
+    eng = make_engine(shape, w, max_live_samples=rows, max_context=3072, max_batch_tokens=8192)
+    steps = 3
+    forced = rng.integers(0, shape.vocab, (rows, steps)).astype(np.int32)
+    worst, worst_lp = teacher_forced_compare(eng, model, toks, offs, n_samples, forced, steps)
+    print(f"contexts {lens} x {n_samples}: max |dlogits| = {worst:.3e}, max |dlogp| = {worst_lp:.3e}")
+    assert worst <= TOL["bf16"] and worst_lp <= TOL["bf16"]
+
+
 def test_decode_attention_of_a_long_tailed_large_batch():
     """128 live rows x 2 KV heads (a workgroup per row and head already fills the chip: no KV
     splits) with contexts of 6 to 700 positions, mean about 60, as a long-tailed rollout leaves
