@@ -169,18 +169,15 @@ def test_c2_shape_slice_matches_oracle(simple):
     eng.close()
 
 
-def test_c2_full_batch_sampled_rows_and_row_invariance():
-    """The benchmark's job as it is launched there - the full model, all 32 prompts x 8 samples
-    (256 live rows: packed prefill of about 9k prompt tokens, 64 x 128 tile projections,
-    one-split attention), teacher-forced for 3 steps - checked two ways.  (1) Rows the oracle
-    can afford, computed one by one: the shortest and the longest prompt, and one sample of each
-    through the decode steps.  (2) A property that holds at any size, on all 256 rows: a row's
-    result does not depend on where it sits in the batch, so samples of one prompt that are fed
-    the same tokens must produce bit-identical logits, and every returned log-prob must be the
-    log-softmax of its own logits row."""
-    shape = workloads.C2_1P5B
+def full_batch_case(shape, load, picks, max_batch_tokens=16384):
+    """The whole batch of a benchmark configuration as bench.py launches it, teacher-forced for 3
+    steps, checked two ways.  (1) Rows the oracle can afford, computed one by one: the prompts
+    `picks` and one sample of each through the decode steps.  (2) A property that holds at any
+    size, on all rows: a row's result does not depend on where it sits in the batch, so samples
+    of one prompt that are fed the same tokens must produce bit-identical logits, and every
+    returned log-prob must be the log-softmax of its own logits row.  Returns the largest
+    logits error on the oracle's rows."""
     w = workloads.make_weights(shape, seed=1)
-    load = workloads.load_c2()
     P, n = load.n_prompts, load.n_samples
     toks, offs = load.prompt_tokens, load.prompt_offsets
     lens = np.diff(offs)
@@ -192,12 +189,11 @@ def test_c2_full_batch_sampled_rows_and_row_invariance():
     kv_per_token = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2
     need = int(lens.sum()) + P * n * (steps + 64)
     eng = make_engine(shape, w, kv_pool_bytes=max(need * kv_per_token, 1 << 30), max_live_samples=P * n,
-                      max_context=int(lens.max()) + steps + 1, max_batch_tokens=16384)
+                      max_context=int(lens.max()) + steps + 1, max_batch_tokens=max_batch_tokens)
     ids, tk, lps, fin = eng.rollout_prefill(toks, offs, n, np.full(P * n, steps, np.int32), forced_first=forced[:, 0])
     assert len(ids) == P * n and np.array_equal(tk, forced[:, 0])
     model = oracle_model(shape, w)
     fwd = T.KVForward(model)
-    picks = [int(np.argmin(lens)), int(np.argmax(lens))]
     gpu = eng.rollout_debug_logits()
     caches, worst = {}, 0.0
     for p in picks:
@@ -224,10 +220,31 @@ def test_c2_full_batch_sampled_rows_and_row_invariance():
                 caches[p] = caches[p].fork()
             ref = fwd.extend([caches[p]], [[int(forced[i, t - 1])]])[0][0]
             worst = max(worst, float(np.max(np.abs(gpu[i] - ref))))
-    print(f"c2 full batch: max |dlogits| on the oracle's rows = {worst:.3e}")
-    assert worst <= TOL["bf16"]
     assert eng.rollout_get_stats()["matrix_core_path"] == 1
     eng.close()
+    return worst
+
+
+def test_c2_full_batch_sampled_rows_and_row_invariance():
+    """The headline job as it is launched in the benchmark - the full 1.5B-shaped model, all 32
+    prompts x 8 samples (256 live rows: packed prefill of about 9k prompt tokens, 64 x 128 tile
+    projections, one-split attention); the oracle takes the shortest and the longest prompt."""
+    load = workloads.load_c2()
+    lens = np.diff(load.prompt_offsets)
+    worst = full_batch_case(workloads.C2_1P5B, load, [int(np.argmin(lens)), int(np.argmax(lens))])
+    print(f"c2 full batch: max |dlogits| on the oracle's rows = {worst:.3e}")
+    assert worst <= TOL["bf16"]
+
+
+def test_c3_full_batch_sampled_rows_and_row_invariance():
+    """Config 3 as it is launched in the benchmark - the 7B-shaped model at its full depth, all
+    64 prompts x 8 samples (512 live rows, about 37k prompt tokens prefilled in chunks of at most
+    16384 rows); the oracle (57 GB of widened weights) takes the shortest prompt."""
+    load = workloads.load_c3()
+    lens = np.diff(load.prompt_offsets)
+    worst = full_batch_case(workloads.C3_7B, load, [int(np.argmin(lens))])
+    print(f"c3 full batch: max |dlogits| on the oracle's rows = {worst:.3e}")
+    assert worst <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("which", ["c3-dense", "c4-moe"])
@@ -476,6 +493,40 @@ def test_logprob_pass_at_config5_logits_shape():
     diff = float(np.max(np.abs(alone - got[cu[3]:cu[4]])))
     print(f"alone vs inside a chunk: max |dlogp| = {diff:.3e}")
     assert diff <= 2e-3
+
+
+def test_logprob_pass_at_config5_full_size():
+    """The teacher-forced pass in the launch configuration the benchmark times: the 7B-shaped
+    model at its full depth, 16384-row chunks, sequences of config 5's lengths (up to 8192
+    tokens) packed with two short ones the fp64 oracle can afford at this depth.  The oracle
+    checks the short sequences; for the rest, properties that hold at any size: every log-prob is
+    finite and not positive, a sequence's first position reads 0, and a long sequence run alone
+    (another chunk composition, another tile plan for its last rows) agrees with its rows inside
+    the batch far inside the tolerance."""
+    shape = workloads.C3_7B
+    w = workloads.make_weights(shape, seed=1)
+    kv_per_token = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2
+    kw = dict(kv_pool_bytes=(16384 + 8192 + 64 * 32) * kv_per_token, max_live_samples=8, max_context=8192,
+              max_batch_tokens=16384)
+    lens = [8192, 6000, 4500, 150, 3000, 120]          # chunks: 14192 rows, 7770 rows
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    toks = np.random.Generator(np.random.Philox(key=[33, 5])).integers(0, shape.vocab, int(cu[-1])).astype(np.int32)
+    eng = make_engine(shape, w, **kw)
+    got = eng.rollout_logprobs(toks, cu, temperature=1.0)
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1 and eng.rollout_get_stats()["pages_in_use"] == 0
+    alone = eng.rollout_logprobs(toks[cu[2]:cu[3]], [0, lens[2]], temperature=1.0)
+    eng.close()
+    assert np.all(np.isfinite(got)) and np.all(got <= 0.0) and all(got[a] == 0.0 for a in cu[:-1])
+    diff = float(np.max(np.abs(alone - got[cu[2]:cu[3]])))
+    model = oracle_model(shape, w)
+    err = 0.0
+    for s in (3, 5):
+        want = T.packed_log_probs(model, toks[cu[s]:cu[s + 1]], [0, lens[s]], temperature=1.0)
+        err = max(err, float(np.max(np.abs(got[cu[s]:cu[s + 1]] - want))))
+    print(f"{shape.name}, all {shape.n_layers} layers, {int(cu[-1])} rows in 2 chunks: max |dlogp| = {err:.3e} on the "
+          f"oracle's sequences; 4500 tokens alone vs inside the batch: {diff:.3e}")
+    assert err <= TOL["bf16"]
+    assert diff <= 5e-3
 
 
 def test_lifecycle_add_abort_eos_and_batch_invariance():
