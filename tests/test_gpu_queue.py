@@ -365,9 +365,9 @@ def test_growing_pages_admit_by_need_and_survive_exhaustion(scenario):
     eng.close()
 
 
-@pytest.mark.parametrize("chunk_rows,grow", [(48, False), (13, False), (40, True)],
-                         ids=["chunks-of-48", "chunks-of-13", "chunks-of-40-growing-pages"])
-def test_chunked_prefill_rides_along_with_decode_steps(chunk_rows, grow):
+@pytest.mark.parametrize("chunk_rows,grow,moe", [(48, False, False), (13, False, False), (40, True, False), (48, False, True)],
+                         ids=["chunks-of-48", "chunks-of-13", "chunks-of-40-growing-pages", "chunks-of-48-experts"])
+def test_chunked_prefill_rides_along_with_decode_steps(chunk_rows, grow, moe):
     """rollout_queue_chunking: a step is one forward pass over a decode row per live sample plus
     at most chunk_rows prompt rows; prompts are cut where the budget ends and go on in the next
     step.  bf16 model on the matrix-core path, 8 prompts x 3 samples through 8 live slots; prompt
@@ -379,10 +379,13 @@ def test_chunked_prefill_rides_along_with_decode_steps(chunk_rows, grow):
       (3) the same queue without chunking emits the same tokens for all but at most two samples
           (rounding differs between batch shapes and may flip a draw on a boundary).
     With growing pages, responses of 80 to 110 tokens and a pool of 20 pages, prompts - half cached ones first -
-    give way when the pool runs out and start over; the final results are checked the same way."""
+    give way when the pool runs out and start over; the final results are checked the same way.
+    The mixture-of-experts model (its block sees decode rows and prompt rows in one batch) is
+    checked against the unchunked run only: the oracle's own routing may differ from the GPU's at a
+    near-tie, which the parity tests handle by passing the GPU's choices."""
     import paper_2506_06122_amd as R
-    shape = workloads.SMALL_BF16
-    w = scaled_weights(shape, seed=1)
+    shape = workloads.SMALL_MOE_BF16 if moe else workloads.SMALL_BF16
+    w = scaled_weights(shape, seed=1, scale=1.5 if moe else 1.0)
     lens = [5, 48, 49, 130, 96, 33, 150, 64]
     P, n, temperature, top_p, seed, slots = len(lens), 3, 0.8, 0.95, 11, 8
     rng = np.random.default_rng(77)
@@ -440,14 +443,19 @@ def test_chunked_prefill_rides_along_with_decode_steps(chunk_rows, grow):
     else:
         assert sum(rows) == sum(lens) and restarts == 0 and qs["prompts_preempted"] == 0
 
-    model = oracle_model(shape, w)
-    forced = {sid: t for sid, (t, _) in seqs.items()}
-    ref = rollout.generate(model, toks, offs, n, max_new, -1, temperature, top_p, seed, forced_tokens=forced)
-    worst = max(abs(a - b) for tr in ref for a, b in zip(tr.logprobs, seqs[tr.sample_id][1]))
     whole = run(0)[0]
     differ = [sid for sid in seqs if seqs[sid][0] != whole[sid][0]]
-    print(f"chunks of {chunk_rows}{' with growing pages' if grow else ''}: {len(trace)} steps, at most {max(rows)} prompt "
-          f"rows in one, peak {peak} live, {qs['prompts_preempted']} preemptions; max |dlogp| vs oracle = {worst:.3e}; "
-          f"{len(differ)} samples differ from the unchunked run")
+    if moe:
+        worst = max(abs(a - b) for sid in seqs if sid not in differ for a, b in zip(seqs[sid][1], whole[sid][1]))
+        against = "the unchunked run"
+    else:
+        model = oracle_model(shape, w)
+        forced = {sid: t for sid, (t, _) in seqs.items()}
+        ref = rollout.generate(model, toks, offs, n, max_new, -1, temperature, top_p, seed, forced_tokens=forced)
+        worst = max(abs(a - b) for tr in ref for a, b in zip(tr.logprobs, seqs[tr.sample_id][1]))
+        against = "the oracle"
+    print(f"chunks of {chunk_rows}{' with growing pages' if grow else ''}{', experts' if moe else ''}: {len(trace)} steps, "
+          f"at most {max(rows)} prompt rows in one, peak {peak} live, {qs['prompts_preempted']} preemptions; "
+          f"max |dlogp| vs {against} = {worst:.3e}; {len(differ)} samples differ from the unchunked run")
     assert worst <= 2e-2
     assert len(differ) <= 2, differ
