@@ -329,6 +329,187 @@ struct StepChunk {
   std::vector<uint8_t> first_finished;
 };
 
+// The forward pass of a step that carries prompt rows: uploads the chunk's rows behind the B decode
+// rows (tokens, positions, page-table rows; one packed sequence per prompt, continuing at its
+// first uncached position), runs the forward, and computes the logits of the decode rows and of
+// the last row of every prompt that ends here (logits rows B, B + 1, ...).  Returns the number of
+// prompts that end.
+static int forward_with_chunk(rollout_ctx& c, int B, const StepChunk& chunk) {
+  const PromptQueue& q = c.queue;
+  const int R = c.r_max, Rq = chunk.rows, n = q.n_samples;
+  const int ns = (int)chunk.seqs.size();
+  // pageable staging: each of these uploads is complete when its call returns
+  std::vector<int> tok(Rq), pos(Rq), slot(Rq), row0(ns), len(ns), srow(ns), pos0(ns), want(B);
+  for (int i = 0; i < B; ++i) want[i] = i;
+  int r = 0, max_len = 0, n_fin = 0;
+  c.chunk_kv_tokens = 0;
+  for (int k = 0; k < ns; ++k) {
+    const ChunkSeq& cs = chunk.seqs[k];
+    const PendingPrompt& pp = q.pending[cs.pending_index];
+    row0[k] = B + r;
+    len[k] = cs.len;
+    srow[k] = pp.table_row;
+    pos0[k] = cs.begin;
+    for (int i = 0; i < cs.len; ++i, ++r) {
+      tok[r] = pp.prompt.tokens[cs.begin + i];
+      pos[r] = cs.begin + i;
+      slot[r] = pp.table_row;
+    }
+    if (cs.last) {
+      want.push_back(B + r - 1);
+      ++n_fin;
+    }
+    max_len = std::max(max_len, cs.len);
+    c.chunk_kv_tokens += (double)cs.len * cs.begin + 0.5 * cs.len * (cs.len + 1.0);
+  }
+  if (ns > rollout_ctx::kTempSlots || B + n_fin > c.logit_rows || (long long)B + (long long)n_fin * n > R)
+    fail(ROLLOUT_E_STATE, "internal: the chunk plan exceeds the workspaces");
+  c.chunk_attn_flops = 4.0 * c.chunk_kv_tokens * c.q_dim;
+  h2d(c.row_token.p + B, tok.data(), Rq * sizeof(int), c.stream);
+  h2d(c.row_pos.p + B, pos.data(), Rq * sizeof(int), c.stream);
+  h2d(c.row_slot.p + B, slot.data(), Rq * sizeof(int), c.stream);
+  h2d(c.seq_row0.p, row0.data(), ns * sizeof(int), c.stream);
+  h2d(c.seq_len.p, len.data(), ns * sizeof(int), c.stream);
+  h2d(c.seq_slot.p, srow.data(), ns * sizeof(int), c.stream);
+  h2d(c.seq_pos0.p, pos0.data(), ns * sizeof(int), c.stream);
+  h2d(c.chunk_ints.p, want.data(), want.size() * sizeof(int), c.stream);
+  SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, ns, max_len};
+  sb.pos0 = c.seq_pos0.p;
+  sb.decode_rows = B;
+  engine_forward_rows(c, B + Rq, &sb);
+  engine_logits(c, c.chunk_ints.p, 0, B + n_fin, c.logits.p);
+  c.last_logit_rows = B + n_fin;
+  c.stats.prompt_tokens += Rq;
+  return n_fin;
+}
+
+// The prompts `fin` end in this step (their last rows' logits are rows B, B + 1, ... of c.logits):
+// private copies of each prompt's partial last page, response position 0 of its n samples drawn
+// through rows B .. of the per-row sampling arrays, the slot state of the samples that go on, and
+// the results on their way to pinned host memory (tokens at h_int + 7 r_max, log-probs at
+// h_float + r_max); the caller waits for the stream.
+static void sample_first_tokens(rollout_ctx& c, int B, const std::vector<PendingPrompt*>& fin) {
+  const rollout_model_desc& m = c.md;
+  const int R = c.r_max, n = c.queue.n_samples, n_fin = (int)fin.size(), Rs = n_fin * n;
+  std::vector<int> pairs, lrow(Rs), step0(Rs, 0), forced(Rs, -1), slots, srows, spos;
+  std::vector<float> inv_t(Rs), top_p(Rs);
+  std::vector<long long> ids(Rs);
+  for (int k = 0; k < n_fin; ++k) {
+    const PendingPrompt& pp = *fin[k];
+    pairs.insert(pairs.end(), pp.copy_pairs.begin(), pp.copy_pairs.end());
+    for (int j = 0; j < n; ++j) {
+      const int i = k * n + j;
+      lrow[i] = B + k;
+      inv_t[i] = 1.0f / pp.prompt.temperature;
+      top_p[i] = pp.prompt.top_p;
+      ids[i] = pp.samples[j].id;
+      if (pp.samples[j].slot >= 0) {
+        slots.push_back(pp.samples[j].slot);
+        srows.push_back(i);
+        spos.push_back(pp.samples[j].prompt_len);
+      }
+    }
+  }
+  const int n_new = (int)slots.size();
+  if (pairs.size() + 3 * (size_t)n_new > 2 * (size_t)R) fail(ROLLOUT_E_STATE, "internal: page copy and slot lists too long");
+  if (!pairs.empty()) {
+    h2d(c.chunk_ints.p + R, pairs.data(), pairs.size() * sizeof(int), c.stream);
+    launch_copy_pages(c.kv_pool.p, c.chunk_ints.p + R, (int)pairs.size() / 2, m.n_layers,
+                      c.geom.layer_stride * c.elem, c.geom.page_stride * c.elem, c.stream);
+  }
+  h2d(c.row_aux.p + B, lrow.data(), Rs * sizeof(int), c.stream);
+  h2d(c.row_forced.p + B, forced.data(), Rs * sizeof(int), c.stream);
+  h2d(c.row_step.p + B, step0.data(), Rs * sizeof(int), c.stream);
+  h2d(c.row_inv_temp.p + B, inv_t.data(), Rs * sizeof(float), c.stream);
+  h2d(c.row_top_p.p + B, top_p.data(), Rs * sizeof(float), c.stream);
+  h2d(c.row_sample_id.p + B, ids.data(), Rs * sizeof(long long), c.stream);
+  SampleRows fr{};
+  fr.logits = c.logits.p;
+  fr.logits_row = c.row_aux.p + B;
+  fr.inv_temp = c.row_inv_temp.p + B;
+  fr.top_p = c.row_top_p.p + B;
+  fr.uniforms = nullptr;
+  fr.sample_id = c.row_sample_id.p + B;
+  fr.step = c.row_step.p + B;
+  fr.forced = c.row_forced.p + B;
+  fr.seed = c.rd.seed;
+  fr.tokens = c.out_tokens.p + B;
+  fr.logprobs = c.out_logprobs.p + B;
+  fr.weight_sums = nullptr;
+  if (Rs <= c.samp_rows) {
+    fr.part_max = c.samp_part_max.p;
+    fr.seg_sums = c.samp_seg_sums.p;
+  }
+  launch_sample(fr, Rs, m.vocab, c.stream);
+  if (n_new) {  // the lists sit behind the page pairs
+    int* lists = c.chunk_ints.p + R + pairs.size();
+    h2d(lists, slots.data(), n_new * sizeof(int), c.stream);
+    h2d(lists + n_new, srows.data(), n_new * sizeof(int), c.stream);
+    h2d(lists + 2 * n_new, spos.data(), n_new * sizeof(int), c.stream);
+    init_slots_kernel<<<ceil_div(n_new, 256), 256, 0, c.stream>>>(c.st, lists, lists + n_new, lists + 2 * n_new,
+                                                                  c.out_tokens.p + B, c.row_sample_id.p + B,
+                                                                  c.row_inv_temp.p + B, c.row_top_p.p + B, n_new);
+  }
+  d2h(c.h_int.p + 7 * R, c.out_tokens.p + B, Rs * sizeof(int), c.stream);
+  d2h(c.h_float.p + R, c.out_logprobs.p + B, Rs * sizeof(float), c.stream);
+}
+
+// Host bookkeeping after a step with prompt rows: the pending prompts' progress; the prompts that
+// ended (`fin`, the first ones of the pending list) hand over to their samples, which go live or
+// are finished at position 0, and leave the list.  Their results go to chunk.first_*.
+static void commit_chunk(rollout_ctx& c, StepChunk& chunk, const std::vector<PendingPrompt*>& fin) {
+  PromptQueue& q = c.queue;
+  const int R = c.r_max, n = q.n_samples, n_fin = (int)fin.size(), Rs = n_fin * n;
+  const int* first_tok = c.h_int.p + 7 * R;
+  const float* first_lp = c.h_float.p + R;
+  for (const ChunkSeq& cs : chunk.seqs) q.pending[cs.pending_index].done += cs.len;
+  chunk.first_ids.resize(Rs);
+  chunk.first_groups.resize(Rs);
+  chunk.first_tokens.resize(Rs);
+  chunk.first_logprobs.resize(Rs);
+  chunk.first_finished.resize(Rs);
+  for (int k = 0; k < n_fin; ++k) {
+    PendingPrompt& pp = *fin[k];
+    q.open[pp.prompt.prompt_id] = n;
+    for (int j = 0; j < n; ++j) {
+      const int i = k * n + j;
+      Sample& s = pp.samples[j];
+      const int tok = first_tok[i];
+      s.n_emitted = 1;
+      s.last_token = tok;
+      const bool done = s.max_new <= 1 || (s.eos_id >= 0 && tok == s.eos_id);
+      chunk.first_ids[i] = s.id;
+      chunk.first_groups[i] = s.group;
+      chunk.first_tokens[i] = tok;
+      chunk.first_logprobs[i] = first_lp[i];
+      chunk.first_finished[i] = done ? 1 : 0;
+      c.stats.tokens_emitted += 1;
+      c.stats.samples_admitted += 1;
+      if (done) {
+        release_sample(c, s);
+        c.stats.samples_finished += 1;
+      } else {
+        const int64_t id = s.id;
+        Sample moved = std::move(s);
+        auto res = c.live.emplace(id, std::move(moved));
+        if (!res.second) {  // cannot happen: ids are handed out once
+          release_sample(c, moved);
+          c.stats.samples_aborted += 1;
+        }
+      }
+    }
+    // the prefill's own references; the samples hold theirs
+    for (int32_t pg : pp.pages.shared) c.pool->release(pg);
+    if (pp.pages.tail >= 0) c.pool->release(pp.pages.tail);
+    q.free_rows.push_back(pp.table_row);
+    if (c.grow_pages) q.admitted.emplace(pp.prompt.prompt_id, std::move(pp.prompt));  // kept: it may have to start over
+    c.stats.prompts_prefilled += 1;
+    c.live_dirty = true;
+  }
+  // finished prompts sit at the front of the pending list (prompts are cached in order)
+  for (int k = 0; k < n_fin; ++k) q.pending.pop_front();
+}
+
 // groups (optional): the prompt counter of every stepped sample, for the queue's bookkeeping
 static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint32_t* uniform_override,
                         int32_t* n_live, int64_t* sample_ids, int32_t* tokens, float* logprobs,
@@ -429,8 +610,6 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
                  (double)c.shared_saved >= 0.2 * c.kv_tokens_this_call;
   c.kv_unique_tokens_this_call = c.kv_tokens_this_call - (double)c.shared_dup;
   c.attn_flops_this_call = 4.0 * c.kv_tokens_this_call * c.q_dim;
-  PromptQueue& q = c.queue;
-  const int n = q.n_samples;
   int n_fin = 0;  // prompts that end in this step: their last rows' logits follow the decode rows'
   c.timer.start_call();
   if (!Rq) {
@@ -439,49 +618,7 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
     engine_logits(c, nullptr, 0, B, c.logits.p);
     c.last_logit_rows = B;
   } else {
-    // pageable staging: each of these uploads is complete when its call returns
-    const int ns = (int)chunk->seqs.size();
-    std::vector<int> tok(Rq), pos(Rq), slot(Rq), row0(ns), len(ns), srow(ns), pos0(ns), want(B);
-    for (int i = 0; i < B; ++i) want[i] = i;
-    int r = 0, max_len = 0;
-    c.chunk_kv_tokens = 0;
-    for (int k = 0; k < ns; ++k) {
-      const ChunkSeq& cs = chunk->seqs[k];
-      const PendingPrompt& pp = q.pending[cs.pending_index];
-      row0[k] = B + r;
-      len[k] = cs.len;
-      srow[k] = pp.table_row;
-      pos0[k] = cs.begin;
-      for (int i = 0; i < cs.len; ++i, ++r) {
-        tok[r] = pp.prompt.tokens[cs.begin + i];
-        pos[r] = cs.begin + i;
-        slot[r] = pp.table_row;
-      }
-      if (cs.last) {
-        want.push_back(B + r - 1);
-        ++n_fin;
-      }
-      max_len = std::max(max_len, cs.len);
-      c.chunk_kv_tokens += (double)cs.len * cs.begin + 0.5 * cs.len * (cs.len + 1.0);
-    }
-    if (ns > rollout_ctx::kTempSlots || B + n_fin > c.logit_rows || (long long)B + (long long)n_fin * n > R)
-      fail(ROLLOUT_E_STATE, "internal: the chunk plan exceeds the workspaces");
-    c.chunk_attn_flops = 4.0 * c.chunk_kv_tokens * c.q_dim;
-    h2d(c.row_token.p + B, tok.data(), Rq * sizeof(int), c.stream);
-    h2d(c.row_pos.p + B, pos.data(), Rq * sizeof(int), c.stream);
-    h2d(c.row_slot.p + B, slot.data(), Rq * sizeof(int), c.stream);
-    h2d(c.seq_row0.p, row0.data(), ns * sizeof(int), c.stream);
-    h2d(c.seq_len.p, len.data(), ns * sizeof(int), c.stream);
-    h2d(c.seq_slot.p, srow.data(), ns * sizeof(int), c.stream);
-    h2d(c.seq_pos0.p, pos0.data(), ns * sizeof(int), c.stream);
-    h2d(c.chunk_ints.p, want.data(), want.size() * sizeof(int), c.stream);
-    SeqBatch sb{c.seq_row0.p, c.seq_len.p, c.seq_slot.p, ns, max_len};
-    sb.pos0 = c.seq_pos0.p;
-    sb.decode_rows = B;
-    engine_forward_rows(c, B + Rq, &sb);
-    engine_logits(c, c.chunk_ints.p, 0, B + n_fin, c.logits.p);
-    c.last_logit_rows = B + n_fin;
-    c.stats.prompt_tokens += Rq;
+    n_fin = forward_with_chunk(c, B, *chunk);
   }
   if (forced_tokens) {
     std::memcpy(hi + R, forced_tokens, B * sizeof(int));
@@ -513,74 +650,12 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
   // pinned host memory is mapped for the device: the kernel stores the step's results there
   launch_scatter_tokens(c.st, c.row_slot.p, c.out_tokens.p, c.out_logprobs.p, B, 1, hi + 3 * R, c.h_float.p, c.stream);
 
-  // ---- prompts that end in this step: response position 0 of their samples (rows B .. of the row arrays) ----
-  const int Rs = n_fin * n;
+  // prompts that end in this step: response position 0 of their samples
   std::vector<PendingPrompt*> fin;
   if (n_fin) {
-    std::vector<int> pairs, lrow(Rs), step0(Rs, 0), forced(Rs, -1), slots, srows, spos;
-    std::vector<float> inv_t(Rs), top_p(Rs);
-    std::vector<long long> ids(Rs);
     for (const ChunkSeq& cs : chunk->seqs)
-      if (cs.last) fin.push_back(&q.pending[cs.pending_index]);
-    for (int k = 0; k < n_fin; ++k) {
-      const PendingPrompt& pp = *fin[k];
-      pairs.insert(pairs.end(), pp.copy_pairs.begin(), pp.copy_pairs.end());
-      for (int j = 0; j < n; ++j) {
-        const int i = k * n + j;
-        lrow[i] = B + k;
-        inv_t[i] = 1.0f / pp.prompt.temperature;
-        top_p[i] = pp.prompt.top_p;
-        ids[i] = pp.samples[j].id;
-        if (pp.samples[j].slot >= 0) {
-          slots.push_back(pp.samples[j].slot);
-          srows.push_back(i);
-          spos.push_back(pp.samples[j].prompt_len);
-        }
-      }
-    }
-    if (pairs.size() > 2 * (size_t)R) fail(ROLLOUT_E_STATE, "internal: page copy list too long");
-    if (!pairs.empty()) {  // private copies of each prompt's partial last page
-      h2d(c.chunk_ints.p + R, pairs.data(), pairs.size() * sizeof(int), c.stream);
-      launch_copy_pages(c.kv_pool.p, c.chunk_ints.p + R, (int)pairs.size() / 2, m.n_layers,
-                        c.geom.layer_stride * c.elem, c.geom.page_stride * c.elem, c.stream);
-    }
-    h2d(c.row_aux.p + B, lrow.data(), Rs * sizeof(int), c.stream);
-    h2d(c.row_forced.p + B, forced.data(), Rs * sizeof(int), c.stream);
-    h2d(c.row_step.p + B, step0.data(), Rs * sizeof(int), c.stream);
-    h2d(c.row_inv_temp.p + B, inv_t.data(), Rs * sizeof(float), c.stream);
-    h2d(c.row_top_p.p + B, top_p.data(), Rs * sizeof(float), c.stream);
-    h2d(c.row_sample_id.p + B, ids.data(), Rs * sizeof(long long), c.stream);
-    SampleRows fr{};
-    fr.logits = c.logits.p;
-    fr.logits_row = c.row_aux.p + B;
-    fr.inv_temp = c.row_inv_temp.p + B;
-    fr.top_p = c.row_top_p.p + B;
-    fr.uniforms = nullptr;
-    fr.sample_id = c.row_sample_id.p + B;
-    fr.step = c.row_step.p + B;
-    fr.forced = c.row_forced.p + B;
-    fr.seed = c.rd.seed;
-    fr.tokens = c.out_tokens.p + B;
-    fr.logprobs = c.out_logprobs.p + B;
-    fr.weight_sums = nullptr;
-    if (Rs <= c.samp_rows) {
-      fr.part_max = c.samp_part_max.p;
-      fr.seg_sums = c.samp_seg_sums.p;
-    }
-    launch_sample(fr, Rs, m.vocab, c.stream);
-    const int n_new = (int)slots.size();
-    if (n_new) {  // the slot state of the samples that go on: the lists sit behind the page pairs
-      int* lists = c.chunk_ints.p + R + pairs.size();
-      if (pairs.size() + 3 * (size_t)n_new > 2 * (size_t)R) fail(ROLLOUT_E_STATE, "internal: slot lists too long");
-      h2d(lists, slots.data(), n_new * sizeof(int), c.stream);
-      h2d(lists + n_new, srows.data(), n_new * sizeof(int), c.stream);
-      h2d(lists + 2 * n_new, spos.data(), n_new * sizeof(int), c.stream);
-      init_slots_kernel<<<ceil_div(n_new, 256), 256, 0, c.stream>>>(c.st, lists, lists + n_new, lists + 2 * n_new,
-                                                                    c.out_tokens.p + B, c.row_sample_id.p + B,
-                                                                    c.row_inv_temp.p + B, c.row_top_p.p + B, n_new);
-    }
-    d2h(hi + 7 * R, c.out_tokens.p + B, Rs * sizeof(int), c.stream);
-    d2h(c.h_float.p + R, c.out_logprobs.p + B, Rs * sizeof(float), c.stream);
+      if (cs.last) fin.push_back(&c.queue.pending[cs.pending_index]);
+    sample_first_tokens(c, B, fin);
   }
   wait_step_done(c);
   c.timer.collect();
@@ -610,55 +685,7 @@ static void decode_impl(rollout_ctx& c, const int32_t* forced_tokens, const uint
   if (B) c.stats.decode_steps += 1;
   c.stats.tokens_emitted += B;
 
-  // ---- chunk bookkeeping: progress of the pending prompts; the finished ones hand over to their samples ----
-  if (chunk) {
-    for (const ChunkSeq& cs : chunk->seqs) q.pending[cs.pending_index].done += cs.len;
-    chunk->first_ids.resize(Rs);
-    chunk->first_groups.resize(Rs);
-    chunk->first_tokens.resize(Rs);
-    chunk->first_logprobs.resize(Rs);
-    chunk->first_finished.resize(Rs);
-    for (int k = 0; k < n_fin; ++k) {
-      PendingPrompt& pp = *fin[k];
-      q.open[pp.prompt.prompt_id] = n;
-      for (int j = 0; j < n; ++j) {
-        const int i = k * n + j;
-        Sample& s = pp.samples[j];
-        const int tok = hi[7 * R + i];
-        s.n_emitted = 1;
-        s.last_token = tok;
-        const bool done = s.max_new <= 1 || (s.eos_id >= 0 && tok == s.eos_id);
-        chunk->first_ids[i] = s.id;
-        chunk->first_groups[i] = s.group;
-        chunk->first_tokens[i] = tok;
-        chunk->first_logprobs[i] = c.h_float.p[R + i];
-        chunk->first_finished[i] = done ? 1 : 0;
-        c.stats.tokens_emitted += 1;
-        c.stats.samples_admitted += 1;
-        if (done) {
-          release_sample(c, s);
-          c.stats.samples_finished += 1;
-        } else {
-          const int64_t id = s.id;
-          Sample moved = std::move(s);
-          auto res = c.live.emplace(id, std::move(moved));
-          if (!res.second) {  // cannot happen: ids are handed out once
-            release_sample(c, moved);
-            c.stats.samples_aborted += 1;
-          }
-        }
-      }
-      // the prefill's own references; the samples hold theirs
-      for (int32_t pg : pp.pages.shared) c.pool->release(pg);
-      if (pp.pages.tail >= 0) c.pool->release(pp.pages.tail);
-      q.free_rows.push_back(pp.table_row);
-      if (c.grow_pages) q.admitted.emplace(pp.prompt.prompt_id, std::move(pp.prompt));  // kept: it may have to start over
-      c.stats.prompts_prefilled += 1;
-      c.live_dirty = true;
-    }
-    // finished prompts sit at the front of the pending list (prompts are cached in order)
-    for (int k = 0; k < n_fin; ++k) q.pending.pop_front();
-  }
+  if (chunk) commit_chunk(c, *chunk, fin);
   refresh_stats(c);
 }
 

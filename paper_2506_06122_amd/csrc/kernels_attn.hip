@@ -232,19 +232,19 @@ __device__ __forceinline__ void sum_query_planes(const AttnArgs& a, const float*
   }
 }
 
-// Query staging.  Thread t of the workgroup (THREADS threads) owns the rotary pairs idx = t + THREADS n, n < N:
+// Query staging.  Thread t of the workgroup owns the rotary pairs idx = t + 256 n, n < N:
 // column idx / 64 (the same in all 64 lanes), pair idx % 64.  rows[n] / heads[n] name the
 // sample row and the query head inside its KV group that column holds (row < 0: the column
 // is empty).  x0 / x1: the projection's elements, planes summed; cs: cos, sin of the row's position.
 // Bias / head norm, the rotary embedding, and the hi + lo half-precision parts into sm.q.
-template <bool EXTRA, int N, int THREADS = 256>
+template <bool EXTRA, int N>
 __device__ __forceinline__ void rotate_and_stage(const AttnArgs& a, const DecodeSmem& sm, int kvh, int G,
                                                  const int (&rows)[N], const int (&heads)[N], float (&x0)[N],
                                                  float (&x1)[N], const float2 (&cs)[N]) {
   const int tid = threadIdx.x, i = tid & 63;
 #pragma unroll
   for (int n = 0; n < N; ++n) {
-    const int col = (tid + THREADS * n) >> 6;
+    const int col = (tid + 256 * n) >> 6;
     float u = 0.f, w = 0.f;
     if (rows[n] >= 0) {  // uniform over the wavefront
       if (EXTRA) qkv_extras(a.extra, (kvh * G + heads[n]) * DH, i, a.extra.q_gain, x0[n], x1[n]);
@@ -277,28 +277,19 @@ __device__ __forceinline__ void stage_queries(const AttnArgs& a, const DecodeSme
   rotate_and_stage<EXTRA, N>(a, sm, kvh, G, rows, heads, x0, x1, cs);
 }
 
-// the W wavefronts' results of 16 columns -> one (max, sum, unnormalised output) per column in
-// sm.o[0..W-1], sm.m, sm.l (columns ml0 ..); every thread of the workgroup calls it
-template <int W = 4>
+// the 4 wavefronts' results of 16 columns -> one (max, sum, unnormalised output) per column in
+// sm.o[0..3], sm.m, sm.l (columns ml0 ..); every thread of the workgroup calls it
 __device__ __forceinline__ float merged_max(const DecodeSmem& sm, int col) {
-  float M = sm.m[col];
-#pragma unroll
-  for (int w = 1; w < W; ++w) M = fmaxf(M, sm.m[w * sm.ml_cols + col]);
-  return M;
+  return fmaxf(fmaxf(sm.m[col], sm.m[sm.ml_cols + col]), fmaxf(sm.m[2 * sm.ml_cols + col], sm.m[3 * sm.ml_cols + col]));
 }
-template <int W = 4>
 __device__ __forceinline__ float merged_sum(const DecodeSmem& sm, int col) {
-  float L = sm.l[col];
-#pragma unroll
-  for (int w = 1; w < W; ++w) L += sm.l[w * sm.ml_cols + col];
-  return L;
+  return sm.l[col] + sm.l[sm.ml_cols + col] + sm.l[2 * sm.ml_cols + col] + sm.l[3 * sm.ml_cols + col];
 }
-template <int W = 4>
 __device__ __forceinline__ void merge_wavefronts(const DecodeSmem& sm, int ml0, float m, float l, const f32x4 (&o)[8],
                                                  int wave, int c, int g) {
   if (g == 0) sm.m[wave * sm.ml_cols + ml0 + c] = m;
   __syncthreads();
-  const float M = merged_max<W>(sm, ml0 + c);
+  const float M = merged_max(sm, ml0 + c);
   const float M_use = (M == -INFINITY) ? 0.f : M;
   const float w = exp2f(m - M_use);
   if (g == 0) sm.l[wave * sm.ml_cols + ml0 + c] = l * w;
@@ -309,12 +300,8 @@ __device__ __forceinline__ void merge_wavefronts(const DecodeSmem& sm, int ml0, 
   __syncthreads();
 }
 // element e of the merged, unnormalised output: the wavefronts' parts in ascending order
-template <int W = 4>
 __device__ __forceinline__ float merged_out(const DecodeSmem& sm, int e) {
-  float acc = sm.o[e];
-#pragma unroll
-  for (int w = 1; w < W; ++w) acc += sm.o[w * 16 * DH + e];
-  return acc;
+  return sm.o[e] + sm.o[16 * DH + e] + sm.o[2 * 16 * DH + e] + sm.o[3 * 16 * DH + e];
 }
 
 // one workgroup = (own-range split, KV head, sample); wavefront w takes the groups w, w + 4, ...
