@@ -273,8 +273,8 @@ def measure_other_configs(args, flags, copy_ceiling_gbs) -> dict:
     kv_per_flop = shape.n_kv_heads * shape.head_dim * 4 / (4.0 * shape.n_q_heads * shape.head_dim)
 
     def brief(roof):
-        keep = ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "avg_launch_us", "timed_launches",
-                "algorithmic_bytes_per_launch", "achieved_without_prefix_reuse", "frac_of_copy_ceiling")
+        keep = ("bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_source", "kernel", "avg_launch_us",
+                "timed_launches", "algorithmic_bytes_per_launch", "achieved_without_prefix_reuse", "frac_of_copy_ceiling")
         r = {k: roof[k] for k in keep if k in roof}
         r["top_kernels"] = roof["per_kernel"][:6]
         return r
@@ -328,7 +328,8 @@ def measure_other_configs(args, flags, copy_ceiling_gbs) -> dict:
         "workload": "teacher-forced log-prob pass, Qwen2.5-7B-shaped dense decoder, bf16, 24 packed sequences (of the "
                     "config's 512), length U{512..8192}, %d tokens; one pass after a one-sequence warm-up" % len(tokens),
         "value": len(tokens) / dt, "unit": "tokens/s", "ms_per_step": 1e3 * dt, "tokens": int(len(tokens)),
-        "roofline": brief(roofline_of(kernels, bracket_ms, None, copy_ceiling_gbs, kv_per_flop))}
+        # the counters of profiles/logprobs_c5_hbm_traffic.txt were taken on this same pass
+        "roofline": brief(roofline_of(kernels, bracket_ms, "logprobs_c5_hbm_traffic.txt", copy_ceiling_gbs, kv_per_flop))}
     eng.close()
     del eng, weights
     torch.cuda.empty_cache()
