@@ -336,6 +336,56 @@ def measure_other_configs(args, flags, copy_ceiling_gbs) -> dict:
     return out
 
 
+def attention_launch_probe(args) -> int:
+    """Decode steps of config 2's shape (4 layers unless --layers says otherwise) with --prompts
+    rows that all hold --context cached positions: what one launch of the decode attention costs
+    as a function of rows and bytes, without a job's mix of both.  Every launch is bracketed by
+    HIP events (the empty bracket is reported beside it); under rocprofv3 --kernel-trace --stats
+    the kernel's own average is the one to read."""
+    import torch
+    import paper_2506_06122_amd as R
+    import workloads
+    from paper_2506_06122_amd import binding as B
+    shape = dataclasses.replace(workloads.C2_1P5B, n_layers=args.layers or 4)
+    weights = workloads.make_weights(shape, seed=1, gains="ones")
+    rows, ctx, steps = args.prompts or 187, args.context, max(args.steps, 12)
+    rng = np.random.default_rng(1)
+    toks = rng.integers(0, shape.vocab, rows * ctx).astype(np.int32)
+    offs = (np.arange(rows + 1) * ctx).astype(np.int32)
+    kv_per_token = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * 2
+    eng = R.Rollout(shape, weights, kv_pool_bytes=rows * (ctx + 128) * kv_per_token + (64 << 20), page_tokens=32,
+                    max_live_samples=rows, max_context=ctx + 64, max_batch_tokens=16384, seed=1,
+                    flags=B.RT_KERNEL_TIMING, timing_stride=1)
+    per_call = max(1, min(64, 16384 // ctx))
+    for i in range(0, rows, per_call):
+        j = min(rows, i + per_call)
+        eng.rollout_prefill(toks[offs[i]:offs[j]], offs[i:j + 1] - offs[i], 1, np.full(j - i, steps + 2, np.int32))
+    before = {k["name"]: k for k in eng.rollout_kernel_stats()}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        eng.rollout_decode_step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    kernels, bracket_ms = kernel_table(eng, before)
+    eng.close()
+    kernels = [dict(name=k["name"], launches=k["launches"], avg_us=1e3 * k["ms"] / k["launches"],
+                    **{"MB": k["bytes"] / k["launches"] / 1e6, "GB/s": k["bytes"] / (k["ms"] * 1e-3) / 1e9}) for k in kernels]
+    attn = [k for k in kernels if k["name"].startswith("attn_decode")]
+    out = {"metric": "decode attention launch on 1 MI355X", "value": attn[0]["avg_us"] if attn else None, "unit": "us",
+           "n_gpus": 1, "steps": steps, "warmup": 0, "ms_per_step": 1e3 * dt, "higher_is_better": False,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "configs[1]'s shape with %d layers, %d rows x %d cached positions each, %d decode steps, "
+                                  "every launch bracketed by HIP events" % (shape.n_layers, rows, ctx, steps)},
+           "roofline": {"bound": "hbm", "achieved": attn[0]["GB/s"] if attn else None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": attn[0]["GB/s"] / HBM_PEAK_GBS if attn else None, "traffic": None,
+                        "kernel": attn[0]["name"] if attn else None, "event_bracket_us": 1e3 * bracket_ms,
+                        "per_kernel": kernels[:8]},
+           "cpu_baseline": None}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -347,7 +397,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true",
                     help="default workload only: skip the one-job measurements of configs[2] and configs[4]")
-    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns", "c2-refresh", "loss"],
+    ap.add_argument("--workload", choices=["c2", "c3", "c4", "c5", "c2-queue", "c2-turns", "c2-refresh", "loss", "c2-attn"],
                     default="c2",
                     help="c2 = headline (1.5B shape); c3 = 7B-shape rollout; c4 = 30B-A3B-shape MoE rollout; "
                          "c5 = teacher-forced log-prob pass on the 7B shape; c2-queue = config 2's model and "
@@ -358,6 +408,8 @@ def main() -> int:
                          "policy-gradient objective over config 5's 512 packed sequences (rollout_policy_loss)")
     ap.add_argument("--prompts", type=int, default=0, help="prompts (c5: sequences); 0 = the workload's own count")
     ap.add_argument("--layers", type=int, default=0, help="cut the model to this many layers (0 = all)")
+    ap.add_argument("--context", type=int, default=400,
+                    help="c2-attn: cached positions of every row (--prompts = the number of rows, default 187)")
     ap.add_argument("--chunk-rows", type=int, default=0,
                     help="c2-queue: chunked prefill, at most this many prompt rows ride along with each decode step "
                          "(0 = whole prompts before the step)")
@@ -428,6 +480,8 @@ def main() -> int:
                                        "kernel": "policy_advantage_kernel + policy_scale_kernel (whole call)"},
                           "cpu_baseline": None}))
         return 0
+    if wl == "c2-attn":
+        return attention_launch_probe(args)
     shape = {"c2": workloads.C2_1P5B, "c3": workloads.C3_7B, "c4": workloads.C4_30B_A3B, "c5": workloads.C3_7B,
              "c2-queue": workloads.C2_1P5B, "c2-turns": workloads.C2_1P5B, "c2-refresh": workloads.C2_1P5B}[wl]
     cut = ""
