@@ -315,6 +315,54 @@ def test_c4_shape_many_rows_four_layers():
     eng.close()
 
 
+def test_c4_shape_512_live_rows_sampled():
+    """Config 4's batch size on its matrix shapes (128 experts, top-8; 4 of the 48 layers): 64
+    prompts x 8 samples = 512 live rows, 32 picks per expert and step on average, every expert's
+    row blocks in use.  The oracle follows three prompts and one sample of each through the
+    decode steps, computing with the expert sets the GPU recorded for exactly those rows - which
+    must be valid top-8 sets of its own router logits."""
+    import dataclasses
+    shape = dataclasses.replace(workloads.C4_30B_A3B, n_layers=4, name="qwen3-30b-a3b-shape-4-layers")
+    w = workloads.make_weights(shape, seed=1)
+    model = oracle_model(shape, w)
+    P, n, steps = 64, 8, 3
+    eng = make_engine(shape, w, kv_pool_bytes=2 << 30, max_live_samples=P * n, max_context=128, max_batch_tokens=4096,
+                      flags=2)
+    toks, offs = workloads.make_prompts(P, 20, 60, shape.vocab, seed=16)
+    forced = np.random.default_rng(10).integers(0, shape.vocab, (P * n, steps)).astype(np.int32)
+    ids, tk, lps, fin = eng.rollout_prefill(toks, offs, n, np.full(P * n, steps, np.int32), forced_first=forced[:, 0])
+    assert len(ids) == P * n and np.array_equal(tk, forced[:, 0])
+    gpu = eng.rollout_debug_logits()
+    routing = eng.rollout_debug_routing(int(offs[-1]))
+    fwd = T.KVForward(model)
+    picks, caches, worst = [0, 31, 63], {}, 0.0
+    for p in picks:
+        model.routing_override = {l: routing[l][offs[p]:offs[p + 1]] for l in range(shape.n_layers)}
+        c = fwd.new_cache()
+        ref = fwd.extend([c], [toks[offs[p]:offs[p + 1]]])[0][-1]
+        worst = max(worst, float(np.max(np.abs(gpu[p] - ref))))
+        caches[p] = c.fork()
+    for t in range(1, steps):
+        ids2, tk, lps, fin = eng.rollout_decode_step(forced_tokens=forced[:, t])
+        assert np.array_equal(ids2, ids)
+        gpu = eng.rollout_debug_logits()
+        routing = eng.rollout_debug_routing(P * n)
+        assert routing.shape == (shape.n_layers, P * n, shape.top_k)
+        for layer in range(shape.n_layers):   # every row picked 8 different experts
+            assert all(len(set(row)) == shape.top_k for row in routing[layer][::37].tolist())
+        for p in picks:
+            i = p * n + 3
+            model.routing_override = {l: routing[l][[i]] for l in range(shape.n_layers)}
+            ref = fwd.extend([caches[p]], [[int(forced[i, t - 1])]])[0][0]
+            worst = max(worst, float(np.max(np.abs(gpu[i] - ref))))
+    below, outside = (max(g[i] for g in model.routing_regret) for i in (0, 1))
+    print(f"{shape.name}, {P * n} live rows: max |dlogits| on the oracle's rows = {worst:.3e}, routing gaps "
+          f"{below:.3e} / {outside:.3e} over {len(model.routing_regret)} decisions")
+    assert eng.rollout_get_stats()["matrix_core_path"] == 1
+    assert worst <= TOL["bf16"] and below <= TOL["bf16"] and outside <= TOL["bf16"]
+    eng.close()
+
+
 @pytest.mark.parametrize("n_prompts,n_samples,lo,hi", [(1, 2, 3, 9), (6, 8, 30, 200)], ids=["few-rows", "many-rows"])
 def test_matrix_core_moe_row_blocks(n_prompts, n_samples, lo, hi):
     """Grouped expert projections: a handful of rows (most experts untouched, one row each) and
