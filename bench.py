@@ -8,8 +8,8 @@ timings gathered by the library on its own stream during the timed steps), and t
 oracle timed on a bounded slice of the same workload.
 
 The default workload (`value`) is configs[1], the Qwen2.5-1.5B shape with 32 prompts x 8
-samples: the largest configuration whose warm-up and timed jobs (25 in the full test run) fit
-a benchmark run of a few minutes - one job of the 7B-shape rollout alone takes about a minute.
+samples: the largest configuration of which a couple of dozen warm-up and timed jobs fit a
+benchmark run of a few minutes - one job of the 7B-shape rollout alone takes about a minute.
 So that the larger configurations are measured in the same run all the same, the default run
 then adds, under "other_configs" of the same JSON line, one job of configs[2] (7B-shape
 rollout, 64 x 8 samples) and one teacher-forced pass over 24 of configs[4]'s packed sequences,
