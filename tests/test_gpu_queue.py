@@ -459,3 +459,48 @@ def test_chunked_prefill_rides_along_with_decode_steps(chunk_rows, grow, moe):
           f"max |dlogp| vs {against} = {worst:.3e}; {len(differ)} samples differ from the unchunked run")
     assert worst <= 2e-2
     assert len(differ) <= 2, differ
+
+
+def test_chunking_is_refused_where_it_cannot_run():
+    """rollout_queue_chunking: E_INVAL for a negative budget, E_STATE on the plain path (the mixed
+    batch is a matrix-core forward) and while a prompt is partly cached; a budget larger than the
+    workspace rows is cut to what a step can carry; the target policy also drops what is pending."""
+    import paper_2506_06122_amd as R
+    plain = make_engine(workloads.C1_TINY, scaled_weights(workloads.C1_TINY, seed=1), max_live_samples=4, max_context=64,
+                        max_batch_tokens=64)
+    assert plain.rollout_get_stats()["matrix_core_path"] == 0
+    with pytest.raises(R.RolloutError) as e:
+        plain.rollout_queue_chunking(16)
+    assert e.value.code == -4
+    plain.rollout_queue_chunking(0)                       # switching it off is always fine
+    plain.close()
+
+    shape = workloads.SMALL_BF16
+    eng = make_engine(shape, scaled_weights(shape, seed=1), max_live_samples=4, max_context=160, max_batch_tokens=96)
+    with pytest.raises(R.RolloutError) as e:
+        eng.rollout_queue_chunking(-1)
+    assert e.value.code == -1
+    eng.rollout_queue_chunking(1 << 20)                   # more than a step's rows: the workspace bounds it
+    eng.rollout_queue_policy(target_prompts=1)
+    toks, offs = workloads.make_prompts(3, 90, 96, shape.vocab, seed=51)
+    eng.rollout_queue_push(toks, offs, 2, np.array([1, 1, 6, 6, 6, 6], np.int32))
+    ids, tk, lps, fin, n_adm = eng.rollout_queue_step()    # 96 workspace rows: prompt 0 and a piece of prompt 1
+    qs = eng.rollout_queue_get_stats()
+    assert n_adm == 2 and ids.tolist() == [0, 1] and fin.all()      # prompt 0: both samples end at position 0
+    assert qs["closed"] and qs["prompts_completed"] == 1 and qs["prompts_pending"] == 0 and qs["prompts_waiting"] == 0
+    assert eng.rollout_get_stats()["pages_in_use"] == 0 and not eng.rollout_queue_busy()
+    eng.close()
+
+    eng = make_engine(shape, scaled_weights(shape, seed=1), max_live_samples=4, max_context=160, max_batch_tokens=96)
+    eng.rollout_queue_chunking(40)
+    eng.rollout_queue_push(toks, offs, 2, np.full(6, 3, np.int32))
+    eng.rollout_queue_step()
+    assert eng.rollout_queue_get_stats()["prompts_pending"] >= 1
+    with pytest.raises(R.RolloutError) as e:
+        eng.rollout_queue_chunking(0)
+    assert e.value.code == -4
+    while eng.rollout_queue_busy():
+        eng.rollout_queue_step()
+    eng.rollout_queue_chunking(0)
+    assert eng.rollout_get_stats()["pages_in_use"] == 0
+    eng.close()
