@@ -221,6 +221,24 @@ def measured_traffic(kernel: str, summary: str):
     return 1024.0 * sum(factor[c] * mean[c] for c in mean)
 
 
+def profiled_launch_us(kernel: str, summary: str):
+    """Average duration of `kernel` in the committed rocprofv3 kernel-trace summary, or None when
+    there is none or the kernel sources have changed since."""
+    from paper_2506_06122_amd import build
+    path = os.path.join(ROOT, "profiles", summary)
+    if not os.path.exists(path):
+        return None
+    digest, want, found = None, kernel.replace(" ", ""), None
+    with open(path) as f:
+        for line in f:
+            if line.startswith("kernel-sources-sha256:"):
+                digest = line.split(":", 1)[1].strip()
+            parts = line.split(None, 4)
+            if len(parts) == 5 and parts[0].isdigit() and parts[4].strip().replace("void ", "").replace(" ", "") == want:
+                found = float(parts[2])
+    return found if digest == build.sources_digest() else None
+
+
 def roofline_of(kernels, bracket_ms, traffic_summary=None, copy_ceiling_gbs=None, kv_bytes_per_attn_flop=None):
     """Roofline object of the kernel with the most time.  Beside the contract's keys: the
     fraction of a measured plain-copy rate, and for the decode attention the rate counted
@@ -249,6 +267,15 @@ def roofline_of(kernels, bracket_ms, traffic_summary=None, copy_ceiling_gbs=None
         if roofline["traffic"] is not None:  # not measured in this run: read from the committed counter summary
             roofline["traffic_source"] = "profiles/" + traffic_summary
     roofline["avg_launch_us"] = 1e3 * top["ms"] / top["launches"]
+    if traffic_summary:
+        # the profiler's own average for the same kernel over a whole run (its timestamps, about
+        # 2 us per launch above the event times with the empty bracket taken off), when the
+        # committed kernel trace of this workload was taken on these kernel sources
+        us = profiled_launch_us(top["name"], traffic_summary.replace("hbm_traffic", "kernel_trace"))
+        if us:
+            roofline["rocprofv3_avg_launch_us"] = us
+            roofline["frac_at_rocprofv3_time"] = top["bytes"] / top["launches"] / (us * 1e-6) / 1e9 / HBM_PEAK_GBS \
+                if roofline["bound"] == "hbm" else top["flops"] / top["launches"] / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS
     roofline["timed_launches"] = top["launches"]
     roofline["event_bracket_us"] = 1e3 * bracket_ms
     roofline["per_kernel"] = [
@@ -274,7 +301,7 @@ def measure_other_configs(args, flags, copy_ceiling_gbs) -> dict:
 
     def brief(roof):
         keep = ("bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_source", "kernel", "avg_launch_us",
-                "timed_launches", "algorithmic_bytes_per_launch", "achieved_without_prefix_reuse", "frac_of_copy_ceiling")
+                "rocprofv3_avg_launch_us", "frac_at_rocprofv3_time", "timed_launches", "algorithmic_bytes_per_launch", "achieved_without_prefix_reuse", "frac_of_copy_ceiling")
         r = {k: roof[k] for k in keep if k in roof}
         r["top_kernels"] = roof["per_kernel"][:6]
         return r

@@ -468,6 +468,17 @@ static void embed_and_norm(rollout_ctx& c, int R) {
 // KV splits per (sample, KV head) of a decode step: one workgroup per CU, at least 256 cached
 // positions each, at most the 16 the merge kernels take.  (Measured: more, shorter splits lose
 // to the per-workgroup prologue and the longer merge.)
+// The second launch of a decode attention whose rows have several partial results: joins the
+// slots of every (row, KV head).  Timed under its own name; bytes = the slots read (output
+// fragments, maxima and sums) and the rows written as two bf16 planes.
+static void merge_attention_slots(rollout_ctx& c, const AttnArgs& at, int rows) {
+  const int slots = at.n_slots ? at.n_slots : at.n_splits;
+  c.timer.begin("attn_merge_fused_kernel",
+                (double)rows * c.md.n_kv_heads * slots * (16 * 128 + 32) * 4.0 + 4.0 * rows * c.q_dim, 0, c.stream);
+  launch_attention_merge(at, c.stream);
+  c.timer.end(c.stream);
+}
+
 static int decode_attention_splits(const rollout_ctx& c, int base) {
   return std::max(1, std::min({ceil_div(256, base), ceil_div(c.decode_max_ctx, 256), c.attn_max_parts / base, 16}));
 }
@@ -689,6 +700,7 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
                       kv_bytes + qo_bytes, c.attn_flops_this_call, s);
         launch_attention_decode_grouped(at, s);
         c.timer.end(s);
+        merge_attention_slots(c, at, Bd);
       } else {
         const int n_splits = decode_attention_splits(c, base);
         at.split_tokens = ceil_div(ceil_div(c.decode_max_ctx, n_splits), 128) * 128;
@@ -697,6 +709,7 @@ static void forward_rows_tiled(rollout_ctx& c, int R, const SeqBatch* seqs) {
                       kv_bytes + qo_bytes, c.attn_flops_this_call, s);
         launch_attention_decode_fused(at, s);
         c.timer.end(s);
+        if (at.n_splits > 1) merge_attention_slots(c, at, Bd);
       }
     }
 
@@ -844,6 +857,7 @@ static void forward_rows_decode(rollout_ctx& c, int R) {
                   c.attn_flops_this_call, s);
     launch_attention_decode_fused(at, s);
     c.timer.end(s);
+    if (at.n_splits > 1) merge_attention_slots(c, at, R);
 
     stream_project(c, c.attn_bf16, c.q_dim, L.wo_p.p, R, d, c.q_dim, EPI_RESID, false, nullptr, d, 0, L.norm2.p);
     stream_project(c, c.h_bf16, d, L.w_gate_up_p.p, R, 2 * f, d, EPI_SWIGLU_BF16, true, c.act_bf16.p, f,

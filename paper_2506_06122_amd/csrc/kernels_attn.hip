@@ -620,7 +620,9 @@ void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s) {
   const dim3 grid(a.n_splits, a.geom.n_kv_heads, a.rows);
   if (a.extra.bias || a.extra.q_gain) attn_decode_fused_kernel<true><<<grid, 256, 0, s>>>(a);
   else attn_decode_fused_kernel<false><<<grid, 256, 0, s>>>(a);
-  if (a.n_splits > 1) attn_merge_fused_kernel<<<dim3(a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
+}
+void launch_attention_merge(const AttnArgs& a, hipStream_t s) {
+  if (a.rows) attn_merge_fused_kernel<<<dim3(a.geom.n_kv_heads, a.rows), 256, 0, s>>>(a);
 }
 
 template <int NCT>
@@ -634,7 +636,6 @@ void launch_attention_decode_grouped(const AttnArgs& a, hipStream_t s) {
   const unsigned grid = (unsigned)(a.n_groups * n_kv * a.n_splits_a + a.rows * n_kv * a.n_splits);
   if (GROUP_MEMBERS * G <= 16) launch_grouped<1>(a, grid, s);
   else launch_grouped<2>(a, grid, s);
-  attn_merge_fused_kernel<<<dim3(n_kv, a.rows), 256, 0, s>>>(a);
 }
 
 // ------------------------------------------------------------------------------ prefill

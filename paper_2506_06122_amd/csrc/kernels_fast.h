@@ -231,9 +231,12 @@ struct AttnArgs {
   int n_seqs, max_seq_len;
 };
 void launch_attention_prefill(const AttnArgs& a, hipStream_t s);
+// Decode attention: partial results per (row, KV head, slot) when a.n_splits > 1 or the launch is
+// the grouped one - launch_attention_merge then joins the slots; with one split the result is final.
 void launch_attention_decode_fused(const AttnArgs& a, hipStream_t s);
 // the same with shared prompts; needs n_q_heads / n_kv_heads <= 8 (4 members x heads <= 32 columns)
 void launch_attention_decode_grouped(const AttnArgs& a, hipStream_t s);
+void launch_attention_merge(const AttnArgs& a, hipStream_t s);
 
 // ---- policy-gradient objective over packed rollouts (kernels_loss.hip) ----------------------
 struct PolicyLossArgs {
